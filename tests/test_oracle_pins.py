@@ -1,0 +1,492 @@
+"""Pins for the CPU oracle: things the paper and the mathematics fix.
+
+Each test is chosen so that a plausible mistake in the oracle (a dropped term,
+a wrong mask bound, a transposed operand, a position off by one) fails it.
+Citations are to arXiv 2406.02657.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle.block_transformer as O
+from synth import CONFIGS, make_prompts, make_weights, tensor_table
+from helpers import tiny_cfg
+
+TOL = 1e-10
+
+
+def build(cfg):
+    return O.Params(make_weights(cfg))
+
+
+# --------------------------------------------------------------------------
+# T1  cached mode == full recomputation (Sec. 2.1; Fig. 1; App. C)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("lb,p", [(1, 1), (2, 1), (4, 2), (8, 3), (4, 1), (1, 0)])
+@pytest.mark.parametrize("parallel", [1, 0])
+@pytest.mark.parametrize("rot", [-1, 0])
+def test_cached_equals_full(lb, p, parallel, rot):
+    cfg = tiny_cfg(block_len=lb, prefix_len=p, parallel_residual=parallel, rotary_dims=rot,
+                   prompt_len=2 * lb, d_model=32, n_heads=2)
+    P = build(cfg)
+    prompts = make_prompts(cfg, batch=3)
+    n_new = 2 * lb + 3
+    ids_f, lg_f = O.generate_full(P, cfg, prompts, n_new)
+    ids_c, lg_c, _ = O.generate_cached(P, cfg, prompts, n_new)
+    assert np.array_equal(ids_f, ids_c)
+    assert np.max(np.abs(lg_f - lg_c)) < TOL
+
+
+def test_teacher_forced_equals_stepwise():
+    cfg = tiny_cfg(block_len=4, prefix_len=2)
+    P = build(cfg)
+    rng = np.random.default_rng(0)
+    toks = rng.integers(0, cfg.vocab, size=(2, 20))
+    tf = O.teacher_forced_logits(P, cfg, toks, [1, 3, 4])
+    for i in (1, 3, 4):
+        for k in range(cfg.block_len):
+            t = i * cfg.block_len + k
+            ref = O.next_token_logits_full(P, cfg, toks[:, :t])
+            assert np.max(np.abs(tf[i][:, k] - ref)) < TOL
+    # and the cached generator forced onto the same history
+    _, lg_c, _ = O.generate_cached(P, cfg, toks[:, :8], 12, forced=toks[:, 8:])
+    for t in range(8, 20):
+        ref = O.next_token_logits_full(P, cfg, toks[:, :t])
+        assert np.max(np.abs(lg_c[:, t - 8] - ref)) < TOL
+
+
+# --------------------------------------------------------------------------
+# T2  locality of the token decoder, causality of the block decoder
+#     (Sec. 2.4: each block is processed independently; Sec. 2.3)
+# --------------------------------------------------------------------------
+def test_token_decoder_locality_bit_identical():
+    cfg = tiny_cfg(block_len=4, prefix_len=2)
+    P = build(cfg)
+    rng = np.random.default_rng(1)
+    c = rng.standard_normal((2, cfg.d_model))
+    blk = rng.integers(0, cfg.vocab, size=(2, 3))
+    base = O.block_logits(P, cfg, c, blk)
+    # block_logits has no other input: anything outside (c, current block) cannot matter.
+    # Same check through the cached generator: hold the context fixed, vary history.
+    toks_a = rng.integers(0, cfg.vocab, size=(2, 12))
+    toks_b = toks_a.copy()
+    toks_b[:, :8] = rng.integers(0, cfg.vocab, size=(2, 8))      # different earlier blocks
+    outs = []
+    for toks in (toks_a, toks_b):
+        g = O.CachedGenerator(P, cfg, 2, 8)
+        g.prefill(toks[:, :8])
+        g.c = c.copy()                                             # inject the context
+        lg = [g.step(forced_ids=toks[:, 8 + k])[0] for k in range(4)]
+        outs.append(np.stack(lg, 1))
+    assert np.array_equal(outs[0], outs[1])                        # bit-identical
+    # a token inside the current block does matter
+    blk2 = blk.copy()
+    blk2[:, 0] = (blk2[:, 0] + 1) % cfg.vocab
+    other = O.block_logits(P, cfg, c, blk2)
+    assert np.array_equal(other[:, 0], base[:, 0])                 # before the edit: same
+    assert np.max(np.abs(other[:, 1:] - base[:, 1:])) > 1e-6       # after it: different
+
+
+def test_block_decoder_causality():
+    cfg = tiny_cfg(block_len=2, prefix_len=1)
+    P = build(cfg)
+    rng = np.random.default_rng(2)
+    toks = rng.integers(0, cfg.vocab, size=(1, 12))
+    base = O.context_embeddings(P, cfg, toks)
+    for j in range(6):
+        t2 = toks.copy()
+        t2[0, 2 * j] = (t2[0, 2 * j] + 1) % cfg.vocab
+        out = O.context_embeddings(P, cfg, t2)
+        assert np.array_equal(out[:, :j], base[:, :j])             # earlier outputs untouched
+        assert np.all(np.max(np.abs(out[:, j:] - base[:, j:]), axis=-1) > 1e-9)  # later all change
+
+
+# --------------------------------------------------------------------------
+# T3  L_B = 1 reduces to a vanilla transformer (Sec. 3.5 "Analysis on vanilla
+#     ... to block": L_B=1 differs from vanilla only by local attention in the
+#     upper layers).  The vanilla model below shares no code with the oracle.
+# --------------------------------------------------------------------------
+def _v_ln(x, g, b, eps):
+    mu = sum(x) / len(x)
+    var = sum((xi - mu) ** 2 for xi in x) / len(x)
+    return np.array([(xi - mu) / math.sqrt(var + eps) for xi in x]) * g + b
+
+
+def _v_gelu(u):
+    return np.array([0.5 * ui * (1.0 + math.erf(ui / math.sqrt(2.0))) for ui in u])
+
+
+def _v_rot(vec, pos, rot):
+    out = vec.copy()
+    for t in range(rot // 2):
+        th = pos * (10000.0 ** (-2.0 * t / rot))
+        a, b = vec[t], vec[t + rot // 2]
+        out[t] = a * math.cos(th) - b * math.sin(th)
+        out[t + rot // 2] = b * math.cos(th) + a * math.sin(th)
+    return out
+
+
+def vanilla_forward(W, x_rows, layers, H, rot, eps, parallel):
+    """Textbook decoder stack on one sequence.  x_rows: [T, D] input embeddings.
+
+    layers: list of (prefix, mask) where mask[i][j] says whether position i may
+    attend to position j, or ("ln", gname, bname) for a LayerNorm stage.
+    Written with per-position, per-head Python loops on purpose.
+    """
+    f = lambda nm: np.asarray(W[nm], dtype=np.float64)
+    T, D = x_rows.shape
+    dh = D // H
+    x = [x_rows[t].astype(np.float64) for t in range(T)]
+    for st in layers:
+        if st[0] == "ln":
+            x = [_v_ln(xt, f(st[1]), f(st[2]), eps) for xt in x]
+            continue
+        pre, mask, positions = st
+
+        def attn(inp):
+            q, k, v = [], [], []
+            for t in range(T):
+                u = _v_ln(inp[t], f(pre + "ln1_g"), f(pre + "ln1_b"), eps)
+                z = f(pre + "W_qkv") @ u + f(pre + "b_qkv")
+                q.append(z[:D]); k.append(z[D:2 * D]); v.append(z[2 * D:])
+            out = []
+            for t in range(T):
+                o = np.zeros(D)
+                for h in range(H):
+                    sl = slice(h * dh, (h + 1) * dh)
+                    qt = _v_rot(q[t][sl], positions[t], rot)
+                    js = [j for j in range(T) if mask[t][j]]
+                    sc = [float(qt @ _v_rot(k[j][sl], positions[j], rot)) / math.sqrt(dh) for j in js]
+                    m = max(sc)
+                    e = [math.exp(s - m) for s in sc]
+                    z = sum(e)
+                    for w8, j in zip(e, js):
+                        o[sl] += (w8 / z) * v[j][sl]
+                out.append(f(pre + "W_o") @ o + f(pre + "b_o"))
+            return out
+
+        def mlp(inp):
+            out = []
+            for t in range(T):
+                u = _v_ln(inp[t], f(pre + "ln2_g"), f(pre + "ln2_b"), eps)
+                out.append(f(pre + "W_down") @ _v_gelu(f(pre + "W_up") @ u + f(pre + "b_up")) + f(pre + "b_down"))
+            return out
+
+        if parallel:
+            a, m = attn(x), mlp(x)
+            x = [x[t] + a[t] + m[t] for t in range(T)]
+        else:
+            a = attn(x)
+            y = [x[t] + a[t] for t in range(T)]
+            m = mlp(y)
+            x = [y[t] + m[t] for t in range(T)]
+    return np.stack(x)
+
+
+@pytest.mark.parametrize("parallel", [1, 0])
+@pytest.mark.parametrize("n_t", [2, 0])
+def test_lb1_reduces_to_vanilla(parallel, n_t):
+    cfg = tiny_cfg(block_len=1, prefix_len=0, n_block_layers=2, n_token_layers=n_t,
+                   parallel_residual=parallel, d_model=16, n_heads=2, d_ff=32, prompt_len=3)
+    W = make_weights(cfg)
+    P = O.Params(W)
+    T = 7
+    toks = np.random.default_rng(3).integers(0, cfg.vocab, size=(1, T))
+    causal = [[j <= i for j in range(T)] for i in range(T)]
+    selfonly = [[j == i for j in range(T)] for i in range(T)]
+    stages = [(f"blk.{l}.", causal, list(range(T))) for l in range(2)]
+    stages.append(("ln", "blk_lnf_g", "blk_lnf_b"))
+    stages += [(f"tok.{l}.", selfonly, [0] * T) for l in range(n_t)]
+    stages.append(("ln", "tok_lnf_g", "tok_lnf_b"))
+    hid = vanilla_forward(W, np.asarray(W["E_emb"], dtype=np.float64)[toks[0]], stages,
+                          cfg.n_heads, cfg.rot, cfg.ln_eps, parallel)
+    ref_logits = hid @ np.asarray(W["W_head"], dtype=np.float64).T       # [T, V]; row t predicts x_{t+1}
+    for t in range(1, T + 1):
+        got = O.next_token_logits_full(P, cfg, toks[:, :t])[0]
+        assert np.max(np.abs(got - ref_logits[t - 1])) < TOL
+    # cached generation follows the same numbers
+    _, lg_c, _ = O.generate_cached(P, cfg, toks[:, :3], 4, forced=toks[:, 3:7])
+    for k in range(4):
+        assert np.max(np.abs(lg_c[0, k] - ref_logits[2 + k])) < TOL
+
+
+def test_lb1_identity_prefix_equals_no_prefix():
+    cfg0 = tiny_cfg(block_len=1, prefix_len=0, d_model=16, n_heads=2, d_ff=32, prompt_len=3)
+    cfg1 = cfg0.with_(prefix_len=1)
+    W = make_weights(cfg0)
+    W1 = dict(W)
+    W1["W_prefix"] = np.eye(16, dtype=np.float32)
+    W1["b_prefix"] = np.zeros(16, dtype=np.float32)
+    toks = np.random.default_rng(4).integers(0, cfg0.vocab, size=(2, 6))
+    a = O.next_token_logits_full(O.Params(W), cfg0, toks)
+    b = O.next_token_logits_full(O.Params(W1), cfg1, toks)
+    assert np.max(np.abs(a - b)) < TOL
+
+
+def test_block_model_against_vanilla_pieces():
+    """L_B=4, P=2: block decoder == vanilla stack over block embeddings; token decoder ==
+    vanilla stack over [prefix, tokens]; glued by concat / projection written out here."""
+    cfg = tiny_cfg(block_len=4, prefix_len=2, d_model=16, n_heads=2, d_ff=32, prompt_len=8, vocab=23)
+    W = make_weights(cfg)
+    P = O.Params(W)
+    f = lambda nm: np.asarray(W[nm], dtype=np.float64)
+    toks = np.random.default_rng(5).integers(0, cfg.vocab, size=(1, 11))   # 2 full blocks + 3
+    nblk = 2
+    e = np.stack([np.concatenate([f("E_emb")[toks[0, j * 4 + k]] for k in range(4)]) for j in range(nblk)])
+    causal = lambda n: [[j <= i for j in range(n)] for i in range(n)]
+    st = [(f"blk.{l}.", causal(nblk), list(range(nblk))) for l in range(cfg.n_block_layers)]
+    st.append(("ln", "blk_lnf_g", "blk_lnf_b"))
+    ctx = vanilla_forward(W, e, st, cfg.n_heads, cfg.rot, cfg.ln_eps, 1)[-1]
+    pre = (f("W_prefix") @ ctx + f("b_prefix")).reshape(2, 16)
+    s = np.concatenate([pre, f("E_tok")[toks[0, 8:11]]], axis=0)          # length 2+3 = 5
+    st = [(f"tok.{l}.", causal(5), list(range(5))) for l in range(cfg.n_token_layers)]
+    st.append(("ln", "tok_lnf_g", "tok_lnf_b"))
+    hid = vanilla_forward(W, s, st, cfg.n_heads, cfg.rot, cfg.ln_eps, 1)
+    ref = hid @ f("W_head").T
+    for r in range(4):          # local position P-1+r predicts token 8+r
+        got = O.next_token_logits_full(P, cfg, toks[:, :8 + r])[0]
+        assert np.max(np.abs(got - ref[1 + r])) < TOL
+
+
+# --------------------------------------------------------------------------
+# T4  brute-force attention in long double; streaming (split) softmax algebra
+# --------------------------------------------------------------------------
+def _brute_attention(q, K, V, n_past):
+    B, n, H, dh = q.shape
+    out = np.zeros(q.shape, dtype=np.longdouble)
+    for b in range(B):
+        for h in range(H):
+            for i in range(n):
+                sc = []
+                for j in range(n_past + i + 1):
+                    acc = np.longdouble(0)
+                    for t in range(dh):
+                        acc += np.longdouble(q[b, i, h, t]) * np.longdouble(K[b, j, h, t])
+                    sc.append(acc / np.sqrt(np.longdouble(dh)))
+                m = max(sc)
+                w = [np.exp(s - m) for s in sc]
+                z = sum(w)
+                for j, wj in enumerate(w):
+                    for t in range(dh):
+                        out[b, i, h, t] += wj / z * np.longdouble(V[b, j, h, t])
+    return out.astype(np.float64)
+
+
+@pytest.mark.parametrize("n_past,n", [(0, 5), (3, 1), (4, 3)])
+def test_attention_brute_force(n_past, n):
+    rng = np.random.default_rng(6)
+    q = rng.standard_normal((2, n, 2, 5)) * 2
+    K = rng.standard_normal((2, n_past + n, 2, 5)) * 2
+    V = rng.standard_normal((2, n_past + n, 2, 5))
+    assert np.max(np.abs(O.attention(q, K, V, n_past) - _brute_attention(q, K, V, n_past))) < 1e-12
+
+
+@pytest.mark.parametrize("chunks", [1, 2, 3, 7])
+def test_split_softmax_combine_matches_attention(chunks):
+    """The partial (max, sum, weighted acc) combine used by split-K decoding is exact algebra."""
+    rng = np.random.default_rng(7)
+    N, dh = 23, 8
+    q = rng.standard_normal((1, 1, 1, dh)) * 3
+    K = rng.standard_normal((1, N, 1, dh)) * 3
+    V = rng.standard_normal((1, N, 1, dh))
+    ref = O.attention(q, K, V, N - 1)[0, 0, 0]
+    bounds = np.linspace(0, N, chunks + 1).astype(int)
+    parts = []
+    for a, b in zip(bounds[:-1], bounds[1:]):
+        if a == b:
+            continue
+        s = (K[0, a:b, 0] @ q[0, 0, 0]) / math.sqrt(dh)
+        m = s.max()
+        w = np.exp(s - m)
+        parts.append((m, w.sum(), w @ V[0, a:b, 0]))
+    M = max(p[0] for p in parts)
+    l = sum(p[1] * math.exp(p[0] - M) for p in parts)
+    acc = sum(p[2] * math.exp(p[0] - M) for p in parts)
+    assert np.max(np.abs(acc / l - ref)) < 1e-12
+
+
+# --------------------------------------------------------------------------
+# T5  closed forms
+# --------------------------------------------------------------------------
+def test_zero_query_gives_running_mean():
+    rng = np.random.default_rng(8)
+    n_past, n = 2, 4
+    V = rng.standard_normal((1, n_past + n, 2, 3))
+    K = rng.standard_normal((1, n_past + n, 2, 3))
+    out = O.attention(np.zeros((1, n, 2, 3)), K, V, n_past)
+    for i in range(n):
+        assert np.max(np.abs(out[0, i] - V[0, :n_past + i + 1].mean(axis=0))) < 1e-13
+
+
+def test_layer_closed_form_running_mean_of_v():
+    cfg = tiny_cfg(block_len=1, prefix_len=0, d_model=8, n_heads=2, d_ff=16, rotary_dims=0)
+    W = make_weights(cfg)
+    D = 8
+    W["blk.0.W_qkv"][:D] = 0; W["blk.0.b_qkv"][:D] = 0           # q == 0
+    W["blk.0.W_o"] = np.eye(D, dtype=np.float32); W["blk.0.b_o"][:] = 0
+    W["blk.0.W_down"][:] = 0; W["blk.0.b_down"][:] = 0            # MLP == 0
+    P = O.Params(W)
+    x = np.random.default_rng(9).standard_normal((1, 5, D))
+    out = O.transformer_layer(P, "blk.0.", x, 0, cfg)
+    g, b = W["blk.0.ln1_g"].astype(np.float64), W["blk.0.ln1_b"].astype(np.float64)
+    u = (x[0] - x[0].mean(-1, keepdims=True)) / np.sqrt(x[0].var(-1, keepdims=True) + cfg.ln_eps) * g + b
+    v = u @ W["blk.0.W_qkv"][2 * D:].astype(np.float64).T + W["blk.0.b_qkv"][2 * D:]
+    for t in range(5):
+        assert np.max(np.abs(out[0, t] - (x[0, t] + v[:t + 1].mean(axis=0)))) < 1e-12
+
+
+def test_constant_logits_pick_index_zero_and_one_hot_head():
+    cfg = tiny_cfg(block_len=2, prefix_len=1, d_model=16, n_heads=2, d_ff=32, prompt_len=4, vocab=16)
+    W = make_weights(cfg)
+    W["W_head"][:] = 0
+    ids, lg, _ = O.generate_cached(O.Params(W), cfg, make_prompts(cfg), 5)
+    assert np.all(lg == 0) and np.all(ids == 0)
+    # one-hot head: logit v reads hidden unit perm[v]
+    perm = np.random.default_rng(10).permutation(16)
+    W["W_head"] = np.eye(16, dtype=np.float32)[perm]
+    P = O.Params(W)
+    toks = make_prompts(cfg)
+    c = O.context_embeddings(P, cfg, toks)[:, -1]
+    hid = O.token_decoder(P, cfg, O.prefix_tokens(P, cfg, c))[:, -1]
+    lg = O.next_token_logits_full(P, cfg, toks)
+    assert np.array_equal(lg, hid[:, perm])
+    assert np.array_equal(O.greedy(lg), np.array([int(np.where(perm == np.argmax(h))[0][0]) for h in hid]))
+    assert O.greedy(np.array([[1.0, 3.0, 3.0, 2.0]]))[0] == 1        # lowest index on ties
+
+
+# --------------------------------------------------------------------------
+# T6  embedder is an exact lookup-and-concatenate (Sec. 2.2)
+# --------------------------------------------------------------------------
+def test_embedder_exact():
+    cfg = tiny_cfg(block_len=4, d_model=32)
+    W = make_weights(cfg)
+    P = O.Params(W)
+    toks = make_prompts(cfg, batch=3, prompt_len=12)
+    e = O.embedder(P, cfg, toks)
+    assert e.shape == (3, 3, 32)
+    de = cfg.d_emb
+    assert de == 32 // 4
+    for b in range(3):
+        for j in range(3):
+            for k in range(4):
+                assert np.array_equal(e[b, j, k * de:(k + 1) * de], W["E_emb"][toks[b, j * 4 + k]].astype(np.float64))
+
+
+# --------------------------------------------------------------------------
+# T7  operation counts the paper states (Sec. 2.3, 2.4, App. C, attention-map caption)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("lb,p,tp,tg", [(4, 2, 8, 9), (4, 1, 8, 8), (2, 1, 4, 7), (1, 1, 3, 5), (8, 2, 16, 17)])
+def test_procedure_counts(lb, p, tp, tg):
+    cfg = tiny_cfg(block_len=lb, prefix_len=p, prompt_len=tp, d_model=32, n_heads=2)
+    P = build(cfg)
+    gen = O.CachedGenerator(P, cfg, 2, (tp + tg) // lb + 1)
+    gen.prefill(make_prompts(cfg))
+    n_p = tp // lb
+    assert gen.token_passes == 0                              # token-decoder prefill is skipped
+    assert gen.blk[0].n == n_p                                # one KV entry per block
+    for _ in range(tg):
+        gen.step()
+    extra = -(-tg // lb) - 1
+    assert gen.block_passes == n_p + extra
+    assert gen.blk[0].n == n_p + extra                        # entries == embedded tokens / L_B
+    assert gen.token_passes == tg
+    assert gen.local_kv_high_water == min(p + lb - 1, p + tg - 1)
+    # cached block entries attended: sum over block steps of (entries incl. the new one)
+    assert gen.block_kv_rows_read == sum(n_p + k + 1 for k in range(extra))
+
+
+def test_kv_ratio_block_vs_vanilla():
+    """KV size / L_B, KV access / L_B^2 (Sec. 2.3): closed-form check of the counters."""
+    def reads(lb, tp, tg):
+        cfg = tiny_cfg(block_len=lb, prefix_len=1, prompt_len=tp, d_model=16, n_heads=2, d_ff=16,
+                       n_block_layers=1, n_token_layers=1)
+        gen = O.CachedGenerator(build(cfg), cfg, 1, (tp + tg) // lb + 1)
+        gen.prefill(make_prompts(cfg, batch=1))
+        for _ in range(tg):
+            gen.step()
+        return gen.block_kv_rows_read, gen.blk[0].n
+    r1, n1 = reads(1, 16, 129)
+    r4, n4 = reads(4, 16, 129)
+    assert abs(n1 / n4 - 4) < 0.2
+    assert abs(r1 / r4 - 16) < 1.0        # -> L_B^2 as lengths grow
+
+
+def test_table3_parameter_counts():
+    """Non-embedding sizes printed in the hyper-parameter table (App. E.2)."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "table3_sizes.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    for n_layers, dim, stated_millions in rows:
+        n_layers, dim, stated = int(n_layers), int(dim), float(stated_millions)
+        cfg = tiny_cfg(d_model=dim, d_ff=4 * dim, n_heads=8, n_block_layers=n_layers, n_token_layers=0,
+                       block_len=1, prefix_len=0, vocab=2)
+        per_layer = sum(int(np.prod(s)) for nm, s, _ in tensor_table(cfg) if nm.startswith("blk.0."))
+        assert per_layer == 12 * dim * dim + 13 * dim
+        # the table prints sizes rounded to whole millions (5M stands for 4.74M)
+        assert abs(n_layers * per_layer / 1e6 - stated) < max(0.6, 0.01 * stated)
+
+
+# --------------------------------------------------------------------------
+# T8  batch independence
+# --------------------------------------------------------------------------
+def test_batch_independence():
+    cfg = tiny_cfg(block_len=4, prefix_len=2)
+    P = build(cfg)
+    prompts = make_prompts(cfg, batch=3)
+    ids, lg, _ = O.generate_cached(P, cfg, prompts, 6)
+    for b in range(3):
+        ids1, lg1, _ = O.generate_cached(P, cfg, prompts[b:b + 1], 6)
+        assert np.array_equal(ids1[0], ids[b])
+        assert np.max(np.abs(lg1[0] - lg[b])) < 1e-12
+
+
+# --------------------------------------------------------------------------
+# T9  rotary: identity at position 0, norm-preserving, relative-position invariance
+# --------------------------------------------------------------------------
+def test_rotary_properties():
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((1, 4, 2, 16))
+    y = rng.standard_normal((1, 4, 2, 16))
+    assert np.array_equal(O.rotary(x, [0, 0, 0, 0], 8), x)
+    r = O.rotary(x, [0, 1, 2, 3], 8)
+    assert np.array_equal(r[..., 8:], x[..., 8:])                   # dims beyond rot untouched
+    assert np.max(np.abs(np.linalg.norm(r, axis=-1) - np.linalg.norm(x, axis=-1))) < 1e-12
+    s0 = np.einsum("bihd,bjhd->bhij", O.rotary(x, [0, 1, 2, 3], 8), O.rotary(y, [0, 1, 2, 3], 8))
+    s1 = np.einsum("bihd,bjhd->bhij", O.rotary(x, [5, 6, 7, 8], 8), O.rotary(y, [5, 6, 7, 8], 8))
+    assert np.max(np.abs(s0 - s1)) < 1e-12
+    # explicit 2-D rotation of the pair (t, t + rot/2) by pos * 10000^(-2t/rot)
+    t, pos, rot = 1, 3, 8
+    th = pos * 10000.0 ** (-2.0 * t / rot)
+    a, b = x[0, 3, 0, t], x[0, 3, 0, t + rot // 2]
+    assert abs(r[0, 3, 0, t] - (a * math.cos(th) - b * math.sin(th))) < 1e-14
+    assert abs(r[0, 3, 0, t + rot // 2] - (b * math.cos(th) + a * math.sin(th))) < 1e-14
+
+
+def test_token_decoder_positions_restart_each_block():
+    """Token-decoder positions are local: the same (context, block tokens) gives the same
+    logits whichever block index it is."""
+    cfg = tiny_cfg(block_len=4, prefix_len=1)
+    P = build(cfg)
+    rng = np.random.default_rng(13)
+    toks = rng.integers(0, cfg.vocab, size=(1, 16))
+    c = rng.standard_normal((1, cfg.d_model))
+    res = []
+    for n_prompt in (4, 12):
+        g = O.CachedGenerator(P, cfg, 1, 8)
+        g.prefill(toks[:, :n_prompt])
+        g.c = c.copy()
+        res.append(np.stack([g.step(forced_ids=[5])[0] for _ in range(4)]))
+    assert np.array_equal(res[0], res[1])
+
+
+# --------------------------------------------------------------------------
+# sanity of LayerNorm / GELU against textbook values
+# --------------------------------------------------------------------------
+def test_layernorm_gelu_values():
+    x = np.array([[1.0, 2.0, 3.0, 6.0]])
+    out = O.layer_norm(x, np.ones(4), np.zeros(4), 0.0)
+    assert abs(out.mean()) < 1e-15 and abs(out.var() - 1.0) < 1e-12      # biased variance
+    assert abs(O.gelu(np.array([0.0]))[0]) == 0.0
+    assert abs(O.gelu(np.array([1.0]))[0] - 0.8413447460685429) < 1e-15   # Phi(1)
+    assert abs(O.gelu(np.array([-2.0]))[0] + 2 * 0.022750131948179195) < 1e-15
