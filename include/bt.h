@@ -1,0 +1,191 @@
+/*
+ * bt.h - C ABI of the MI355X (gfx950) Block Transformer generation library.
+ *
+ * The library computes the batched autoregressive generation step of the Block
+ * Transformer (arXiv 2406.02657): embedder lookup-and-concatenate (Sec. 2.2),
+ * block decoder over a block-level KV cache, run once per L_B tokens
+ * (Sec. 2.3), projection of the context embedding into prefix tokens and a
+ * token decoder whose attention stays inside the current block (Sec. 2.4,
+ * App. D.2 "Prefix"), LM head and greedy argmax; procedure per Sec. 2.1,
+ * Fig. 1 and App. C (prefill runs the block decoder only; decoding emits one
+ * token per sequence per step).  Layer type: Pythia / GPT-NeoX (Sec. 3.1).
+ *
+ * Conventions
+ *   - "dev" pointers are HIP device pointers, "host" pointers ordinary memory.
+ *   - The library allocates NO device memory: weights, token buffers, outputs
+ *     and one workspace are caller-owned and must outlive the model.
+ *   - All work is enqueued on the HIP stream given to bt_create and is
+ *     asynchronous; outputs are valid once the caller synchronises that stream.
+ *   - Every function returns BT_OK (0) or a negative bt_status.  Argument and
+ *     state errors are detected on the host before anything is enqueued and
+ *     leave the model unchanged.  No exceptions, no exit(), no global state.
+ *   - One model must not be used from two threads at once.
+ *
+ * Tensor layouts
+ *   - Every linear map W is [out_features, in_features] row-major and is
+ *     applied as y = x * W^T + b.  W_qkv rows: q (D), k (D), v (D); inside each
+ *     part head h owns rows [h*d_head, (h+1)*d_head).  W_prefix is
+ *     [P*D, D]; prefix token p is output slice [p*D, (p+1)*D).
+ *   - dtype BT_F32: every tensor is float.  dtype BT_BF16: matrices and
+ *     embedding tables (E_emb, E_tok, W_prefix, W_head, W_qkv, W_o, W_up,
+ *     W_down) are bfloat16; biases and LayerNorm gamma/beta stay float.
+ *     In bf16 mode GEMM operands and both KV caches are bf16; accumulation,
+ *     residual stream, LayerNorm statistics, softmax and logits are float.
+ */
+#ifndef BT_H_
+#define BT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BT_OK = 0,
+  BT_ERR_ARG = -1,       /* null pointer, size out of range, unsupported shape */
+  BT_ERR_STATE = -2,     /* decode before prefill, batch differs from prefill */
+  BT_ERR_CAPACITY = -3,  /* block KV cache or workspace too small */
+  BT_ERR_HIP = -4        /* HIP runtime error; text via bt_last_error */
+} bt_status;
+
+enum { BT_F32 = 0, BT_BF16 = 1 };
+
+/* Model and capacity description (plain data, filled by the caller).
+ * Shape limits: d_model % n_heads == 0; d_head = d_model/n_heads in
+ * {32, 64, 128}; d_model % block_len == 0 (d_emb = d_model/block_len, a
+ * multiple of 8); rotary_dims even and <= d_head; prefix_len >= 1, or 0 with
+ * block_len == 1 (then the context embedding itself is the token decoder's
+ * single input row).  In bf16 mode d_model and d_ff must be multiples of 64. */
+typedef struct {
+  int32_t vocab;
+  int32_t block_len;        /* L_B */
+  int32_t d_model;          /* D, both decoders */
+  int32_t n_heads;
+  int32_t d_ff;
+  int32_t n_block_layers;
+  int32_t n_token_layers;
+  int32_t prefix_len;       /* P */
+  int32_t dtype;            /* BT_F32 or BT_BF16 */
+  int32_t max_batch;
+  int32_t max_blocks;       /* block-KV capacity per sequence (prompt + generated blocks) */
+  int32_t rotary_dims;      /* per head, even; 0 = no position rotation */
+  int32_t parallel_residual;/* 1: x + Attn(LN1 x) + MLP(LN2 x); 0: sequential */
+  int32_t prefill_rows;     /* prompt blocks processed per prefill chunk; 0 = default (16384) */
+  float   ln_eps;
+} bt_config;
+
+/* Device pointers of one transformer layer (dtype as described above). */
+typedef struct {
+  const void *ln1_g, *ln1_b;     /* [D] float */
+  const void *W_qkv, *b_qkv;     /* [3D, D], [3D] */
+  const void *W_o,   *b_o;       /* [D, D],  [D]  */
+  const void *ln2_g, *ln2_b;     /* [D] float */
+  const void *W_up,  *b_up;      /* [F, D],  [F]  */
+  const void *W_down,*b_down;    /* [D, F],  [D]  */
+} bt_layer_weights;
+
+typedef struct {
+  const void *E_emb;             /* [V, D/L_B]  embedder table (Sec. 2.2) */
+  const void *E_tok;             /* [V, D]      token decoder table (Sec. 2.4); unused when L_B == 1 */
+  const void *W_prefix;          /* [P*D, D]    context -> prefix tokens (App. D.2); NULL when P == 0 */
+  const void *b_prefix;          /* [P*D] float */
+  const void *W_head;            /* [V, D]      classifier, no bias */
+  const void *blk_lnf_g, *blk_lnf_b;   /* final LayerNorm of the block decoder, [D] float */
+  const void *tok_lnf_g, *tok_lnf_b;   /* final LayerNorm of the token decoder, [D] float */
+  const bt_layer_weights *block_layers;  /* host array [n_block_layers] of device pointers */
+  const bt_layer_weights *token_layers;  /* host array [n_token_layers] */
+} bt_weights;
+
+/* Counters of the procedure (host side, updated as work is enqueued). */
+typedef struct {
+  int64_t block_passes;        /* block-decoder passes, counted per block (prefill: N_p) */
+  int64_t token_passes;        /* token-decoder invocations (0 right after prefill) */
+  int64_t token_rows;          /* rows pushed through the token decoder, per sequence */
+  int64_t block_kv_rows_read;  /* cached block entries attended by decode steps, per sequence */
+  int64_t block_kv_bytes_read; /* same, in bytes over batch, layers, K and V */
+  int32_t n_blocks;            /* entries now in the block KV cache (N) */
+  int32_t r;                   /* tokens already generated in the open block */
+  int32_t batch;               /* batch of the last prefill, 0 before */
+  int32_t local_kv_high_water; /* most local KV entries ever live in one block */
+  /* profiling (bt_set_profile): summed HIP-event time of the block-decoder
+   * decode attention launches and their count since the last reset */
+  double  attn_block_ms;
+  int64_t attn_block_launches;
+  int64_t attn_block_bytes;    /* algorithmic K+V bytes those launches streamed */
+} bt_stats;
+
+typedef struct bt_model bt_model;
+
+/* Bytes of device workspace bt_create needs for this config (block KV cache,
+ * local KV cache, activations, split-K partials, logits).  host out pointer. */
+int bt_workspace_bytes(const bt_config *cfg, size_t *bytes);
+
+/* Build a model.  cfg, w: host structs (copied).  workspace_dev: device memory
+ * of at least bt_workspace_bytes, 256-byte aligned, owned by the caller.
+ * hip_stream: a hipStream_t (NULL = the default stream).  *out receives the
+ * handle.  Errors: BT_ERR_ARG (bad config / null), BT_ERR_CAPACITY (workspace
+ * too small), BT_ERR_HIP. */
+int bt_create(const bt_config *cfg, const bt_weights *w, void *workspace_dev,
+              size_t workspace_bytes, void *hip_stream, bt_model **out);
+
+/* Prefill (Fig. 1; Sec. 2.4; App. C): run the embedder and the block decoder
+ * over all prompt blocks, fill the block KV cache with prompt_len/L_B entries
+ * per sequence and keep the context embedding for the first generated block.
+ * The token decoder is not run.  Resets all sequence state (re-entrant).
+ * tokens_dev: int32 [batch, prompt_len] row-major, device; ids are not
+ * range-checked.  Errors: BT_ERR_ARG if batch < 1, batch > max_batch,
+ * prompt_len < L_B or prompt_len % L_B != 0; BT_ERR_CAPACITY if
+ * prompt_len/L_B > max_blocks. */
+int bt_prefill(bt_model *m, const int32_t *tokens_dev, int32_t batch, int32_t prompt_len);
+
+/* One decode step (Sec. 2.1): emits exactly one token per sequence.  At the
+ * first step of a block the finished block is embedded and pushed through the
+ * block decoder (attention over the whole block KV cache), its context
+ * embedding is projected to the prefix and the token decoder runs over the
+ * prefix rows; at the other steps the token decoder runs over one row per
+ * sequence with attention over the current block's local KV only.  Then LM
+ * head and greedy argmax (lowest index on ties).
+ * next_ids_dev: int32 [batch], device, receives the tokens.
+ * Errors: BT_ERR_STATE before prefill or if batch differs from the prefill's;
+ * BT_ERR_CAPACITY if the step needs a block slot >= max_blocks. */
+int bt_decode_step(bt_model *m, int32_t batch, int32_t *next_ids_dev);
+
+/* Embedder alone (Sec. 2.2; App. D.1 "Lookup"): out_dev[m, j*d_emb + e] =
+ * E_emb[tokens_dev[m*L_B + j], e] widened to float.  tokens_dev: int32
+ * [n_rows, L_B], out_dev: float [n_rows, D], both device.  Does not touch the
+ * sequence state.  Errors: BT_ERR_ARG on null pointers or n_rows < 0. */
+int bt_embed(bt_model *m, const int32_t *tokens_dev, int32_t n_rows, float *out_dev);
+
+/* Copy the float logits [batch, vocab] of the last decode step to logits_dev
+ * (device), on the model's stream.  For parity checks. */
+int bt_get_logits(bt_model *m, float *logits_dev);
+
+/* Replace the token that the last decode step appended to each sequence's
+ * history (teacher forcing for parity checks).  ids_dev: int32 [batch], device.
+ * Must follow a bt_decode_step and precede the next one. */
+int bt_force_last_ids(bt_model *m, const int32_t *ids_dev);
+
+/* Copy the current context embedding [batch, D] (model dtype) out / in, on the
+ * model's stream (locality checks inject a context).  Device pointers. */
+int bt_get_context(bt_model *m, void *ctx_dev);
+int bt_set_context(bt_model *m, const void *ctx_dev);
+
+/* Profiling: when on, HIP events bracket every block-decoder decode attention
+ * launch; bt_get_stats (which then synchronises the stream) reports their sum.
+ * bt_reset_profile clears the sums. */
+int bt_set_profile(bt_model *m, int32_t on);
+int bt_reset_profile(bt_model *m);
+
+int bt_get_stats(bt_model *m, bt_stats *out);
+
+/* Text of the last error on this model (host string owned by the model). */
+const char *bt_last_error(const bt_model *m);
+
+void bt_destroy(bt_model *m);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BT_H_ */

@@ -1,0 +1,204 @@
+"""ctypes binding of libbt.so: argument marshalling only.
+
+PyTorch is used for device memory (weights, workspace, token and output
+buffers) and for the current HIP stream; every step of the computation runs in
+the library's kernels.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+lib_path = os.path.join(HERE, "libbt.so")
+if not os.path.exists(lib_path):
+    raise ImportError(
+        f"{lib_path} is missing: build it first (python -m paper_2406_02657_amd.build, "
+        "or __graft_entry__.build()).  There is no fallback path.")
+lib = C.CDLL(lib_path)
+
+BT_F32, BT_BF16 = 0, 1
+BT_OK, BT_ERR_ARG, BT_ERR_STATE, BT_ERR_CAPACITY, BT_ERR_HIP = 0, -1, -2, -3, -4
+
+
+class bt_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "vocab", "block_len", "d_model", "n_heads", "d_ff", "n_block_layers", "n_token_layers",
+        "prefix_len", "dtype", "max_batch", "max_blocks", "rotary_dims", "parallel_residual",
+        "prefill_rows")] + [("ln_eps", C.c_float)]
+
+
+_LAYER_FIELDS = ("ln1_g", "ln1_b", "W_qkv", "b_qkv", "W_o", "b_o", "ln2_g", "ln2_b", "W_up", "b_up", "W_down", "b_down")
+
+
+class bt_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _LAYER_FIELDS]
+
+
+class bt_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in (
+        "E_emb", "E_tok", "W_prefix", "b_prefix", "W_head", "blk_lnf_g", "blk_lnf_b", "tok_lnf_g", "tok_lnf_b")] + [
+        ("block_layers", C.POINTER(bt_layer_weights)), ("token_layers", C.POINTER(bt_layer_weights))]
+
+
+class bt_stats(C.Structure):
+    _fields_ = [("block_passes", C.c_int64), ("token_passes", C.c_int64), ("token_rows", C.c_int64),
+                ("block_kv_rows_read", C.c_int64), ("block_kv_bytes_read", C.c_int64),
+                ("n_blocks", C.c_int32), ("r", C.c_int32), ("batch", C.c_int32),
+                ("local_kv_high_water", C.c_int32), ("attn_block_ms", C.c_double),
+                ("attn_block_launches", C.c_int64), ("attn_block_bytes", C.c_int64)]
+
+
+_P = C.c_void_p
+lib.bt_workspace_bytes.argtypes = [C.POINTER(bt_config), C.POINTER(C.c_size_t)]
+lib.bt_create.argtypes = [C.POINTER(bt_config), C.POINTER(bt_weights), _P, C.c_size_t, _P, C.POINTER(_P)]
+lib.bt_prefill.argtypes = [_P, _P, C.c_int32, C.c_int32]
+lib.bt_decode_step.argtypes = [_P, C.c_int32, _P]
+lib.bt_get_logits.argtypes = [_P, _P]
+lib.bt_force_last_ids.argtypes = [_P, _P]
+lib.bt_get_context.argtypes = [_P, _P]
+lib.bt_set_context.argtypes = [_P, _P]
+lib.bt_set_profile.argtypes = [_P, C.c_int32]
+lib.bt_reset_profile.argtypes = [_P]
+lib.bt_get_stats.argtypes = [_P, C.POINTER(bt_stats)]
+lib.bt_last_error.argtypes = [_P]
+lib.bt_last_error.restype = C.c_char_p
+lib.bt_destroy.argtypes = [_P]
+lib.bt_destroy.restype = None
+lib.bt_embed.argtypes = [_P, _P, C.c_int32, _P]
+for _f in ("bt_workspace_bytes", "bt_create", "bt_prefill", "bt_decode_step", "bt_get_logits", "bt_force_last_ids",
+           "bt_get_context", "bt_set_context", "bt_set_profile", "bt_reset_profile", "bt_get_stats", "bt_embed"):
+    getattr(lib, _f).restype = C.c_int
+
+
+class BTError(RuntimeError):
+    def __init__(self, code, msg=""):
+        super().__init__(f"bt status {code}: {msg}")
+        self.code = code
+
+
+def make_config(cfg, max_batch=None, max_blocks=None, prefill_rows=0) -> bt_config:
+    """cfg: any object with the fields of synth.BTConfig."""
+    return bt_config(
+        vocab=cfg.vocab, block_len=cfg.block_len, d_model=cfg.d_model, n_heads=cfg.n_heads, d_ff=cfg.d_ff,
+        n_block_layers=cfg.n_block_layers, n_token_layers=cfg.n_token_layers, prefix_len=cfg.prefix_len,
+        dtype=BT_BF16 if cfg.dtype == "bf16" else BT_F32,
+        max_batch=cfg.batch if max_batch is None else max_batch,
+        max_blocks=cfg.max_blocks if max_blocks is None else max_blocks,
+        rotary_dims=cfg.rot, parallel_residual=cfg.parallel_residual, prefill_rows=prefill_rows,
+        ln_eps=cfg.ln_eps)
+
+
+class Model:
+    """Owns the device copies of the weights and the workspace; forwards to the C ABI."""
+
+    def __init__(self, cfg, weights, max_batch=None, max_blocks=None, prefill_rows=0, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.device = torch.device(device)
+        self.cfg = cfg
+        self.c = make_config(cfg, max_batch, max_blocks, prefill_rows)
+        self._keep = {}
+        for name, arr in weights.items():
+            a = np.ascontiguousarray(arr)
+            t = torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(self.device)
+            self._keep[name] = t
+        ptr = lambda n: self._keep[n].data_ptr() if n in self._keep else None
+
+        def layers(stack, n):
+            arr = (bt_layer_weights * max(n, 1))()
+            for i in range(n):
+                for f in _LAYER_FIELDS:
+                    setattr(arr[i], f, ptr(f"{stack}.{i}.{f}"))
+            return arr
+
+        self._blk = layers("blk", cfg.n_block_layers)
+        self._tok = layers("tok", cfg.n_token_layers)
+        self.w = bt_weights(E_emb=ptr("E_emb"), E_tok=ptr("E_tok"), W_prefix=ptr("W_prefix"), b_prefix=ptr("b_prefix"),
+                            W_head=ptr("W_head"), blk_lnf_g=ptr("blk_lnf_g"), blk_lnf_b=ptr("blk_lnf_b"),
+                            tok_lnf_g=ptr("tok_lnf_g"), tok_lnf_b=ptr("tok_lnf_b"),
+                            block_layers=self._blk, token_layers=self._tok)
+        nbytes = C.c_size_t(0)
+        rc = lib.bt_workspace_bytes(C.byref(self.c), C.byref(nbytes))
+        if rc:
+            raise BTError(rc, "bt_workspace_bytes")
+        self.workspace_bytes = nbytes.value
+        self.workspace = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=self.device)
+        base = (self.workspace.data_ptr() + 255) // 256 * 256
+        self.h = _P()
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        rc = lib.bt_create(C.byref(self.c), C.byref(self.w), base, nbytes.value, stream, C.byref(self.h))
+        if rc:
+            raise BTError(rc, "bt_create")
+        self.batch = 0
+
+    def _chk(self, rc):
+        if rc:
+            raise BTError(rc, (lib.bt_last_error(self.h) or b"").decode())
+
+    def bt_prefill(self, tokens):
+        """tokens: int32 cuda tensor [batch, prompt_len]."""
+        assert tokens.dtype == self.torch.int32 and tokens.is_cuda and tokens.is_contiguous()
+        self._chk(lib.bt_prefill(self.h, tokens.data_ptr(), tokens.shape[0], tokens.shape[1]))
+        self.batch = tokens.shape[0]
+        self._ids = self.torch.empty(self.batch, dtype=self.torch.int32, device=self.device)
+
+    def bt_decode_step(self, out=None):
+        ids = self._ids if out is None else out
+        self._chk(lib.bt_decode_step(self.h, self.batch, ids.data_ptr()))
+        return ids
+
+    def bt_get_logits(self):
+        lg = self.torch.empty(self.batch, self.cfg.vocab, dtype=self.torch.float32, device=self.device)
+        self._chk(lib.bt_get_logits(self.h, lg.data_ptr()))
+        return lg
+
+    def bt_force_last_ids(self, ids):
+        assert ids.dtype == self.torch.int32 and ids.is_cuda
+        self._chk(lib.bt_force_last_ids(self.h, ids.data_ptr()))
+
+    def _ctx_dtype(self):
+        if self.cfg.prefix_len == 0 or self.cfg.dtype != "bf16":
+            return self.torch.float32
+        return self.torch.bfloat16
+
+    def bt_get_context(self):
+        c = self.torch.empty(self.batch, self.cfg.d_model, dtype=self._ctx_dtype(), device=self.device)
+        self._chk(lib.bt_get_context(self.h, c.data_ptr()))
+        return c
+
+    def bt_set_context(self, c):
+        assert c.dtype == self._ctx_dtype() and c.is_cuda and c.is_contiguous()
+        self._chk(lib.bt_set_context(self.h, c.data_ptr()))
+
+    def bt_embed(self, tokens):
+        """Embedder alone: int32 cuda [n_rows, L_B] -> float32 [n_rows, D]."""
+        assert tokens.dtype == self.torch.int32 and tokens.is_cuda and tokens.is_contiguous()
+        n = tokens.numel() // self.cfg.block_len
+        out = self.torch.empty(n, self.cfg.d_model, dtype=self.torch.float32, device=self.device)
+        self._chk(lib.bt_embed(self.h, tokens.data_ptr(), n, out.data_ptr()))
+        return out
+
+    def bt_set_profile(self, on):
+        self._chk(lib.bt_set_profile(self.h, int(on)))
+
+    def bt_reset_profile(self):
+        self._chk(lib.bt_reset_profile(self.h))
+
+    def bt_get_stats(self) -> bt_stats:
+        st = bt_stats()
+        self._chk(lib.bt_get_stats(self.h, C.byref(st)))
+        return st
+
+    def close(self):
+        if self.h:
+            lib.bt_destroy(self.h)
+            self.h = _P()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

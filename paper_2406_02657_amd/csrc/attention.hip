@@ -1,0 +1,389 @@
+// Attention kernels.
+//   * block decoder, decode step (Sec. 2.3): one query per (sequence, head)
+//     against the whole block-level KV cache - the memory-bound heart of the
+//     step.  The cache rows of one (b, h) are contiguous, so a wavefront streams
+//     them with 16-byte loads; the waves of a workgroup split the rows
+//     (split-K) and merge their partial softmaxes through LDS.
+//   * block decoder, prefill: causal attention over the prompt's blocks.
+//   * token decoder (Sec. 2.4): attention inside the current block only; the
+//     whole local KV of a (b, h) sits in LDS, reductions are wave shuffles.
+// Scores, softmax and accumulation are fp32; K and V are read in storage dtype.
+#include "common.h"
+#include "kernels.h"
+#include "../../include/bt.h"
+
+namespace bt {
+
+constexpr float kNegBig = -1.0e30f;
+
+template <class T, int DH>
+struct RowMap {
+  static constexpr int EPC = Chunk<T>::EPC;   // elements per 16-byte chunk
+  static constexpr int LPR = DH / EPC;        // lanes per cache row
+  static constexpr int RPL = kWave / LPR;     // rows per wave-wide load
+};
+
+// One wavefront attends one query to rows [j0, j1) of K, V ([row][DH]).
+// Lane = (slot rr = lane / LPR, chunk sub = lane % LPR); q holds the lane's EPC
+// query elements already scaled by 1/sqrt(DH).  Each slot runs an online
+// softmax over its rows; at the end the slots are merged, so every lane
+// returns the wave-wide (m, l, acc) for its chunk of dims.
+template <class T, int DH>
+__device__ __forceinline__ void wave_attend(const float* q, const T* __restrict__ K, const T* __restrict__ V,
+                                            int j0, int j1, float& m_out, float& l_out, float* acc) {
+  using R = RowMap<T, DH>;
+  constexpr int EPC = R::EPC, LPR = R::LPR, RPL = R::RPL, U = 4;
+  const int lane = threadIdx.x & 63;
+  const int sub = lane % LPR, rr = lane / LPR;
+  float m = kNegBig, l = 0.f;
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) acc[e] = 0.f;
+
+  for (int base = j0; base < j1; base += RPL * U) {
+    uint4 kraw[U], vraw[U];
+    bool valid[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = base + u * RPL + rr;
+      valid[u] = j < j1;
+      const size_t off = (size_t)(valid[u] ? j : j0) * DH + sub * EPC;
+      kraw[u] = *reinterpret_cast<const uint4*>(K + off);
+      vraw[u] = *reinterpret_cast<const uint4*>(V + off);
+    }
+    float s[U];
+    float mx = m;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[EPC];
+      Chunk<T>::unpack(kraw[u], kf);
+      float dot = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) dot = fmaf(q[e], kf[e], dot);
+#pragma unroll
+      for (int o = LPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, kWave);
+      s[u] = valid[u] ? dot : kNegBig;
+      mx = fmaxf(mx, s[u]);
+    }
+    const float scale = __expf(m - mx);
+    l *= scale;
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) acc[e] *= scale;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float p = valid[u] ? __expf(s[u] - mx) : 0.f;
+      float vf[EPC];
+      Chunk<T>::unpack(vraw[u], vf);
+      l += p;
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
+    }
+    m = mx;
+  }
+  // merge the RPL slots (lanes that share `sub`)
+#pragma unroll
+  for (int o = LPR; o < kWave; o <<= 1) {
+    const float m2 = __shfl_xor(m, o, kWave);
+    const float l2 = __shfl_xor(l, o, kWave);
+    const float M = fmaxf(m, m2);
+    const float a = __expf(m - M), b = __expf(m2 - M);
+    l = l * a + l2 * b;
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) {
+      const float a2 = __shfl_xor(acc[e], o, kWave);
+      acc[e] = acc[e] * a + a2 * b;
+    }
+    m = M;
+  }
+  m_out = m;
+  l_out = l;
+}
+
+// ---------------------------------------------------------------------------
+// Block decoder, decode step.  Grid: one workgroup per (b, h); NW waves split
+// the n_keys cache rows; partial (m, l, acc) meet in LDS.
+// ---------------------------------------------------------------------------
+template <class T, int DH, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(const float* __restrict__ qkv, const T* __restrict__ Kc,
+                                                                    const T* __restrict__ Vc, T* __restrict__ out,
+                                                                    int n_heads, int n_keys, int n_cap) {
+  using R = RowMap<T, DH>;
+  constexpr int EPC = R::EPC, LPR = R::LPR;
+  __shared__ float s_m[NW], s_l[NW];
+  __shared__ float s_acc[NW][DH];
+  const int bh = blockIdx.x;
+  const int b = bh / n_heads, h = bh - b * n_heads;
+  const int D = n_heads * DH;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR;
+  const float sc = rsqrtf((float)DH);
+  float q[EPC];
+  const float* qp = qkv + (size_t)b * 3 * D + h * DH + sub * EPC;
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) q[e] = qp[e] * sc;
+
+  const int per = (n_keys + NW - 1) / NW;
+  const int j0 = min(wave * per, n_keys), j1 = min(j0 + per, n_keys);
+  const T* K = Kc + (size_t)bh * n_cap * DH;
+  const T* V = Vc + (size_t)bh * n_cap * DH;
+  float m, l, acc[EPC];
+  wave_attend<T, DH>(q, K, V, j0, j1, m, l, acc);
+  if (lane < LPR) {
+    if (lane == 0) { s_m[wave] = m; s_l[wave] = l; }
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) s_acc[wave][sub * EPC + e] = acc[e];
+  }
+  __syncthreads();
+  for (int d = threadIdx.x; d < DH; d += NW * 64) {
+    float M = s_m[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, s_m[w]);
+    float L = 0.f, o = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float f = __expf(s_m[w] - M);
+      L += s_l[w] * f;
+      o += s_acc[w][d] * f;
+    }
+    out[(size_t)b * D + h * DH + d] = from_float<T>(o / L);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Block decoder, prefill: one wave per query, query i attends rows [0, i].
+// ---------------------------------------------------------------------------
+template <class T, int DH>
+__global__ __launch_bounds__(256) void attn_block_prefill_kernel(const float* __restrict__ qkv, const T* __restrict__ Kc,
+                                                                 const T* __restrict__ Vc, T* __restrict__ out,
+                                                                 int n_heads, int n_q, int n_cap) {
+  using R = RowMap<T, DH>;
+  constexpr int EPC = R::EPC, LPR = R::LPR;
+  const int bh = blockIdx.x;
+  const int b = bh / n_heads, h = bh - b * n_heads;
+  const int D = n_heads * DH;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i = n_q - 1 - (blockIdx.y * 4 + wave);      // long rows first
+  if (i < 0) return;
+  const int sub = lane % LPR;
+  const size_t row = (size_t)b * n_q + i;
+  const float sc = rsqrtf((float)DH);
+  float q[EPC];
+  const float* qp = qkv + row * 3 * D + h * DH + sub * EPC;
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) q[e] = qp[e] * sc;
+  const T* K = Kc + (size_t)bh * n_cap * DH;
+  const T* V = Vc + (size_t)bh * n_cap * DH;
+  float m, l, acc[EPC];
+  wave_attend<T, DH>(q, K, V, 0, i + 1, m, l, acc);
+  if (lane < LPR) {
+    const float inv = 1.0f / l;
+    float o[EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) o[e] = acc[e] * inv;
+    *reinterpret_cast<uint4*>(out + row * D + h * DH + sub * EPC) = Chunk<T>::pack(o);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Block decoder: rotary on q (in place) and k, append k, v to the block cache.
+// One workgroup per row.
+// ---------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(256) void rope_append_kernel(float* __restrict__ qkv, T* __restrict__ Kc, T* __restrict__ Vc,
+                                                          const float2* __restrict__ rope, int n_new, int pos0,
+                                                          int n_heads, int DH, int rot, int n_cap) {
+  const int m = blockIdx.x;
+  const int b = m / n_new, pos = pos0 + (m - b * n_new);
+  const int D = n_heads * DH, half = rot / 2;
+  float* q = qkv + (size_t)m * 3 * D;
+  const float* k = q + D;
+  const float* v = q + 2 * D;
+  for (int idx = threadIdx.x; idx < n_heads * half; idx += blockDim.x) {
+    const int h = idx / half, t = idx - h * half;
+    const float2 cs = rope[(size_t)pos * half + t];
+    const int d0 = h * DH + t, d1 = d0 + half;
+    const float q0 = q[d0], q1 = q[d1];
+    q[d0] = q0 * cs.x - q1 * cs.y;
+    q[d1] = q1 * cs.x + q0 * cs.y;
+    const float k0 = k[d0], k1 = k[d1];
+    const size_t base = ((size_t)(b * n_heads + h) * n_cap + pos) * DH;
+    Kc[base + t] = from_float<T>(k0 * cs.x - k1 * cs.y);
+    Kc[base + t + half] = from_float<T>(k1 * cs.x + k0 * cs.y);
+  }
+  for (int idx = threadIdx.x; idx < D; idx += blockDim.x) {
+    const int h = idx / DH, d = idx - h * DH;
+    const size_t base = ((size_t)(b * n_heads + h) * n_cap + pos) * DH;
+    if (d >= rot) Kc[base + d] = from_float<T>(k[idx]);
+    Vc[base + d] = from_float<T>(v[idx]);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Token decoder local attention.  One wave per (b, h); the local K, V of the
+// pair (<= l_cap rows) are staged in LDS as floats of the stored values.
+// LDS per wave: K [l_cap][DH], V [l_cap][DH], raw q [DH], raw k [DH].
+// ---------------------------------------------------------------------------
+template <class T, int DH>
+__global__ void attn_local_kernel(const float* __restrict__ qkv, T* __restrict__ Kl, T* __restrict__ Vl,
+                                  const float2* __restrict__ rope, T* __restrict__ out, int n_pairs, int n_heads,
+                                  int rot, int rows, int pos0, int l_cap) {
+  extern __shared__ float smem[];
+  constexpr int DPL = (DH + 63) / 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nw = blockDim.x >> 6;
+  const int pair_raw = blockIdx.x * nw + wave;
+  const bool active = pair_raw < n_pairs;
+  const int pair = active ? pair_raw : n_pairs - 1;     // idle waves shadow a valid pair, write nothing
+  const int b = pair / n_heads, h = pair - b * n_heads;
+  const int D = n_heads * DH, half = rot / 2;
+  float* sK = smem + (size_t)wave * (2 * l_cap + 2) * DH;
+  float* sV = sK + l_cap * DH;
+  float* sq = sV + l_cap * DH;
+  float* sk = sq + DH;
+  T* Kg = Kl + (size_t)pair * l_cap * DH;
+  T* Vg = Vl + (size_t)pair * l_cap * DH;
+  const float sc = rsqrtf((float)DH);
+
+  for (int idx = lane; idx < pos0 * DH; idx += 64) {
+    sK[idx] = to_float<T>(Kg[idx]);
+    sV[idx] = to_float<T>(Vg[idx]);
+  }
+  for (int i = 0; i < rows; ++i) {
+    const int pos = pos0 + i;
+    const size_t row = (size_t)b * rows + i;
+    const float* src = qkv + row * 3 * D + h * DH;
+    float vv[DPL];
+#pragma unroll
+    for (int c = 0; c < DPL; ++c) {
+      const int d = lane + 64 * c;
+      if (d < DH) { sq[d] = src[d]; sk[d] = src[D + d]; vv[c] = src[2 * D + d]; }
+    }
+    __syncthreads();
+    float qv[DPL];
+#pragma unroll
+    for (int c = 0; c < DPL; ++c) {
+      const int d = lane + 64 * c;
+      if (d < DH) {
+        float qd = sq[d], kd = sk[d];
+        if (d < rot) {
+          const int t = d < half ? d : d - half;
+          const float2 cs = rope[(size_t)pos * half + t];
+          if (d < half) { qd = qd * cs.x - sq[d + half] * cs.y; kd = kd * cs.x - sk[d + half] * cs.y; }
+          else          { qd = qd * cs.x + sq[d - half] * cs.y; kd = kd * cs.x + sk[d - half] * cs.y; }
+        }
+        qv[c] = qd * sc;
+        const T kt = from_float<T>(kd), vt = from_float<T>(vv[c]);
+        sK[pos * DH + d] = to_float<T>(kt);
+        sV[pos * DH + d] = to_float<T>(vt);
+        if (active) { Kg[pos * DH + d] = kt; Vg[pos * DH + d] = vt; }
+      } else {
+        qv[c] = 0.f;
+      }
+    }
+    __syncthreads();
+    float m = kNegBig, l = 0.f, acc[DPL];
+#pragma unroll
+    for (int c = 0; c < DPL; ++c) acc[c] = 0.f;
+    for (int j = 0; j <= pos; ++j) {
+      float dot = 0.f;
+#pragma unroll
+      for (int c = 0; c < DPL; ++c) {
+        const int d = lane + 64 * c;
+        if (d < DH) dot = fmaf(qv[c], sK[j * DH + d], dot);
+      }
+      dot = wave_sum(dot);
+      const float mx = fmaxf(m, dot);
+      const float scale = __expf(m - mx), p = __expf(dot - mx);
+      l = l * scale + p;
+#pragma unroll
+      for (int c = 0; c < DPL; ++c) {
+        const int d = lane + 64 * c;
+        if (d < DH) acc[c] = acc[c] * scale + p * sV[j * DH + d];
+      }
+      m = mx;
+    }
+    if (active) {
+#pragma unroll
+      for (int c = 0; c < DPL; ++c) {
+        const int d = lane + 64 * c;
+        if (d < DH) out[row * D + h * DH + d] = from_float<T>(acc[c] / l);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+#define BT_DISPATCH_DH(DHV, ...)                         \
+  switch (DHV) {                                         \
+    case 32:  { constexpr int DH = 32;  __VA_ARGS__; break; }  \
+    case 64:  { constexpr int DH = 64;  __VA_ARGS__; break; }  \
+    case 128: { constexpr int DH = 128; __VA_ARGS__; break; }  \
+    default: return hipErrorInvalidValue;                \
+  }
+
+hipError_t launch_rope_append(int dtype, float* qkv, void* Kc, void* Vc, const float2* rope,
+                              int n_rows, int n_new, int pos0, int n_heads, int d_head, int rot,
+                              int n_cap, hipStream_t s) {
+  if (n_rows <= 0) return hipSuccess;
+  if (dtype == BT_F32)
+    rope_append_kernel<float><<<n_rows, 256, 0, s>>>(qkv, (float*)Kc, (float*)Vc, rope, n_new, pos0, n_heads, d_head, rot, n_cap);
+  else
+    rope_append_kernel<bf16_t><<<n_rows, 256, 0, s>>>(qkv, (bf16_t*)Kc, (bf16_t*)Vc, rope, n_new, pos0, n_heads, d_head, rot, n_cap);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_block_decode(int dtype, const float* qkv, const void* Kc, const void* Vc,
+                                    void* out, int batch, int n_heads, int d_head, int n_keys,
+                                    int n_cap, hipStream_t s) {
+  if (n_keys < 1 || n_keys > n_cap) return hipErrorInvalidValue;
+  constexpr int NW = 4;
+  const int grid = batch * n_heads;
+  if (dtype == BT_F32) {
+    BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<float, DH, NW><<<grid, NW * 64, 0, s>>>(
+        qkv, (const float*)Kc, (const float*)Vc, (float*)out, n_heads, n_keys, n_cap)));
+  } else {
+    BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<bf16_t, DH, NW><<<grid, NW * 64, 0, s>>>(
+        qkv, (const bf16_t*)Kc, (const bf16_t*)Vc, (bf16_t*)out, n_heads, n_keys, n_cap)));
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_block_prefill(int dtype, const float* qkv, const void* Kc, const void* Vc,
+                                     void* out, int batch, int n_heads, int d_head, int n_q,
+                                     int n_cap, hipStream_t s) {
+  if (n_q < 1 || n_q > n_cap) return hipErrorInvalidValue;
+  const dim3 grid(batch * n_heads, (n_q + 3) / 4);
+  if (dtype == BT_F32) {
+    BT_DISPATCH_DH(d_head, (attn_block_prefill_kernel<float, DH><<<grid, 256, 0, s>>>(
+        qkv, (const float*)Kc, (const float*)Vc, (float*)out, n_heads, n_q, n_cap)));
+  } else {
+    BT_DISPATCH_DH(d_head, (attn_block_prefill_kernel<bf16_t, DH><<<grid, 256, 0, s>>>(
+        qkv, (const bf16_t*)Kc, (const bf16_t*)Vc, (bf16_t*)out, n_heads, n_q, n_cap)));
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_local(int dtype, const float* qkv, void* Kl, void* Vl, const float2* rope,
+                             void* out, int batch, int n_heads, int d_head, int rot, int rows,
+                             int pos0, int l_cap, hipStream_t s) {
+  if (rows < 1 || pos0 < 0 || pos0 + rows > l_cap) return hipErrorInvalidValue;
+  const int n_pairs = batch * n_heads;
+  const size_t per_wave = (size_t)(2 * l_cap + 2) * d_head * sizeof(float);
+  int nw = 4;
+  while (nw > 1 && per_wave * nw > 60 * 1024) nw >>= 1;
+  if (per_wave * nw > 60 * 1024) return hipErrorInvalidValue;
+  const int grid = (n_pairs + nw - 1) / nw;
+  const size_t shm = per_wave * nw;
+  if (dtype == BT_F32) {
+    BT_DISPATCH_DH(d_head, (attn_local_kernel<float, DH><<<grid, nw * 64, shm, s>>>(
+        qkv, (float*)Kl, (float*)Vl, rope, (float*)out, n_pairs, n_heads, rot, rows, pos0, l_cap)));
+  } else {
+    BT_DISPATCH_DH(d_head, (attn_local_kernel<bf16_t, DH><<<grid, nw * 64, shm, s>>>(
+        qkv, (bf16_t*)Kl, (bf16_t*)Vl, rope, (bf16_t*)out, n_pairs, n_heads, rot, rows, pos0, l_cap)));
+  }
+  return hipGetLastError();
+}
+
+}  // namespace bt

@@ -1,0 +1,526 @@
+// C ABI of the library: argument checks, workspace layout, and the host-side
+// sequencing of the generation step (Sec. 2.1, Fig. 1, App. C of the paper).
+// Every step of the path runs in the HIP kernels declared in kernels.h; this
+// file only decides which launch comes next.
+#include "../../include/bt.h"
+#include "kernels.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace bt;
+
+namespace {
+
+constexpr int kDefaultPrefillRows = 16384;
+constexpr int kMaxSplits = 16;
+constexpr int kSkinnyRows = 256;     // GEMMs with at most this many rows may split K
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+struct Layout {
+  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, ctx, hfin, logits, cur, total;
+  size_t blk_layer_stride, loc_layer_stride;   // bytes between layers (K then V inside)
+  size_t part_elems;                           // floats in each partial buffer
+  int m_rows, l_cap, n_pref, rope_len, esz;
+};
+
+int check_config(const bt_config& c, std::string* why) {
+  auto bad = [&](const char* s) { if (why) *why = s; return (int)BT_ERR_ARG; };
+  if (c.dtype != BT_F32 && c.dtype != BT_BF16) return bad("dtype must be BT_F32 or BT_BF16");
+  if (c.vocab < 1 || c.block_len < 1 || c.d_model < 1 || c.n_heads < 1 || c.d_ff < 1) return bad("non-positive size");
+  if (c.n_block_layers < 0 || c.n_token_layers < 0) return bad("negative layer count");
+  if (c.max_batch < 1 || c.max_blocks < 1) return bad("max_batch and max_blocks must be >= 1");
+  if (c.d_model % c.n_heads) return bad("d_model % n_heads != 0");
+  const int dh = c.d_model / c.n_heads;
+  if (dh != 32 && dh != 64 && dh != 128) return bad("d_head must be 32, 64 or 128");
+  if (c.d_model % c.block_len) return bad("d_model % block_len != 0");
+  if ((c.d_model / c.block_len) % 8) return bad("d_emb must be a multiple of 8");
+  if (c.d_model > 4096) return bad("d_model > 4096");
+  if (c.rotary_dims < 0 || (c.rotary_dims & 1) || c.rotary_dims > dh) return bad("rotary_dims must be even and <= d_head");
+  if (c.prefix_len < 0 || (c.prefix_len == 0 && c.block_len != 1)) return bad("prefix_len == 0 needs block_len == 1");
+  if (c.dtype == BT_BF16 && (c.d_model % 64 || c.d_ff % 64)) return bad("bf16 mode needs d_model, d_ff multiples of 64");
+  if (c.d_ff % 8) return bad("d_ff must be a multiple of 8");
+  if (c.prefill_rows < 0) return bad("prefill_rows < 0");
+  if (!(c.ln_eps >= 0.f)) return bad("ln_eps < 0");
+  const int l_cap = (c.prefix_len > 0 ? c.prefix_len : 1) + c.block_len;
+  if ((size_t)(2 * l_cap + 2) * dh * sizeof(float) > 60 * 1024) return bad("prefix_len + block_len too large for the local-attention kernel");
+  return BT_OK;
+}
+
+void make_layout(const bt_config& c, Layout& L) {
+  const size_t D = c.d_model, F = c.d_ff, B = c.max_batch, H = c.n_heads, dh = D / H;
+  L.esz = c.dtype == BT_BF16 ? 2 : 4;
+  L.n_pref = c.prefix_len > 0 ? c.prefix_len : 1;
+  L.l_cap = L.n_pref + c.block_len;
+  L.rope_len = c.max_blocks > L.l_cap ? c.max_blocks : L.l_cap;
+  size_t pr = c.prefill_rows > 0 ? c.prefill_rows : kDefaultPrefillRows;
+  if (pr < (size_t)c.max_blocks) pr = c.max_blocks;
+  if (pr > B * (size_t)c.max_blocks) pr = B * (size_t)c.max_blocks;
+  size_t m_rows = pr;
+  if (m_rows < B * L.n_pref) m_rows = B * L.n_pref;
+  L.m_rows = (int)m_rows;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  L.blk_layer_stride = align_up(2 * B * H * c.max_blocks * dh * L.esz);
+  L.blk_kv = take(L.blk_layer_stride * c.n_block_layers);
+  L.loc_layer_stride = align_up(2 * B * H * L.l_cap * dh * L.esz);
+  L.loc_kv = take(L.loc_layer_stride * c.n_token_layers);
+  L.rope = take((size_t)L.rope_len * (c.rotary_dims / 2 + 1) * sizeof(float2));
+  L.x = take(m_rows * D * 4);
+  L.u1 = take(m_rows * D * 4);          // sized for float so that fp32 mode fits
+  L.u2 = take(m_rows * D * 4);
+  L.qkv = take(m_rows * 3 * D * 4);
+  L.ao = take(m_rows * D * 4);
+  L.hmid = take(m_rows * F * 4);
+  const size_t skinny = m_rows < (size_t)kSkinnyRows ? m_rows : (size_t)kSkinnyRows;
+  L.part_elems = m_rows * D;
+  if (L.part_elems < kMaxSplits * skinny * D) L.part_elems = kMaxSplits * skinny * D;
+  L.part_o = take(L.part_elems * 4);
+  L.part_d = take(L.part_elems * 4);
+  L.ctx = take(B * D * 4);
+  L.hfin = take(B * D * 4);
+  L.logits = take(B * (size_t)c.vocab * 4);
+  L.cur = take(B * c.block_len * 4);
+  L.total = off;
+}
+
+}  // namespace
+
+struct bt_model {
+  bt_config cfg;
+  bt_weights w;
+  std::vector<bt_layer_weights> blk, tok;
+  Layout L;
+  char* ws;
+  hipStream_t stream;
+  int batch, n_blocks, r;
+  bool have_context, stepped;
+  bt_stats st;
+  bool profile;
+  std::vector<hipEvent_t> ev;      // pairs (start, stop)
+  size_t ev_used;
+  std::string err;
+
+  template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+};
+
+namespace {
+
+int fail(bt_model* m, int code, const std::string& msg) {
+  if (m) m->err = msg;
+  return code;
+}
+
+#define BT_HIP(m, expr)                                                                  \
+  do {                                                                                   \
+    hipError_t e_ = (expr);                                                              \
+    if (e_ != hipSuccess)                                                                \
+      return fail((m), BT_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));   \
+  } while (0)
+
+enum Mode { MODE_BLOCK_PREFILL, MODE_BLOCK_DECODE, MODE_TOKEN };
+
+struct StackArgs {
+  Mode mode;
+  int M;           // rows in the residual stream
+  int batch;       // sequences in this call
+  int b0;          // first sequence (cache offset)
+  int rows;        // rows per sequence (prefill: N_p; decode: 1; token: P or 1)
+  int pos0;        // first position of the new rows
+};
+
+// Final LayerNorm of a stack on row (i*in_mul + in_off) of x, for i < n.
+int final_ln(bt_model* m, const StackArgs& a, const float* pendO, const float* biasO, int sO,
+             const float* pendD, const float* biasD, int sD, const void* g, const void* b,
+             void* out, int out_f32, int n, int in_mul, int in_off) {
+  ResidLnArgs r{};
+  r.x = m->at<float>(m->L.x);
+  r.partA = pendO; r.biasA = biasO; r.splitsA = sO;
+  r.partB = pendD; r.biasB = biasD; r.splitsB = sD;
+  r.part_stride = (size_t)a.M * m->cfg.d_model;
+  r.g1 = (const float*)g; r.b1 = (const float*)b; r.u1 = out; r.u1_f32 = out_f32;
+  r.g2 = nullptr; r.b2 = nullptr; r.u2 = nullptr;
+  r.n_rows = n; r.D = m->cfg.d_model; r.in_mul = in_mul; r.in_off = in_off; r.write_x = 0;
+  r.eps = m->cfg.ln_eps;
+  BT_HIP(m, launch_resid_ln(m->cfg.dtype, r, m->stream));
+  return BT_OK;
+}
+
+// Runs n_layers decoder layers over x [M, D] and the stack's final LayerNorm.
+int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const StackArgs& a,
+              const void* fin_g, const void* fin_b, void* fin_out, int fin_f32, int fin_n, int fin_mul, int fin_off) {
+  const bt_config& c = m->cfg;
+  const Layout& L = m->L;
+  const int D = c.d_model, F = c.d_ff, H = c.n_heads, dh = D / H, dt = c.dtype;
+  float* x = m->at<float>(L.x);
+  void* u1 = m->at<void>(L.u1);
+  void* u2 = m->at<void>(L.u2);
+  float* qkv = m->at<float>(L.qkv);
+  void* ao = m->at<void>(L.ao);
+  void* hmid = m->at<void>(L.hmid);
+  float* part_o = m->at<float>(L.part_o);
+  float* part_d = m->at<float>(L.part_d);
+  const float2* rope = m->at<float2>(L.rope);
+  hipStream_t s = m->stream;
+  const int M = a.M;
+  const int sO = gemm_pick_splits(dt, M, D, D), sD = gemm_pick_splits(dt, M, D, F);
+  if ((size_t)sO * M * D > L.part_elems || (size_t)sD * M * D > L.part_elems)
+    return fail(m, BT_ERR_CAPACITY, "split-K partial buffer too small");
+
+  auto ln = [&](const float* pO, const float* bO, int nO, const float* pD, const float* bD, int nD,
+                const void* g1, const void* b1, const void* g2, const void* b2) -> int {
+    ResidLnArgs r{};
+    r.x = x;
+    r.partA = pO; r.biasA = bO; r.splitsA = nO;
+    r.partB = pD; r.biasB = bD; r.splitsB = nD;
+    r.part_stride = (size_t)M * D;
+    r.g1 = (const float*)g1; r.b1 = (const float*)b1; r.u1 = u1; r.u1_f32 = 0;
+    r.g2 = (const float*)g2; r.b2 = (const float*)b2; r.u2 = u2;
+    r.n_rows = M; r.D = D; r.in_mul = 1; r.in_off = 0; r.write_x = (pO || pD) ? 1 : 0;
+    r.eps = c.ln_eps;
+    BT_HIP(m, launch_resid_ln(dt, r, s));
+    return BT_OK;
+  };
+  auto attention = [&](int l) -> int {
+    if (a.mode == MODE_TOKEN) {
+      char* base = m->ws + L.loc_kv + (size_t)l * L.loc_layer_stride;
+      const size_t half = (size_t)c.max_batch * H * L.l_cap * dh * L.esz;
+      BT_HIP(m, launch_attn_local(dt, qkv, base, base + half, rope, ao, a.batch, H, dh, c.rotary_dims,
+                                  a.rows, a.pos0, L.l_cap, s));
+      return BT_OK;
+    }
+    char* base = m->ws + L.blk_kv + (size_t)l * L.blk_layer_stride;
+    const size_t half = (size_t)c.max_batch * H * c.max_blocks * dh * L.esz;
+    const size_t seq = (size_t)a.b0 * H * c.max_blocks * dh * L.esz;
+    char* Kc = base + seq;
+    char* Vc = base + half + seq;
+    BT_HIP(m, launch_rope_append(dt, qkv, Kc, Vc, rope, M, a.rows, a.pos0, H, dh, c.rotary_dims, c.max_blocks, s));
+    if (a.mode == MODE_BLOCK_PREFILL) {
+      BT_HIP(m, launch_attn_block_prefill(dt, qkv, Kc, Vc, ao, a.batch, H, dh, a.rows, c.max_blocks, s));
+    } else {
+      const int n_keys = a.pos0 + 1;
+      hipEvent_t e0 = nullptr, e1 = nullptr;
+      if (m->profile) {
+        if (m->ev_used + 2 > m->ev.size()) {
+          hipEvent_t n0, n1;
+          BT_HIP(m, hipEventCreate(&n0));
+          BT_HIP(m, hipEventCreate(&n1));
+          m->ev.push_back(n0);
+          m->ev.push_back(n1);
+        }
+        e0 = m->ev[m->ev_used];
+        e1 = m->ev[m->ev_used + 1];
+        m->ev_used += 2;
+        BT_HIP(m, hipEventRecord(e0, s));
+      }
+      BT_HIP(m, launch_attn_block_decode(dt, qkv, Kc, Vc, ao, a.batch, H, dh, n_keys, c.max_blocks, s));
+      if (m->profile) {
+        BT_HIP(m, hipEventRecord(e1, s));
+        m->st.attn_block_launches += 1;
+        m->st.attn_block_bytes += (int64_t)2 * n_keys * D * L.esz * a.batch;
+      }
+    }
+    return BT_OK;
+  };
+
+  int rc;
+  if (n_layers == 0) {
+    return final_ln(m, a, nullptr, nullptr, 0, nullptr, nullptr, 0, fin_g, fin_b, fin_out, fin_f32, fin_n, fin_mul, fin_off);
+  }
+  if (c.parallel_residual) {
+    if ((rc = ln(nullptr, nullptr, 0, nullptr, nullptr, 0, lw[0].ln1_g, lw[0].ln1_b, lw[0].ln2_g, lw[0].ln2_b))) return rc;
+    for (int l = 0; l < n_layers; ++l) {
+      GemmProblem p[2];
+      p[0] = GemmProblem{u1, lw[l].W_qkv, (const float*)lw[l].b_qkv, qkv, M, 3 * D, D, D, 3 * D, EPI_F32, 1};
+      p[1] = GemmProblem{u2, lw[l].W_up, (const float*)lw[l].b_up, hmid, M, F, D, D, F, EPI_GELU, 1};
+      BT_HIP(m, launch_gemm(dt, p, 2, s));
+      if ((rc = attention(l))) return rc;
+      p[0] = GemmProblem{ao, lw[l].W_o, nullptr, part_o, M, D, D, D, D, EPI_PARTIAL, sO};
+      p[1] = GemmProblem{hmid, lw[l].W_down, nullptr, part_d, M, D, F, F, D, EPI_PARTIAL, sD};
+      BT_HIP(m, launch_gemm(dt, p, 2, s));
+      if (l + 1 < n_layers) {
+        if ((rc = ln(part_o, (const float*)lw[l].b_o, sO, part_d, (const float*)lw[l].b_down, sD,
+                     lw[l + 1].ln1_g, lw[l + 1].ln1_b, lw[l + 1].ln2_g, lw[l + 1].ln2_b))) return rc;
+      } else {
+        return final_ln(m, a, part_o, (const float*)lw[l].b_o, sO, part_d, (const float*)lw[l].b_down, sD,
+                        fin_g, fin_b, fin_out, fin_f32, fin_n, fin_mul, fin_off);
+      }
+    }
+  } else {
+    if ((rc = ln(nullptr, nullptr, 0, nullptr, nullptr, 0, lw[0].ln1_g, lw[0].ln1_b, nullptr, nullptr))) return rc;
+    for (int l = 0; l < n_layers; ++l) {
+      GemmProblem p;
+      p = GemmProblem{u1, lw[l].W_qkv, (const float*)lw[l].b_qkv, qkv, M, 3 * D, D, D, 3 * D, EPI_F32, 1};
+      BT_HIP(m, launch_gemm(dt, &p, 1, s));
+      if ((rc = attention(l))) return rc;
+      p = GemmProblem{ao, lw[l].W_o, nullptr, part_o, M, D, D, D, D, EPI_PARTIAL, sO};
+      BT_HIP(m, launch_gemm(dt, &p, 1, s));
+      if ((rc = ln(part_o, (const float*)lw[l].b_o, sO, nullptr, nullptr, 0, lw[l].ln2_g, lw[l].ln2_b, nullptr, nullptr))) return rc;
+      p = GemmProblem{u1, lw[l].W_up, (const float*)lw[l].b_up, hmid, M, F, D, D, F, EPI_GELU, 1};
+      BT_HIP(m, launch_gemm(dt, &p, 1, s));
+      p = GemmProblem{hmid, lw[l].W_down, nullptr, part_d, M, D, F, F, D, EPI_PARTIAL, sD};
+      BT_HIP(m, launch_gemm(dt, &p, 1, s));
+      if (l + 1 < n_layers) {
+        if ((rc = ln(nullptr, nullptr, 0, part_d, (const float*)lw[l].b_down, sD, lw[l + 1].ln1_g, lw[l + 1].ln1_b, nullptr, nullptr))) return rc;
+      } else {
+        return final_ln(m, a, nullptr, nullptr, 0, part_d, (const float*)lw[l].b_down, sD,
+                        fin_g, fin_b, fin_out, fin_f32, fin_n, fin_mul, fin_off);
+      }
+    }
+  }
+  return BT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bt_workspace_bytes(const bt_config* cfg, size_t* bytes) {
+  if (!cfg || !bytes) return BT_ERR_ARG;
+  int rc = check_config(*cfg, nullptr);
+  if (rc) return rc;
+  Layout L;
+  make_layout(*cfg, L);
+  *bytes = L.total;
+  return BT_OK;
+}
+
+int bt_create(const bt_config* cfg, const bt_weights* w, void* workspace_dev, size_t workspace_bytes,
+              void* hip_stream, bt_model** out) {
+  if (!cfg || !w || !out) return BT_ERR_ARG;
+  *out = nullptr;
+  if (!workspace_dev || ((uintptr_t)workspace_dev & 255)) return BT_ERR_ARG;
+  int rc = check_config(*cfg, nullptr);
+  if (rc) return rc;
+  const bool need_tok_table = cfg->block_len > 1;
+  if (!w->E_emb || !w->W_head || !w->blk_lnf_g || !w->blk_lnf_b || !w->tok_lnf_g || !w->tok_lnf_b) return BT_ERR_ARG;
+  if (need_tok_table && !w->E_tok) return BT_ERR_ARG;
+  if (cfg->prefix_len > 0 && (!w->W_prefix || !w->b_prefix)) return BT_ERR_ARG;
+  if ((cfg->n_block_layers > 0 && !w->block_layers) || (cfg->n_token_layers > 0 && !w->token_layers)) return BT_ERR_ARG;
+  auto layer_ok = [](const bt_layer_weights& l) {
+    return l.ln1_g && l.ln1_b && l.W_qkv && l.b_qkv && l.W_o && l.b_o && l.ln2_g && l.ln2_b && l.W_up && l.b_up &&
+           l.W_down && l.b_down;
+  };
+  for (int i = 0; i < cfg->n_block_layers; ++i) if (!layer_ok(w->block_layers[i])) return BT_ERR_ARG;
+  for (int i = 0; i < cfg->n_token_layers; ++i) if (!layer_ok(w->token_layers[i])) return BT_ERR_ARG;
+  Layout L;
+  make_layout(*cfg, L);
+  if (workspace_bytes < L.total) return BT_ERR_CAPACITY;
+
+  bt_model* m = new (std::nothrow) bt_model();
+  if (!m) return BT_ERR_ARG;
+  m->cfg = *cfg;
+  m->w = *w;
+  m->blk.assign(w->block_layers, w->block_layers + cfg->n_block_layers);
+  m->tok.assign(w->token_layers, w->token_layers + cfg->n_token_layers);
+  m->w.block_layers = m->blk.data();
+  m->w.token_layers = m->tok.data();
+  m->L = L;
+  m->ws = reinterpret_cast<char*>(workspace_dev);
+  m->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  m->batch = 0; m->n_blocks = 0; m->r = 0;
+  m->have_context = false; m->stepped = false;
+  std::memset(&m->st, 0, sizeof(m->st));
+  m->profile = false;
+  m->ev_used = 0;
+
+  // rotary table: (cos, sin) of pos * 10000^(-2t/rot), computed in double on the host
+  const int half = cfg->rotary_dims / 2;
+  if (half > 0) {
+    std::vector<float2> tab((size_t)L.rope_len * half);
+    for (int pos = 0; pos < L.rope_len; ++pos)
+      for (int t = 0; t < half; ++t) {
+        const double ang = (double)pos * std::pow(10000.0, -2.0 * t / cfg->rotary_dims);
+        tab[(size_t)pos * half + t] = make_float2((float)std::cos(ang), (float)std::sin(ang));
+      }
+    hipError_t e = hipMemcpyAsync(m->ws + L.rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, m->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+    if (e != hipSuccess) { delete m; return BT_ERR_HIP; }
+  }
+  *out = m;
+  return BT_OK;
+}
+
+int bt_prefill(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t prompt_len) {
+  if (!m) return BT_ERR_ARG;
+  const bt_config& c = m->cfg;
+  if (!tokens_dev) return fail(m, BT_ERR_ARG, "tokens_dev is null");
+  if (batch < 1 || batch > c.max_batch) return fail(m, BT_ERR_ARG, "batch out of range");
+  if (prompt_len < c.block_len || prompt_len % c.block_len) return fail(m, BT_ERR_ARG, "prompt_len must be a positive multiple of block_len");
+  const int n_p = prompt_len / c.block_len;
+  if (n_p > c.max_blocks) return fail(m, BT_ERR_CAPACITY, "prompt needs more block slots than max_blocks");
+  const Layout& L = m->L;
+  int per = L.m_rows / n_p;
+  if (per < 1) return fail(m, BT_ERR_CAPACITY, "workspace rows < prompt blocks");
+  const bool ctx_f32 = c.prefix_len == 0;
+  const size_t ctx_esz = ctx_f32 ? 4 : L.esz;
+  for (int b0 = 0; b0 < batch; b0 += per) {
+    const int bc = batch - b0 < per ? batch - b0 : per;
+    BT_HIP(m, launch_embed_concat(c.dtype, m->w.E_emb, tokens_dev + (size_t)b0 * prompt_len, m->at<float>(L.x),
+                                  bc * n_p, c.block_len, c.d_model / c.block_len, m->stream));
+    StackArgs a{MODE_BLOCK_PREFILL, bc * n_p, bc, b0, n_p, 0};
+    int rc = run_stack(m, m->blk.data(), c.n_block_layers, a, m->w.blk_lnf_g, m->w.blk_lnf_b,
+                       m->ws + L.ctx + (size_t)b0 * c.d_model * ctx_esz, ctx_f32, bc, n_p, n_p - 1);
+    if (rc) return rc;
+  }
+  m->batch = batch;
+  m->n_blocks = n_p;
+  m->r = 0;
+  m->have_context = true;
+  m->stepped = false;
+  bt_stats& st = m->st;
+  st.block_passes = n_p;
+  st.token_passes = st.token_rows = st.block_kv_rows_read = st.block_kv_bytes_read = 0;
+  st.local_kv_high_water = 0;
+  return BT_OK;
+}
+
+int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
+  if (!m) return BT_ERR_ARG;
+  const bt_config& c = m->cfg;
+  if (!next_ids_dev) return fail(m, BT_ERR_ARG, "next_ids_dev is null");
+  if (m->batch == 0) return fail(m, BT_ERR_STATE, "decode before prefill");
+  if (batch != m->batch) return fail(m, BT_ERR_STATE, "batch differs from the prefill's");
+  const Layout& L = m->L;
+  const int D = c.d_model, B = batch;
+  hipStream_t s = m->stream;
+  int32_t* cur = m->at<int32_t>(L.cur);
+  float* x = m->at<float>(L.x);
+  const bool ctx_f32 = c.prefix_len == 0;
+  int rows, pos0;
+  if (m->r == 0) {
+    if (!m->have_context) {
+      if (m->n_blocks >= c.max_blocks) return fail(m, BT_ERR_CAPACITY, "block KV cache is full");
+      BT_HIP(m, launch_embed_concat(c.dtype, m->w.E_emb, cur, x, B, c.block_len, D / c.block_len, s));
+      StackArgs a{MODE_BLOCK_DECODE, B, B, 0, 1, m->n_blocks};
+      int rc = run_stack(m, m->blk.data(), c.n_block_layers, a, m->w.blk_lnf_g, m->w.blk_lnf_b,
+                         m->ws + L.ctx, ctx_f32, B, 1, 0);
+      if (rc) return rc;
+      m->st.block_passes += 1;
+      m->st.block_kv_rows_read += m->n_blocks + 1;
+      m->st.block_kv_bytes_read += (int64_t)(m->n_blocks + 1) * B * c.n_block_layers * 2 * D * L.esz;
+      m->n_blocks += 1;
+    }
+    if (c.prefix_len > 0) {
+      GemmProblem p{m->ws + L.ctx, m->w.W_prefix, (const float*)m->w.b_prefix, x, B, c.prefix_len * D, D, D,
+                    c.prefix_len * D, EPI_F32, 1};
+      BT_HIP(m, launch_gemm(c.dtype, &p, 1, s));
+    } else {
+      BT_HIP(m, hipMemcpyAsync(x, m->ws + L.ctx, (size_t)B * D * 4, hipMemcpyDeviceToDevice, s));
+    }
+    rows = L.n_pref;
+    pos0 = 0;
+    m->have_context = false;
+  } else {
+    BT_HIP(m, launch_token_embed(c.dtype, m->w.E_tok, cur, x, B, c.block_len, m->r - 1, D, s));
+    rows = 1;
+    pos0 = L.n_pref + m->r - 1;
+  }
+  StackArgs a{MODE_TOKEN, B * rows, B, 0, rows, pos0};
+  int rc = run_stack(m, m->tok.data(), c.n_token_layers, a, m->w.tok_lnf_g, m->w.tok_lnf_b,
+                     m->ws + L.hfin, 0, B, rows, rows - 1);
+  if (rc) return rc;
+  GemmProblem p{m->ws + L.hfin, m->w.W_head, nullptr, m->ws + L.logits, B, c.vocab, D, D, c.vocab, EPI_F32, 1};
+  BT_HIP(m, launch_gemm(c.dtype, &p, 1, s));
+  BT_HIP(m, launch_argmax(m->at<float>(L.logits), B, c.vocab, next_ids_dev, cur, c.block_len, m->r, s));
+  m->st.token_passes += 1;
+  m->st.token_rows += rows;
+  if (c.n_token_layers > 0 && pos0 + rows > m->st.local_kv_high_water) m->st.local_kv_high_water = pos0 + rows;
+  m->r = (m->r + 1) % c.block_len;
+  m->stepped = true;
+  return BT_OK;
+}
+
+int bt_embed(bt_model* m, const int32_t* tokens_dev, int32_t n_rows, float* out_dev) {
+  if (!m) return BT_ERR_ARG;
+  if (!tokens_dev || !out_dev || n_rows < 0) return fail(m, BT_ERR_ARG, "bt_embed: null pointer or negative n_rows");
+  BT_HIP(m, launch_embed_concat(m->cfg.dtype, m->w.E_emb, tokens_dev, out_dev, n_rows, m->cfg.block_len,
+                                m->cfg.d_model / m->cfg.block_len, m->stream));
+  return BT_OK;
+}
+
+int bt_get_logits(bt_model* m, float* logits_dev) {
+  if (!m) return BT_ERR_ARG;
+  if (!logits_dev) return fail(m, BT_ERR_ARG, "logits_dev is null");
+  if (!m->stepped) return fail(m, BT_ERR_STATE, "no decode step yet");
+  BT_HIP(m, hipMemcpyAsync(logits_dev, m->ws + m->L.logits, (size_t)m->batch * m->cfg.vocab * 4,
+                           hipMemcpyDeviceToDevice, m->stream));
+  return BT_OK;
+}
+
+int bt_force_last_ids(bt_model* m, const int32_t* ids_dev) {
+  if (!m) return BT_ERR_ARG;
+  if (!ids_dev) return fail(m, BT_ERR_ARG, "ids_dev is null");
+  if (!m->stepped) return fail(m, BT_ERR_STATE, "no decode step yet");
+  const int L_B = m->cfg.block_len;
+  BT_HIP(m, launch_scatter_ids(ids_dev, m->at<int32_t>(m->L.cur), m->batch, L_B, (m->r + L_B - 1) % L_B, m->stream));
+  return BT_OK;
+}
+
+int bt_get_context(bt_model* m, void* ctx_dev) {
+  if (!m) return BT_ERR_ARG;
+  if (!ctx_dev) return fail(m, BT_ERR_ARG, "ctx_dev is null");
+  if (m->batch == 0) return fail(m, BT_ERR_STATE, "no prefill yet");
+  const size_t esz = m->cfg.prefix_len == 0 ? 4 : m->L.esz;
+  BT_HIP(m, hipMemcpyAsync(ctx_dev, m->ws + m->L.ctx, (size_t)m->batch * m->cfg.d_model * esz, hipMemcpyDeviceToDevice, m->stream));
+  return BT_OK;
+}
+
+int bt_set_context(bt_model* m, const void* ctx_dev) {
+  if (!m) return BT_ERR_ARG;
+  if (!ctx_dev) return fail(m, BT_ERR_ARG, "ctx_dev is null");
+  if (m->batch == 0) return fail(m, BT_ERR_STATE, "no prefill yet");
+  const size_t esz = m->cfg.prefix_len == 0 ? 4 : m->L.esz;
+  BT_HIP(m, hipMemcpyAsync(m->ws + m->L.ctx, ctx_dev, (size_t)m->batch * m->cfg.d_model * esz, hipMemcpyDeviceToDevice, m->stream));
+  return BT_OK;
+}
+
+int bt_set_profile(bt_model* m, int32_t on) {
+  if (!m) return BT_ERR_ARG;
+  m->profile = on != 0;
+  return BT_OK;
+}
+
+int bt_reset_profile(bt_model* m) {
+  if (!m) return BT_ERR_ARG;
+  BT_HIP(m, hipStreamSynchronize(m->stream));
+  m->ev_used = 0;
+  m->st.attn_block_ms = 0.0;
+  m->st.attn_block_launches = 0;
+  m->st.attn_block_bytes = 0;
+  return BT_OK;
+}
+
+int bt_get_stats(bt_model* m, bt_stats* out) {
+  if (!m || !out) return BT_ERR_ARG;
+  if (m->ev_used > 0) {
+    BT_HIP(m, hipStreamSynchronize(m->stream));
+    double ms = 0.0;
+    for (size_t i = 0; i + 1 < m->ev_used; i += 2) {
+      float t = 0.f;
+      BT_HIP(m, hipEventElapsedTime(&t, m->ev[i], m->ev[i + 1]));
+      ms += t;
+    }
+    m->st.attn_block_ms = ms;
+  }
+  m->st.n_blocks = m->n_blocks;
+  m->st.r = m->r;
+  m->st.batch = m->batch;
+  *out = m->st;
+  return BT_OK;
+}
+
+const char* bt_last_error(const bt_model* m) { return m ? m->err.c_str() : "null model"; }
+
+void bt_destroy(bt_model* m) {
+  if (!m) return;
+  for (hipEvent_t e : m->ev) (void)hipEventDestroy(e);
+  delete m;
+}
+
+}  // extern "C"

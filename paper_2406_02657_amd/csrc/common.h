@@ -1,0 +1,70 @@
+// Device-side helpers shared by the gfx950 kernels: storage types, conversions,
+// wavefront (64-lane) reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bt {
+
+constexpr int kWave = 64;
+
+// Storage element of bf16 mode: raw bits, converted by hand (round to nearest even).
+struct bf16_t { uint16_t v; };
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <class T> __device__ __forceinline__ float to_float(T x);
+template <> __device__ __forceinline__ float to_float<float>(float x) { return x; }
+template <> __device__ __forceinline__ float to_float<bf16_t>(bf16_t x) { return bf16_bits_to_float(x.v); }
+
+template <class T> __device__ __forceinline__ T from_float(float x);
+template <> __device__ __forceinline__ float from_float<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float x) { bf16_t r; r.v = float_to_bf16_bits(x); return r; }
+
+// 16-byte chunk of storage elements <-> floats.  EPC = elements per chunk.
+template <class T> struct Chunk;
+template <> struct Chunk<float> {
+  static constexpr int EPC = 4;
+  __device__ __forceinline__ static void unpack(const uint4& c, float* f) {
+    f[0] = __uint_as_float(c.x); f[1] = __uint_as_float(c.y);
+    f[2] = __uint_as_float(c.z); f[3] = __uint_as_float(c.w);
+  }
+  __device__ __forceinline__ static uint4 pack(const float* f) {
+    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+  }
+};
+template <> struct Chunk<bf16_t> {
+  static constexpr int EPC = 8;
+  __device__ __forceinline__ static void unpack(const uint4& c, float* f) {
+    f[0] = __uint_as_float(c.x << 16); f[1] = __uint_as_float(c.x & 0xFFFF0000u);
+    f[2] = __uint_as_float(c.y << 16); f[3] = __uint_as_float(c.y & 0xFFFF0000u);
+    f[4] = __uint_as_float(c.z << 16); f[5] = __uint_as_float(c.z & 0xFFFF0000u);
+    f[6] = __uint_as_float(c.w << 16); f[7] = __uint_as_float(c.w & 0xFFFF0000u);
+  }
+  __device__ __forceinline__ static uint4 pack(const float* f) {
+    uint4 c;
+    c.x = (uint32_t)float_to_bf16_bits(f[0]) | ((uint32_t)float_to_bf16_bits(f[1]) << 16);
+    c.y = (uint32_t)float_to_bf16_bits(f[2]) | ((uint32_t)float_to_bf16_bits(f[3]) << 16);
+    c.z = (uint32_t)float_to_bf16_bits(f[4]) | ((uint32_t)float_to_bf16_bits(f[5]) << 16);
+    c.w = (uint32_t)float_to_bf16_bits(f[6]) | ((uint32_t)float_to_bf16_bits(f[7]) << 16);
+    return c;
+  }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+
+}  // namespace bt

@@ -1,0 +1,197 @@
+// Embedder gather-concat, token-embedding gather, fused residual + LayerNorm,
+// greedy argmax.  All bandwidth-trivial; written for 64-lane wavefronts.
+#include "common.h"
+#include "kernels.h"
+#include "../../include/bt.h"
+
+namespace bt {
+
+// ---------------------------------------------------------------------------
+// Embedder (Sec. 2.2): one workgroup per block row; 16-byte chunks of the table
+// rows are copied (widened to float) into the residual stream.
+// ---------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(256) void embed_concat_kernel(const T* __restrict__ E, const int32_t* __restrict__ tokens,
+                                                           float* __restrict__ x, int block_len, int d_emb) {
+  constexpr int EPC = Chunk<T>::EPC;
+  const int m = blockIdx.x;
+  const int chunks_per_tok = d_emb / EPC;
+  const int n_chunks = block_len * chunks_per_tok;
+  float* xr = x + (size_t)m * block_len * d_emb;
+  for (int c = threadIdx.x; c < n_chunks; c += blockDim.x) {
+    const int j = c / chunks_per_tok, cc = c - j * chunks_per_tok;
+    const int tok = tokens[(size_t)m * block_len + j];
+    const uint4 raw = *reinterpret_cast<const uint4*>(E + (size_t)tok * d_emb + cc * EPC);
+    float f[EPC];
+    Chunk<T>::unpack(raw, f);
+    float* dst = xr + j * d_emb + cc * EPC;
+#pragma unroll
+    for (int e = 0; e < EPC; e += 4)
+      *reinterpret_cast<float4*>(dst + e) = make_float4(f[e], f[e + 1], f[e + 2], f[e + 3]);
+  }
+}
+
+hipError_t launch_embed_concat(int dtype, const void* E_emb, const int32_t* tokens, float* x,
+                               int n_rows, int block_len, int d_emb, hipStream_t s) {
+  if (n_rows <= 0) return hipSuccess;
+  if (dtype == BT_F32)
+    embed_concat_kernel<float><<<n_rows, 256, 0, s>>>((const float*)E_emb, tokens, x, block_len, d_emb);
+  else
+    embed_concat_kernel<bf16_t><<<n_rows, 256, 0, s>>>((const bf16_t*)E_emb, tokens, x, block_len, d_emb);
+  return hipGetLastError();
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void token_embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ cur,
+                                                          float* __restrict__ x, int block_len, int r_prev, int D) {
+  constexpr int EPC = Chunk<T>::EPC;
+  const int b = blockIdx.x;
+  const int tok = cur[b * block_len + r_prev];
+  for (int c = threadIdx.x; c < D / EPC; c += blockDim.x) {
+    const uint4 raw = *reinterpret_cast<const uint4*>(E + (size_t)tok * D + c * EPC);
+    float f[EPC];
+    Chunk<T>::unpack(raw, f);
+    float* dst = x + (size_t)b * D + c * EPC;
+#pragma unroll
+    for (int e = 0; e < EPC; e += 4)
+      *reinterpret_cast<float4*>(dst + e) = make_float4(f[e], f[e + 1], f[e + 2], f[e + 3]);
+  }
+}
+
+hipError_t launch_token_embed(int dtype, const void* E_tok, const int32_t* cur, float* x,
+                              int batch, int block_len, int r_prev, int d_model, hipStream_t s) {
+  if (dtype == BT_F32)
+    token_embed_kernel<float><<<batch, 256, 0, s>>>((const float*)E_tok, cur, x, block_len, r_prev, d_model);
+  else
+    token_embed_kernel<bf16_t><<<batch, 256, 0, s>>>((const bf16_t*)E_tok, cur, x, block_len, r_prev, d_model);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Residual update + LayerNorm.  One workgroup (256 threads) per row, the row
+// lives in registers (D <= 256 * kMaxPerThread).  Mean and biased variance are
+// taken in two passes over the registers, as the definition states them.
+// ---------------------------------------------------------------------------
+constexpr int kLnThreads = 256;
+constexpr int kMaxPerThread = 16;   // D <= 4096
+
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+template <class T>
+__global__ __launch_bounds__(kLnThreads) void resid_ln_kernel(ResidLnArgs a) {
+  __shared__ float red[4];
+  const int i = blockIdx.x;
+  const size_t row = (size_t)i * a.in_mul + a.in_off;
+  const int D = a.D;
+  float v[kMaxPerThread];
+  float* xr = a.x + row * D;
+#pragma unroll
+  for (int c = 0; c < kMaxPerThread; ++c) {
+    const int d = threadIdx.x + c * kLnThreads;
+    float acc = 0.f;
+    if (d < D) {
+      acc = xr[d];
+      if (a.partA) {
+        float t = a.biasA ? a.biasA[d] : 0.f;
+        for (int s = 0; s < a.splitsA; ++s) t += a.partA[(size_t)s * a.part_stride + row * D + d];
+        acc += t;
+      }
+      if (a.partB) {
+        float t = a.biasB ? a.biasB[d] : 0.f;
+        for (int s = 0; s < a.splitsB; ++s) t += a.partB[(size_t)s * a.part_stride + row * D + d];
+        acc += t;
+      }
+      if (a.write_x) xr[d] = acc;
+    }
+    v[c] = acc;
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < kMaxPerThread; ++c) sum += v[c];          // entries past D are 0
+  const float mean = block_sum_256(sum, red) / (float)D;
+  float sq = 0.f;
+#pragma unroll
+  for (int c = 0; c < kMaxPerThread; ++c) {
+    const float t = (threadIdx.x + c * kLnThreads < D) ? v[c] - mean : 0.f;
+    sq += t * t;
+  }
+  const float var = block_sum_256(sq, red) / (float)D;
+  const float rstd = 1.0f / sqrtf(var + a.eps);
+#pragma unroll
+  for (int c = 0; c < kMaxPerThread; ++c) {
+    const int d = threadIdx.x + c * kLnThreads;
+    if (d < D) {
+      const float n = (v[c] - mean) * rstd;
+      const float o1 = n * a.g1[d] + a.b1[d];
+      if (a.u1_f32) reinterpret_cast<float*>(a.u1)[(size_t)i * D + d] = o1;
+      else reinterpret_cast<T*>(a.u1)[(size_t)i * D + d] = from_float<T>(o1);
+      if (a.g2) reinterpret_cast<T*>(a.u2)[(size_t)i * D + d] = from_float<T>(n * a.g2[d] + a.b2[d]);
+    }
+  }
+}
+
+hipError_t launch_resid_ln(int dtype, const ResidLnArgs& a, hipStream_t s) {
+  if (a.n_rows <= 0) return hipSuccess;
+  if (a.D > kLnThreads * kMaxPerThread) return hipErrorInvalidValue;
+  if (dtype == BT_F32) resid_ln_kernel<float><<<a.n_rows, kLnThreads, 0, s>>>(a);
+  else resid_ln_kernel<bf16_t><<<a.n_rows, kLnThreads, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Greedy argmax, lowest index on ties.  One workgroup per sequence.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int vocab,
+                                                     int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
+                                                     int block_len, int r) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  const int b = blockIdx.x;
+  const float* lg = logits + (size_t)b * vocab;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int v = threadIdx.x; v < vocab; v += 256) {
+    const float x = lg[v];
+    if (x > best || bi == 0x7fffffff) { best = x; bi = v; }   // ascending v: first maximum kept
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(best, o, kWave);
+    const int oi = __shfl_xor(bi, o, kWave);
+    if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+  }
+  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = best; si[threadIdx.x >> 6] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
+    if (next_ids) next_ids[b] = bi;
+    cur[b * block_len + r] = bi;
+  }
+}
+
+hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next_ids,
+                         int32_t* cur, int block_len, int r, hipStream_t s) {
+  argmax_kernel<<<batch, 256, 0, s>>>(logits, vocab, next_ids, cur, block_len, r);
+  return hipGetLastError();
+}
+
+__global__ void scatter_ids_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ cur, int batch,
+                                   int block_len, int r) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < batch) cur[b * block_len + r] = ids[b];
+}
+
+hipError_t launch_scatter_ids(const int32_t* ids, int32_t* cur, int batch, int block_len, int r, hipStream_t s) {
+  scatter_ids_kernel<<<(batch + 255) / 256, 256, 0, s>>>(ids, cur, batch, block_len, r);
+  return hipGetLastError();
+}
+
+}  // namespace bt

@@ -1,0 +1,262 @@
+// GEMMs of the projections (QKV, O, MLP up/down, prefix, LM head):
+//   out[M, N] = A[M, K] * W[N, K]^T  (+ bias, GELU, or split-K partial sums)
+// bf16 mode: MFMA (v_mfma_f32_16x16x32_bf16) with LDS-staged tiles, fp32
+// accumulation.  fp32 mode: an LDS-tiled VALU kernel (small models only).
+// Both operands are K-contiguous, so a lane's MFMA fragment (8 consecutive k of
+// one row) is one 16-byte load.  Up to two independent problems share a launch.
+#include "common.h"
+#include "kernels.h"
+#include "../../include/bt.h"
+
+namespace bt {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+struct GemmDesc {
+  const void* A;
+  const void* W;
+  const float* bias;
+  void* out;
+  int M, N, K, lda, ldo, epi, splits;
+  int tiles_m, tiles_n, tile_begin;   // tiles of this problem occupy blocks [tile_begin, tile_begin + tiles_m*tiles_n*splits)
+};
+struct GemmGroup {
+  GemmDesc p[2];
+  int n;
+};
+
+__device__ __forceinline__ float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
+
+template <class T>
+__device__ __forceinline__ void epilogue_store(const GemmDesc& d, int split, int row, int col, float acc) {
+  if (row >= d.M || col >= d.N) return;
+  if (d.epi == EPI_PARTIAL) {
+    reinterpret_cast<float*>(d.out)[((size_t)split * d.M + row) * d.N + col] = acc;
+  } else {
+    if (d.bias) acc += d.bias[col];
+    if (d.epi == EPI_F32) reinterpret_cast<float*>(d.out)[(size_t)row * d.ldo + col] = acc;
+    else reinterpret_cast<T*>(d.out)[(size_t)row * d.ldo + col] = from_float<T>(gelu_erf(acc));
+  }
+}
+
+// ---------------------------------------------------------------------------
+// bf16 MFMA kernel.  256 threads = 4 waves laid out WM x WN over a BM x BN tile,
+// BK = 64 per stage.  Global -> registers -> LDS with the next stage's loads in
+// flight while the current stage is multiplied.
+// ---------------------------------------------------------------------------
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmGroup g) {
+  constexpr int BK = 64;
+  constexpr int LDS = BK + 8;                   // row stride in elements (pad against bank conflicts)
+  constexpr int TM = BM / WM / 16, TN = BN / WN / 16;
+  constexpr int A_CH = BM * (BK / 8) / 256;     // 16-byte chunks per thread
+  constexpr int B_CH = BN * (BK / 8) / 256;
+  static_assert(WM * WN == 4 && A_CH >= 1 && B_CH >= 1, "tile shape");
+  __shared__ __attribute__((aligned(16))) uint16_t sA[BM * LDS];
+  __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LDS];
+
+  const int bid = blockIdx.x;
+  const GemmDesc& d = (g.n > 1 && bid >= g.p[1].tile_begin) ? g.p[1] : g.p[0];
+  int t = bid - d.tile_begin;
+  const int split = t / (d.tiles_m * d.tiles_n);
+  t -= split * d.tiles_m * d.tiles_n;
+  const int tm_idx = t % d.tiles_m, tn_idx = t / d.tiles_m;
+  const int m0 = tm_idx * BM, n0 = tn_idx * BN;
+  const int Ks = d.K / d.splits;
+  const int k_begin = split * Ks;
+  const int KT = Ks / BK;
+
+  const uint16_t* A = reinterpret_cast<const uint16_t*>(d.A);
+  const uint16_t* W = reinterpret_cast<const uint16_t*>(d.W);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WM, wn = wave / WM;
+
+  // per-thread global chunk coordinates
+  const uint16_t* a_ptr[A_CH];
+  const uint16_t* b_ptr[B_CH];
+  int a_lds[A_CH], b_lds[B_CH];
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) {
+    const int c = tid + i * 256, row = c >> 3, kc = c & 7;
+    const int gr = min(m0 + row, d.M - 1);
+    a_ptr[i] = A + (size_t)gr * d.lda + k_begin + kc * 8;
+    a_lds[i] = row * LDS + kc * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) {
+    const int c = tid + i * 256, row = c >> 3, kc = c & 7;
+    const int gr = min(n0 + row, d.N - 1);
+    b_ptr[i] = W + (size_t)gr * d.K + k_begin + kc * 8;
+    b_lds[i] = row * LDS + kc * 8;
+  }
+
+  f32x4_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  uint4 ra[A_CH], rb[B_CH];
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) ra[i] = *reinterpret_cast<const uint4*>(a_ptr[i]);
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_ptr[i]);
+
+  const int frag_row = lane & 15, frag_k = (lane >> 4) * 8;
+  for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4*>(&sA[a_lds[i]]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4*>(&sB[b_lds[i]]) = rb[i];
+    __syncthreads();
+    if (kt + 1 < KT) {
+#pragma unroll
+      for (int i = 0; i < A_CH; ++i) ra[i] = *reinterpret_cast<const uint4*>(a_ptr[i] + (size_t)(kt + 1) * BK);
+#pragma unroll
+      for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_ptr[i] + (size_t)(kt + 1) * BK);
+    }
+#pragma unroll
+    for (int ks = 0; ks < BK / 32; ++ks) {
+      bf16x8_t fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = wm * (BM / WM) + i * 16 + frag_row;
+        fa[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&sA[row * LDS + ks * 32 + frag_k]));
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int row = wn * (BN / WN) + j * 16 + frag_row;
+        fb[j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&sB[row * LDS + ks * 32 + frag_k]));
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  // C layout of the 16x16 MFMA: lane holds column lane%16, rows 4*(lane/16) + 0..3
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wn * (BN / WN) + j * 16 + (lane & 15);
+      const int row0 = m0 + wm * (BM / WM) + i * 16 + (lane >> 4) * 4;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) epilogue_store<bf16_t>(d, split, row0 + r, col, acc[i][j][r]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// fp32 VALU kernel: 64 x 64 tile, BK = 16, each thread a 4 x 4 patch.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmGroup g) {
+  constexpr int BM = 64, BN = 64, BK = 16;
+  __shared__ float sA[BK][BM + 4];
+  __shared__ float sB[BK][BN + 4];
+  const int bid = blockIdx.x;
+  const GemmDesc& d = (g.n > 1 && bid >= g.p[1].tile_begin) ? g.p[1] : g.p[0];
+  int t = bid - d.tile_begin;
+  const int split = t / (d.tiles_m * d.tiles_n);
+  t -= split * d.tiles_m * d.tiles_n;
+  const int m0 = (t % d.tiles_m) * BM, n0 = (t / d.tiles_m) * BN;
+  const int Ks = d.K / d.splits, k_begin = split * Ks;
+  const float* A = reinterpret_cast<const float*>(d.A);
+  const float* W = reinterpret_cast<const float*>(d.W);
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < Ks; k0 += BK) {
+    for (int c = tid; c < BM * BK; c += 256) {
+      const int row = c / BK, kk = c % BK;
+      const int gr = m0 + row, gk = k0 + kk;
+      sA[kk][row] = (gr < d.M && gk < Ks) ? A[(size_t)gr * d.lda + k_begin + gk] : 0.f;
+    }
+    for (int c = tid; c < BN * BK; c += 256) {
+      const int row = c / BK, kk = c % BK;
+      const int gr = n0 + row, gk = k0 + kk;
+      sB[kk][row] = (gr < d.N && gk < Ks) ? W[(size_t)gr * d.K + k_begin + gk] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < BK; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = sA[kk][ty * 4 + i]; b[i] = sB[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) epilogue_store<float>(d, split, m0 + ty * 4 + i, n0 + tx * 4 + j, acc[i][j]);
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+int gemm_pick_splits(int dtype, int M, int N, int K) {
+  if (M > 256) return 1;
+  const int unit = (dtype == BT_BF16) ? 64 : 16;
+  const int tiles = ((N + 63) / 64);
+  int best = 1;
+  for (int s = 1; s <= 16; ++s) {
+    if (K % s) continue;
+    const int ks = K / s;
+    if (ks % unit || ks < 2 * unit) continue;
+    best = s;
+    if (tiles * s >= 512) break;
+  }
+  return best;
+}
+
+template <int BM, int BN>
+static void fill_tiles(GemmGroup& g) {
+  int begin = 0;
+  for (int i = 0; i < g.n; ++i) {
+    g.p[i].tiles_m = (g.p[i].M + BM - 1) / BM;
+    g.p[i].tiles_n = (g.p[i].N + BN - 1) / BN;
+    g.p[i].tile_begin = begin;
+    begin += g.p[i].tiles_m * g.p[i].tiles_n * g.p[i].splits;
+  }
+}
+
+hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, hipStream_t s) {
+  if (n_probs < 1 || n_probs > 2) return hipErrorInvalidValue;
+  GemmGroup g;
+  g.n = n_probs;
+  int max_m = 0;
+  for (int i = 0; i < n_probs; ++i) {
+    const GemmProblem& p = probs[i];
+    if (p.M <= 0 || p.N <= 0 || p.K <= 0 || p.splits < 1 || p.K % p.splits) return hipErrorInvalidValue;
+    if (p.splits > 1 && p.epi != EPI_PARTIAL) return hipErrorInvalidValue;
+    if (dtype == BT_BF16 && ((p.K / p.splits) % 64 || p.lda % 8)) return hipErrorInvalidValue;
+    g.p[i].A = p.A; g.p[i].W = p.W; g.p[i].bias = p.bias; g.p[i].out = p.out;
+    g.p[i].M = p.M; g.p[i].N = p.N; g.p[i].K = p.K; g.p[i].lda = p.lda; g.p[i].ldo = p.ldo;
+    g.p[i].epi = p.epi; g.p[i].splits = p.splits;
+    max_m = p.M > max_m ? p.M : max_m;
+  }
+  auto total = [&]() {
+    const GemmDesc& l = g.p[g.n - 1];
+    return l.tile_begin + l.tiles_m * l.tiles_n * l.splits;
+  };
+  if (dtype == BT_F32) {
+    fill_tiles<64, 64>(g);
+    gemm_f32_kernel<<<total(), 256, 0, s>>>(g);
+  } else if (max_m > 256) {
+    fill_tiles<128, 128>(g);
+    gemm_bf16_kernel<128, 128, 2, 2><<<total(), 256, 0, s>>>(g);
+  } else {
+    fill_tiles<64, 64>(g);
+    gemm_bf16_kernel<64, 64, 1, 4><<<total(), 256, 0, s>>>(g);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace bt

@@ -1,0 +1,98 @@
+// Host-side launchers of the gfx950 kernels.  Every launcher enqueues on the
+// given stream and returns hipGetLastError().  `dtype` is BT_F32 or BT_BF16 and
+// selects the storage type of matrices, GEMM operands and KV caches.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace bt {
+
+// ---------------------------------------------------------------- elementwise
+// Embedder (Sec. 2.2): x[m, j*d_emb + e] = E_emb[tokens[m*L_B + j], e], float out.
+hipError_t launch_embed_concat(int dtype, const void* E_emb, const int32_t* tokens, float* x,
+                               int n_rows, int block_len, int d_emb, hipStream_t s);
+
+// Token-decoder input row: x[b, :] = E_tok[cur[b*L_B + r_prev], :], float out.
+hipError_t launch_token_embed(int dtype, const void* E_tok, const int32_t* cur, float* x,
+                              int batch, int block_len, int r_prev, int d_model, hipStream_t s);
+
+// Residual update + LayerNorm(s) of one row per workgroup.
+//   in row  = i * in_mul + in_off   (for x and the partial sums)
+//   x_new   = x + (biasA + sum_s partA[s]) + (biasB + sum_s partB[s])
+//   u1[i]   = LN(x_new; g1, b1)  (storage dtype, or float when u1_f32)
+//   u2[i]   = LN(x_new; g2, b2)  (optional)
+struct ResidLnArgs {
+  float* x;              // [*, D] residual stream (updated in place when write_x)
+  const float* partA;    // [splitsA][part_rows][D] or null
+  const float* biasA;
+  int splitsA;
+  const float* partB;
+  const float* biasB;
+  int splitsB;
+  size_t part_stride;    // elements between consecutive splits
+  const float *g1, *b1;
+  void* u1;
+  int u1_f32;
+  const float *g2, *b2;  // null: no second output
+  void* u2;
+  int n_rows, D, in_mul, in_off, write_x;
+  float eps;
+};
+hipError_t launch_resid_ln(int dtype, const ResidLnArgs& a, hipStream_t s);
+
+// Greedy argmax over logits [batch, vocab] (lowest index on ties); writes
+// next_ids[b] (if non-null) and cur[b*L_B + r].
+hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next_ids,
+                         int32_t* cur, int block_len, int r, hipStream_t s);
+
+hipError_t launch_scatter_ids(const int32_t* ids, int32_t* cur, int batch, int block_len, int r, hipStream_t s);
+
+// ----------------------------------------------------------------------- GEMM
+enum { EPI_F32 = 0,        // out float [M, ldo]: acc + bias
+       EPI_GELU = 1,       // out storage dtype: gelu(acc + bias)
+       EPI_PARTIAL = 2 };  // out float [splits][M][N]: raw partial sums (no bias)
+
+// out[M, N] = A[M, K] * W[N, K]^T (+ bias).  A, W in the storage dtype, row-major,
+// lda / K contiguous.  splits > 1 only with EPI_PARTIAL (K split in equal parts).
+struct GemmProblem {
+  const void* A;
+  const void* W;
+  const float* bias;
+  void* out;
+  int M, N, K, lda, ldo, epi, splits;
+};
+// Up to two independent problems in one launch.
+hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, hipStream_t s);
+// Heuristic: number of K splits for a partial-sum GEMM with M rows.
+int gemm_pick_splits(int dtype, int M, int N, int K);
+
+// ------------------------------------------------------------------ attention
+// Rotary tables: rope[pos * (rot/2) + t] = (cos, sin) of pos * 10000^(-2t/rot).
+//
+// Block decoder, after the QKV GEMM: rotate q in place (float, inside qkv),
+// rotate k, and store k, v into the block KV cache at position pos0 + m % n_new
+// of sequence m / n_new.  Cache layout per layer: K [B][H][n_cap][d_h], V same.
+hipError_t launch_rope_append(int dtype, float* qkv, void* Kc, void* Vc, const float2* rope,
+                              int n_rows, int n_new, int pos0, int n_heads, int d_head, int rot,
+                              int n_cap, hipStream_t s);
+
+// Block decoder decode step: one query per (b, h) over cache rows [0, n_keys).
+// q read from qkv[b, h*d_h ...] (row stride 3D); out [B, D] storage dtype.
+hipError_t launch_attn_block_decode(int dtype, const float* qkv, const void* Kc, const void* Vc,
+                                    void* out, int batch, int n_heads, int d_head, int n_keys,
+                                    int n_cap, hipStream_t s);
+
+// Block decoder prefill: causal attention of n_q queries per (b, h); query i sees rows [0, i].
+hipError_t launch_attn_block_prefill(int dtype, const float* qkv, const void* Kc, const void* Vc,
+                                     void* out, int batch, int n_heads, int d_head, int n_q,
+                                     int n_cap, hipStream_t s);
+
+// Token decoder: `rows` new local positions pos0 .. pos0+rows-1 per sequence.
+// Rotates q, k; appends k, v to the local cache [B][H][l_cap][d_h]; causal
+// attention over local rows [0, pos0+i]; out [B*rows, D] storage dtype.
+hipError_t launch_attn_local(int dtype, const float* qkv, void* Kl, void* Vl, const float2* rope,
+                             void* out, int batch, int n_heads, int d_head, int rot, int rows,
+                             int pos0, int l_cap, hipStream_t s);
+
+}  // namespace bt

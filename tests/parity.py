@@ -1,0 +1,52 @@
+"""GPU-vs-oracle parity protocol, shared by the GPU tests, smoke() and nothing else.
+
+The GPU free-runs greedy decoding through the C ABI; the oracle is
+teacher-forced on the ids the GPU emitted and produces float64 logits for the
+same history.  Logits must agree within `tol`; the GPU id must equal the
+oracle's argmax unless the oracle's top-2 margin is below `margin`.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def gpu_generate(model, prompts_np, n_new, want_logits=True):
+    """Run prefill + n_new decode steps.  Returns (ids [B, n_new], logits [B, n_new, V] or None)."""
+    import torch
+    toks = torch.from_numpy(np.ascontiguousarray(prompts_np, dtype=np.int32)).to(model.device)
+    model.bt_prefill(toks)
+    ids, lgs = [], []
+    for _ in range(n_new):
+        ids.append(model.bt_decode_step().clone())
+        if want_logits:
+            lgs.append(model.bt_get_logits())
+    torch.cuda.synchronize()
+    ids = torch.stack(ids, 1).cpu().numpy()
+    lgs = torch.stack(lgs, 1).cpu().numpy() if want_logits else None
+    return ids, lgs
+
+
+def compare_with_oracle(cfg, weights, prompts_np, gpu_ids, gpu_logits, tol, margin=2e-2, seqs=None):
+    """Teacher-force the cached oracle on gpu_ids; returns a report dict and asserts nothing."""
+    import oracle.block_transformer as O
+    sel = list(range(prompts_np.shape[0])) if seqs is None else list(seqs)
+    P = O.Params(weights)
+    n_new = gpu_ids.shape[1]
+    _, o_logits, _ = O.generate_cached(P, cfg, prompts_np[sel], n_new, forced=gpu_ids[sel])
+    diff = np.abs(gpu_logits[sel].astype(np.float64) - o_logits)
+    srt = np.sort(o_logits, axis=-1)
+    o_margin = srt[..., -1] - srt[..., -2] if o_logits.shape[-1] > 1 else np.full(o_logits.shape[:2], np.inf)
+    o_ids = np.argmax(o_logits, axis=-1)
+    mism = gpu_ids[sel] != o_ids
+    return {
+        "max_abs_logit_diff": float(diff.max()),
+        "steps": int(mism.size),
+        "exempt_mismatches": int(np.sum(mism & (o_margin < margin))),
+        "true_mismatches": int(np.sum(mism & (o_margin >= margin))),
+        "tol": tol,
+    }
+
+
+def assert_parity(rep):
+    assert rep["max_abs_logit_diff"] <= rep["tol"], rep
+    assert rep["true_mismatches"] == 0, rep
