@@ -1,0 +1,175 @@
+"""Benchmark of the Block Transformer generation path on one MI355X.
+
+One "step" is one whole generation job of the workload: prefill of the batch
+of prompts plus all decode steps (embedder, block decoder over the block KV
+cache once per L_B tokens, prefix projection, token decoder, LM head, argmax).
+Inputs are synthetic and already resident in HBM when the timed region starts.
+Prints ONE JSON line on stdout; everything else goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(cfg, W, prompts, decode_steps=16):
+    """The oracle as it stands, timed on the host: full-batch prefill + a few decode steps."""
+    import numpy as np
+    import oracle.block_transformer as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    P = O.Params(W)
+    gen = O.CachedGenerator(P, cfg, prompts.shape[0], cfg.max_blocks)
+    t0 = time.perf_counter()
+    gen.prefill(prompts)
+    t1 = time.perf_counter()
+    gen.step()                      # first step also widens the token-decoder weights: not timed
+    t2 = time.perf_counter()
+    for _ in range(decode_steps):
+        gen.step()
+    t3 = time.perf_counter()
+    per_step = (t3 - t2) / decode_steps
+    total = (t1 - t0) + per_step * cfg.gen_len
+    return {
+        "value": prompts.shape[0] * cfg.gen_len / total, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"{cfg.name}: prefill of the full batch ({t1 - t0:.2f} s, includes widening weights to f64) + "
+                  f"{decode_steps} decode steps of the full batch ({per_step * 1e3:.1f} ms/step); "
+                  f"decode time scaled to {cfg.gen_len} steps",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg1", help="cfg1 (decode-heavy, the headline), cfg2, cfg3, cfg4, cfg4v, cfg0")
+    ap.add_argument("--gen-len", type=int, default=0, help="override the number of generated tokens (0 = the workload's)")
+    ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-attn-events", action="store_true", help="do not bracket block-attention launches with HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (the path shards by batch with no exchange; "
+            "see DESIGN.md); --gpus must be 1")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from synth import CONFIGS, make_prompts, make_weights
+    import paper_2406_02657_amd as amd
+
+    cfg = CONFIGS[args.workload]
+    if args.gen_len:
+        cfg = cfg.with_(gen_len=args.gen_len)
+    if args.batch:
+        cfg = cfg.with_(batch=args.batch)
+    log(f"workload {cfg.name}: B={cfg.batch} prompt={cfg.prompt_len} gen={cfg.gen_len} L_B={cfg.block_len} "
+        f"D={cfg.d_model} layers={cfg.n_block_layers}+{cfg.n_token_layers} P={cfg.prefix_len} dtype={cfg.dtype}")
+    t0 = time.perf_counter()
+    W = make_weights(cfg)
+    prompts = make_prompts(cfg)
+    log(f"inputs generated in {time.perf_counter() - t0:.1f} s")
+    model = amd.Model(cfg, W)
+    toks = torch.from_numpy(prompts).cuda()
+    out_ids = torch.empty(cfg.gen_len, cfg.batch, dtype=torch.int32, device="cuda")
+    log(f"workspace {model.workspace_bytes / 2**30:.2f} GiB")
+
+    def job():
+        model.bt_prefill(toks)
+        for t in range(cfg.gen_len):
+            model.bt_decode_step(out_ids[t])
+
+    def timed_job():
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record()
+        model.bt_prefill(toks)
+        ev[1].record()
+        for t in range(cfg.gen_len):
+            model.bt_decode_step(out_ids[t])
+        ev[2].record()
+        return ev
+
+    for _ in range(args.warmup):
+        job()
+    torch.cuda.synchronize()
+    model.bt_set_profile(not args.no_attn_events)
+    model.bt_reset_profile()
+    evs = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        evs.append(timed_job())
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    st = model.bt_get_stats()
+    model.bt_set_profile(False)
+    ms_per_step = wall * 1e3 / args.steps
+    prefill_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    decode_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    value = cfg.batch * cfg.gen_len / (ms_per_step / 1e3)
+
+    roofline = None
+    if st.attn_block_launches > 0 and st.attn_block_ms > 0:
+        ach = st.attn_block_bytes / (st.attn_block_ms * 1e-3) / 1e9
+        roofline = {
+            "kernel": "attn_block_decode_kernel (block-decoder decode attention over the block KV cache)",
+            "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+            "traffic": None,
+            "launches": int(st.attn_block_launches),
+            "avg_launch_us": st.attn_block_ms * 1e3 / st.attn_block_launches,
+            "avg_bytes_per_launch": st.attn_block_bytes / st.attn_block_launches,
+        }
+    # whole decode step against the HBM roofline: algorithmic bytes per step (weights + block KV)
+    D, F, V, esz = cfg.d_model, cfg.d_ff, cfg.vocab, (2 if cfg.dtype == "bf16" else 4)
+    p_layer = 12 * D * D + 13 * D
+    w_tok = cfg.n_token_layers * p_layer * esz
+    w_blk = cfg.n_block_layers * p_layer * esz
+    w_head = V * D * esz
+    n_block_steps = -(-cfg.gen_len // cfg.block_len) - 1
+    n_p = cfg.prompt_len // cfg.block_len
+    kv_total = sum((n_p + k + 1) for k in range(n_block_steps)) * cfg.batch * cfg.n_block_layers * 2 * D * esz
+    alg_bytes_decode = cfg.gen_len * (w_tok + w_head) + n_block_steps * w_blk + kv_total
+    step_roof = {
+        "algorithmic_bytes_per_decode_step": alg_bytes_decode / cfg.gen_len,
+        "achieved_GBs": alg_bytes_decode / (decode_ms * 1e-3) / 1e9,
+        "frac_of_hbm_peak": alg_bytes_decode / (decode_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+    }
+    res = {
+        "metric": "output tokens/sec on 1 MI355X", "value": value, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: decode-heavy" if cfg.name in ("cfg1", "cfg3") else cfg.name,
+                   "batch": cfg.batch, "prompt_len": cfg.prompt_len, "gen_len": cfg.gen_len,
+                   "block_len": cfg.block_len, "d_model": cfg.d_model, "layers": [cfg.n_block_layers, cfg.n_token_layers],
+                   "prefix_len": cfg.prefix_len, "vocab": cfg.vocab},
+        "prefill_ms": prefill_ms, "decode_ms_per_token_step": decode_ms / cfg.gen_len,
+        "roofline": roofline, "decode_step_roofline": step_roof,
+    }
+    model.close()
+    del model
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        t0 = time.perf_counter()
+        res["cpu_baseline"] = cpu_baseline(cfg, W, prompts)
+        log(f"cpu baseline took {time.perf_counter() - t0:.1f} s")
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

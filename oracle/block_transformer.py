@@ -317,6 +317,7 @@ class CachedGenerator:
                     for _ in range(cfg.n_token_layers)]
         self.cur = np.zeros((batch, cfg.block_len), dtype=np.int64)   # tokens of the open block
         self.r = 0                      # tokens already generated in the open block
+        self.n_blocks = 0               # blocks pushed through the block decoder so far
         self.have_context = False
         self.c = None
         # counters for the statements the paper makes about the procedure
@@ -334,7 +335,7 @@ class CachedGenerator:
         for c in self.blk + self.loc:
             c.clear()
         ctx = block_decoder(self.P, cfg, embedder(self.P, cfg, prompts), 0, self.blk)
-        self.block_passes = T // cfg.block_len
+        self.block_passes = self.n_blocks = T // cfg.block_len
         self.c = ctx[:, -1]
         self.have_context = True
         self.r = 0
@@ -351,10 +352,11 @@ class CachedGenerator:
         P, cfg = self.P, self.cfg
         if self.r == 0:
             if not self.have_context:
-                n_before = self.blk[0].n
+                n_before = self.n_blocks
                 e = embedder(P, cfg, self.cur)
                 self.c = block_decoder(P, cfg, e, n_before, self.blk)[:, -1]
                 self.block_passes += 1
+                self.n_blocks += 1
                 self.block_kv_rows_read += n_before + 1
             for c in self.loc:
                 c.clear()
