@@ -168,7 +168,28 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
   const float2* rope = m->at<float2>(L.rope);
   hipStream_t s = m->stream;
   const int M = a.M;
-  const int sO = gemm_pick_splits(dt, M, D, D), sD = gemm_pick_splits(dt, M, D, F);
+  // GEMM problems of one layer (pointers to weights filled per layer) and their plans
+  GemmProblem pq{u1, nullptr, nullptr, qkv, M, 3 * D, D, D, 3 * D, EPI_F32};
+  GemmProblem pu{nullptr, nullptr, nullptr, hmid, M, F, D, D, F, EPI_GELU};
+  GemmProblem po{ao, nullptr, nullptr, part_o, M, D, D, D, D, EPI_PARTIAL};
+  GemmProblem pd{hmid, nullptr, nullptr, part_d, M, D, F, F, D, EPI_PARTIAL};
+  pu.A = c.parallel_residual ? u2 : u1;
+  GemmPlan plan_in{}, plan_out{}, plan_q{}, plan_u{}, plan_o{}, plan_d{};
+  int sO, sD;
+  if (c.parallel_residual) {
+    GemmProblem gi[2] = {pq, pu}, go[2] = {po, pd};
+    BT_HIP(m, gemm_plan(dt, gi, 2, &plan_in));
+    BT_HIP(m, gemm_plan(dt, go, 2, &plan_out));
+    sO = plan_out.splits[0];
+    sD = plan_out.splits[1];
+  } else {
+    BT_HIP(m, gemm_plan(dt, &pq, 1, &plan_q));
+    BT_HIP(m, gemm_plan(dt, &pu, 1, &plan_u));
+    BT_HIP(m, gemm_plan(dt, &po, 1, &plan_o));
+    BT_HIP(m, gemm_plan(dt, &pd, 1, &plan_d));
+    sO = plan_o.splits[0];
+    sD = plan_d.splits[0];
+  }
   if ((size_t)sO * M * D > L.part_elems || (size_t)sD * M * D > L.part_elems)
     return fail(m, BT_ERR_CAPACITY, "split-K partial buffer too small");
 
@@ -235,14 +256,14 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
   if (c.parallel_residual) {
     if ((rc = ln(nullptr, nullptr, 0, nullptr, nullptr, 0, lw[0].ln1_g, lw[0].ln1_b, lw[0].ln2_g, lw[0].ln2_b))) return rc;
     for (int l = 0; l < n_layers; ++l) {
-      GemmProblem p[2];
-      p[0] = GemmProblem{u1, lw[l].W_qkv, (const float*)lw[l].b_qkv, qkv, M, 3 * D, D, D, 3 * D, EPI_F32, 1};
-      p[1] = GemmProblem{u2, lw[l].W_up, (const float*)lw[l].b_up, hmid, M, F, D, D, F, EPI_GELU, 1};
-      BT_HIP(m, launch_gemm(dt, p, 2, s));
+      GemmProblem p[2] = {pq, pu};
+      p[0].W = lw[l].W_qkv; p[0].bias = (const float*)lw[l].b_qkv;
+      p[1].W = lw[l].W_up;  p[1].bias = (const float*)lw[l].b_up;
+      BT_HIP(m, launch_gemm(dt, p, 2, plan_in, s));
       if ((rc = attention(l))) return rc;
-      p[0] = GemmProblem{ao, lw[l].W_o, nullptr, part_o, M, D, D, D, D, EPI_PARTIAL, sO};
-      p[1] = GemmProblem{hmid, lw[l].W_down, nullptr, part_d, M, D, F, F, D, EPI_PARTIAL, sD};
-      BT_HIP(m, launch_gemm(dt, p, 2, s));
+      p[0] = po; p[0].W = lw[l].W_o;
+      p[1] = pd; p[1].W = lw[l].W_down;
+      BT_HIP(m, launch_gemm(dt, p, 2, plan_out, s));
       if (l + 1 < n_layers) {
         if ((rc = ln(part_o, (const float*)lw[l].b_o, sO, part_d, (const float*)lw[l].b_down, sD,
                      lw[l + 1].ln1_g, lw[l + 1].ln1_b, lw[l + 1].ln2_g, lw[l + 1].ln2_b))) return rc;
@@ -254,17 +275,17 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
   } else {
     if ((rc = ln(nullptr, nullptr, 0, nullptr, nullptr, 0, lw[0].ln1_g, lw[0].ln1_b, nullptr, nullptr))) return rc;
     for (int l = 0; l < n_layers; ++l) {
-      GemmProblem p;
-      p = GemmProblem{u1, lw[l].W_qkv, (const float*)lw[l].b_qkv, qkv, M, 3 * D, D, D, 3 * D, EPI_F32, 1};
-      BT_HIP(m, launch_gemm(dt, &p, 1, s));
+      GemmProblem p = pq;
+      p.W = lw[l].W_qkv; p.bias = (const float*)lw[l].b_qkv;
+      BT_HIP(m, launch_gemm(dt, &p, 1, plan_q, s));
       if ((rc = attention(l))) return rc;
-      p = GemmProblem{ao, lw[l].W_o, nullptr, part_o, M, D, D, D, D, EPI_PARTIAL, sO};
-      BT_HIP(m, launch_gemm(dt, &p, 1, s));
+      p = po; p.W = lw[l].W_o;
+      BT_HIP(m, launch_gemm(dt, &p, 1, plan_o, s));
       if ((rc = ln(part_o, (const float*)lw[l].b_o, sO, nullptr, nullptr, 0, lw[l].ln2_g, lw[l].ln2_b, nullptr, nullptr))) return rc;
-      p = GemmProblem{u1, lw[l].W_up, (const float*)lw[l].b_up, hmid, M, F, D, D, F, EPI_GELU, 1};
-      BT_HIP(m, launch_gemm(dt, &p, 1, s));
-      p = GemmProblem{hmid, lw[l].W_down, nullptr, part_d, M, D, F, F, D, EPI_PARTIAL, sD};
-      BT_HIP(m, launch_gemm(dt, &p, 1, s));
+      p = pu; p.W = lw[l].W_up; p.bias = (const float*)lw[l].b_up;
+      BT_HIP(m, launch_gemm(dt, &p, 1, plan_u, s));
+      p = pd; p.W = lw[l].W_down;
+      BT_HIP(m, launch_gemm(dt, &p, 1, plan_d, s));
       if (l + 1 < n_layers) {
         if ((rc = ln(nullptr, nullptr, 0, part_d, (const float*)lw[l].b_down, sD, lw[l + 1].ln1_g, lw[l + 1].ln1_b, nullptr, nullptr))) return rc;
       } else {
@@ -408,8 +429,10 @@ int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
     }
     if (c.prefix_len > 0) {
       GemmProblem p{m->ws + L.ctx, m->w.W_prefix, (const float*)m->w.b_prefix, x, B, c.prefix_len * D, D, D,
-                    c.prefix_len * D, EPI_F32, 1};
-      BT_HIP(m, launch_gemm(c.dtype, &p, 1, s));
+                    c.prefix_len * D, EPI_F32};
+      GemmPlan pl{};
+      BT_HIP(m, gemm_plan(c.dtype, &p, 1, &pl));
+      BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));
     } else {
       BT_HIP(m, hipMemcpyAsync(x, m->ws + L.ctx, (size_t)B * D * 4, hipMemcpyDeviceToDevice, s));
     }
@@ -425,8 +448,10 @@ int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
   int rc = run_stack(m, m->tok.data(), c.n_token_layers, a, m->w.tok_lnf_g, m->w.tok_lnf_b,
                      m->ws + L.hfin, 0, B, rows, rows - 1);
   if (rc) return rc;
-  GemmProblem p{m->ws + L.hfin, m->w.W_head, nullptr, m->ws + L.logits, B, c.vocab, D, D, c.vocab, EPI_F32, 1};
-  BT_HIP(m, launch_gemm(c.dtype, &p, 1, s));
+  GemmProblem p{m->ws + L.hfin, m->w.W_head, nullptr, m->ws + L.logits, B, c.vocab, D, D, c.vocab, EPI_F32};
+  GemmPlan pl{};
+  BT_HIP(m, gemm_plan(c.dtype, &p, 1, &pl));
+  BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));
   BT_HIP(m, launch_argmax(m->at<float>(L.logits), B, c.vocab, next_ids_dev, cur, c.block_len, m->r, s));
   m->st.token_passes += 1;
   m->st.token_rows += rows;

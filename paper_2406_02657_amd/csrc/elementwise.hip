@@ -100,11 +100,13 @@ __global__ __launch_bounds__(kLnThreads) void resid_ln_kernel(ResidLnArgs a) {
       acc = xr[d];
       if (a.partA) {
         float t = a.biasA ? a.biasA[d] : 0.f;
+#pragma unroll 4
         for (int s = 0; s < a.splitsA; ++s) t += a.partA[(size_t)s * a.part_stride + row * D + d];
         acc += t;
       }
       if (a.partB) {
         float t = a.biasB ? a.biasB[d] : 0.f;
+#pragma unroll 4
         for (int s = 0; s < a.splitsB; ++s) t += a.partB[(size_t)s * a.part_stride + row * D + d];
         acc += t;
       }
@@ -146,32 +148,46 @@ hipError_t launch_resid_ln(int dtype, const ResidLnArgs& a, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------
-// Greedy argmax, lowest index on ties.  One workgroup per sequence.
+// Greedy argmax, lowest index on ties.  One workgroup of 1024 threads per
+// sequence; each thread scans 16-byte groups of logits (all loads independent),
+// then wave shuffles and one pass over the 16 wave results.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int vocab,
-                                                     int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
-                                                     int block_len, int r) {
-  __shared__ float sv[4];
-  __shared__ int si[4];
+__device__ __forceinline__ void argmax_take(float v, int i, float& best, int& bi) {
+  if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+}
+
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int vocab,
+                                                      int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
+                                                      int block_len, int r) {
+  __shared__ float sv[16];
+  __shared__ int si[16];
   const int b = blockIdx.x;
   const float* lg = logits + (size_t)b * vocab;
   float best = -INFINITY;
   int bi = 0x7fffffff;
-  for (int v = threadIdx.x; v < vocab; v += 256) {
-    const float x = lg[v];
-    if (x > best || bi == 0x7fffffff) { best = x; bi = v; }   // ascending v: first maximum kept
+  if ((vocab & 3) == 0) {
+    const float4* lg4 = reinterpret_cast<const float4*>(lg);
+    for (int g = threadIdx.x; g < vocab / 4; g += 1024) {
+      const float4 q = lg4[g];
+      argmax_take(q.x, 4 * g, best, bi);
+      argmax_take(q.y, 4 * g + 1, best, bi);
+      argmax_take(q.z, 4 * g + 2, best, bi);
+      argmax_take(q.w, 4 * g + 3, best, bi);
+    }
+  } else {
+    for (int v = threadIdx.x; v < vocab; v += 1024) argmax_take(lg[v], v, best, bi);
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     const float ov = __shfl_xor(best, o, kWave);
     const int oi = __shfl_xor(bi, o, kWave);
-    if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+    argmax_take(ov, oi, best, bi);
   }
   if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = best; si[threadIdx.x >> 6] = bi; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    for (int w = 1; w < 4; ++w)
-      if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
+    for (int w = 1; w < 16; ++w) argmax_take(sv[w], si[w], best, bi);
+    if (bi == 0x7fffffff) bi = 0;           // every logit was NaN or -inf
     if (next_ids) next_ids[b] = bi;
     cur[b * block_len + r] = bi;
   }
@@ -179,7 +195,7 @@ __global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ l
 
 hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next_ids,
                          int32_t* cur, int block_len, int r, hipStream_t s) {
-  argmax_kernel<<<batch, 256, 0, s>>>(logits, vocab, next_ids, cur, block_len, r);
+  argmax_kernel<<<batch, 1024, 0, s>>>(logits, vocab, next_ids, cur, block_len, r);
   return hipGetLastError();
 }
 

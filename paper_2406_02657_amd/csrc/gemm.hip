@@ -199,12 +199,72 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmGroup g) {
 }
 
 // ---------------------------------------------------------------------------
+// bf16 weight-streaming kernel for skinny problems (M <= 256: decode steps).
+// These GEMMs are bound by reading W once from HBM, so the design goal is bytes
+// in flight, not MFMA rate: a workgroup owns 16 output columns and a K chunk of
+// 4 * 32 * NKF; each of its 4 waves takes a quarter of the chunk and issues all
+// of its W fragment loads (NKF x 16 bytes per lane) before anything else.  The
+// activations (small, L2-resident) are read straight into MFMA fragments.  The
+// four waves' partial tiles meet in LDS, then bias / GELU / partial store.
+// ---------------------------------------------------------------------------
+template <int NKF>
+__global__ __launch_bounds__(256) void gemm_stream_kernel(GemmGroup g) {
+  constexpr int KW = 32 * NKF;                       // k range of one wave
+  __shared__ float red[4][64 * 16];
+  const int bid = blockIdx.x;
+  const GemmDesc& d = (g.n > 1 && bid >= g.p[1].tile_begin) ? g.p[1] : g.p[0];
+  const int t = bid - d.tile_begin;
+  const int split = t / d.tiles_n, tn = t - split * d.tiles_n;
+  const int n0 = tn * 16;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int k0 = split * 4 * KW + wave * KW + (lane >> 4) * 8;
+  const uint16_t* A = reinterpret_cast<const uint16_t*>(d.A);
+  const uint16_t* W = reinterpret_cast<const uint16_t*>(d.W);
+
+  bf16x8_t wf[NKF];
+  {
+    const uint16_t* wp = W + (size_t)min(n0 + (lane & 15), d.N - 1) * d.K + k0;
+#pragma unroll
+    for (int kf = 0; kf < NKF; ++kf) wf[kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wp + kf * 32));
+  }
+  for (int m0 = 0; m0 < d.M; m0 += 64) {
+    f32x4_t acc[4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+      acc[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      if (m0 + mt * 16 < d.M) {
+        const uint16_t* ap = A + (size_t)min(m0 + mt * 16 + (lane & 15), d.M - 1) * d.lda + k0;
+        bf16x8_t af[NKF];
+#pragma unroll
+        for (int kf = 0; kf < NKF; ++kf) af[kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(ap + kf * 32));
+#pragma unroll
+        for (int kf = 0; kf < NKF; ++kf) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[kf], wf[kf], acc[mt], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) red[wave][(mt * 16 + (lane >> 4) * 4 + r) * 16 + (lane & 15)] = acc[mt][r];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int o = tid + i * 256;
+      const float sum = red[0][o] + red[1][o] + red[2][o] + red[3][o];
+      epilogue_store<bf16_t>(d, split, m0 + (o >> 4), n0 + (o & 15), sum);
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
-int gemm_pick_splits(int dtype, int M, int N, int K) {
-  if (M > 256) return 1;
-  const int unit = (dtype == BT_BF16) ? 64 : 16;
-  const int tiles = ((N + 63) / 64);
+namespace {
+enum { KIND_F32 = 0, KIND_TILE128 = 1, KIND_TILE64 = 2, KIND_STREAM = 3 };
+constexpr int kMaxSkinnyRows = 256;
+
+int tile64_splits(int unit, int N, int K) {
+  const int tiles = (N + 63) / 64;
   int best = 1;
   for (int s = 1; s <= 16; ++s) {
     if (K % s) continue;
@@ -215,9 +275,52 @@ int gemm_pick_splits(int dtype, int M, int N, int K) {
   }
   return best;
 }
+}  // namespace
+
+hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan* plan) {
+  if (n_probs < 1 || n_probs > 2 || !plan) return hipErrorInvalidValue;
+  int max_m = 0;
+  for (int i = 0; i < n_probs; ++i) {
+    const GemmProblem& p = probs[i];
+    if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
+    if (dtype == BT_BF16 && (p.K % 64 || p.lda % 8)) return hipErrorInvalidValue;
+    max_m = p.M > max_m ? p.M : max_m;
+    plan->splits[i] = 1;
+  }
+  plan->nkf = 0;
+  if (dtype == BT_F32) {
+    plan->kind = KIND_F32;
+    if (max_m <= kMaxSkinnyRows)
+      for (int i = 0; i < n_probs; ++i)
+        if (probs[i].epi == EPI_PARTIAL) plan->splits[i] = tile64_splits(16, probs[i].N, probs[i].K);
+    return hipSuccess;
+  }
+  if (max_m > kMaxSkinnyRows) { plan->kind = KIND_TILE128; return hipSuccess; }
+  // streaming kernel: one NKF for the whole group; full-K problems need K == 128*NKF
+  static const int cand[] = {16, 12, 8, 6, 4, 2};
+  for (int c : cand) {
+    bool ok = true;
+    for (int i = 0; i < n_probs && ok; ++i) {
+      const GemmProblem& p = probs[i];
+      if (p.K % (128 * c)) ok = false;
+      else if (p.epi != EPI_PARTIAL && p.K != 128 * c) ok = false;
+      else if (p.K / (128 * c) > 16) ok = false;
+    }
+    if (ok) {
+      plan->kind = KIND_STREAM;
+      plan->nkf = c;
+      for (int i = 0; i < n_probs; ++i) plan->splits[i] = probs[i].K / (128 * c);
+      return hipSuccess;
+    }
+  }
+  plan->kind = KIND_TILE64;
+  for (int i = 0; i < n_probs; ++i)
+    if (probs[i].epi == EPI_PARTIAL) plan->splits[i] = tile64_splits(64, probs[i].N, probs[i].K);
+  return hipSuccess;
+}
 
 template <int BM, int BN>
-static void fill_tiles(GemmGroup& g) {
+static int fill_tiles(GemmGroup& g) {
   int begin = 0;
   for (int i = 0; i < g.n; ++i) {
     g.p[i].tiles_m = (g.p[i].M + BM - 1) / BM;
@@ -225,36 +328,46 @@ static void fill_tiles(GemmGroup& g) {
     g.p[i].tile_begin = begin;
     begin += g.p[i].tiles_m * g.p[i].tiles_n * g.p[i].splits;
   }
+  return begin;
 }
 
-hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, hipStream_t s) {
+hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const GemmPlan& plan, hipStream_t s) {
   if (n_probs < 1 || n_probs > 2) return hipErrorInvalidValue;
   GemmGroup g;
   g.n = n_probs;
-  int max_m = 0;
   for (int i = 0; i < n_probs; ++i) {
     const GemmProblem& p = probs[i];
-    if (p.M <= 0 || p.N <= 0 || p.K <= 0 || p.splits < 1 || p.K % p.splits) return hipErrorInvalidValue;
-    if (p.splits > 1 && p.epi != EPI_PARTIAL) return hipErrorInvalidValue;
-    if (dtype == BT_BF16 && ((p.K / p.splits) % 64 || p.lda % 8)) return hipErrorInvalidValue;
+    const int sp = plan.splits[i];
+    if (sp < 1 || p.K % sp || (sp > 1 && p.epi != EPI_PARTIAL)) return hipErrorInvalidValue;
     g.p[i].A = p.A; g.p[i].W = p.W; g.p[i].bias = p.bias; g.p[i].out = p.out;
     g.p[i].M = p.M; g.p[i].N = p.N; g.p[i].K = p.K; g.p[i].lda = p.lda; g.p[i].ldo = p.ldo;
-    g.p[i].epi = p.epi; g.p[i].splits = p.splits;
-    max_m = p.M > max_m ? p.M : max_m;
+    g.p[i].epi = p.epi; g.p[i].splits = sp;
   }
-  auto total = [&]() {
-    const GemmDesc& l = g.p[g.n - 1];
-    return l.tile_begin + l.tiles_m * l.tiles_n * l.splits;
-  };
-  if (dtype == BT_F32) {
-    fill_tiles<64, 64>(g);
-    gemm_f32_kernel<<<total(), 256, 0, s>>>(g);
-  } else if (max_m > 256) {
-    fill_tiles<128, 128>(g);
-    gemm_bf16_kernel<128, 128, 2, 2><<<total(), 256, 0, s>>>(g);
-  } else {
-    fill_tiles<64, 64>(g);
-    gemm_bf16_kernel<64, 64, 1, 4><<<total(), 256, 0, s>>>(g);
+  switch (plan.kind) {
+    case KIND_F32:
+      gemm_f32_kernel<<<fill_tiles<64, 64>(g), 256, 0, s>>>(g);
+      break;
+    case KIND_TILE128:
+      gemm_bf16_kernel<128, 128, 2, 2><<<fill_tiles<128, 128>(g), 256, 0, s>>>(g);
+      break;
+    case KIND_TILE64:
+      gemm_bf16_kernel<64, 64, 1, 4><<<fill_tiles<64, 64>(g), 256, 0, s>>>(g);
+      break;
+    case KIND_STREAM: {
+      const int grid = fill_tiles<1 << 30, 16>(g);      // tiles_m == 1: the kernel loops over rows
+      switch (plan.nkf) {
+        case 2:  gemm_stream_kernel<2><<<grid, 256, 0, s>>>(g); break;
+        case 4:  gemm_stream_kernel<4><<<grid, 256, 0, s>>>(g); break;
+        case 6:  gemm_stream_kernel<6><<<grid, 256, 0, s>>>(g); break;
+        case 8:  gemm_stream_kernel<8><<<grid, 256, 0, s>>>(g); break;
+        case 12: gemm_stream_kernel<12><<<grid, 256, 0, s>>>(g); break;
+        case 16: gemm_stream_kernel<16><<<grid, 256, 0, s>>>(g); break;
+        default: return hipErrorInvalidValue;
+      }
+      break;
+    }
+    default:
+      return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }

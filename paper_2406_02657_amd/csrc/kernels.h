@@ -54,18 +54,23 @@ enum { EPI_F32 = 0,        // out float [M, ldo]: acc + bias
        EPI_PARTIAL = 2 };  // out float [splits][M][N]: raw partial sums (no bias)
 
 // out[M, N] = A[M, K] * W[N, K]^T (+ bias).  A, W in the storage dtype, row-major,
-// lda / K contiguous.  splits > 1 only with EPI_PARTIAL (K split in equal parts).
+// lda / K contiguous.
 struct GemmProblem {
   const void* A;
   const void* W;
   const float* bias;
   void* out;
-  int M, N, K, lda, ldo, epi, splits;
+  int M, N, K, lda, ldo, epi;
 };
+// Which kernel serves a group of up to two problems, and into how many equal K
+// parts each EPI_PARTIAL problem is split (others: 1).  Depends on shapes only.
+struct GemmPlan {
+  int kind, nkf;
+  int splits[2];
+};
+hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan* plan);
 // Up to two independent problems in one launch.
-hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, hipStream_t s);
-// Heuristic: number of K splits for a partial-sum GEMM with M rows.
-int gemm_pick_splits(int dtype, int M, int N, int K);
+hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const GemmPlan& plan, hipStream_t s);
 
 // ------------------------------------------------------------------ attention
 // Rotary tables: rope[pos * (rot/2) + t] = (cos, sin) of pos * 10000^(-2t/rot).

@@ -98,6 +98,16 @@ def test_bf16_small(amd, lb, p, par):
     run_case(amd, cfg, 3 * lb + 2, batch=5)
 
 
+@pytest.mark.parametrize("d,h,f,b,p,lb", [(256, 4, 1024, 5, 1, 4), (768, 12, 3072, 70, 2, 4), (512, 4, 2048, 33, 1, 2),
+                                           (1024, 8, 4096, 17, 1, 1)])
+def test_bf16_streaming_gemm_shapes(amd, d, h, f, b, p, lb):
+    """Model widths served by the weight-streaming decode GEMM (K a multiple of 256), with row
+    counts that leave ragged 16-row and 64-row tiles."""
+    cfg = tiny_cfg(dtype="bf16", block_len=lb, prefix_len=p, d_model=d, n_heads=h, d_ff=f, vocab=1000,
+                   prompt_len=4 * lb, n_block_layers=2, n_token_layers=2)
+    run_case(amd, cfg, 2 * lb + 1, batch=b)
+
+
 def test_bf16_ragged_tiles(amd):
     """Batch, vocab and row counts that do not fill the GEMM tiles; prompt long enough to span
     several attention chunks and prefill chunks (prefill_rows forces chunking over the batch)."""
