@@ -73,6 +73,8 @@ typedef struct {
   int32_t rotary_dims;      /* per head, even; 0 = no position rotation */
   int32_t parallel_residual;/* 1: x + Attn(LN1 x) + MLP(LN2 x); 0: sequential */
   int32_t prefill_rows;     /* prompt blocks processed per prefill chunk; 0 = default (16384) */
+  int32_t act_split;        /* bf16 mode only: activations enter the MFMA GEMMs as hi + lo bf16 pairs
+                               (about 16 mantissa bits): 0 never, 1 in decode steps, 2 also in prefill */
   float   ln_eps;
 } bt_config;
 

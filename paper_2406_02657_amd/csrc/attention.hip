@@ -105,7 +105,7 @@ __device__ __forceinline__ void wave_attend(const float* q, const T* __restrict_
 template <class T, int DH, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(const float* __restrict__ qkv, const T* __restrict__ Kc,
                                                                     const T* __restrict__ Vc, T* __restrict__ out,
-                                                                    int n_heads, int n_keys, int n_cap) {
+                                                                    size_t out_lo_off, int n_heads, int n_keys, int n_cap) {
   using R = RowMap<T, DH>;
   constexpr int EPC = R::EPC, LPR = R::LPR;
   __shared__ float s_m[NW], s_l[NW];
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(const float*
       L += s_l[w] * f;
       o += s_acc[w][d] * f;
     }
-    out[(size_t)b * D + h * DH + d] = from_float<T>(o / L);
+    store_act<T>(out, (size_t)b * D + h * DH + d, out_lo_off, o / L);
   }
 }
 
@@ -154,7 +154,7 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(const float*
 template <class T, int DH>
 __global__ __launch_bounds__(256) void attn_block_prefill_kernel(const float* __restrict__ qkv, const T* __restrict__ Kc,
                                                                  const T* __restrict__ Vc, T* __restrict__ out,
-                                                                 int n_heads, int n_q, int n_cap) {
+                                                                 size_t out_lo_off, int n_heads, int n_q, int n_cap) {
   using R = RowMap<T, DH>;
   constexpr int EPC = R::EPC, LPR = R::LPR;
   const int bh = blockIdx.x;
@@ -179,7 +179,16 @@ __global__ __launch_bounds__(256) void attn_block_prefill_kernel(const float* __
     float o[EPC];
 #pragma unroll
     for (int e = 0; e < EPC; ++e) o[e] = acc[e] * inv;
-    *reinterpret_cast<uint4*>(out + row * D + h * DH + sub * EPC) = Chunk<T>::pack(o);
+    T* dst = out + row * D + h * DH + sub * EPC;
+    const uint4 hi = Chunk<T>::pack(o);
+    *reinterpret_cast<uint4*>(dst) = hi;
+    if (out_lo_off) {
+      float back[EPC];
+      Chunk<T>::unpack(hi, back);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) o[e] -= back[e];
+      *reinterpret_cast<uint4*>(dst + out_lo_off) = Chunk<T>::pack(o);
+    }
   }
 }
 
@@ -224,8 +233,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(float* __restrict__ qk
 // ---------------------------------------------------------------------------
 template <class T, int DH>
 __global__ void attn_local_kernel(const float* __restrict__ qkv, T* __restrict__ Kl, T* __restrict__ Vl,
-                                  const float2* __restrict__ rope, T* __restrict__ out, int n_pairs, int n_heads,
-                                  int rot, int rows, int pos0, int l_cap) {
+                                  const float2* __restrict__ rope, T* __restrict__ out, size_t out_lo_off,
+                                  int n_pairs, int n_heads, int rot, int rows, int pos0, int l_cap) {
   extern __shared__ float smem[];
   constexpr int DPL = (DH + 63) / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -305,7 +314,7 @@ __global__ void attn_local_kernel(const float* __restrict__ qkv, T* __restrict__
 #pragma unroll
       for (int c = 0; c < DPL; ++c) {
         const int d = lane + 64 * c;
-        if (d < DH) out[row * D + h * DH + d] = from_float<T>(acc[c] / l);
+        if (d < DH) store_act<T>(out, row * D + h * DH + d, out_lo_off, acc[c] / l);
       }
     }
     __syncthreads();
@@ -335,38 +344,38 @@ hipError_t launch_rope_append(int dtype, float* qkv, void* Kc, void* Vc, const f
 }
 
 hipError_t launch_attn_block_decode(int dtype, const float* qkv, const void* Kc, const void* Vc,
-                                    void* out, int batch, int n_heads, int d_head, int n_keys,
+                                    void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_keys,
                                     int n_cap, hipStream_t s) {
   if (n_keys < 1 || n_keys > n_cap) return hipErrorInvalidValue;
   constexpr int NW = 4;
   const int grid = batch * n_heads;
   if (dtype == BT_F32) {
     BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<float, DH, NW><<<grid, NW * 64, 0, s>>>(
-        qkv, (const float*)Kc, (const float*)Vc, (float*)out, n_heads, n_keys, n_cap)));
+        qkv, (const float*)Kc, (const float*)Vc, (float*)out, 0, n_heads, n_keys, n_cap)));
   } else {
     BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<bf16_t, DH, NW><<<grid, NW * 64, 0, s>>>(
-        qkv, (const bf16_t*)Kc, (const bf16_t*)Vc, (bf16_t*)out, n_heads, n_keys, n_cap)));
+        qkv, (const bf16_t*)Kc, (const bf16_t*)Vc, (bf16_t*)out, out_lo_off, n_heads, n_keys, n_cap)));
   }
   return hipGetLastError();
 }
 
 hipError_t launch_attn_block_prefill(int dtype, const float* qkv, const void* Kc, const void* Vc,
-                                     void* out, int batch, int n_heads, int d_head, int n_q,
+                                     void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_q,
                                      int n_cap, hipStream_t s) {
   if (n_q < 1 || n_q > n_cap) return hipErrorInvalidValue;
   const dim3 grid(batch * n_heads, (n_q + 3) / 4);
   if (dtype == BT_F32) {
     BT_DISPATCH_DH(d_head, (attn_block_prefill_kernel<float, DH><<<grid, 256, 0, s>>>(
-        qkv, (const float*)Kc, (const float*)Vc, (float*)out, n_heads, n_q, n_cap)));
+        qkv, (const float*)Kc, (const float*)Vc, (float*)out, 0, n_heads, n_q, n_cap)));
   } else {
     BT_DISPATCH_DH(d_head, (attn_block_prefill_kernel<bf16_t, DH><<<grid, 256, 0, s>>>(
-        qkv, (const bf16_t*)Kc, (const bf16_t*)Vc, (bf16_t*)out, n_heads, n_q, n_cap)));
+        qkv, (const bf16_t*)Kc, (const bf16_t*)Vc, (bf16_t*)out, out_lo_off, n_heads, n_q, n_cap)));
   }
   return hipGetLastError();
 }
 
 hipError_t launch_attn_local(int dtype, const float* qkv, void* Kl, void* Vl, const float2* rope,
-                             void* out, int batch, int n_heads, int d_head, int rot, int rows,
+                             void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int rot, int rows,
                              int pos0, int l_cap, hipStream_t s) {
   if (rows < 1 || pos0 < 0 || pos0 + rows > l_cap) return hipErrorInvalidValue;
   const int n_pairs = batch * n_heads;
@@ -378,10 +387,10 @@ hipError_t launch_attn_local(int dtype, const float* qkv, void* Kl, void* Vl, co
   const size_t shm = per_wave * nw;
   if (dtype == BT_F32) {
     BT_DISPATCH_DH(d_head, (attn_local_kernel<float, DH><<<grid, nw * 64, shm, s>>>(
-        qkv, (float*)Kl, (float*)Vl, rope, (float*)out, n_pairs, n_heads, rot, rows, pos0, l_cap)));
+        qkv, (float*)Kl, (float*)Vl, rope, (float*)out, 0, n_pairs, n_heads, rot, rows, pos0, l_cap)));
   } else {
     BT_DISPATCH_DH(d_head, (attn_local_kernel<bf16_t, DH><<<grid, nw * 64, shm, s>>>(
-        qkv, (bf16_t*)Kl, (bf16_t*)Vl, rope, (bf16_t*)out, n_pairs, n_heads, rot, rows, pos0, l_cap)));
+        qkv, (bf16_t*)Kl, (bf16_t*)Vl, rope, (bf16_t*)out, out_lo_off, n_pairs, n_heads, rot, rows, pos0, l_cap)));
   }
   return hipGetLastError();
 }

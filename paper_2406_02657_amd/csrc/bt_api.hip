@@ -46,6 +46,7 @@ int check_config(const bt_config& c, std::string* why) {
   if (c.dtype == BT_BF16 && (c.d_model % 64 || c.d_ff % 64)) return bad("bf16 mode needs d_model, d_ff multiples of 64");
   if (c.d_ff % 8) return bad("d_ff must be a multiple of 8");
   if (c.prefill_rows < 0) return bad("prefill_rows < 0");
+  if (c.act_split < 0 || c.act_split > 2) return bad("act_split must be 0, 1 or 2");
   if (!(c.ln_eps >= 0.f)) return bad("ln_eps < 0");
   const int l_cap = (c.prefix_len > 0 ? c.prefix_len : 1) + c.block_len;
   if ((size_t)(2 * l_cap + 2) * dh * sizeof(float) > 60 * 1024) return bad("prefix_len + block_len too large for the local-attention kernel");
@@ -139,6 +140,7 @@ int final_ln(bt_model* m, const StackArgs& a, const float* pendO, const float* b
              const float* pendD, const float* biasD, int sD, const void* g, const void* b,
              void* out, int out_f32, int n, int in_mul, int in_off) {
   ResidLnArgs r{};
+  r.lo_off = (!out_f32 && m->cfg.dtype == BT_BF16 && m->cfg.act_split >= 1) ? (size_t)m->cfg.max_batch * m->cfg.d_model : 0;
   r.x = m->at<float>(m->L.x);
   r.partA = pendO; r.biasA = biasO; r.splitsA = sO;
   r.partB = pendD; r.biasB = biasD; r.splitsB = sD;
@@ -168,12 +170,17 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
   const float2* rope = m->at<float2>(L.rope);
   hipStream_t s = m->stream;
   const int M = a.M;
+  // bf16 mode: activations that feed GEMMs are kept as hi + remainder planes (see bt.h, act_split)
+  const bool split = dt == BT_BF16 && (c.act_split == 2 || (c.act_split == 1 && a.mode != MODE_BLOCK_PREFILL));
+  const size_t loD = split ? (size_t)L.m_rows * D : 0, loF = split ? (size_t)L.m_rows * F : 0;
+  auto lo = [&](void* p, size_t off) -> const void* { return off ? (const char*)p + off * 2 : nullptr; };
   // GEMM problems of one layer (pointers to weights filled per layer) and their plans
-  GemmProblem pq{u1, nullptr, nullptr, qkv, M, 3 * D, D, D, 3 * D, EPI_F32};
-  GemmProblem pu{nullptr, nullptr, nullptr, hmid, M, F, D, D, F, EPI_GELU};
-  GemmProblem po{ao, nullptr, nullptr, part_o, M, D, D, D, D, EPI_PARTIAL};
-  GemmProblem pd{hmid, nullptr, nullptr, part_d, M, D, F, F, D, EPI_PARTIAL};
+  GemmProblem pq{u1, nullptr, nullptr, qkv, M, 3 * D, D, D, 3 * D, EPI_F32, lo(u1, loD), 0};
+  GemmProblem pu{nullptr, nullptr, nullptr, hmid, M, F, D, D, F, EPI_GELU, nullptr, loF};
+  GemmProblem po{ao, nullptr, nullptr, part_o, M, D, D, D, D, EPI_PARTIAL, lo(ao, loD), 0};
+  GemmProblem pd{hmid, nullptr, nullptr, part_d, M, D, F, F, D, EPI_PARTIAL, lo(hmid, loF), 0};
   pu.A = c.parallel_residual ? u2 : u1;
+  pu.A_lo = lo(const_cast<void*>(pu.A), loD);
   GemmPlan plan_in{}, plan_out{}, plan_q{}, plan_u{}, plan_o{}, plan_d{};
   int sO, sD;
   if (c.parallel_residual) {
@@ -204,6 +211,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     r.g2 = (const float*)g2; r.b2 = (const float*)b2; r.u2 = u2;
     r.n_rows = M; r.D = D; r.in_mul = 1; r.in_off = 0; r.write_x = (pO || pD) ? 1 : 0;
     r.eps = c.ln_eps;
+    r.lo_off = loD;
     BT_HIP(m, launch_resid_ln(dt, r, s));
     return BT_OK;
   };
@@ -211,7 +219,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     if (a.mode == MODE_TOKEN) {
       char* base = m->ws + L.loc_kv + (size_t)l * L.loc_layer_stride;
       const size_t half = (size_t)c.max_batch * H * L.l_cap * dh * L.esz;
-      BT_HIP(m, launch_attn_local(dt, qkv, base, base + half, rope, ao, a.batch, H, dh, c.rotary_dims,
+      BT_HIP(m, launch_attn_local(dt, qkv, base, base + half, rope, ao, loD, a.batch, H, dh, c.rotary_dims,
                                   a.rows, a.pos0, L.l_cap, s));
       return BT_OK;
     }
@@ -222,7 +230,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     char* Vc = base + half + seq;
     BT_HIP(m, launch_rope_append(dt, qkv, Kc, Vc, rope, M, a.rows, a.pos0, H, dh, c.rotary_dims, c.max_blocks, s));
     if (a.mode == MODE_BLOCK_PREFILL) {
-      BT_HIP(m, launch_attn_block_prefill(dt, qkv, Kc, Vc, ao, a.batch, H, dh, a.rows, c.max_blocks, s));
+      BT_HIP(m, launch_attn_block_prefill(dt, qkv, Kc, Vc, ao, loD, a.batch, H, dh, a.rows, c.max_blocks, s));
     } else {
       const int n_keys = a.pos0 + 1;
       hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -239,7 +247,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
         m->ev_used += 2;
         BT_HIP(m, hipEventRecord(e0, s));
       }
-      BT_HIP(m, launch_attn_block_decode(dt, qkv, Kc, Vc, ao, a.batch, H, dh, n_keys, c.max_blocks, s));
+      BT_HIP(m, launch_attn_block_decode(dt, qkv, Kc, Vc, ao, loD, a.batch, H, dh, n_keys, c.max_blocks, s));
       if (m->profile) {
         BT_HIP(m, hipEventRecord(e1, s));
         m->st.attn_block_launches += 1;
@@ -413,6 +421,7 @@ int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
   int32_t* cur = m->at<int32_t>(L.cur);
   float* x = m->at<float>(L.x);
   const bool ctx_f32 = c.prefix_len == 0;
+  const size_t fin_lo = (c.dtype == BT_BF16 && c.act_split >= 1) ? (size_t)c.max_batch * D : 0;
   int rows, pos0;
   if (m->r == 0) {
     if (!m->have_context) {
@@ -429,7 +438,7 @@ int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
     }
     if (c.prefix_len > 0) {
       GemmProblem p{m->ws + L.ctx, m->w.W_prefix, (const float*)m->w.b_prefix, x, B, c.prefix_len * D, D, D,
-                    c.prefix_len * D, EPI_F32};
+                    c.prefix_len * D, EPI_F32, fin_lo ? m->ws + L.ctx + fin_lo * 2 : nullptr, 0};
       GemmPlan pl{};
       BT_HIP(m, gemm_plan(c.dtype, &p, 1, &pl));
       BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));
@@ -448,7 +457,8 @@ int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
   int rc = run_stack(m, m->tok.data(), c.n_token_layers, a, m->w.tok_lnf_g, m->w.tok_lnf_b,
                      m->ws + L.hfin, 0, B, rows, rows - 1);
   if (rc) return rc;
-  GemmProblem p{m->ws + L.hfin, m->w.W_head, nullptr, m->ws + L.logits, B, c.vocab, D, D, c.vocab, EPI_F32};
+  GemmProblem p{m->ws + L.hfin, m->w.W_head, nullptr, m->ws + L.logits, B, c.vocab, D, D, c.vocab, EPI_F32,
+                fin_lo ? m->ws + L.hfin + fin_lo * 2 : nullptr, 0};
   GemmPlan pl{};
   BT_HIP(m, gemm_plan(c.dtype, &p, 1, &pl));
   BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));
@@ -502,6 +512,9 @@ int bt_set_context(bt_model* m, const void* ctx_dev) {
   if (m->batch == 0) return fail(m, BT_ERR_STATE, "no prefill yet");
   const size_t esz = m->cfg.prefix_len == 0 ? 4 : m->L.esz;
   BT_HIP(m, hipMemcpyAsync(m->ws + m->L.ctx, ctx_dev, (size_t)m->batch * m->cfg.d_model * esz, hipMemcpyDeviceToDevice, m->stream));
+  if (m->cfg.prefix_len > 0 && m->cfg.dtype == BT_BF16 && m->cfg.act_split >= 1)   // remainder plane of an injected context is zero
+    BT_HIP(m, hipMemsetAsync(m->ws + m->L.ctx + (size_t)m->cfg.max_batch * m->cfg.d_model * 2, 0,
+                             (size_t)m->batch * m->cfg.d_model * 2, m->stream));
   return BT_OK;
 }
 

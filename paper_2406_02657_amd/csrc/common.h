@@ -56,6 +56,16 @@ template <> struct Chunk<bf16_t> {
   }
 };
 
+// Store an activation that will be a GEMM operand.  With lo_off != 0 (bf16 mode) the
+// value is kept as two bf16 numbers, hi at p[i] and the rounding remainder lo at
+// p[i + lo_off], so that hi + lo carries about 16 mantissa bits into the MFMAs.
+template <class T>
+__device__ __forceinline__ void store_act(T* p, size_t i, size_t lo_off, float v) {
+  const T hi = from_float<T>(v);
+  p[i] = hi;
+  if (lo_off) p[i + lo_off] = from_float<T>(v - to_float<T>(hi));
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

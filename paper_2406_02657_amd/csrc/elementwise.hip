@@ -133,8 +133,8 @@ __global__ __launch_bounds__(kLnThreads) void resid_ln_kernel(ResidLnArgs a) {
       const float n = (v[c] - mean) * rstd;
       const float o1 = n * a.g1[d] + a.b1[d];
       if (a.u1_f32) reinterpret_cast<float*>(a.u1)[(size_t)i * D + d] = o1;
-      else reinterpret_cast<T*>(a.u1)[(size_t)i * D + d] = from_float<T>(o1);
-      if (a.g2) reinterpret_cast<T*>(a.u2)[(size_t)i * D + d] = from_float<T>(n * a.g2[d] + a.b2[d]);
+      else store_act<T>(reinterpret_cast<T*>(a.u1), (size_t)i * D + d, a.lo_off, o1);
+      if (a.g2) store_act<T>(reinterpret_cast<T*>(a.u2), (size_t)i * D + d, a.lo_off, n * a.g2[d] + a.b2[d]);
     }
   }
 }

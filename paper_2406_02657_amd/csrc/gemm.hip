@@ -19,6 +19,8 @@ struct GemmDesc {
   const float* bias;
   void* out;
   int M, N, K, lda, ldo, epi, splits;
+  const void* A_lo;      // bf16 remainder plane of A (null: none)
+  size_t out_lo_off;     // EPI_GELU: != 0 writes the output as hi / remainder planes
   int tiles_m, tiles_n, tile_begin;   // tiles of this problem occupy blocks [tile_begin, tile_begin + tiles_m*tiles_n*splits)
 };
 struct GemmGroup {
@@ -36,7 +38,7 @@ __device__ __forceinline__ void epilogue_store(const GemmDesc& d, int split, int
   } else {
     if (d.bias) acc += d.bias[col];
     if (d.epi == EPI_F32) reinterpret_cast<float*>(d.out)[(size_t)row * d.ldo + col] = acc;
-    else reinterpret_cast<T*>(d.out)[(size_t)row * d.ldo + col] = from_float<T>(gelu_erf(acc));
+    else store_act<T>(reinterpret_cast<T*>(d.out), (size_t)row * d.ldo + col, d.out_lo_off, gelu_erf(acc));
   }
 }
 
@@ -45,7 +47,7 @@ __device__ __forceinline__ void epilogue_store(const GemmDesc& d, int split, int
 // BK = 64 per stage.  Global -> registers -> LDS with the next stage's loads in
 // flight while the current stage is multiplied.
 // ---------------------------------------------------------------------------
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, bool HL>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmGroup g) {
   constexpr int BK = 64;
   constexpr int LDS = BK + 8;                   // row stride in elements (pad against bank conflicts)
@@ -54,6 +56,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmGroup g) {
   constexpr int B_CH = BN * (BK / 8) / 256;
   static_assert(WM * WN == 4 && A_CH >= 1 && B_CH >= 1, "tile shape");
   __shared__ __attribute__((aligned(16))) uint16_t sA[BM * LDS];
+  __shared__ __attribute__((aligned(16))) uint16_t sAl[HL ? BM * LDS : 8];
   __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LDS];
 
   const int bid = blockIdx.x;
@@ -83,6 +86,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmGroup g) {
     a_ptr[i] = A + (size_t)gr * d.lda + k_begin + kc * 8;
     a_lds[i] = row * LDS + kc * 8;
   }
+  const ptrdiff_t lo_delta = HL ? reinterpret_cast<const uint16_t*>(d.A_lo) - A : 0;
 #pragma unroll
   for (int i = 0; i < B_CH; ++i) {
     const int c = tid + i * 256, row = c >> 3, kc = c & 7;
@@ -97,32 +101,42 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmGroup g) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  uint4 ra[A_CH], rb[B_CH];
+  uint4 ra[A_CH], rb[B_CH], rl[HL ? A_CH : 1];
 #pragma unroll
-  for (int i = 0; i < A_CH; ++i) ra[i] = *reinterpret_cast<const uint4*>(a_ptr[i]);
+  for (int i = 0; i < A_CH; ++i) {
+    ra[i] = *reinterpret_cast<const uint4*>(a_ptr[i]);
+    if constexpr (HL) rl[i] = *reinterpret_cast<const uint4*>(a_ptr[i] + lo_delta);
+  }
 #pragma unroll
   for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_ptr[i]);
 
   const int frag_row = lane & 15, frag_k = (lane >> 4) * 8;
   for (int kt = 0; kt < KT; ++kt) {
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4*>(&sA[a_lds[i]]) = ra[i];
+    for (int i = 0; i < A_CH; ++i) {
+      *reinterpret_cast<uint4*>(&sA[a_lds[i]]) = ra[i];
+      if constexpr (HL) *reinterpret_cast<uint4*>(&sAl[a_lds[i]]) = rl[i];
+    }
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4*>(&sB[b_lds[i]]) = rb[i];
     __syncthreads();
     if (kt + 1 < KT) {
 #pragma unroll
-      for (int i = 0; i < A_CH; ++i) ra[i] = *reinterpret_cast<const uint4*>(a_ptr[i] + (size_t)(kt + 1) * BK);
+      for (int i = 0; i < A_CH; ++i) {
+        ra[i] = *reinterpret_cast<const uint4*>(a_ptr[i] + (size_t)(kt + 1) * BK);
+        if constexpr (HL) rl[i] = *reinterpret_cast<const uint4*>(a_ptr[i] + lo_delta + (size_t)(kt + 1) * BK);
+      }
 #pragma unroll
       for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_ptr[i] + (size_t)(kt + 1) * BK);
     }
 #pragma unroll
     for (int ks = 0; ks < BK / 32; ++ks) {
-      bf16x8_t fa[TM], fb[TN];
+      bf16x8_t fa[TM], fb[TN], fl[HL ? TM : 1];
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int row = wm * (BM / WM) + i * 16 + frag_row;
         fa[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&sA[row * LDS + ks * 32 + frag_k]));
+        if constexpr (HL) fl[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&sAl[row * LDS + ks * 32 + frag_k]));
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
@@ -132,8 +146,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmGroup g) {
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TN; ++j) {
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          if constexpr (HL) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fl[i], fb[j], acc[i][j], 0, 0, 0);
+        }
     }
     __syncthreads();
   }
@@ -207,7 +223,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmGroup g) {
 // activations (small, L2-resident) are read straight into MFMA fragments.  The
 // four waves' partial tiles meet in LDS, then bias / GELU / partial store.
 // ---------------------------------------------------------------------------
-template <int NKF>
+template <int NKF, int NT, bool HL>
 __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmGroup g) {
   constexpr int KW = 32 * NKF;                       // k range of one wave
   __shared__ float red[4][64 * 16];
@@ -215,44 +231,60 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmGroup g) {
   const GemmDesc& d = (g.n > 1 && bid >= g.p[1].tile_begin) ? g.p[1] : g.p[0];
   const int t = bid - d.tile_begin;
   const int split = t / d.tiles_n, tn = t - split * d.tiles_n;
-  const int n0 = tn * 16;
+  const int n0 = tn * 16 * NT;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int k0 = split * 4 * KW + wave * KW + (lane >> 4) * 8;
   const uint16_t* A = reinterpret_cast<const uint16_t*>(d.A);
   const uint16_t* W = reinterpret_cast<const uint16_t*>(d.W);
+  const ptrdiff_t lo_delta = HL ? reinterpret_cast<const uint16_t*>(d.A_lo) - A : 0;
 
-  bf16x8_t wf[NKF];
-  {
-    const uint16_t* wp = W + (size_t)min(n0 + (lane & 15), d.N - 1) * d.K + k0;
+  bf16x8_t wf[NT][NKF];
 #pragma unroll
-    for (int kf = 0; kf < NKF; ++kf) wf[kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wp + kf * 32));
+  for (int nt = 0; nt < NT; ++nt) {
+    const uint16_t* wp = W + (size_t)min(n0 + nt * 16 + (lane & 15), d.N - 1) * d.K + k0;
+#pragma unroll
+    for (int kf = 0; kf < NKF; ++kf) wf[nt][kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wp + kf * 32));
   }
   for (int m0 = 0; m0 < d.M; m0 += 64) {
-    f32x4_t acc[4];
+    f32x4_t acc[NT][4];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) acc[nt][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
-      acc[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
       if (m0 + mt * 16 < d.M) {
         const uint16_t* ap = A + (size_t)min(m0 + mt * 16 + (lane & 15), d.M - 1) * d.lda + k0;
-        bf16x8_t af[NKF];
+        bf16x8_t af[NKF], al[HL ? NKF : 1];
 #pragma unroll
-        for (int kf = 0; kf < NKF; ++kf) af[kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(ap + kf * 32));
+        for (int kf = 0; kf < NKF; ++kf) {
+          af[kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(ap + kf * 32));
+          if constexpr (HL) al[kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(ap + lo_delta + kf * 32));
+        }
 #pragma unroll
-        for (int kf = 0; kf < NKF; ++kf) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[kf], wf[kf], acc[mt], 0, 0, 0);
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int kf = 0; kf < NKF; ++kf) {
+            acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[kf], wf[nt][kf], acc[nt][mt], 0, 0, 0);
+            if constexpr (HL) acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[kf], wf[nt][kf], acc[nt][mt], 0, 0, 0);
+          }
       }
     }
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) red[wave][(mt * 16 + (lane >> 4) * 4 + r) * 16 + (lane & 15)] = acc[mt][r];
-    __syncthreads();
+      for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int o = tid + i * 256;
-      const float sum = red[0][o] + red[1][o] + red[2][o] + red[3][o];
-      epilogue_store<bf16_t>(d, split, m0 + (o >> 4), n0 + (o & 15), sum);
+        for (int r = 0; r < 4; ++r) red[wave][(mt * 16 + (lane >> 4) * 4 + r) * 16 + (lane & 15)] = acc[nt][mt][r];
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int o = tid + i * 256;
+        const float sum = red[0][o] + red[1][o] + red[2][o] + red[3][o];
+        epilogue_store<bf16_t>(d, split, m0 + (o >> 4), n0 + nt * 16 + (o & 15), sum);
+      }
+      __syncthreads();
     }
-    __syncthreads();
   }
 }
 
@@ -288,6 +320,7 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
     plan->splits[i] = 1;
   }
   plan->nkf = 0;
+  plan->nt = 1;
   if (dtype == BT_F32) {
     plan->kind = KIND_F32;
     if (max_m <= kMaxSkinnyRows)
@@ -310,6 +343,15 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
       plan->kind = KIND_STREAM;
       plan->nkf = c;
       for (int i = 0; i < n_probs; ++i) plan->splits[i] = probs[i].K / (128 * c);
+      // columns per workgroup = 16 * nt: wider tiles re-read the activations less often,
+      // as long as the launch still has >= 2 workgroups per CU and W fits in registers
+      plan->nt = 1;
+      for (int nt = 4; nt > 1; nt >>= 1) {
+        if (nt * c > 32) continue;
+        int wgs = 0;
+        for (int i = 0; i < n_probs; ++i) wgs += ((probs[i].N + 16 * nt - 1) / (16 * nt)) * plan->splits[i];
+        if (wgs >= 512) { plan->nt = nt; break; }
+      }
       return hipSuccess;
     }
   }
@@ -342,28 +384,45 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
     g.p[i].A = p.A; g.p[i].W = p.W; g.p[i].bias = p.bias; g.p[i].out = p.out;
     g.p[i].M = p.M; g.p[i].N = p.N; g.p[i].K = p.K; g.p[i].lda = p.lda; g.p[i].ldo = p.ldo;
     g.p[i].epi = p.epi; g.p[i].splits = sp;
+    g.p[i].A_lo = p.A_lo; g.p[i].out_lo_off = p.out_lo_off;
+    if ((p.A_lo != nullptr) != (probs[0].A_lo != nullptr)) return hipErrorInvalidValue;
   }
+  const bool hl = probs[0].A_lo != nullptr;
+  if (hl && dtype != BT_BF16) return hipErrorInvalidValue;
   switch (plan.kind) {
     case KIND_F32:
       gemm_f32_kernel<<<fill_tiles<64, 64>(g), 256, 0, s>>>(g);
       break;
     case KIND_TILE128:
-      gemm_bf16_kernel<128, 128, 2, 2><<<fill_tiles<128, 128>(g), 256, 0, s>>>(g);
+      if (hl) gemm_bf16_kernel<128, 128, 2, 2, true><<<fill_tiles<128, 128>(g), 256, 0, s>>>(g);
+      else gemm_bf16_kernel<128, 128, 2, 2, false><<<fill_tiles<128, 128>(g), 256, 0, s>>>(g);
       break;
     case KIND_TILE64:
-      gemm_bf16_kernel<64, 64, 1, 4><<<fill_tiles<64, 64>(g), 256, 0, s>>>(g);
+      if (hl) gemm_bf16_kernel<64, 64, 1, 4, true><<<fill_tiles<64, 64>(g), 256, 0, s>>>(g);
+      else gemm_bf16_kernel<64, 64, 1, 4, false><<<fill_tiles<64, 64>(g), 256, 0, s>>>(g);
       break;
     case KIND_STREAM: {
-      const int grid = fill_tiles<1 << 30, 16>(g);      // tiles_m == 1: the kernel loops over rows
+      // tiles_m == 1: the kernel loops over rows itself
+#define BT_STREAM(NKF_, NT_)                                                                          \
+  do {                                                                                                \
+    if (hl) gemm_stream_kernel<NKF_, NT_, true><<<fill_tiles<1 << 30, 16 * NT_>(g), 256, 0, s>>>(g);  \
+    else gemm_stream_kernel<NKF_, NT_, false><<<fill_tiles<1 << 30, 16 * NT_>(g), 256, 0, s>>>(g);    \
+  } while (0)
+#define BT_STREAM_NT(NKF_)                                      \
+  if (plan.nt == 4) { if constexpr (NKF_ * 4 <= 32) BT_STREAM(NKF_, 4); else return hipErrorInvalidValue; } \
+  else if (plan.nt == 2) { if constexpr (NKF_ * 2 <= 32) BT_STREAM(NKF_, 2); else return hipErrorInvalidValue; } \
+  else BT_STREAM(NKF_, 1)
       switch (plan.nkf) {
-        case 2:  gemm_stream_kernel<2><<<grid, 256, 0, s>>>(g); break;
-        case 4:  gemm_stream_kernel<4><<<grid, 256, 0, s>>>(g); break;
-        case 6:  gemm_stream_kernel<6><<<grid, 256, 0, s>>>(g); break;
-        case 8:  gemm_stream_kernel<8><<<grid, 256, 0, s>>>(g); break;
-        case 12: gemm_stream_kernel<12><<<grid, 256, 0, s>>>(g); break;
-        case 16: gemm_stream_kernel<16><<<grid, 256, 0, s>>>(g); break;
+        case 2:  BT_STREAM_NT(2); break;
+        case 4:  BT_STREAM_NT(4); break;
+        case 6:  BT_STREAM_NT(6); break;
+        case 8:  BT_STREAM_NT(8); break;
+        case 12: BT_STREAM_NT(12); break;
+        case 16: BT_STREAM_NT(16); break;
         default: return hipErrorInvalidValue;
       }
+#undef BT_STREAM_NT
+#undef BT_STREAM
       break;
     }
     default:

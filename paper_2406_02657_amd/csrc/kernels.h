@@ -38,6 +38,7 @@ struct ResidLnArgs {
   void* u2;
   int n_rows, D, in_mul, in_off, write_x;
   float eps;
+  size_t lo_off;         // != 0: u1 / u2 also get the bf16 remainder plane at +lo_off elements
 };
 hipError_t launch_resid_ln(int dtype, const ResidLnArgs& a, hipStream_t s);
 
@@ -55,17 +56,21 @@ enum { EPI_F32 = 0,        // out float [M, ldo]: acc + bias
 
 // out[M, N] = A[M, K] * W[N, K]^T (+ bias).  A, W in the storage dtype, row-major,
 // lda / K contiguous.
+// A_lo (optional, bf16 mode): remainder plane of A, so that the product uses A + A_lo.
+// out_lo_off (EPI_GELU, bf16 mode): != 0 stores the output as hi / remainder planes.
 struct GemmProblem {
   const void* A;
   const void* W;
   const float* bias;
   void* out;
   int M, N, K, lda, ldo, epi;
+  const void* A_lo;
+  size_t out_lo_off;
 };
 // Which kernel serves a group of up to two problems, and into how many equal K
 // parts each EPI_PARTIAL problem is split (others: 1).  Depends on shapes only.
 struct GemmPlan {
-  int kind, nkf;
+  int kind, nkf, nt;
   int splits[2];
 };
 hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan* plan);
@@ -84,20 +89,21 @@ hipError_t launch_rope_append(int dtype, float* qkv, void* Kc, void* Vc, const f
 
 // Block decoder decode step: one query per (b, h) over cache rows [0, n_keys).
 // q read from qkv[b, h*d_h ...] (row stride 3D); out [B, D] storage dtype.
+// out_lo_off != 0 (here and below): out also gets the bf16 remainder plane.
 hipError_t launch_attn_block_decode(int dtype, const float* qkv, const void* Kc, const void* Vc,
-                                    void* out, int batch, int n_heads, int d_head, int n_keys,
+                                    void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_keys,
                                     int n_cap, hipStream_t s);
 
 // Block decoder prefill: causal attention of n_q queries per (b, h); query i sees rows [0, i].
 hipError_t launch_attn_block_prefill(int dtype, const float* qkv, const void* Kc, const void* Vc,
-                                     void* out, int batch, int n_heads, int d_head, int n_q,
+                                     void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_q,
                                      int n_cap, hipStream_t s);
 
 // Token decoder: `rows` new local positions pos0 .. pos0+rows-1 per sequence.
 // Rotates q, k; appends k, v to the local cache [B][H][l_cap][d_h]; causal
 // attention over local rows [0, pos0+i]; out [B*rows, D] storage dtype.
 hipError_t launch_attn_local(int dtype, const float* qkv, void* Kl, void* Vl, const float2* rope,
-                             void* out, int batch, int n_heads, int d_head, int rot, int rows,
+                             void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int rot, int rows,
                              int pos0, int l_cap, hipStream_t s);
 
 }  // namespace bt

@@ -1,0 +1,75 @@
+"""Parity at the workloads' full sizes, in the launch configuration bench.py times.
+
+The GPU runs the whole batch; the oracle (plain definition, teacher-forced on
+the ids the GPU emitted) checks sampled decode steps of sampled sequences:
+the first and the last of the batch, which are independent of the others.
+"""
+import time
+
+import numpy as np
+import pytest
+
+from parity import assert_parity, compare_sampled_with_oracle, gpu_generate_sampled, sample_steps
+from synth import CONFIGS, make_prompts, make_weights
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def amd():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2406_02657_amd as amd
+    return amd
+
+
+def full_size_case(amd, cfg, n_new, seqs, batch=None, prompt_len=None):
+    t0 = time.time()
+    W = make_weights(cfg)
+    prompts = make_prompts(cfg, batch=batch, prompt_len=prompt_len)
+    B, T = prompts.shape
+    print(f"[{cfg.name}] inputs {time.time() - t0:.1f}s", flush=True)
+    m = amd.Model(cfg, W, max_batch=B, max_blocks=(T + n_new) // cfg.block_len + 1)
+    steps = sample_steps(cfg, n_new)
+    t0 = time.time()
+    ids, lgs = gpu_generate_sampled(m, prompts, n_new, seqs, steps)
+    st = m.bt_get_stats()
+    m.close()
+    print(f"[{cfg.name}] gpu {time.time() - t0:.1f}s  B={B} T_p={T} n_new={n_new}", flush=True)
+    assert ids.min() >= 0 and ids.max() < cfg.vocab
+    n_p = T // cfg.block_len
+    assert st.block_passes == n_p + -(-n_new // cfg.block_len) - 1
+    assert st.token_passes == n_new
+    t0 = time.time()
+    rep = compare_sampled_with_oracle(cfg, W, prompts, ids, lgs, seqs, 2e-2)
+    print(f"[{cfg.name}] oracle {time.time() - t0:.1f}s {rep}", flush=True)
+    assert_parity(rep)
+
+
+def test_cfg1_decode_heavy_full(amd):
+    cfg = CONFIGS["cfg1"]
+    full_size_case(amd, cfg, cfg.gen_len, [0, cfg.batch - 1])
+
+
+def test_cfg2_prefill_heavy_full(amd):
+    cfg = CONFIGS["cfg2"]
+    full_size_case(amd, cfg, cfg.gen_len, [0, cfg.batch - 1])
+
+
+def test_cfg3_medium_full(amd):
+    cfg = CONFIGS["cfg3"]
+    full_size_case(amd, cfg, cfg.gen_len, [0, cfg.batch - 1])
+
+
+def test_cfg4_large(amd):
+    """Full batch and full prompt; 256 decode steps (the oracle's block-decoder pass over the
+    history of one sequence is what bounds this)."""
+    cfg = CONFIGS["cfg4"]
+    full_size_case(amd, cfg, 256, [cfg.batch - 1])
+
+
+def test_cfg4v_vanilla_equivalent(amd):
+    """L_B = 1, no prefix, at cfg4's width and depth; batch and lengths reduced (one KV entry per
+    token makes the full 256 x 4096 cache 206 GB; the oracle pass is the other bound)."""
+    cfg = CONFIGS["cfg4v"]
+    full_size_case(amd, cfg, 64, [7], batch=8, prompt_len=512)
