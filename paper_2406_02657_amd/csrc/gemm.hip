@@ -346,6 +346,10 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
       // columns per workgroup = 16 * nt: wider tiles re-read the activations less often,
       // as long as the launch still has >= 2 workgroups per CU and W fits in registers
       plan->nt = 1;
+#ifdef BT_FORCE_NT
+      plan->nt = BT_FORCE_NT; if (plan->nt * c > 32) plan->nt = 32 / c >= 2 ? 2 : 1;
+      return hipSuccess;
+#endif
       for (int nt = 4; nt > 1; nt >>= 1) {
         if (nt * c > 32) continue;
         int wgs = 0;
