@@ -16,6 +16,47 @@ namespace bt {
 
 constexpr float kNegBig = -1.0e30f;
 
+__device__ __forceinline__ float partial_value(const PartialSrc& p, size_t idx, int col) {
+  float v = p.bias ? p.bias[col] : 0.f;
+#pragma unroll 4
+  for (int s = 0; s < p.splits; ++s) v += p.base[(size_t)s * p.stride + idx];
+  return v;
+}
+
+__device__ __forceinline__ float gelu_erf_f(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
+
+// Extra workgroups of an attention launch (or a launch of its own): block `blk` of `nblk`
+// turns its share of the up-projection partial sums into the MLP hidden activation.
+template <class T>
+__device__ __forceinline__ void gelu_reduce_block(const GeluJob& j, int blk, int nblk) {
+  const size_t groups = (size_t)j.rows * j.cols / 4;
+  T* out = reinterpret_cast<T*>(j.out);
+  for (size_t gi = (size_t)blk * blockDim.x + threadIdx.x; gi < groups; gi += (size_t)nblk * blockDim.x) {
+    const size_t idx = gi * 4;
+    const int col = (int)(idx % j.cols);
+    float4 v = j.src.bias ? *reinterpret_cast<const float4*>(j.src.bias + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int s = 0; s < j.src.splits; ++s) {
+      const float4 p = *reinterpret_cast<const float4*>(j.src.base + (size_t)s * j.src.stride + idx);
+      v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    store_act<T>(out, idx, j.out_lo_off, gelu_erf_f(v.x));
+    store_act<T>(out, idx + 1, j.out_lo_off, gelu_erf_f(v.y));
+    store_act<T>(out, idx + 2, j.out_lo_off, gelu_erf_f(v.z));
+    store_act<T>(out, idx + 3, j.out_lo_off, gelu_erf_f(v.w));
+  }
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void gelu_reduce_kernel(GeluJob j) { gelu_reduce_block<T>(j, blockIdx.x, gridDim.x); }
+
+__host__ inline int gelu_blocks(const GeluJob& j) {
+  if (j.rows <= 0) return 0;
+  const size_t groups = (size_t)j.rows * j.cols / 4;
+  size_t b = (groups + 1023) / 1024;          // about four 16-byte groups per thread
+  return (int)(b < 1 ? 1 : (b > 1024 ? 1024 : b));
+}
+
 template <class T, int DH>
 struct RowMap {
   static constexpr int EPC = Chunk<T>::EPC;   // elements per 16-byte chunk
@@ -105,11 +146,16 @@ __device__ __forceinline__ void wave_attend(const float* q, const T* __restrict_
 template <class T, int DH, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(const float* __restrict__ qkv, const T* __restrict__ Kc,
                                                                     const T* __restrict__ Vc, T* __restrict__ out,
-                                                                    size_t out_lo_off, int n_heads, int n_keys, int n_cap) {
+                                                                    size_t out_lo_off, int n_heads, int n_keys, int n_cap,
+                                                                    int n_attn_blocks, GeluJob gelu) {
   using R = RowMap<T, DH>;
   constexpr int EPC = R::EPC, LPR = R::LPR;
   __shared__ float s_m[NW], s_l[NW];
   __shared__ float s_acc[NW][DH];
+  if ((int)blockIdx.x >= n_attn_blocks) {
+    gelu_reduce_block<T>(gelu, blockIdx.x - n_attn_blocks, gridDim.x - n_attn_blocks);
+    return;
+  }
   const int bh = blockIdx.x;
   const int b = bh / n_heads, h = bh - b * n_heads;
   const int D = n_heads * DH;
@@ -197,23 +243,23 @@ __global__ __launch_bounds__(256) void attn_block_prefill_kernel(const float* __
 // One workgroup per row.
 // ---------------------------------------------------------------------------
 template <class T>
-__global__ __launch_bounds__(256) void rope_append_kernel(float* __restrict__ qkv, T* __restrict__ Kc, T* __restrict__ Vc,
+__global__ __launch_bounds__(256) void rope_append_kernel(PartialSrc src, T* __restrict__ Kc, T* __restrict__ Vc,
                                                           const float2* __restrict__ rope, int n_new, int pos0,
                                                           int n_heads, int DH, int rot, int n_cap) {
   const int m = blockIdx.x;
   const int b = m / n_new, pos = pos0 + (m - b * n_new);
   const int D = n_heads * DH, half = rot / 2;
-  float* q = qkv + (size_t)m * 3 * D;
-  const float* k = q + D;
-  const float* v = q + 2 * D;
+  const size_t rbase = (size_t)m * 3 * D;
+  float* q = const_cast<float*>(src.base) + rbase;      // plane 0 receives the finished q
+  const bool pieces = src.splits > 1 || src.bias != nullptr;
   for (int idx = threadIdx.x; idx < n_heads * half; idx += blockDim.x) {
     const int h = idx / half, t = idx - h * half;
     const float2 cs = rope[(size_t)pos * half + t];
     const int d0 = h * DH + t, d1 = d0 + half;
-    const float q0 = q[d0], q1 = q[d1];
+    const float q0 = partial_value(src, rbase + d0, d0), q1 = partial_value(src, rbase + d1, d1);
     q[d0] = q0 * cs.x - q1 * cs.y;
     q[d1] = q1 * cs.x + q0 * cs.y;
-    const float k0 = k[d0], k1 = k[d1];
+    const float k0 = partial_value(src, rbase + D + d0, D + d0), k1 = partial_value(src, rbase + D + d1, D + d1);
     const size_t base = ((size_t)(b * n_heads + h) * n_cap + pos) * DH;
     Kc[base + t] = from_float<T>(k0 * cs.x - k1 * cs.y);
     Kc[base + t + half] = from_float<T>(k1 * cs.x + k0 * cs.y);
@@ -221,8 +267,11 @@ __global__ __launch_bounds__(256) void rope_append_kernel(float* __restrict__ qk
   for (int idx = threadIdx.x; idx < D; idx += blockDim.x) {
     const int h = idx / DH, d = idx - h * DH;
     const size_t base = ((size_t)(b * n_heads + h) * n_cap + pos) * DH;
-    if (d >= rot) Kc[base + d] = from_float<T>(k[idx]);
-    Vc[base + d] = from_float<T>(v[idx]);
+    if (d >= rot) {
+      Kc[base + d] = from_float<T>(partial_value(src, rbase + D + idx, D + idx));
+      if (pieces) q[idx] = partial_value(src, rbase + idx, idx);
+    }
+    Vc[base + d] = from_float<T>(partial_value(src, rbase + 2 * D + idx, 2 * D + idx));
   }
 }
 
@@ -232,10 +281,15 @@ __global__ __launch_bounds__(256) void rope_append_kernel(float* __restrict__ qk
 // LDS per wave: K [l_cap][DH], V [l_cap][DH], raw q [DH], raw k [DH].
 // ---------------------------------------------------------------------------
 template <class T, int DH>
-__global__ void attn_local_kernel(const float* __restrict__ qkv, T* __restrict__ Kl, T* __restrict__ Vl,
+__global__ void attn_local_kernel(PartialSrc qkv, T* __restrict__ Kl, T* __restrict__ Vl,
                                   const float2* __restrict__ rope, T* __restrict__ out, size_t out_lo_off,
-                                  int n_pairs, int n_heads, int rot, int rows, int pos0, int l_cap) {
+                                  int n_pairs, int n_heads, int rot, int rows, int pos0, int l_cap,
+                                  int n_attn_blocks, GeluJob gelu) {
   extern __shared__ float smem[];
+  if ((int)blockIdx.x >= n_attn_blocks) {
+    gelu_reduce_block<T>(gelu, blockIdx.x - n_attn_blocks, gridDim.x - n_attn_blocks);
+    return;
+  }
   constexpr int DPL = (DH + 63) / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nw = blockDim.x >> 6;
@@ -259,12 +313,16 @@ __global__ void attn_local_kernel(const float* __restrict__ qkv, T* __restrict__
   for (int i = 0; i < rows; ++i) {
     const int pos = pos0 + i;
     const size_t row = (size_t)b * rows + i;
-    const float* src = qkv + row * 3 * D + h * DH;
+    const size_t src = row * 3 * D + h * DH;
     float vv[DPL];
 #pragma unroll
     for (int c = 0; c < DPL; ++c) {
       const int d = lane + 64 * c;
-      if (d < DH) { sq[d] = src[d]; sk[d] = src[D + d]; vv[c] = src[2 * D + d]; }
+      if (d < DH) {
+        sq[d] = partial_value(qkv, src + d, h * DH + d);
+        sk[d] = partial_value(qkv, src + D + d, D + h * DH + d);
+        vv[c] = partial_value(qkv, src + 2 * D + d, 2 * D + h * DH + d);
+      }
     }
     __syncthreads();
     float qv[DPL];
@@ -332,29 +390,40 @@ __global__ void attn_local_kernel(const float* __restrict__ qkv, T* __restrict__
     default: return hipErrorInvalidValue;                \
   }
 
-hipError_t launch_rope_append(int dtype, float* qkv, void* Kc, void* Vc, const float2* rope,
+hipError_t launch_rope_append(int dtype, const PartialSrc& src, void* Kc, void* Vc, const float2* rope,
                               int n_rows, int n_new, int pos0, int n_heads, int d_head, int rot,
                               int n_cap, hipStream_t s) {
   if (n_rows <= 0) return hipSuccess;
   if (dtype == BT_F32)
-    rope_append_kernel<float><<<n_rows, 256, 0, s>>>(qkv, (float*)Kc, (float*)Vc, rope, n_new, pos0, n_heads, d_head, rot, n_cap);
+    rope_append_kernel<float><<<n_rows, 256, 0, s>>>(src, (float*)Kc, (float*)Vc, rope, n_new, pos0, n_heads, d_head, rot, n_cap);
   else
-    rope_append_kernel<bf16_t><<<n_rows, 256, 0, s>>>(qkv, (bf16_t*)Kc, (bf16_t*)Vc, rope, n_new, pos0, n_heads, d_head, rot, n_cap);
+    rope_append_kernel<bf16_t><<<n_rows, 256, 0, s>>>(src, (bf16_t*)Kc, (bf16_t*)Vc, rope, n_new, pos0, n_heads, d_head, rot, n_cap);
+  return hipGetLastError();
+}
+
+hipError_t launch_gelu_reduce(int dtype, const GeluJob& job, hipStream_t s) {
+  const int nb = gelu_blocks(job);
+  if (nb == 0) return hipSuccess;
+  if (job.cols % 4) return hipErrorInvalidValue;
+  if (dtype == BT_F32) gelu_reduce_kernel<float><<<nb, 256, 0, s>>>(job);
+  else gelu_reduce_kernel<bf16_t><<<nb, 256, 0, s>>>(job);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_block_decode(int dtype, const float* qkv, const void* Kc, const void* Vc,
                                     void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_keys,
-                                    int n_cap, hipStream_t s) {
+                                    int n_cap, const GeluJob& gelu, hipStream_t s) {
   if (n_keys < 1 || n_keys > n_cap) return hipErrorInvalidValue;
+  if (gelu.rows > 0 && gelu.cols % 4) return hipErrorInvalidValue;
   constexpr int NW = 4;
-  const int grid = batch * n_heads;
+  const int n_attn = batch * n_heads;
+  const int grid = n_attn + gelu_blocks(gelu);
   if (dtype == BT_F32) {
     BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<float, DH, NW><<<grid, NW * 64, 0, s>>>(
-        qkv, (const float*)Kc, (const float*)Vc, (float*)out, 0, n_heads, n_keys, n_cap)));
+        qkv, (const float*)Kc, (const float*)Vc, (float*)out, 0, n_heads, n_keys, n_cap, n_attn, gelu)));
   } else {
     BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<bf16_t, DH, NW><<<grid, NW * 64, 0, s>>>(
-        qkv, (const bf16_t*)Kc, (const bf16_t*)Vc, (bf16_t*)out, out_lo_off, n_heads, n_keys, n_cap)));
+        qkv, (const bf16_t*)Kc, (const bf16_t*)Vc, (bf16_t*)out, out_lo_off, n_heads, n_keys, n_cap, n_attn, gelu)));
   }
   return hipGetLastError();
 }
@@ -374,23 +443,25 @@ hipError_t launch_attn_block_prefill(int dtype, const float* qkv, const void* Kc
   return hipGetLastError();
 }
 
-hipError_t launch_attn_local(int dtype, const float* qkv, void* Kl, void* Vl, const float2* rope,
+hipError_t launch_attn_local(int dtype, const PartialSrc& qkv, void* Kl, void* Vl, const float2* rope,
                              void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int rot, int rows,
-                             int pos0, int l_cap, hipStream_t s) {
+                             int pos0, int l_cap, const GeluJob& gelu, hipStream_t s) {
   if (rows < 1 || pos0 < 0 || pos0 + rows > l_cap) return hipErrorInvalidValue;
+  if (gelu.rows > 0 && gelu.cols % 4) return hipErrorInvalidValue;
   const int n_pairs = batch * n_heads;
   const size_t per_wave = (size_t)(2 * l_cap + 2) * d_head * sizeof(float);
   int nw = 4;
   while (nw > 1 && per_wave * nw > 60 * 1024) nw >>= 1;
   if (per_wave * nw > 60 * 1024) return hipErrorInvalidValue;
-  const int grid = (n_pairs + nw - 1) / nw;
+  const int n_attn = (n_pairs + nw - 1) / nw;
+  const int grid = n_attn + gelu_blocks(gelu);
   const size_t shm = per_wave * nw;
   if (dtype == BT_F32) {
     BT_DISPATCH_DH(d_head, (attn_local_kernel<float, DH><<<grid, nw * 64, shm, s>>>(
-        qkv, (float*)Kl, (float*)Vl, rope, (float*)out, 0, n_pairs, n_heads, rot, rows, pos0, l_cap)));
+        qkv, (float*)Kl, (float*)Vl, rope, (float*)out, 0, n_pairs, n_heads, rot, rows, pos0, l_cap, n_attn, gelu)));
   } else {
     BT_DISPATCH_DH(d_head, (attn_local_kernel<bf16_t, DH><<<grid, nw * 64, shm, s>>>(
-        qkv, (bf16_t*)Kl, (bf16_t*)Vl, rope, (bf16_t*)out, out_lo_off, n_pairs, n_heads, rot, rows, pos0, l_cap)));
+        qkv, (bf16_t*)Kl, (bf16_t*)Vl, rope, (bf16_t*)out, out_lo_off, n_pairs, n_heads, rot, rows, pos0, l_cap, n_attn, gelu)));
   }
   return hipGetLastError();
 }

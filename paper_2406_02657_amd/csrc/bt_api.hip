@@ -23,9 +23,10 @@ constexpr int kSkinnyRows = 256;     // GEMMs with at most this many rows may sp
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct Layout {
-  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, ctx, hfin, logits, cur, total;
+  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cur, total;
   size_t blk_layer_stride, loc_layer_stride;   // bytes between layers (K then V inside)
-  size_t part_elems;                           // floats in each partial buffer
+  size_t part_elems;                           // floats in each of part_o, part_d
+  size_t qkv_elems, part_u_elems;              // floats in qkv (may hold split-K pieces) and part_u
   int m_rows, l_cap, n_pref, rope_len, esz;
 };
 
@@ -75,14 +76,21 @@ void make_layout(const bt_config& c, Layout& L) {
   L.x = take(m_rows * D * 4);
   L.u1 = take(m_rows * D * 4);          // sized for float so that fp32 mode fits
   L.u2 = take(m_rows * D * 4);
-  L.qkv = take(m_rows * 3 * D * 4);
+  // Skinny (decode) GEMMs may leave up to K/64 split-K pieces for their consumers.
+  const size_t skinny = m_rows < (size_t)kSkinnyRows ? m_rows : (size_t)kSkinnyRows;
+  const size_t sD = D / 64 > 0 ? D / 64 : 1, sF = F / 64 > 0 ? F / 64 : 1;
+  L.qkv_elems = m_rows * 3 * D;
+  if (L.qkv_elems < sD * skinny * 3 * D) L.qkv_elems = sD * skinny * 3 * D;
+  L.qkv = take(L.qkv_elems * 4);
   L.ao = take(m_rows * D * 4);
   L.hmid = take(m_rows * F * 4);
-  const size_t skinny = m_rows < (size_t)kSkinnyRows ? m_rows : (size_t)kSkinnyRows;
   L.part_elems = m_rows * D;
-  if (L.part_elems < kMaxSplits * skinny * D) L.part_elems = kMaxSplits * skinny * D;
+  const size_t sMax = sF > (size_t)kMaxSplits ? sF : (size_t)kMaxSplits;
+  if (L.part_elems < sMax * skinny * D) L.part_elems = sMax * skinny * D;
   L.part_o = take(L.part_elems * 4);
   L.part_d = take(L.part_elems * 4);
+  L.part_u_elems = sD * skinny * F;
+  L.part_u = take(L.part_u_elems * 4);
   L.ctx = take(B * D * 4);
   L.hfin = take(B * D * 4);
   L.logits = take(B * (size_t)c.vocab * 4);
@@ -167,37 +175,43 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
   void* hmid = m->at<void>(L.hmid);
   float* part_o = m->at<float>(L.part_o);
   float* part_d = m->at<float>(L.part_d);
+  float* part_u = m->at<float>(L.part_u);
   const float2* rope = m->at<float2>(L.rope);
   hipStream_t s = m->stream;
   const int M = a.M;
+  if (n_layers == 0)
+    return final_ln(m, a, nullptr, nullptr, 0, nullptr, nullptr, 0, fin_g, fin_b, fin_out, fin_f32, fin_n, fin_mul, fin_off);
+
   // bf16 mode: activations that feed GEMMs are kept as hi + remainder planes (see bt.h, act_split)
   const bool split = dt == BT_BF16 && (c.act_split == 2 || (c.act_split == 1 && a.mode != MODE_BLOCK_PREFILL));
   const size_t loD = split ? (size_t)L.m_rows * D : 0, loF = split ? (size_t)L.m_rows * F : 0;
-  auto lo = [&](void* p, size_t off) -> const void* { return off ? (const char*)p + off * 2 : nullptr; };
-  // GEMM problems of one layer (pointers to weights filled per layer) and their plans
-  GemmProblem pq{u1, nullptr, nullptr, qkv, M, 3 * D, D, D, 3 * D, EPI_F32, lo(u1, loD), 0};
-  GemmProblem pu{nullptr, nullptr, nullptr, hmid, M, F, D, D, F, EPI_GELU, nullptr, loF};
+  auto lo = [&](const void* p, size_t off) -> const void* { return off ? (const char*)p + off * 2 : nullptr; };
+  // Skinny bf16 GEMMs (decode steps) hand raw split-K partial sums to their consumers, which add
+  // bias / GELU / rotary; large or fp32 GEMMs finish their own epilogue.
+  const bool pieces = dt == BT_BF16 && M <= kSkinnyRows;
+  const void* a_up = c.parallel_residual ? u2 : u1;
+  GemmProblem pq{u1, nullptr, nullptr, qkv, M, 3 * D, D, D, 3 * D, pieces ? EPI_PARTIAL : EPI_F32, lo(u1, loD), 0};
+  GemmProblem pu{a_up, nullptr, nullptr, pieces ? (void*)part_u : hmid, M, F, D, D, F, pieces ? EPI_PARTIAL : EPI_GELU,
+                 lo(a_up, loD), loF};
   GemmProblem po{ao, nullptr, nullptr, part_o, M, D, D, D, D, EPI_PARTIAL, lo(ao, loD), 0};
   GemmProblem pd{hmid, nullptr, nullptr, part_d, M, D, F, F, D, EPI_PARTIAL, lo(hmid, loF), 0};
-  pu.A = c.parallel_residual ? u2 : u1;
-  pu.A_lo = lo(const_cast<void*>(pu.A), loD);
   GemmPlan plan_in{}, plan_out{}, plan_q{}, plan_u{}, plan_o{}, plan_d{};
-  int sO, sD;
+  int sQ, sU, sO, sD;
   if (c.parallel_residual) {
     GemmProblem gi[2] = {pq, pu}, go[2] = {po, pd};
     BT_HIP(m, gemm_plan(dt, gi, 2, &plan_in));
     BT_HIP(m, gemm_plan(dt, go, 2, &plan_out));
-    sO = plan_out.splits[0];
-    sD = plan_out.splits[1];
+    sQ = plan_in.splits[0]; sU = plan_in.splits[1];
+    sO = plan_out.splits[0]; sD = plan_out.splits[1];
   } else {
     BT_HIP(m, gemm_plan(dt, &pq, 1, &plan_q));
     BT_HIP(m, gemm_plan(dt, &pu, 1, &plan_u));
     BT_HIP(m, gemm_plan(dt, &po, 1, &plan_o));
     BT_HIP(m, gemm_plan(dt, &pd, 1, &plan_d));
-    sO = plan_o.splits[0];
-    sD = plan_d.splits[0];
+    sQ = plan_q.splits[0]; sU = plan_u.splits[0]; sO = plan_o.splits[0]; sD = plan_d.splits[0];
   }
-  if ((size_t)sO * M * D > L.part_elems || (size_t)sD * M * D > L.part_elems)
+  if ((size_t)sO * M * D > L.part_elems || (size_t)sD * M * D > L.part_elems ||
+      (size_t)sQ * M * 3 * D > L.qkv_elems || (pieces && (size_t)sU * M * F > L.part_u_elems))
     return fail(m, BT_ERR_CAPACITY, "split-K partial buffer too small");
 
   auto ln = [&](const float* pO, const float* bO, int nO, const float* pD, const float* bD, int nD,
@@ -215,12 +229,14 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     BT_HIP(m, launch_resid_ln(dt, r, s));
     return BT_OK;
   };
-  auto attention = [&](int l) -> int {
+  // attention of layer l; `gelu` (may be empty) rides along as extra workgroups where possible
+  auto attention = [&](int l, const GeluJob& gelu) -> int {
+    const PartialSrc qsrc{qkv, pieces ? (const float*)lw[l].b_qkv : nullptr, sQ, (size_t)M * 3 * D};
     if (a.mode == MODE_TOKEN) {
       char* base = m->ws + L.loc_kv + (size_t)l * L.loc_layer_stride;
       const size_t half = (size_t)c.max_batch * H * L.l_cap * dh * L.esz;
-      BT_HIP(m, launch_attn_local(dt, qkv, base, base + half, rope, ao, loD, a.batch, H, dh, c.rotary_dims,
-                                  a.rows, a.pos0, L.l_cap, s));
+      BT_HIP(m, launch_attn_local(dt, qsrc, base, base + half, rope, ao, loD, a.batch, H, dh, c.rotary_dims,
+                                  a.rows, a.pos0, L.l_cap, gelu, s));
       return BT_OK;
     }
     char* base = m->ws + L.blk_kv + (size_t)l * L.blk_layer_stride;
@@ -228,9 +244,10 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     const size_t seq = (size_t)a.b0 * H * c.max_blocks * dh * L.esz;
     char* Kc = base + seq;
     char* Vc = base + half + seq;
-    BT_HIP(m, launch_rope_append(dt, qkv, Kc, Vc, rope, M, a.rows, a.pos0, H, dh, c.rotary_dims, c.max_blocks, s));
+    BT_HIP(m, launch_rope_append(dt, qsrc, Kc, Vc, rope, M, a.rows, a.pos0, H, dh, c.rotary_dims, c.max_blocks, s));
     if (a.mode == MODE_BLOCK_PREFILL) {
       BT_HIP(m, launch_attn_block_prefill(dt, qkv, Kc, Vc, ao, loD, a.batch, H, dh, a.rows, c.max_blocks, s));
+      BT_HIP(m, launch_gelu_reduce(dt, gelu, s));
     } else {
       const int n_keys = a.pos0 + 1;
       hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -247,7 +264,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
         m->ev_used += 2;
         BT_HIP(m, hipEventRecord(e0, s));
       }
-      BT_HIP(m, launch_attn_block_decode(dt, qkv, Kc, Vc, ao, loD, a.batch, H, dh, n_keys, c.max_blocks, s));
+      BT_HIP(m, launch_attn_block_decode(dt, qkv, Kc, Vc, ao, loD, a.batch, H, dh, n_keys, c.max_blocks, gelu, s));
       if (m->profile) {
         BT_HIP(m, hipEventRecord(e1, s));
         m->st.attn_block_launches += 1;
@@ -256,19 +273,25 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     }
     return BT_OK;
   };
+  auto gelu_job = [&](int l) {
+    GeluJob j{};
+    if (pieces) {
+      j.src = PartialSrc{part_u, (const float*)lw[l].b_up, sU, (size_t)M * F};
+      j.out = hmid; j.out_lo_off = loF; j.rows = M; j.cols = F;
+    }
+    return j;
+  };
+  const GeluJob no_job{};
 
   int rc;
-  if (n_layers == 0) {
-    return final_ln(m, a, nullptr, nullptr, 0, nullptr, nullptr, 0, fin_g, fin_b, fin_out, fin_f32, fin_n, fin_mul, fin_off);
-  }
   if (c.parallel_residual) {
     if ((rc = ln(nullptr, nullptr, 0, nullptr, nullptr, 0, lw[0].ln1_g, lw[0].ln1_b, lw[0].ln2_g, lw[0].ln2_b))) return rc;
     for (int l = 0; l < n_layers; ++l) {
       GemmProblem p[2] = {pq, pu};
-      p[0].W = lw[l].W_qkv; p[0].bias = (const float*)lw[l].b_qkv;
-      p[1].W = lw[l].W_up;  p[1].bias = (const float*)lw[l].b_up;
+      p[0].W = lw[l].W_qkv; p[1].W = lw[l].W_up;
+      if (!pieces) { p[0].bias = (const float*)lw[l].b_qkv; p[1].bias = (const float*)lw[l].b_up; }
       BT_HIP(m, launch_gemm(dt, p, 2, plan_in, s));
-      if ((rc = attention(l))) return rc;
+      if ((rc = attention(l, gelu_job(l)))) return rc;
       p[0] = po; p[0].W = lw[l].W_o;
       p[1] = pd; p[1].W = lw[l].W_down;
       BT_HIP(m, launch_gemm(dt, p, 2, plan_out, s));
@@ -284,14 +307,17 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     if ((rc = ln(nullptr, nullptr, 0, nullptr, nullptr, 0, lw[0].ln1_g, lw[0].ln1_b, nullptr, nullptr))) return rc;
     for (int l = 0; l < n_layers; ++l) {
       GemmProblem p = pq;
-      p.W = lw[l].W_qkv; p.bias = (const float*)lw[l].b_qkv;
+      p.W = lw[l].W_qkv;
+      if (!pieces) p.bias = (const float*)lw[l].b_qkv;
       BT_HIP(m, launch_gemm(dt, &p, 1, plan_q, s));
-      if ((rc = attention(l))) return rc;
+      if ((rc = attention(l, no_job))) return rc;
       p = po; p.W = lw[l].W_o;
       BT_HIP(m, launch_gemm(dt, &p, 1, plan_o, s));
       if ((rc = ln(part_o, (const float*)lw[l].b_o, sO, nullptr, nullptr, 0, lw[l].ln2_g, lw[l].ln2_b, nullptr, nullptr))) return rc;
-      p = pu; p.W = lw[l].W_up; p.bias = (const float*)lw[l].b_up;
+      p = pu; p.W = lw[l].W_up;
+      if (!pieces) p.bias = (const float*)lw[l].b_up;
       BT_HIP(m, launch_gemm(dt, &p, 1, plan_u, s));
+      BT_HIP(m, launch_gelu_reduce(dt, gelu_job(l), s));
       p = pd; p.W = lw[l].W_down;
       BT_HIP(m, launch_gemm(dt, &p, 1, plan_d, s));
       if (l + 1 < n_layers) {

@@ -215,97 +215,138 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmGroup g) {
 }
 
 // ---------------------------------------------------------------------------
-// bf16 weight-streaming kernel for skinny problems (M <= 256: decode steps).
-// These GEMMs are bound by reading W once from HBM, so the design goal is bytes
-// in flight, not MFMA rate: a workgroup owns 16 output columns and a K chunk of
-// 4 * 32 * NKF; each of its 4 waves takes a quarter of the chunk and issues all
-// of its W fragment loads (NKF x 16 bytes per lane) before anything else.  The
-// activations (small, L2-resident) are read straight into MFMA fragments.  The
-// four waves' partial tiles meet in LDS, then bias / GELU / partial store.
+// bf16 kernel for skinny problems (M <= 256: decode steps).  These GEMMs are
+// bound by reading W once from HBM, and a CU ingests only a few tens of GB/s,
+// so the design goal is few bytes per workgroup and all of them in flight at
+// once.  A workgroup owns 64*NT output columns (16*NT per wave) and a run of
+// k_iters K-slices of 32*KF; per slice it stages the activation slice (all M
+// rows, hi and lo planes) in LDS once for its four waves, while every wave holds
+// its weight fragments in registers, loaded before anything else.  Each K-split
+// writes raw partial sums [split][M][N]; the consumer adds bias / activation.
+// With one split the usual epilogue (bias, GELU) is applied here.
 // ---------------------------------------------------------------------------
-template <int NKF, int NT, bool HL>
-__global__ __launch_bounds__(256) void gemm_stream_kernel(GemmGroup g) {
-  constexpr int KW = 32 * NKF;                       // k range of one wave
-  __shared__ float red[4][64 * 16];
+template <int KF, int NT, int MC, bool HL>
+__global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
+  constexpr int KS = 32 * KF, LDK = KS + 8, CPR = KS / 8, PL = HL ? 2 : 1;
+  extern __shared__ __attribute__((aligned(16))) uint16_t sA[];
   const int bid = blockIdx.x;
   const GemmDesc& d = (g.n > 1 && bid >= g.p[1].tile_begin) ? g.p[1] : g.p[0];
   const int t = bid - d.tile_begin;
   const int split = t / d.tiles_n, tn = t - split * d.tiles_n;
-  const int n0 = tn * 16 * NT;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int k0 = split * 4 * KW + wave * KW + (lane >> 4) * 8;
+  const int n0 = tn * 64 * NT + wave * 16 * NT;
+  const int Mpad = (d.M + 15) & ~15;
+  const int k_iters = d.K / KS / d.splits;
   const uint16_t* A = reinterpret_cast<const uint16_t*>(d.A);
   const uint16_t* W = reinterpret_cast<const uint16_t*>(d.W);
   const ptrdiff_t lo_delta = HL ? reinterpret_cast<const uint16_t*>(d.A_lo) - A : 0;
 
-  bf16x8_t wf[NT][NKF];
+  f32x4_t acc[MC][NT][4];
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const uint16_t* wp = W + (size_t)min(n0 + nt * 16 + (lane & 15), d.N - 1) * d.K + k0;
-#pragma unroll
-    for (int kf = 0; kf < NKF; ++kf) wf[nt][kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wp + kf * 32));
-  }
-  for (int m0 = 0; m0 < d.M; m0 += 64) {
-    f32x4_t acc[NT][4];
+  for (int mc = 0; mc < MC; ++mc)
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) acc[nt][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-      if (m0 + mt * 16 < d.M) {
-        const uint16_t* ap = A + (size_t)min(m0 + mt * 16 + (lane & 15), d.M - 1) * d.lda + k0;
-        bf16x8_t af[NKF], al[HL ? NKF : 1];
-#pragma unroll
-        for (int kf = 0; kf < NKF; ++kf) {
-          af[kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(ap + kf * 32));
-          if constexpr (HL) al[kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(ap + lo_delta + kf * 32));
-        }
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-          for (int kf = 0; kf < NKF; ++kf) {
-            acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[kf], wf[nt][kf], acc[nt][mt], 0, 0, 0);
-            if constexpr (HL) acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[kf], wf[nt][kf], acc[nt][mt], 0, 0, 0);
-          }
-      }
-    }
+      for (int mt = 0; mt < 4; ++mt) acc[mc][nt][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  const int total = Mpad * CPR;                 // 16-byte chunks of one plane of the slice
+  for (int it = 0; it < k_iters; ++it) {
+    const int kbase = (split * k_iters + it) * KS;
+    // weight fragments of this wave: issued first, they come from HBM
+    bf16x8_t wf[NT][KF];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
+      const uint16_t* wp = W + (size_t)min(n0 + nt * 16 + (lane & 15), d.N - 1) * d.K + kbase + (lane >> 4) * 8;
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) red[wave][(mt * 16 + (lane >> 4) * 4 + r) * 16 + (lane & 15)] = acc[nt][mt][r];
-      __syncthreads();
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int o = tid + i * 256;
-        const float sum = red[0][o] + red[1][o] + red[2][o] + red[3][o];
-        epilogue_store<bf16_t>(d, split, m0 + (o >> 4), n0 + nt * 16 + (o & 15), sum);
-      }
-      __syncthreads();
+      for (int kf = 0; kf < KF; ++kf) wf[nt][kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wp + kf * 32));
     }
+    // activation slice -> LDS (rows past M repeat the last row; never stored)
+    for (int c0 = 0; c0 < total; c0 += 256 * 6) {
+      uint4 r[PL][6];
+#pragma unroll
+      for (int u = 0; u < 6; ++u) {
+        const int c = c0 + u * 256 + tid;
+        if (c < total) {
+          const int row = c / CPR, kc = c - row * CPR;
+          const uint16_t* ap = A + (size_t)min(row, d.M - 1) * d.lda + kbase + kc * 8;
+          r[0][u] = *reinterpret_cast<const uint4*>(ap);
+          if constexpr (HL) r[1][u] = *reinterpret_cast<const uint4*>(ap + lo_delta);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 6; ++u) {
+        const int c = c0 + u * 256 + tid;
+        if (c < total) {
+          const int row = c / CPR, kc = c - row * CPR;
+          *reinterpret_cast<uint4*>(&sA[row * LDK + kc * 8]) = r[0][u];
+          if constexpr (HL) *reinterpret_cast<uint4*>(&sA[(Mpad + row) * LDK + kc * 8]) = r[1][u];
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int mc = 0; mc < MC; ++mc) {
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        const int row0 = mc * 64 + mt * 16;
+        if (row0 < Mpad) {
+          const uint16_t* sp = &sA[(row0 + (lane & 15)) * LDK + (lane >> 4) * 8];
+          bf16x8_t af[KF], al[HL ? KF : 1];
+#pragma unroll
+          for (int kf = 0; kf < KF; ++kf) {
+            af[kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(sp + kf * 32));
+            if constexpr (HL) al[kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(sp + Mpad * LDK + kf * 32));
+          }
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int kf = 0; kf < KF; ++kf) {
+              acc[mc][nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[kf], wf[nt][kf], acc[mc][nt][mt], 0, 0, 0);
+              if constexpr (HL)
+                acc[mc][nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[kf], wf[nt][kf], acc[mc][nt][mt], 0, 0, 0);
+            }
+        }
+      }
+    }
+    __syncthreads();
   }
+#pragma unroll
+  for (int mc = 0; mc < MC; ++mc)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        const int col = n0 + nt * 16 + (lane & 15);
+        const int row0 = mc * 64 + mt * 16 + (lane >> 4) * 4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) epilogue_store<bf16_t>(d, split, row0 + r, col, acc[mc][nt][mt][r]);
+      }
 }
 
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 namespace {
-enum { KIND_F32 = 0, KIND_TILE128 = 1, KIND_TILE64 = 2, KIND_STREAM = 3 };
+enum { KIND_F32 = 0, KIND_TILE128 = 1, KIND_KSLICE = 2 };
 constexpr int kMaxSkinnyRows = 256;
+constexpr int kNumCU = 256;
 
-int tile64_splits(int unit, int N, int K) {
+int f32_splits(int N, int K) {
   const int tiles = (N + 63) / 64;
   int best = 1;
   for (int s = 1; s <= 16; ++s) {
     if (K % s) continue;
     const int ks = K / s;
-    if (ks % unit || ks < 2 * unit) continue;
+    if (ks % 16 || ks < 32) continue;
     best = s;
     if (tiles * s >= 512) break;
   }
   return best;
+}
+
+size_t kslice_lds_bytes(int M, int kf, bool hl) {
+  const int Mpad = (M + 15) & ~15;
+  return (size_t)Mpad * (32 * kf + 8) * 2 * (hl ? 2 : 1);
 }
 }  // namespace
 
@@ -316,52 +357,70 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
     const GemmProblem& p = probs[i];
     if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
     if (dtype == BT_BF16 && (p.K % 64 || p.lda % 8)) return hipErrorInvalidValue;
+    if (p.M != probs[0].M) return hipErrorInvalidValue;
     max_m = p.M > max_m ? p.M : max_m;
     plan->splits[i] = 1;
   }
-  plan->nkf = 0;
+  plan->kf = 0;
   plan->nt = 1;
+  plan->mc = 1;
+  const bool hl = probs[0].A_lo != nullptr;
   if (dtype == BT_F32) {
     plan->kind = KIND_F32;
     if (max_m <= kMaxSkinnyRows)
       for (int i = 0; i < n_probs; ++i)
-        if (probs[i].epi == EPI_PARTIAL) plan->splits[i] = tile64_splits(16, probs[i].N, probs[i].K);
+        if (probs[i].epi == EPI_PARTIAL) plan->splits[i] = f32_splits(probs[i].N, probs[i].K);
     return hipSuccess;
   }
   if (max_m > kMaxSkinnyRows) { plan->kind = KIND_TILE128; return hipSuccess; }
-  // streaming kernel: one NKF for the whole group; full-K problems need K == 128*NKF
-  static const int cand[] = {16, 12, 8, 6, 4, 2};
-  for (int c : cand) {
-    bool ok = true;
-    for (int i = 0; i < n_probs && ok; ++i) {
+
+  // K-slice kernel.  Slice length: the longest of 256/192/128/64 that divides every K and keeps
+  // the staged activation slice within 80 KB of LDS (two workgroups per CU).
+  plan->kind = KIND_KSLICE;
+  plan->mc = (max_m + 63) / 64;
+  if (plan->mc == 3) plan->mc = 4;
+  int kf = 2;
+  for (int c : {8, 6, 4, 2}) {
+    bool ok = kslice_lds_bytes(max_m, c, hl) <= 80 * 1024;
+    for (int i = 0; i < n_probs && ok; ++i) ok = probs[i].K % (32 * c) == 0;
+    if (ok) { kf = c; break; }
+  }
+  plan->kf = kf;
+  // Columns per workgroup (64*nt) and K-splits: minimise the bytes a launch moves besides W
+  // (activation re-reads + partial-sum write and read-back) while keeping every CU busy.
+  double best_cost = 1e300;
+  for (int nt : {4, 2, 1}) {
+    if (nt * plan->mc > 8) continue;                       // accumulator registers
+    int spl[2] = {1, 1};
+    int wgs = 0;
+    double cost = 0;
+    // first pass: workgroups with no K split at all
+    for (int i = 0; i < n_probs; ++i) wgs += (probs[i].N + 64 * nt - 1) / (64 * nt);
+    for (int i = 0; i < n_probs; ++i) {
       const GemmProblem& p = probs[i];
-      if (p.K % (128 * c)) ok = false;
-      else if (p.epi != EPI_PARTIAL && p.K != 128 * c) ok = false;
-      else if (p.K / (128 * c) > 16) ok = false;
-    }
-    if (ok) {
-      plan->kind = KIND_STREAM;
-      plan->nkf = c;
-      for (int i = 0; i < n_probs; ++i) plan->splits[i] = probs[i].K / (128 * c);
-      // columns per workgroup = 16 * nt: wider tiles re-read the activations less often,
-      // as long as the launch still has >= 2 workgroups per CU and W fits in registers
-      plan->nt = 1;
-#ifdef BT_FORCE_NT
-      plan->nt = BT_FORCE_NT; if (plan->nt * c > 32) plan->nt = 32 / c >= 2 ? 2 : 1;
-      return hipSuccess;
-#endif
-      for (int nt = 4; nt > 1; nt >>= 1) {
-        if (nt * c > 32) continue;
-        int wgs = 0;
-        for (int i = 0; i < n_probs; ++i) wgs += ((probs[i].N + 16 * nt - 1) / (16 * nt)) * plan->splits[i];
-        if (wgs >= 512) { plan->nt = nt; break; }
+      const int tiles = (p.N + 64 * nt - 1) / (64 * nt), slices = p.K / (32 * kf);
+      if (p.epi == EPI_PARTIAL) {
+        // split until the launch has about two workgroups per CU, or one slice per workgroup
+        int s = 1;
+        while (s < slices && wgs < 2 * kNumCU) {
+          int nx = s + 1;
+          while (nx < slices && slices % nx) ++nx;
+          wgs += tiles * (nx - s);
+          s = nx;
+        }
+        spl[i] = s;
       }
-      return hipSuccess;
+      cost += (double)tiles * p.M * p.K * (hl ? 4 : 2);                          // activation reads
+      if (spl[i] > 1 || p.epi == EPI_PARTIAL) cost += (double)spl[i] * p.M * p.N * 8;   // partials out and back
+    }
+    if (wgs < kNumCU) cost *= (double)kNumCU / wgs;        // idle CUs stretch the launch
+    if (cost < best_cost) {
+      best_cost = cost;
+      plan->nt = nt;
+      plan->splits[0] = spl[0];
+      plan->splits[1] = spl[1];
     }
   }
-  plan->kind = KIND_TILE64;
-  for (int i = 0; i < n_probs; ++i)
-    if (probs[i].epi == EPI_PARTIAL) plan->splits[i] = tile64_splits(64, probs[i].N, probs[i].K);
   return hipSuccess;
 }
 
@@ -375,6 +434,35 @@ static int fill_tiles(GemmGroup& g) {
     begin += g.p[i].tiles_m * g.p[i].tiles_n * g.p[i].splits;
   }
   return begin;
+}
+
+template <int KF, int NT, int MC, bool HL>
+static hipError_t launch_kslice(GemmGroup& g, size_t lds, hipStream_t s) {
+  static bool attr_set = false;
+  auto kern = gemm_kslice_kernel<KF, NT, MC, HL>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  kern<<<fill_tiles<1 << 30, 64 * NT>(g), 256, lds, s>>>(g);
+  return hipSuccess;
+}
+
+template <int KF, bool HL>
+static hipError_t launch_kslice_kf(GemmGroup& g, int nt, int mc, size_t lds, hipStream_t s) {
+  const int key = nt * 10 + mc;
+  switch (key) {
+    case 11: return launch_kslice<KF, 1, 1, HL>(g, lds, s);
+    case 12: return launch_kslice<KF, 1, 2, HL>(g, lds, s);
+    case 14: return launch_kslice<KF, 1, 4, HL>(g, lds, s);
+    case 21: return launch_kslice<KF, 2, 1, HL>(g, lds, s);
+    case 22: return launch_kslice<KF, 2, 2, HL>(g, lds, s);
+    case 24: return launch_kslice<KF, 2, 4, HL>(g, lds, s);
+    case 41: return launch_kslice<KF, 4, 1, HL>(g, lds, s);
+    case 42: return launch_kslice<KF, 4, 2, HL>(g, lds, s);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const GemmPlan& plan, hipStream_t s) {
@@ -401,32 +489,24 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
       if (hl) gemm_bf16_kernel<128, 128, 2, 2, true><<<fill_tiles<128, 128>(g), 256, 0, s>>>(g);
       else gemm_bf16_kernel<128, 128, 2, 2, false><<<fill_tiles<128, 128>(g), 256, 0, s>>>(g);
       break;
-    case KIND_TILE64:
-      if (hl) gemm_bf16_kernel<64, 64, 1, 4, true><<<fill_tiles<64, 64>(g), 256, 0, s>>>(g);
-      else gemm_bf16_kernel<64, 64, 1, 4, false><<<fill_tiles<64, 64>(g), 256, 0, s>>>(g);
-      break;
-    case KIND_STREAM: {
-      // tiles_m == 1: the kernel loops over rows itself
-#define BT_STREAM(NKF_, NT_)                                                                          \
-  do {                                                                                                \
-    if (hl) gemm_stream_kernel<NKF_, NT_, true><<<fill_tiles<1 << 30, 16 * NT_>(g), 256, 0, s>>>(g);  \
-    else gemm_stream_kernel<NKF_, NT_, false><<<fill_tiles<1 << 30, 16 * NT_>(g), 256, 0, s>>>(g);    \
-  } while (0)
-#define BT_STREAM_NT(NKF_)                                      \
-  if (plan.nt == 4) { if constexpr (NKF_ * 4 <= 32) BT_STREAM(NKF_, 4); else return hipErrorInvalidValue; } \
-  else if (plan.nt == 2) { if constexpr (NKF_ * 2 <= 32) BT_STREAM(NKF_, 2); else return hipErrorInvalidValue; } \
-  else BT_STREAM(NKF_, 1)
-      switch (plan.nkf) {
-        case 2:  BT_STREAM_NT(2); break;
-        case 4:  BT_STREAM_NT(4); break;
-        case 6:  BT_STREAM_NT(6); break;
-        case 8:  BT_STREAM_NT(8); break;
-        case 12: BT_STREAM_NT(12); break;
-        case 16: BT_STREAM_NT(16); break;
-        default: return hipErrorInvalidValue;
+    case KIND_KSLICE: {
+      for (int i = 0; i < n_probs; ++i)
+        if (probs[i].K % (32 * plan.kf * plan.splits[i])) return hipErrorInvalidValue;
+      const size_t lds = kslice_lds_bytes(probs[0].M, plan.kf, hl);
+      if (lds > 96 * 1024) return hipErrorInvalidValue;
+      hipError_t e;
+      switch (plan.kf * 2 + (hl ? 1 : 0)) {
+        case 4:  e = launch_kslice_kf<2, false>(g, plan.nt, plan.mc, lds, s); break;
+        case 5:  e = launch_kslice_kf<2, true>(g, plan.nt, plan.mc, lds, s); break;
+        case 8:  e = launch_kslice_kf<4, false>(g, plan.nt, plan.mc, lds, s); break;
+        case 9:  e = launch_kslice_kf<4, true>(g, plan.nt, plan.mc, lds, s); break;
+        case 12: e = launch_kslice_kf<6, false>(g, plan.nt, plan.mc, lds, s); break;
+        case 13: e = launch_kslice_kf<6, true>(g, plan.nt, plan.mc, lds, s); break;
+        case 16: e = launch_kslice_kf<8, false>(g, plan.nt, plan.mc, lds, s); break;
+        case 17: e = launch_kslice_kf<8, true>(g, plan.nt, plan.mc, lds, s); break;
+        default: e = hipErrorInvalidValue;
       }
-#undef BT_STREAM_NT
-#undef BT_STREAM
+      if (e != hipSuccess) return e;
       break;
     }
     default:

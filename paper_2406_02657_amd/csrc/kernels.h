@@ -52,7 +52,8 @@ hipError_t launch_scatter_ids(const int32_t* ids, int32_t* cur, int batch, int b
 // ----------------------------------------------------------------------- GEMM
 enum { EPI_F32 = 0,        // out float [M, ldo]: acc + bias
        EPI_GELU = 1,       // out storage dtype: gelu(acc + bias)
-       EPI_PARTIAL = 2 };  // out float [splits][M][N]: raw partial sums (no bias)
+       EPI_PARTIAL = 2 };  // out float [splits][M][N]: raw partial sums (no bias); the consumer
+                           // sums the splits in order and applies bias / activation
 
 // out[M, N] = A[M, K] * W[N, K]^T (+ bias).  A, W in the storage dtype, row-major,
 // lda / K contiguous.
@@ -70,12 +71,32 @@ struct GemmProblem {
 // Which kernel serves a group of up to two problems, and into how many equal K
 // parts each EPI_PARTIAL problem is split (others: 1).  Depends on shapes only.
 struct GemmPlan {
-  int kind, nkf, nt;
+  int kind, kf, nt, mc;
   int splits[2];
 };
 hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan* plan);
 // Up to two independent problems in one launch.
 hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const GemmPlan& plan, hipStream_t s);
+
+// A matrix [rows, ld] that may still be in pieces: value(row, col) =
+// (bias ? bias[col] : 0) + sum over s < splits of base[s * stride + row * ld + col].
+struct PartialSrc {
+  const float* base;
+  const float* bias;
+  int splits;
+  size_t stride;
+};
+
+// MLP hidden activation from the up-projection's partial sums:
+// out[row, col] = gelu(value(row, col)) stored as a GEMM operand (hi / lo planes when out_lo_off).
+// Can ride along an attention launch (extra workgroups) or run alone.
+struct GeluJob {
+  PartialSrc src;
+  void* out;
+  size_t out_lo_off;
+  int rows, cols;      // rows == 0: no job
+};
+hipError_t launch_gelu_reduce(int dtype, const GeluJob& job, hipStream_t s);
 
 // ------------------------------------------------------------------ attention
 // Rotary tables: rope[pos * (rot/2) + t] = (cos, sin) of pos * 10000^(-2t/rot).
@@ -83,7 +104,9 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
 // Block decoder, after the QKV GEMM: rotate q in place (float, inside qkv),
 // rotate k, and store k, v into the block KV cache at position pos0 + m % n_new
 // of sequence m / n_new.  Cache layout per layer: K [B][H][n_cap][d_h], V same.
-hipError_t launch_rope_append(int dtype, float* qkv, void* Kc, void* Vc, const float2* rope,
+// qkv may arrive as split-K partials (src.splits > 1 and/or src.bias): the rotated q is then
+// written complete into plane 0 (src.base), which is what the attention kernels read.
+hipError_t launch_rope_append(int dtype, const PartialSrc& src, void* Kc, void* Vc, const float2* rope,
                               int n_rows, int n_new, int pos0, int n_heads, int d_head, int rot,
                               int n_cap, hipStream_t s);
 
@@ -92,7 +115,7 @@ hipError_t launch_rope_append(int dtype, float* qkv, void* Kc, void* Vc, const f
 // out_lo_off != 0 (here and below): out also gets the bf16 remainder plane.
 hipError_t launch_attn_block_decode(int dtype, const float* qkv, const void* Kc, const void* Vc,
                                     void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_keys,
-                                    int n_cap, hipStream_t s);
+                                    int n_cap, const GeluJob& gelu, hipStream_t s);
 
 // Block decoder prefill: causal attention of n_q queries per (b, h); query i sees rows [0, i].
 hipError_t launch_attn_block_prefill(int dtype, const float* qkv, const void* Kc, const void* Vc,
@@ -102,8 +125,8 @@ hipError_t launch_attn_block_prefill(int dtype, const float* qkv, const void* Kc
 // Token decoder: `rows` new local positions pos0 .. pos0+rows-1 per sequence.
 // Rotates q, k; appends k, v to the local cache [B][H][l_cap][d_h]; causal
 // attention over local rows [0, pos0+i]; out [B*rows, D] storage dtype.
-hipError_t launch_attn_local(int dtype, const float* qkv, void* Kl, void* Vl, const float2* rope,
+hipError_t launch_attn_local(int dtype, const PartialSrc& qkv, void* Kl, void* Vl, const float2* rope,
                              void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int rot, int rows,
-                             int pos0, int l_cap, hipStream_t s);
+                             int pos0, int l_cap, const GeluJob& gelu, hipStream_t s);
 
 }  // namespace bt
