@@ -68,12 +68,14 @@ hipError_t launch_token_embed(int dtype, const void* E_tok, const int32_t* cur, 
 }
 
 // ---------------------------------------------------------------------------
-// Residual update + LayerNorm.  One workgroup (256 threads) per row, the row
-// lives in registers (D <= 256 * kMaxPerThread).  Mean and biased variance are
-// taken in two passes over the registers, as the definition states them.
+// Residual update + LayerNorm.  One workgroup (256 threads) per row; a thread
+// owns VPT groups of four consecutive floats, kept in registers (D <= 1024*VPT).
+// The split-K partial sums of the two producing GEMMs are added in a fixed order
+// (deterministic); their loads are issued eight at a time without branches.
+// Mean and biased variance are taken in two passes over the registers, as the
+// definition states them.
 // ---------------------------------------------------------------------------
 constexpr int kLnThreads = 256;
-constexpr int kMaxPerThread = 16;   // D <= 4096
 
 __device__ __forceinline__ float block_sum_256(float v, float* red) {
   v = wave_sum(v);
@@ -84,67 +86,105 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
   return red[0] + red[1] + red[2] + red[3];
 }
 
-template <class T>
+__device__ __forceinline__ void add4(float4& a, const float4& b) { a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; }
+
+// acc += sum over s < splits of part[s * stride + off .. off+3], eight loads in flight
+__device__ __forceinline__ void add_partials(float4& acc, const float* part, int splits, size_t stride, size_t off) {
+  for (int s0 = 0; s0 < splits; s0 += 8) {
+    float4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s = min(s0 + u, splits - 1);
+      v[u] = *reinterpret_cast<const float4*>(part + (size_t)s * stride + off);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float k = (s0 + u < splits) ? 1.f : 0.f;
+      acc.x += k * v[u].x; acc.y += k * v[u].y; acc.z += k * v[u].z; acc.w += k * v[u].w;
+    }
+  }
+}
+
+template <class T, int VPT>
 __global__ __launch_bounds__(kLnThreads) void resid_ln_kernel(ResidLnArgs a) {
   __shared__ float red[4];
   const int i = blockIdx.x;
   const size_t row = (size_t)i * a.in_mul + a.in_off;
-  const int D = a.D;
-  float v[kMaxPerThread];
+  const int D = a.D, G = D >> 2;
+  float4 v[VPT];
   float* xr = a.x + row * D;
 #pragma unroll
-  for (int c = 0; c < kMaxPerThread; ++c) {
-    const int d = threadIdx.x + c * kLnThreads;
-    float acc = 0.f;
-    if (d < D) {
-      acc = xr[d];
-      if (a.partA) {
-        float t = a.biasA ? a.biasA[d] : 0.f;
-#pragma unroll 4
-        for (int s = 0; s < a.splitsA; ++s) t += a.partA[(size_t)s * a.part_stride + row * D + d];
-        acc += t;
-      }
-      if (a.partB) {
-        float t = a.biasB ? a.biasB[d] : 0.f;
-#pragma unroll 4
-        for (int s = 0; s < a.splitsB; ++s) t += a.partB[(size_t)s * a.part_stride + row * D + d];
-        acc += t;
-      }
-      if (a.write_x) xr[d] = acc;
+  for (int c = 0; c < VPT; ++c) {
+    const int g = min((int)threadIdx.x + c * kLnThreads, G - 1);     // clamped: no branch around the loads
+    float4 acc = *reinterpret_cast<const float4*>(xr + 4 * g);
+    if (a.partA) {
+      if (a.biasA) add4(acc, *reinterpret_cast<const float4*>(a.biasA + 4 * g));
+      add_partials(acc, a.partA, a.splitsA, a.part_stride, row * D + 4 * g);
+    }
+    if (a.partB) {
+      if (a.biasB) add4(acc, *reinterpret_cast<const float4*>(a.biasB + 4 * g));
+      add_partials(acc, a.partB, a.splitsB, a.part_stride, row * D + 4 * g);
     }
     v[c] = acc;
   }
   float sum = 0.f;
 #pragma unroll
-  for (int c = 0; c < kMaxPerThread; ++c) sum += v[c];          // entries past D are 0
+  for (int c = 0; c < VPT; ++c) {
+    const bool live = (int)threadIdx.x + c * kLnThreads < G;
+    if (live) {
+      if (a.write_x) *reinterpret_cast<float4*>(xr + 4 * (threadIdx.x + c * kLnThreads)) = v[c];
+      sum += (v[c].x + v[c].y) + (v[c].z + v[c].w);
+    }
+  }
   const float mean = block_sum_256(sum, red) / (float)D;
   float sq = 0.f;
 #pragma unroll
-  for (int c = 0; c < kMaxPerThread; ++c) {
-    const float t = (threadIdx.x + c * kLnThreads < D) ? v[c] - mean : 0.f;
-    sq += t * t;
+  for (int c = 0; c < VPT; ++c) {
+    if ((int)threadIdx.x + c * kLnThreads < G) {
+      const float t0 = v[c].x - mean, t1 = v[c].y - mean, t2 = v[c].z - mean, t3 = v[c].w - mean;
+      sq += (t0 * t0 + t1 * t1) + (t2 * t2 + t3 * t3);
+    }
   }
   const float var = block_sum_256(sq, red) / (float)D;
   const float rstd = 1.0f / sqrtf(var + a.eps);
 #pragma unroll
-  for (int c = 0; c < kMaxPerThread; ++c) {
-    const int d = threadIdx.x + c * kLnThreads;
-    if (d < D) {
-      const float n = (v[c] - mean) * rstd;
-      const float o1 = n * a.g1[d] + a.b1[d];
-      if (a.u1_f32) reinterpret_cast<float*>(a.u1)[(size_t)i * D + d] = o1;
-      else store_act<T>(reinterpret_cast<T*>(a.u1), (size_t)i * D + d, a.lo_off, o1);
-      if (a.g2) store_act<T>(reinterpret_cast<T*>(a.u2), (size_t)i * D + d, a.lo_off, n * a.g2[d] + a.b2[d]);
+  for (int c = 0; c < VPT; ++c) {
+    const int g = threadIdx.x + c * kLnThreads;
+    if (g < G) {
+      const float n[4] = {(v[c].x - mean) * rstd, (v[c].y - mean) * rstd, (v[c].z - mean) * rstd, (v[c].w - mean) * rstd};
+      const float4 g1 = *reinterpret_cast<const float4*>(a.g1 + 4 * g), b1 = *reinterpret_cast<const float4*>(a.b1 + 4 * g);
+      const float o1[4] = {n[0] * g1.x + b1.x, n[1] * g1.y + b1.y, n[2] * g1.z + b1.z, n[3] * g1.w + b1.w};
+      const size_t o = (size_t)i * D + 4 * g;
+      if (a.u1_f32) {
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.u1) + o) = make_float4(o1[0], o1[1], o1[2], o1[3]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) store_act<T>(reinterpret_cast<T*>(a.u1), o + e, a.lo_off, o1[e]);
+      }
+      if (a.g2) {
+        const float4 g2 = *reinterpret_cast<const float4*>(a.g2 + 4 * g), b2 = *reinterpret_cast<const float4*>(a.b2 + 4 * g);
+        const float o2[4] = {n[0] * g2.x + b2.x, n[1] * g2.y + b2.y, n[2] * g2.z + b2.z, n[3] * g2.w + b2.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) store_act<T>(reinterpret_cast<T*>(a.u2), o + e, a.lo_off, o2[e]);
+      }
     }
   }
 }
 
+template <class T>
+static hipError_t launch_resid_ln_t(const ResidLnArgs& a, hipStream_t s) {
+  const int G = a.D / 4;
+  if (G <= kLnThreads) resid_ln_kernel<T, 1><<<a.n_rows, kLnThreads, 0, s>>>(a);
+  else if (G <= 2 * kLnThreads) resid_ln_kernel<T, 2><<<a.n_rows, kLnThreads, 0, s>>>(a);
+  else if (G <= 4 * kLnThreads) resid_ln_kernel<T, 4><<<a.n_rows, kLnThreads, 0, s>>>(a);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
 hipError_t launch_resid_ln(int dtype, const ResidLnArgs& a, hipStream_t s) {
   if (a.n_rows <= 0) return hipSuccess;
-  if (a.D > kLnThreads * kMaxPerThread) return hipErrorInvalidValue;
-  if (dtype == BT_F32) resid_ln_kernel<float><<<a.n_rows, kLnThreads, 0, s>>>(a);
-  else resid_ln_kernel<bf16_t><<<a.n_rows, kLnThreads, 0, s>>>(a);
-  return hipGetLastError();
+  if (a.D % 4) return hipErrorInvalidValue;
+  return dtype == BT_F32 ? launch_resid_ln_t<float>(a, s) : launch_resid_ln_t<bf16_t>(a, s);
 }
 
 // ---------------------------------------------------------------------------

@@ -260,27 +260,26 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
 #pragma unroll
       for (int kf = 0; kf < KF; ++kf) wf[nt][kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wp + kf * 32));
     }
-    // activation slice -> LDS (rows past M repeat the last row; never stored)
+    // activation slice -> LDS.  No branches here: chunk indices past the end are clamped to the
+    // last chunk (which is then loaded and stored more than once, with the same bytes), so the
+    // compiler keeps all loads in flight together instead of sinking them into conditionals.
+    // Rows past M repeat the last row; their products are never stored.
     for (int c0 = 0; c0 < total; c0 += 256 * 6) {
       uint4 r[PL][6];
+      int lds_off[6];
 #pragma unroll
       for (int u = 0; u < 6; ++u) {
-        const int c = c0 + u * 256 + tid;
-        if (c < total) {
-          const int row = c / CPR, kc = c - row * CPR;
-          const uint16_t* ap = A + (size_t)min(row, d.M - 1) * d.lda + kbase + kc * 8;
-          r[0][u] = *reinterpret_cast<const uint4*>(ap);
-          if constexpr (HL) r[1][u] = *reinterpret_cast<const uint4*>(ap + lo_delta);
-        }
+        const int c = min(c0 + u * 256 + tid, total - 1);
+        const int row = c / CPR, kc = c - row * CPR;
+        const uint16_t* ap = A + (size_t)min(row, d.M - 1) * d.lda + kbase + kc * 8;
+        lds_off[u] = row * LDK + kc * 8;
+        r[0][u] = *reinterpret_cast<const uint4*>(ap);
+        if constexpr (HL) r[1][u] = *reinterpret_cast<const uint4*>(ap + lo_delta);
       }
 #pragma unroll
       for (int u = 0; u < 6; ++u) {
-        const int c = c0 + u * 256 + tid;
-        if (c < total) {
-          const int row = c / CPR, kc = c - row * CPR;
-          *reinterpret_cast<uint4*>(&sA[row * LDK + kc * 8]) = r[0][u];
-          if constexpr (HL) *reinterpret_cast<uint4*>(&sA[(Mpad + row) * LDK + kc * 8]) = r[1][u];
-        }
+        *reinterpret_cast<uint4*>(&sA[lds_off[u]]) = r[0][u];
+        if constexpr (HL) *reinterpret_cast<uint4*>(&sA[Mpad * LDK + lds_off[u]]) = r[1][u];
       }
     }
     __syncthreads();
@@ -375,50 +374,46 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
   if (max_m > kMaxSkinnyRows) { plan->kind = KIND_TILE128; return hipSuccess; }
 
   // K-slice kernel.  Slice length: the longest of 256/192/128/64 that divides every K and keeps
-  // the staged activation slice within 80 KB of LDS (two workgroups per CU).
+  // the staged activation slice within 64 KB of LDS (at least two workgroups per CU).
   plan->kind = KIND_KSLICE;
   plan->mc = (max_m + 63) / 64;
   if (plan->mc == 3) plan->mc = 4;
   int kf = 2;
   for (int c : {8, 6, 4, 2}) {
-    bool ok = kslice_lds_bytes(max_m, c, hl) <= 80 * 1024;
+    bool ok = kslice_lds_bytes(max_m, c, hl) <= 64 * 1024;
     for (int i = 0; i < n_probs && ok; ++i) ok = probs[i].K % (32 * c) == 0;
     if (ok) { kf = c; break; }
   }
   plan->kf = kf;
-  // Columns per workgroup (64*nt) and K-splits: minimise the bytes a launch moves besides W
-  // (activation re-reads + partial-sum write and read-back) while keeping every CU busy.
+  // Columns per workgroup (64*nt) and K-slices per workgroup (q): minimise the bytes a launch
+  // moves besides W (activation re-reads + partial sums written and read back) while keeping
+  // every CU busy.  Problems that must finish their own epilogue keep all slices in one workgroup.
   double best_cost = 1e300;
   for (int nt : {4, 2, 1}) {
     if (nt * plan->mc > 8) continue;                       // accumulator registers
-    int spl[2] = {1, 1};
-    int wgs = 0;
-    double cost = 0;
-    // first pass: workgroups with no K split at all
-    for (int i = 0; i < n_probs; ++i) wgs += (probs[i].N + 64 * nt - 1) / (64 * nt);
-    for (int i = 0; i < n_probs; ++i) {
-      const GemmProblem& p = probs[i];
-      const int tiles = (p.N + 64 * nt - 1) / (64 * nt), slices = p.K / (32 * kf);
-      if (p.epi == EPI_PARTIAL) {
-        // split until the launch has about two workgroups per CU, or one slice per workgroup
-        int s = 1;
-        while (s < slices && wgs < 2 * kNumCU) {
-          int nx = s + 1;
-          while (nx < slices && slices % nx) ++nx;
-          wgs += tiles * (nx - s);
-          s = nx;
+    for (int q : {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 128}) {
+      int spl[2] = {1, 1};
+      int wgs = 0;
+      double cost = 0;
+      for (int i = 0; i < n_probs; ++i) {
+        const GemmProblem& p = probs[i];
+        const int tiles = (p.N + 64 * nt - 1) / (64 * nt), slices = p.K / (32 * kf);
+        if (p.epi == EPI_PARTIAL) {
+          int qi = q < slices ? q : slices;
+          while (slices % qi) --qi;                        // largest divisor of slices <= q
+          spl[i] = slices / qi;
         }
-        spl[i] = s;
+        wgs += tiles * spl[i];
+        cost += (double)tiles * p.M * p.K * (hl ? 4 : 2);                  // activation reads
+        if (p.epi == EPI_PARTIAL) cost += (double)spl[i] * p.M * p.N * 8;  // partials out and back
       }
-      cost += (double)tiles * p.M * p.K * (hl ? 4 : 2);                          // activation reads
-      if (spl[i] > 1 || p.epi == EPI_PARTIAL) cost += (double)spl[i] * p.M * p.N * 8;   // partials out and back
-    }
-    if (wgs < kNumCU) cost *= (double)kNumCU / wgs;        // idle CUs stretch the launch
-    if (cost < best_cost) {
-      best_cost = cost;
-      plan->nt = nt;
-      plan->splits[0] = spl[0];
-      plan->splits[1] = spl[1];
+      if (wgs < kNumCU) cost *= (double)kNumCU / wgs;      // idle CUs stretch the launch
+      if (cost < best_cost) {
+        best_cost = cost;
+        plan->nt = nt;
+        plan->splits[0] = spl[0];
+        plan->splits[1] = spl[1];
+      }
     }
   }
   return hipSuccess;
