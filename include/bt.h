@@ -75,6 +75,8 @@ typedef struct {
   int32_t prefill_rows;     /* prompt blocks processed per prefill chunk; 0 = default (16384) */
   int32_t act_split;        /* bf16 mode only: activations enter the MFMA GEMMs as hi + lo bf16 pairs
                                (about 16 mantissa bits): 0 never, 1 in decode steps, 2 also in prefill */
+  int32_t use_graphs;       /* 1: decode steps are captured into HIP graphs (one per position in the
+                               block) and replayed; 0: every launch is issued eagerly */
   float   ln_eps;
 } bt_config;
 

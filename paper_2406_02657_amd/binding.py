@@ -27,7 +27,7 @@ class bt_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "vocab", "block_len", "d_model", "n_heads", "d_ff", "n_block_layers", "n_token_layers",
         "prefix_len", "dtype", "max_batch", "max_blocks", "rotary_dims", "parallel_residual",
-        "prefill_rows", "act_split")] + [("ln_eps", C.c_float)]
+        "prefill_rows", "act_split", "use_graphs")] + [("ln_eps", C.c_float)]
 
 
 _LAYER_FIELDS = ("ln1_g", "ln1_b", "W_qkv", "b_qkv", "W_o", "b_o", "ln2_g", "ln2_b", "W_up", "b_up", "W_down", "b_down")
@@ -82,7 +82,7 @@ class BTError(RuntimeError):
 DEFAULT_ACT_SPLIT = 2
 
 
-def make_config(cfg, max_batch=None, max_blocks=None, prefill_rows=0, act_split=None) -> bt_config:
+def make_config(cfg, max_batch=None, max_blocks=None, prefill_rows=0, act_split=None, use_graphs=1) -> bt_config:
     """cfg: any object with the fields of synth.BTConfig."""
     return bt_config(
         vocab=cfg.vocab, block_len=cfg.block_len, d_model=cfg.d_model, n_heads=cfg.n_heads, d_ff=cfg.d_ff,
@@ -91,19 +91,20 @@ def make_config(cfg, max_batch=None, max_blocks=None, prefill_rows=0, act_split=
         max_batch=cfg.batch if max_batch is None else max_batch,
         max_blocks=cfg.max_blocks if max_blocks is None else max_blocks,
         rotary_dims=cfg.rot, parallel_residual=cfg.parallel_residual, prefill_rows=prefill_rows,
-        act_split=DEFAULT_ACT_SPLIT if act_split is None else act_split, ln_eps=cfg.ln_eps)
+        act_split=DEFAULT_ACT_SPLIT if act_split is None else act_split, use_graphs=int(use_graphs),
+        ln_eps=cfg.ln_eps)
 
 
 class Model:
     """Owns the device copies of the weights and the workspace; forwards to the C ABI."""
 
     def __init__(self, cfg, weights, max_batch=None, max_blocks=None, prefill_rows=0, act_split=None,
-                 device="cuda:0"):
+                 use_graphs=1, device="cuda:0"):
         import torch
         self.torch = torch
         self.device = torch.device(device)
         self.cfg = cfg
-        self.c = make_config(cfg, max_batch, max_blocks, prefill_rows, act_split)
+        self.c = make_config(cfg, max_batch, max_blocks, prefill_rows, act_split, use_graphs)
         self._keep = {}
         for name, arr in weights.items():
             a = np.ascontiguousarray(arr)

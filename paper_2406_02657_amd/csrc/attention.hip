@@ -146,16 +146,15 @@ __device__ __forceinline__ void wave_attend(const float* q, const T* __restrict_
 template <class T, int DH, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(const float* __restrict__ qkv, const T* __restrict__ Kc,
                                                                     const T* __restrict__ Vc, T* __restrict__ out,
-                                                                    size_t out_lo_off, int n_heads, int n_keys, int n_cap,
-                                                                    int n_attn_blocks, GeluJob gelu) {
+                                                                    size_t out_lo_off, int n_heads, int n_keys_arg,
+                                                                    const int* __restrict__ n_dev, int n_cap) {
   using R = RowMap<T, DH>;
   constexpr int EPC = R::EPC, LPR = R::LPR;
   __shared__ float s_m[NW], s_l[NW];
   __shared__ float s_acc[NW][DH];
-  if ((int)blockIdx.x >= n_attn_blocks) {
-    gelu_reduce_block<T>(gelu, blockIdx.x - n_attn_blocks, gridDim.x - n_attn_blocks);
-    return;
-  }
+  // the number of cached blocks may live in device memory, so that a captured graph of the
+  // step stays valid while the cache grows
+  const int n_keys = n_dev ? min(*n_dev + 1, n_cap) : n_keys_arg;
   const int bh = blockIdx.x;
   const int b = bh / n_heads, h = bh - b * n_heads;
   const int D = n_heads * DH;
@@ -244,8 +243,14 @@ __global__ __launch_bounds__(256) void attn_block_prefill_kernel(const float* __
 // ---------------------------------------------------------------------------
 template <class T>
 __global__ __launch_bounds__(256) void rope_append_kernel(PartialSrc src, T* __restrict__ Kc, T* __restrict__ Vc,
-                                                          const float2* __restrict__ rope, int n_new, int pos0,
-                                                          int n_heads, int DH, int rot, int n_cap) {
+                                                          const float2* __restrict__ rope, int n_new, int pos0_arg,
+                                                          const int* __restrict__ n_dev, int n_heads, int DH, int rot,
+                                                          int n_cap, int n_rows, GeluJob gelu) {
+  if ((int)blockIdx.x >= n_rows) {
+    gelu_reduce_block<T>(gelu, blockIdx.x - n_rows, gridDim.x - n_rows);
+    return;
+  }
+  const int pos0 = n_dev ? min(*n_dev, n_cap - 1) : pos0_arg;
   const int m = blockIdx.x;
   const int b = m / n_new, pos = pos0 + (m - b * n_new);
   const int D = n_heads * DH, half = rot / 2;
@@ -391,13 +396,16 @@ __global__ void attn_local_kernel(PartialSrc qkv, T* __restrict__ Kl, T* __restr
   }
 
 hipError_t launch_rope_append(int dtype, const PartialSrc& src, void* Kc, void* Vc, const float2* rope,
-                              int n_rows, int n_new, int pos0, int n_heads, int d_head, int rot,
-                              int n_cap, hipStream_t s) {
+                              int n_rows, int n_new, int pos0, const int* n_dev, int n_heads, int d_head, int rot,
+                              int n_cap, const GeluJob& gelu, hipStream_t s) {
   if (n_rows <= 0) return hipSuccess;
+  if (n_dev && n_new != 1) return hipErrorInvalidValue;
+  if (gelu.rows > 0 && gelu.cols % 4) return hipErrorInvalidValue;
+  const int grid = n_rows + gelu_blocks(gelu);
   if (dtype == BT_F32)
-    rope_append_kernel<float><<<n_rows, 256, 0, s>>>(src, (float*)Kc, (float*)Vc, rope, n_new, pos0, n_heads, d_head, rot, n_cap);
+    rope_append_kernel<float><<<grid, 256, 0, s>>>(src, (float*)Kc, (float*)Vc, rope, n_new, pos0, n_dev, n_heads, d_head, rot, n_cap, n_rows, gelu);
   else
-    rope_append_kernel<bf16_t><<<n_rows, 256, 0, s>>>(src, (bf16_t*)Kc, (bf16_t*)Vc, rope, n_new, pos0, n_heads, d_head, rot, n_cap);
+    rope_append_kernel<bf16_t><<<grid, 256, 0, s>>>(src, (bf16_t*)Kc, (bf16_t*)Vc, rope, n_new, pos0, n_dev, n_heads, d_head, rot, n_cap, n_rows, gelu);
   return hipGetLastError();
 }
 
@@ -412,18 +420,16 @@ hipError_t launch_gelu_reduce(int dtype, const GeluJob& job, hipStream_t s) {
 
 hipError_t launch_attn_block_decode(int dtype, const float* qkv, const void* Kc, const void* Vc,
                                     void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_keys,
-                                    int n_cap, const GeluJob& gelu, hipStream_t s) {
-  if (n_keys < 1 || n_keys > n_cap) return hipErrorInvalidValue;
-  if (gelu.rows > 0 && gelu.cols % 4) return hipErrorInvalidValue;
+                                    const int* n_dev, int n_cap, hipStream_t s) {
+  if (!n_dev && (n_keys < 1 || n_keys > n_cap)) return hipErrorInvalidValue;
   constexpr int NW = 4;
-  const int n_attn = batch * n_heads;
-  const int grid = n_attn + gelu_blocks(gelu);
+  const int grid = batch * n_heads;
   if (dtype == BT_F32) {
     BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<float, DH, NW><<<grid, NW * 64, 0, s>>>(
-        qkv, (const float*)Kc, (const float*)Vc, (float*)out, 0, n_heads, n_keys, n_cap, n_attn, gelu)));
+        qkv, (const float*)Kc, (const float*)Vc, (float*)out, 0, n_heads, n_keys, n_dev, n_cap)));
   } else {
     BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<bf16_t, DH, NW><<<grid, NW * 64, 0, s>>>(
-        qkv, (const bf16_t*)Kc, (const bf16_t*)Vc, (bf16_t*)out, out_lo_off, n_heads, n_keys, n_cap, n_attn, gelu)));
+        qkv, (const bf16_t*)Kc, (const bf16_t*)Vc, (bf16_t*)out, out_lo_off, n_heads, n_keys, n_dev, n_cap)));
   }
   return hipGetLastError();
 }

@@ -23,7 +23,7 @@ constexpr int kSkinnyRows = 256;     // GEMMs with at most this many rows may sp
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct Layout {
-  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cur, total;
+  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cur, state, total;
   size_t blk_layer_stride, loc_layer_stride;   // bytes between layers (K then V inside)
   size_t part_elems;                           // floats in each of part_o, part_d
   size_t qkv_elems, part_u_elems;              // floats in qkv (may hold split-K pieces) and part_u
@@ -48,6 +48,7 @@ int check_config(const bt_config& c, std::string* why) {
   if (c.d_ff % 8) return bad("d_ff must be a multiple of 8");
   if (c.prefill_rows < 0) return bad("prefill_rows < 0");
   if (c.act_split < 0 || c.act_split > 2) return bad("act_split must be 0, 1 or 2");
+  if (c.use_graphs < 0 || c.use_graphs > 1) return bad("use_graphs must be 0 or 1");
   if (!(c.ln_eps >= 0.f)) return bad("ln_eps < 0");
   const int l_cap = (c.prefix_len > 0 ? c.prefix_len : 1) + c.block_len;
   if ((size_t)(2 * l_cap + 2) * dh * sizeof(float) > 60 * 1024) return bad("prefix_len + block_len too large for the local-attention kernel");
@@ -95,6 +96,7 @@ void make_layout(const bt_config& c, Layout& L) {
   L.hfin = take(B * D * 4);
   L.logits = take(B * (size_t)c.vocab * 4);
   L.cur = take(B * c.block_len * 4);
+  L.state = take(256);
   L.total = off;
 }
 
@@ -114,6 +116,9 @@ struct bt_model {
   std::vector<hipEvent_t> ev;      // pairs (start, stop)
   size_t ev_used;
   std::string err;
+  struct StepGraph { hipGraphExec_t exec = nullptr; int seen = 0; };
+  std::vector<StepGraph> graphs;   // one per step kind: r = 0..L_B-1 without, [L_B] with the block decoder
+  bool graphs_ok;
 
   template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
 };
@@ -131,6 +136,14 @@ int fail(bt_model* m, int code, const std::string& msg) {
     if (e_ != hipSuccess)                                                                \
       return fail((m), BT_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));   \
   } while (0)
+
+void drop_graphs(bt_model* m) {
+  for (auto& g : m->graphs) {
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    g.exec = nullptr;
+    g.seen = 0;
+  }
+}
 
 enum Mode { MODE_BLOCK_PREFILL, MODE_BLOCK_DECODE, MODE_TOKEN };
 
@@ -229,7 +242,8 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     BT_HIP(m, launch_resid_ln(dt, r, s));
     return BT_OK;
   };
-  // attention of layer l; `gelu` (may be empty) rides along as extra workgroups where possible
+  // attention of layer l; `gelu` (may be empty) rides along as extra workgroups of the local
+  // attention or of the rotary/append launch
   auto attention = [&](int l, const GeluJob& gelu) -> int {
     const PartialSrc qsrc{qkv, pieces ? (const float*)lw[l].b_qkv : nullptr, sQ, (size_t)M * 3 * D};
     if (a.mode == MODE_TOKEN) {
@@ -244,10 +258,11 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     const size_t seq = (size_t)a.b0 * H * c.max_blocks * dh * L.esz;
     char* Kc = base + seq;
     char* Vc = base + half + seq;
-    BT_HIP(m, launch_rope_append(dt, qsrc, Kc, Vc, rope, M, a.rows, a.pos0, H, dh, c.rotary_dims, c.max_blocks, s));
+    BT_HIP(m, launch_rope_append(dt, qsrc, Kc, Vc, rope, M, a.rows, a.pos0,
+                                 a.mode == MODE_BLOCK_DECODE ? m->at<int>(L.state) : nullptr, H, dh, c.rotary_dims,
+                                 c.max_blocks, gelu, s));
     if (a.mode == MODE_BLOCK_PREFILL) {
       BT_HIP(m, launch_attn_block_prefill(dt, qkv, Kc, Vc, ao, loD, a.batch, H, dh, a.rows, c.max_blocks, s));
-      BT_HIP(m, launch_gelu_reduce(dt, gelu, s));
     } else {
       const int n_keys = a.pos0 + 1;
       hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -264,7 +279,8 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
         m->ev_used += 2;
         BT_HIP(m, hipEventRecord(e0, s));
       }
-      BT_HIP(m, launch_attn_block_decode(dt, qkv, Kc, Vc, ao, loD, a.batch, H, dh, n_keys, c.max_blocks, gelu, s));
+      BT_HIP(m, launch_attn_block_decode(dt, qkv, Kc, Vc, ao, loD, a.batch, H, dh, n_keys, m->at<int>(L.state),
+                                         c.max_blocks, s));
       if (m->profile) {
         BT_HIP(m, hipEventRecord(e1, s));
         m->st.attn_block_launches += 1;
@@ -383,6 +399,8 @@ int bt_create(const bt_config* cfg, const bt_weights* w, void* workspace_dev, si
   std::memset(&m->st, 0, sizeof(m->st));
   m->profile = false;
   m->ev_used = 0;
+  m->graphs.assign(cfg->block_len + 1, bt_model::StepGraph());
+  m->graphs_ok = true;
 
   // rotary table: (cos, sin) of pos * 10000^(-2t/rot), computed in double on the host
   const int half = cfg->rotary_dims / 2;
@@ -423,6 +441,8 @@ int bt_prefill(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t pr
                        m->ws + L.ctx + (size_t)b0 * c.d_model * ctx_esz, ctx_f32, bc, n_p, n_p - 1);
     if (rc) return rc;
   }
+  BT_HIP(m, launch_state_set(m->at<int>(L.state), n_p, m->stream));
+  if (batch != m->batch) drop_graphs(m);      // captured launches are sized for one batch
   m->batch = batch;
   m->n_blocks = n_p;
   m->r = 0;
@@ -435,32 +455,28 @@ int bt_prefill(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t pr
   return BT_OK;
 }
 
-int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
-  if (!m) return BT_ERR_ARG;
+// Enqueue every launch of one decode step.  with_block: embed the finished block and run the
+// block decoder first (r == 0 only).  ids_out: where argmax writes the ids besides the open
+// block's buffer (null inside a captured graph, whose launches must not depend on the caller's
+// output pointer).
+static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
   const bt_config& c = m->cfg;
-  if (!next_ids_dev) return fail(m, BT_ERR_ARG, "next_ids_dev is null");
-  if (m->batch == 0) return fail(m, BT_ERR_STATE, "decode before prefill");
-  if (batch != m->batch) return fail(m, BT_ERR_STATE, "batch differs from the prefill's");
   const Layout& L = m->L;
-  const int D = c.d_model, B = batch;
+  const int D = c.d_model, B = m->batch;
   hipStream_t s = m->stream;
   int32_t* cur = m->at<int32_t>(L.cur);
   float* x = m->at<float>(L.x);
   const bool ctx_f32 = c.prefix_len == 0;
   const size_t fin_lo = (c.dtype == BT_BF16 && c.act_split >= 1) ? (size_t)c.max_batch * D : 0;
   int rows, pos0;
-  if (m->r == 0) {
-    if (!m->have_context) {
-      if (m->n_blocks >= c.max_blocks) return fail(m, BT_ERR_CAPACITY, "block KV cache is full");
+  if (r == 0) {
+    if (with_block) {
       BT_HIP(m, launch_embed_concat(c.dtype, m->w.E_emb, cur, x, B, c.block_len, D / c.block_len, s));
       StackArgs a{MODE_BLOCK_DECODE, B, B, 0, 1, m->n_blocks};
       int rc = run_stack(m, m->blk.data(), c.n_block_layers, a, m->w.blk_lnf_g, m->w.blk_lnf_b,
                          m->ws + L.ctx, ctx_f32, B, 1, 0);
       if (rc) return rc;
-      m->st.block_passes += 1;
-      m->st.block_kv_rows_read += m->n_blocks + 1;
-      m->st.block_kv_bytes_read += (int64_t)(m->n_blocks + 1) * B * c.n_block_layers * 2 * D * L.esz;
-      m->n_blocks += 1;
+      BT_HIP(m, launch_state_add(m->at<int>(L.state), 1, s));
     }
     if (c.prefix_len > 0) {
       GemmProblem p{m->ws + L.ctx, m->w.W_prefix, (const float*)m->w.b_prefix, x, B, c.prefix_len * D, D, D,
@@ -473,11 +489,10 @@ int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
     }
     rows = L.n_pref;
     pos0 = 0;
-    m->have_context = false;
   } else {
-    BT_HIP(m, launch_token_embed(c.dtype, m->w.E_tok, cur, x, B, c.block_len, m->r - 1, D, s));
+    BT_HIP(m, launch_token_embed(c.dtype, m->w.E_tok, cur, x, B, c.block_len, r - 1, D, s));
     rows = 1;
-    pos0 = L.n_pref + m->r - 1;
+    pos0 = L.n_pref + r - 1;
   }
   StackArgs a{MODE_TOKEN, B * rows, B, 0, rows, pos0};
   int rc = run_stack(m, m->tok.data(), c.n_token_layers, a, m->w.tok_lnf_g, m->w.tok_lnf_b,
@@ -488,11 +503,73 @@ int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
   GemmPlan pl{};
   BT_HIP(m, gemm_plan(c.dtype, &p, 1, &pl));
   BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));
-  BT_HIP(m, launch_argmax(m->at<float>(L.logits), B, c.vocab, next_ids_dev, cur, c.block_len, m->r, s));
+  BT_HIP(m, launch_argmax(m->at<float>(L.logits), B, c.vocab, ids_out, cur, c.block_len, r, s));
+  return BT_OK;
+}
+
+int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
+  if (!m) return BT_ERR_ARG;
+  const bt_config& c = m->cfg;
+  if (!next_ids_dev) return fail(m, BT_ERR_ARG, "next_ids_dev is null");
+  if (m->batch == 0) return fail(m, BT_ERR_STATE, "decode before prefill");
+  if (batch != m->batch) return fail(m, BT_ERR_STATE, "batch differs from the prefill's");
+  const Layout& L = m->L;
+  const int r = m->r;
+  const bool with_block = r == 0 && !m->have_context;
+  if (with_block && m->n_blocks >= c.max_blocks) return fail(m, BT_ERR_CAPACITY, "block KV cache is full");
+  hipStream_t s = m->stream;
+
+  // A step kind (position in the block, with or without the block decoder) is a fixed launch
+  // sequence: the count of cached blocks is read from device memory.  Its first occurrence runs
+  // eagerly, the second is captured into a graph, later ones replay it.
+  const int kind = with_block ? c.block_len : r;
+  bool done = false;
+  if (m->graphs_ok && c.use_graphs && !m->profile && c.prefix_len > 0) {
+    bt_model::StepGraph& g = m->graphs[kind];
+    if (g.exec) {
+      BT_HIP(m, hipGraphLaunch(g.exec, s));
+      done = true;
+    } else if (g.seen >= 1) {
+      hipGraph_t graph = nullptr;
+      hipError_t e = hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal);
+      if (e == hipSuccess) {
+        const int rc = enqueue_step(m, r, with_block, nullptr);
+        e = hipStreamEndCapture(s, &graph);
+        if (rc != BT_OK || e != hipSuccess || !graph) {
+          if (graph) (void)hipGraphDestroy(graph);
+          (void)hipGetLastError();
+          m->graphs_ok = false;          // fall back to eager launches for good
+        } else {
+          e = hipGraphInstantiate(&g.exec, graph, nullptr, nullptr, 0);
+          (void)hipGraphDestroy(graph);
+          if (e != hipSuccess) { g.exec = nullptr; m->graphs_ok = false; (void)hipGetLastError(); }
+          else { BT_HIP(m, hipGraphLaunch(g.exec, s)); done = true; }
+        }
+      } else {
+        (void)hipGetLastError();
+        m->graphs_ok = false;
+      }
+    }
+    g.seen += 1;
+  }
+  if (done) {
+    BT_HIP(m, launch_gather_ids(m->at<int32_t>(L.cur), next_ids_dev, batch, c.block_len, r, s));
+  } else {
+    const int rc = enqueue_step(m, r, with_block, next_ids_dev);
+    if (rc) return rc;
+  }
+  const int rows = r == 0 ? L.n_pref : 1, pos0 = r == 0 ? 0 : L.n_pref + r - 1;
+  if (with_block) {
+    m->st.block_passes += 1;
+    m->st.block_kv_rows_read += m->n_blocks + 1;
+    m->st.block_kv_bytes_read += (int64_t)(m->n_blocks + 1) * batch * c.n_block_layers * 2 * c.d_model * L.esz;
+    m->n_blocks += 1;
+  }
+  if (r == 0) m->have_context = false;
   m->st.token_passes += 1;
   m->st.token_rows += rows;
   if (c.n_token_layers > 0 && pos0 + rows > m->st.local_kv_high_water) m->st.local_kv_high_water = pos0 + rows;
-  m->r = (m->r + 1) % c.block_len;
+  m->r = (r + 1) % c.block_len;
   m->stepped = true;
   return BT_OK;
 }
@@ -584,6 +661,7 @@ const char* bt_last_error(const bt_model* m) { return m ? m->err.c_str() : "null
 void bt_destroy(bt_model* m) {
   if (!m) return;
   for (hipEvent_t e : m->ev) (void)hipEventDestroy(e);
+  for (auto& g : m->graphs) if (g.exec) (void)hipGraphExecDestroy(g.exec);
   delete m;
 }
 

@@ -250,4 +250,27 @@ hipError_t launch_scatter_ids(const int32_t* ids, int32_t* cur, int batch, int b
   return hipGetLastError();
 }
 
+__global__ void gather_ids_kernel(const int32_t* __restrict__ cur, int32_t* __restrict__ out, int batch,
+                                  int block_len, int r) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < batch) out[b] = cur[b * block_len + r];
+}
+
+hipError_t launch_gather_ids(const int32_t* cur, int32_t* out, int batch, int block_len, int r, hipStream_t s) {
+  gather_ids_kernel<<<(batch + 255) / 256, 256, 0, s>>>(cur, out, batch, block_len, r);
+  return hipGetLastError();
+}
+
+__global__ void state_set_kernel(int* p, int value) { *p = value; }
+__global__ void state_add_kernel(int* p, int delta) { *p += delta; }
+
+hipError_t launch_state_set(int* p, int value, hipStream_t s) {
+  state_set_kernel<<<1, 1, 0, s>>>(p, value);
+  return hipGetLastError();
+}
+hipError_t launch_state_add(int* p, int delta, hipStream_t s) {
+  state_add_kernel<<<1, 1, 0, s>>>(p, delta);
+  return hipGetLastError();
+}
+
 }  // namespace bt

@@ -48,6 +48,11 @@ hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* nex
                          int32_t* cur, int block_len, int r, hipStream_t s);
 
 hipError_t launch_scatter_ids(const int32_t* ids, int32_t* cur, int batch, int block_len, int r, hipStream_t s);
+// out[b] = cur[b*L_B + r]
+hipError_t launch_gather_ids(const int32_t* cur, int32_t* out, int batch, int block_len, int r, hipStream_t s);
+// *p = value, or *p += delta (one thread): the device-side count of cached blocks
+hipError_t launch_state_set(int* p, int value, hipStream_t s);
+hipError_t launch_state_add(int* p, int delta, hipStream_t s);
 
 // ----------------------------------------------------------------------- GEMM
 enum { EPI_F32 = 0,        // out float [M, ldo]: acc + bias
@@ -107,15 +112,18 @@ hipError_t launch_gelu_reduce(int dtype, const GeluJob& job, hipStream_t s);
 // qkv may arrive as split-K partials (src.splits > 1 and/or src.bias): the rotated q is then
 // written complete into plane 0 (src.base), which is what the attention kernels read.
 hipError_t launch_rope_append(int dtype, const PartialSrc& src, void* Kc, void* Vc, const float2* rope,
-                              int n_rows, int n_new, int pos0, int n_heads, int d_head, int rot,
-                              int n_cap, hipStream_t s);
+                              int n_rows, int n_new, int pos0, const int* n_dev, int n_heads, int d_head, int rot,
+                              int n_cap, const GeluJob& gelu, hipStream_t s);
 
 // Block decoder decode step: one query per (b, h) over cache rows [0, n_keys).
 // q read from qkv[b, h*d_h ...] (row stride 3D); out [B, D] storage dtype.
+// n_dev (here and in launch_rope_append, decode only): when non-null the number of blocks
+// already cached is read from device memory (*n_dev; the new entry goes to slot *n_dev and
+// n_keys = *n_dev + 1), so that a captured graph stays valid while the cache grows.
 // out_lo_off != 0 (here and below): out also gets the bf16 remainder plane.
 hipError_t launch_attn_block_decode(int dtype, const float* qkv, const void* Kc, const void* Vc,
                                     void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_keys,
-                                    int n_cap, const GeluJob& gelu, hipStream_t s);
+                                    const int* n_dev, int n_cap, hipStream_t s);
 
 // Block decoder prefill: causal attention of n_q queries per (b, h); query i sees rows [0, i].
 hipError_t launch_attn_block_prefill(int dtype, const float* qkv, const void* Kc, const void* Vc,

@@ -148,6 +148,28 @@ def test_determinism_and_reentrancy(amd):
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
 
 
+def test_graph_replay_equals_eager(amd):
+    """Captured decode steps replayed many times (with eager work and synchronisations between
+    the replays) give bit-identical ids and logits to eager launches."""
+    import torch
+    cfg = tiny_cfg(dtype="bf16", d_model=256, n_heads=4, d_ff=512, vocab=500, block_len=4, prefix_len=2, prompt_len=24)
+    W = make_weights(cfg)
+    prompts = make_prompts(cfg, batch=6)
+    out = {}
+    for mode in (0, 1):
+        m = amd.Model(cfg, W, max_batch=6, max_blocks=40, use_graphs=mode)
+        runs = []
+        for rep in range(2):                      # second pass: graphs already instantiated, state reset by prefill
+            ids, lgs = gpu_generate(m, prompts, 37)
+            torch.cuda.synchronize()
+            runs.append((ids, lgs))
+        m.close()
+        assert np.array_equal(runs[0][0], runs[1][0]) and np.array_equal(runs[0][1], runs[1][1])
+        out[mode] = runs[0]
+    assert np.array_equal(out[0][0], out[1][0])
+    assert np.array_equal(out[0][1], out[1][1])
+
+
 def test_batch_independence(amd):
     cfg = tiny_cfg(dtype="bf16", d_model=128, n_heads=2, d_ff=256, vocab=300, prompt_len=16)
     W = make_weights(cfg)
