@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attn-events", action="store_true", help="do not bracket block-attention launches with HIP events")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="only run a few plain device copies of MIB MiB and exit: under rocprofv3 --pmc FETCH_SIZE / "
+                         "WRITE_SIZE this gives the factor between the counters and real HBM bytes")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (the path shards by batch with no exchange; "
@@ -71,6 +74,17 @@ def main():
 
     import numpy as np
     import torch
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(7)
+        dst = torch.empty_like(src)
+        scratch = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")      # evicts the caches between copies
+        for _ in range(4):
+            scratch.fill_(1)
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "copies": 4}))
+        return
     from synth import CONFIGS, make_prompts, make_weights
     import paper_2406_02657_amd as amd
 
@@ -124,13 +138,24 @@ def main():
     decode_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
     value = cfg.batch * cfg.gen_len / (ms_per_step / 1e3)
 
+    # HBM traffic of that kernel relative to its algorithmic bytes, from the committed rocprofv3
+    # --pmc summary (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size)
+    traffic_ratio = None
+    try:
+        for line in open(os.path.join(ROOT, "profiles", "cfg1_hbm_traffic_pmc.txt")):
+            if line.startswith("traffic_over_algorithmic="):
+                traffic_ratio = float(line.split("=")[1])
+    except OSError:
+        pass
     roofline = None
     if st.attn_block_launches > 0 and st.attn_block_ms > 0:
         ach = st.attn_block_bytes / (st.attn_block_ms * 1e-3) / 1e9
         roofline = {
             "kernel": "attn_block_decode_kernel (block-decoder decode attention over the block KV cache)",
             "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": (traffic_ratio * st.attn_block_bytes / st.attn_block_launches) if traffic_ratio else None,
+            "traffic_note": "HBM bytes per launch = measured traffic/algorithmic ratio of profiles/cfg1_hbm_traffic_pmc.txt "
+                            "(rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE) x this run's algorithmic bytes per launch",
             "launches": int(st.attn_block_launches),
             "avg_launch_us": st.attn_block_ms * 1e3 / st.attn_block_launches,
             "avg_bytes_per_launch": st.attn_block_bytes / st.attn_block_launches,

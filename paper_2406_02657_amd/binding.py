@@ -79,7 +79,7 @@ class BTError(RuntimeError):
         self.code = code
 
 
-DEFAULT_ACT_SPLIT = 2
+DEFAULT_ACT_SPLIT = int(os.environ.get("BT_ACT_SPLIT", "2"))
 
 
 def make_config(cfg, max_batch=None, max_blocks=None, prefill_rows=0, act_split=None, use_graphs=1) -> bt_config:
@@ -91,7 +91,8 @@ def make_config(cfg, max_batch=None, max_blocks=None, prefill_rows=0, act_split=
         max_batch=cfg.batch if max_batch is None else max_batch,
         max_blocks=cfg.max_blocks if max_blocks is None else max_blocks,
         rotary_dims=cfg.rot, parallel_residual=cfg.parallel_residual, prefill_rows=prefill_rows,
-        act_split=DEFAULT_ACT_SPLIT if act_split is None else act_split, use_graphs=int(use_graphs),
+        act_split=DEFAULT_ACT_SPLIT if act_split is None else act_split,
+        use_graphs=int(use_graphs) if "BT_USE_GRAPHS" not in os.environ else int(os.environ["BT_USE_GRAPHS"]),
         ln_eps=cfg.ln_eps)
 
 

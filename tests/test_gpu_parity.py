@@ -108,6 +108,22 @@ def test_bf16_streaming_gemm_shapes(amd, d, h, f, b, p, lb):
     run_case(amd, cfg, 2 * lb + 1, batch=b)
 
 
+def test_bf16_prefill_large_tiles_ragged(amd):
+    """Prefill big enough for the 256 x 256 MFMA tiles (>= 256 tiles) with a ragged last row tile
+    (3300 = 12 * 256 + 228 block rows) and column tiles that do not fill the 4 x 8 tile blocks."""
+    from parity import compare_sampled_with_oracle, gpu_generate_sampled
+    cfg = tiny_cfg(dtype="bf16", block_len=4, prefix_len=1, d_model=768, n_heads=12, d_ff=3072, vocab=1000,
+                   prompt_len=1200, n_block_layers=2, n_token_layers=1)
+    W = make_weights(cfg)
+    prompts = make_prompts(cfg, batch=11)
+    m = amd.Model(cfg, W, max_batch=11, max_blocks=304, prefill_rows=4096)
+    ids, lgs = gpu_generate_sampled(m, prompts, 6, [0, 10], range(6))
+    m.close()
+    rep = compare_sampled_with_oracle(cfg, W, prompts, ids, lgs, [0, 10], TOL_BF16)
+    print(rep)
+    assert_parity(rep)
+
+
 def test_bf16_ragged_tiles(amd):
     """Batch, vocab and row counts that do not fill the GEMM tiles; prompt long enough to span
     several attention chunks and prefill chunks (prefill_rows forces chunking over the batch)."""
