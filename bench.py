@@ -62,7 +62,11 @@ def main():
     ap.add_argument("--gen-len", type=int, default=0, help="override the number of generated tokens (0 = the workload's)")
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-attn-events", action="store_true", help="do not bracket block-attention launches with HIP events")
+    ap.add_argument("--no-attn-events", action="store_true", help="skip the profiled pass that brackets the "
+                    "block-attention launches with HIP events (no roofline object)")
+    ap.add_argument("--events-in-timed-region", action="store_true",
+                    help="record those events inside the timed steps themselves; this turns the HIP-graph replay of "
+                         "the decode steps off for the timed region (launches are then issued one by one)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="only run a few plain device copies of MIB MiB and exit: under rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE this gives the factor between the counters and real HBM bytes")
@@ -122,7 +126,8 @@ def main():
     for _ in range(args.warmup):
         job()
     torch.cuda.synchronize()
-    model.bt_set_profile(not args.no_attn_events)
+    in_region = args.events_in_timed_region and not args.no_attn_events
+    model.bt_set_profile(in_region)
     model.bt_reset_profile()
     evs = []
     torch.cuda.synchronize()
@@ -131,6 +136,15 @@ def main():
         evs.append(timed_job())
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    if not in_region and not args.no_attn_events:
+        # One more job of the same workload, right after the timed steps, with HIP events around
+        # every block-attention launch (recorded by the library on the launch stream).  Events
+        # cannot sit inside a captured graph, so this pass issues its launches one by one; the
+        # kernel, its inputs and its launch shape are those of the timed steps.
+        model.bt_set_profile(True)
+        model.bt_reset_profile()
+        job()
+        torch.cuda.synchronize()
     st = model.bt_get_stats()
     model.bt_set_profile(False)
     ms_per_step = wall * 1e3 / args.steps
@@ -151,7 +165,9 @@ def main():
     if st.attn_block_launches > 0 and st.attn_block_ms > 0:
         ach = st.attn_block_bytes / (st.attn_block_ms * 1e-3) / 1e9
         roofline = {
-            "kernel": "attn_block_decode_kernel (block-decoder decode attention over the block KV cache)",
+            "kernel": "attn_block_decode_kernel (block-decoder decode attention over the block KV cache; the launch "
+                      "also finishes q/k/v of the new block, appends them, and carries the MLP GELU as extra workgroups)",
+            "events": "inside the timed steps" if in_region else "one extra job of the same workload after the timed steps",
             "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
             "traffic": (traffic_ratio * st.attn_block_bytes / st.attn_block_launches) if traffic_ratio else None,
             "traffic_note": "HBM bytes per launch = measured traffic/algorithmic ratio of profiles/cfg1_hbm_traffic_pmc.txt "

@@ -140,36 +140,81 @@ __device__ __forceinline__ void wave_attend(const float* q, const T* __restrict_
 }
 
 // ---------------------------------------------------------------------------
-// Block decoder, decode step.  Grid: one workgroup per (b, h); NW waves split
-// the n_keys cache rows; partial (m, l, acc) meet in LDS.
+// Block decoder, decode step.  Grid: one workgroup per (b, h) (+ optional extra
+// workgroups that turn the MLP up-projection into its activation).  The
+// workgroup first finishes this head's q, k, v (split-K pieces + bias, rotary),
+// appends k, v to the cache at slot n_old, then its NW waves split the n_old
+// cached rows; partial (m, l, acc) meet in LDS, where the new row joins them.
 // ---------------------------------------------------------------------------
 template <class T, int DH, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(const float* __restrict__ qkv, const T* __restrict__ Kc,
-                                                                    const T* __restrict__ Vc, T* __restrict__ out,
-                                                                    size_t out_lo_off, int n_heads, int n_keys_arg,
-                                                                    const int* __restrict__ n_dev, int n_cap) {
+__global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(PartialSrc qkv, T* __restrict__ Kc, T* __restrict__ Vc,
+                                                                    const float2* __restrict__ rope, int rot,
+                                                                    T* __restrict__ out, size_t out_lo_off, int n_heads,
+                                                                    int n_old_arg, const int* __restrict__ n_dev, int n_cap,
+                                                                    int n_attn_blocks, GeluJob gelu) {
   using R = RowMap<T, DH>;
   constexpr int EPC = R::EPC, LPR = R::LPR;
   __shared__ float s_m[NW], s_l[NW];
   __shared__ float s_acc[NW][DH];
+  __shared__ float s_q[DH], s_k[DH], s_v[DH];
+  __shared__ float s_new;
+  if ((int)blockIdx.x >= n_attn_blocks) {
+    gelu_reduce_block<T>(gelu, blockIdx.x - n_attn_blocks, gridDim.x - n_attn_blocks);
+    return;
+  }
   // the number of cached blocks may live in device memory, so that a captured graph of the
   // step stays valid while the cache grows
-  const int n_keys = n_dev ? min(*n_dev + 1, n_cap) : n_keys_arg;
+  const int n_old = n_dev ? min(*n_dev, n_cap - 1) : n_old_arg;
   const int bh = blockIdx.x;
   const int b = bh / n_heads, h = bh - b * n_heads;
-  const int D = n_heads * DH;
+  const int D = n_heads * DH, half = rot / 2;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR;
-  const float sc = rsqrtf((float)DH);
-  float q[EPC];
-  const float* qp = qkv + (size_t)b * 3 * D + h * DH + sub * EPC;
-#pragma unroll
-  for (int e = 0; e < EPC; ++e) q[e] = qp[e] * sc;
+  T* K = Kc + (size_t)bh * n_cap * DH;
+  T* V = Vc + (size_t)bh * n_cap * DH;
 
-  const int per = (n_keys + NW - 1) / NW;
-  const int j0 = min(wave * per, n_keys), j1 = min(j0 + per, n_keys);
-  const T* K = Kc + (size_t)bh * n_cap * DH;
-  const T* V = Vc + (size_t)bh * n_cap * DH;
+  // q, k, v of this head: sum the pieces, rotate q and k at position n_old, append k and v
+  const int d = threadIdx.x;
+  if (d < DH) {
+    const size_t base = (size_t)b * 3 * D + h * DH + d;
+    s_q[d] = partial_value(qkv, base, h * DH + d);
+    s_k[d] = partial_value(qkv, base + D, D + h * DH + d);
+    s_v[d] = partial_value(qkv, base + 2 * D, 2 * D + h * DH + d);
+  }
+  __syncthreads();
+  float qd = 0.f, kd = 0.f;
+  if (d < DH) {
+    qd = s_q[d];
+    kd = s_k[d];
+    if (d < rot) {
+      const int t = d < half ? d : d - half;
+      const float2 cs = rope[(size_t)n_old * half + t];
+      if (d < half) { qd = qd * cs.x - s_q[d + half] * cs.y; kd = kd * cs.x - s_k[d + half] * cs.y; }
+      else          { qd = qd * cs.x + s_q[d - half] * cs.y; kd = kd * cs.x + s_k[d - half] * cs.y; }
+    }
+  }
+  __syncthreads();
+  if (d < DH) {
+    const T kt = from_float<T>(kd), vt = from_float<T>(s_v[d]);
+    K[(size_t)n_old * DH + d] = kt;
+    V[(size_t)n_old * DH + d] = vt;
+    s_q[d] = qd * rsqrtf((float)DH);
+    s_k[d] = to_float<T>(kt);          // the new row takes part with its stored (rounded) values
+    s_v[d] = to_float<T>(vt);
+  }
+  __syncthreads();
+  if (wave == 0) {
+    float dot = 0.f;
+    for (int e = lane; e < DH; e += 64) dot = fmaf(s_q[e], s_k[e], dot);
+    dot = wave_sum(dot);
+    if (lane == 0) s_new = dot;
+  }
+  float q[EPC];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) q[e] = s_q[sub * EPC + e];
+
+  const int per = (n_old + NW - 1) / NW;
+  const int j0 = min(wave * per, n_old), j1 = min(j0 + per, n_old);
   float m, l, acc[EPC];
   wave_attend<T, DH>(q, K, V, j0, j1, m, l, acc);
   if (lane < LPR) {
@@ -178,18 +223,19 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(const float*
     for (int e = 0; e < EPC; ++e) s_acc[wave][sub * EPC + e] = acc[e];
   }
   __syncthreads();
-  for (int d = threadIdx.x; d < DH; d += NW * 64) {
-    float M = s_m[0];
+  for (int dd = threadIdx.x; dd < DH; dd += NW * 64) {
+    float M = s_new;
 #pragma unroll
-    for (int w = 1; w < NW; ++w) M = fmaxf(M, s_m[w]);
-    float L = 0.f, o = 0.f;
+    for (int w = 0; w < NW; ++w) M = fmaxf(M, s_m[w]);
+    const float fn = __expf(s_new - M);
+    float L = fn, o = fn * s_v[dd];
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
       const float f = __expf(s_m[w] - M);
       L += s_l[w] * f;
-      o += s_acc[w][d] * f;
+      o += s_acc[w][dd] * f;
     }
-    store_act<T>(out, (size_t)b * D + h * DH + d, out_lo_off, o / L);
+    store_act<T>(out, (size_t)b * D + h * DH + dd, out_lo_off, o / L);
   }
 }
 
@@ -418,18 +464,20 @@ hipError_t launch_gelu_reduce(int dtype, const GeluJob& job, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_attn_block_decode(int dtype, const float* qkv, const void* Kc, const void* Vc,
-                                    void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_keys,
-                                    const int* n_dev, int n_cap, hipStream_t s) {
-  if (!n_dev && (n_keys < 1 || n_keys > n_cap)) return hipErrorInvalidValue;
+hipError_t launch_attn_block_decode(int dtype, const PartialSrc& qkv, void* Kc, void* Vc, const float2* rope, int rot,
+                                    void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_old,
+                                    const int* n_dev, int n_cap, const GeluJob& gelu, hipStream_t s) {
+  if (!n_dev && (n_old < 0 || n_old >= n_cap)) return hipErrorInvalidValue;
+  if (gelu.rows > 0 && gelu.cols % 4) return hipErrorInvalidValue;
   constexpr int NW = 4;
-  const int grid = batch * n_heads;
+  const int n_attn = batch * n_heads;
+  const int grid = n_attn + gelu_blocks(gelu);
   if (dtype == BT_F32) {
     BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<float, DH, NW><<<grid, NW * 64, 0, s>>>(
-        qkv, (const float*)Kc, (const float*)Vc, (float*)out, 0, n_heads, n_keys, n_dev, n_cap)));
+        qkv, (float*)Kc, (float*)Vc, rope, rot, (float*)out, 0, n_heads, n_old, n_dev, n_cap, n_attn, gelu)));
   } else {
     BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<bf16_t, DH, NW><<<grid, NW * 64, 0, s>>>(
-        qkv, (const bf16_t*)Kc, (const bf16_t*)Vc, (bf16_t*)out, out_lo_off, n_heads, n_keys, n_dev, n_cap)));
+        qkv, (bf16_t*)Kc, (bf16_t*)Vc, rope, rot, (bf16_t*)out, out_lo_off, n_heads, n_old, n_dev, n_cap, n_attn, gelu)));
   }
   return hipGetLastError();
 }

@@ -258,13 +258,12 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     const size_t seq = (size_t)a.b0 * H * c.max_blocks * dh * L.esz;
     char* Kc = base + seq;
     char* Vc = base + half + seq;
-    BT_HIP(m, launch_rope_append(dt, qsrc, Kc, Vc, rope, M, a.rows, a.pos0,
-                                 a.mode == MODE_BLOCK_DECODE ? m->at<int>(L.state) : nullptr, H, dh, c.rotary_dims,
-                                 c.max_blocks, gelu, s));
     if (a.mode == MODE_BLOCK_PREFILL) {
+      BT_HIP(m, launch_rope_append(dt, qsrc, Kc, Vc, rope, M, a.rows, a.pos0, nullptr, H, dh, c.rotary_dims,
+                                   c.max_blocks, gelu, s));
       BT_HIP(m, launch_attn_block_prefill(dt, qkv, Kc, Vc, ao, loD, a.batch, H, dh, a.rows, c.max_blocks, s));
     } else {
-      const int n_keys = a.pos0 + 1;
+      const int n_old = a.pos0;
       hipEvent_t e0 = nullptr, e1 = nullptr;
       if (m->profile) {
         if (m->ev_used + 2 > m->ev.size()) {
@@ -279,12 +278,12 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
         m->ev_used += 2;
         BT_HIP(m, hipEventRecord(e0, s));
       }
-      BT_HIP(m, launch_attn_block_decode(dt, qkv, Kc, Vc, ao, loD, a.batch, H, dh, n_keys, m->at<int>(L.state),
-                                         c.max_blocks, s));
+      BT_HIP(m, launch_attn_block_decode(dt, qsrc, Kc, Vc, rope, c.rotary_dims, ao, loD, a.batch, H, dh, n_old,
+                                         m->at<int>(L.state), c.max_blocks, gelu, s));
       if (m->profile) {
         BT_HIP(m, hipEventRecord(e1, s));
         m->st.attn_block_launches += 1;
-        m->st.attn_block_bytes += (int64_t)2 * n_keys * D * L.esz * a.batch;
+        m->st.attn_block_bytes += (int64_t)2 * (n_old + 1) * D * L.esz * a.batch;
       }
     }
     return BT_OK;

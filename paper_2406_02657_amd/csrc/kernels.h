@@ -106,7 +106,7 @@ hipError_t launch_gelu_reduce(int dtype, const GeluJob& job, hipStream_t s);
 // ------------------------------------------------------------------ attention
 // Rotary tables: rope[pos * (rot/2) + t] = (cos, sin) of pos * 10000^(-2t/rot).
 //
-// Block decoder, after the QKV GEMM: rotate q in place (float, inside qkv),
+// Block decoder prefill, after the QKV GEMM: rotate q in place (float, inside qkv),
 // rotate k, and store k, v into the block KV cache at position pos0 + m % n_new
 // of sequence m / n_new.  Cache layout per layer: K [B][H][n_cap][d_h], V same.
 // qkv may arrive as split-K partials (src.splits > 1 and/or src.bias): the rotated q is then
@@ -115,15 +115,15 @@ hipError_t launch_rope_append(int dtype, const PartialSrc& src, void* Kc, void* 
                               int n_rows, int n_new, int pos0, const int* n_dev, int n_heads, int d_head, int rot,
                               int n_cap, const GeluJob& gelu, hipStream_t s);
 
-// Block decoder decode step: one query per (b, h) over cache rows [0, n_keys).
-// q read from qkv[b, h*d_h ...] (row stride 3D); out [B, D] storage dtype.
-// n_dev (here and in launch_rope_append, decode only): when non-null the number of blocks
-// already cached is read from device memory (*n_dev; the new entry goes to slot *n_dev and
-// n_keys = *n_dev + 1), so that a captured graph stays valid while the cache grows.
-// out_lo_off != 0 (here and below): out also gets the bf16 remainder plane.
-hipError_t launch_attn_block_decode(int dtype, const float* qkv, const void* Kc, const void* Vc,
-                                    void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_keys,
-                                    const int* n_dev, int n_cap, hipStream_t s);
+// Block decoder decode step, fused: finish q, k, v of every (b, h) from the (possibly split-K)
+// QKV output, rotate q and k at position n_old, append k, v to the cache at slot n_old, and
+// attend the one query to cache rows [0, n_old].  out [B, D] storage dtype (out_lo_off != 0:
+// also the bf16 remainder plane).  n_dev: when non-null n_old is read from device memory
+// (*n_dev), so that a captured graph stays valid while the cache grows.  gelu: optional job
+// done by extra workgroups of the same launch.
+hipError_t launch_attn_block_decode(int dtype, const PartialSrc& qkv, void* Kc, void* Vc, const float2* rope, int rot,
+                                    void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_old,
+                                    const int* n_dev, int n_cap, const GeluJob& gelu, hipStream_t s);
 
 // Block decoder prefill: causal attention of n_q queries per (b, h); query i sees rows [0, i].
 hipError_t launch_attn_block_prefill(int dtype, const float* qkv, const void* Kc, const void* Vc,
