@@ -69,28 +69,45 @@ struct RowMap {
 // query elements already scaled by 1/sqrt(DH).  Each slot runs an online
 // softmax over its rows; at the end the slots are merged, so every lane
 // returns the wave-wide (m, l, acc) for its chunk of dims.
+// The row stream is double-buffered in registers: attend_issue() puts the loads
+// of one batch (U row groups of K and of V) in flight, and the main loop issues
+// batch i+1 before it consumes batch i.  The first batch can be issued before
+// the query is known (its loads do not depend on it).
+constexpr int kAttnU = 4;
+
 template <class T, int DH>
-__device__ __forceinline__ void wave_attend(const float* q, const T* __restrict__ K, const T* __restrict__ V,
-                                            int j0, int j1, float& m_out, float& l_out, float* acc) {
+__device__ __forceinline__ void attend_issue(const T* __restrict__ K, const T* __restrict__ V, int base, int j0, int j1,
+                                             uint4* kraw, uint4* vraw) {
   using R = RowMap<T, DH>;
-  constexpr int EPC = R::EPC, LPR = R::LPR, RPL = R::RPL, U = 4;
+  constexpr int EPC = R::EPC, LPR = R::LPR, RPL = R::RPL;
   const int lane = threadIdx.x & 63;
   const int sub = lane % LPR, rr = lane / LPR;
+#pragma unroll
+  for (int u = 0; u < kAttnU; ++u) {
+    const int j = base + u * RPL + rr;
+    const size_t off = (size_t)(j < j1 ? j : j0) * DH + sub * EPC;      // clamped: no branch around the loads
+    kraw[u] = *reinterpret_cast<const uint4*>(K + off);
+    vraw[u] = *reinterpret_cast<const uint4*>(V + off);
+  }
+}
+
+// kraw / vraw: the batch at base = j0, already issued by attend_issue (only if j0 < j1).
+template <class T, int DH>
+__device__ __forceinline__ void wave_attend(const float* q, const T* __restrict__ K, const T* __restrict__ V,
+                                            int j0, int j1, uint4* kraw, uint4* vraw,
+                                            float& m_out, float& l_out, float* acc) {
+  using R = RowMap<T, DH>;
+  constexpr int EPC = R::EPC, LPR = R::LPR, RPL = R::RPL, U = kAttnU;
+  const int lane = threadIdx.x & 63;
+  const int rr = lane / LPR;
   float m = kNegBig, l = 0.f;
 #pragma unroll
   for (int e = 0; e < EPC; ++e) acc[e] = 0.f;
 
   for (int base = j0; base < j1; base += RPL * U) {
-    uint4 kraw[U], vraw[U];
-    bool valid[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int j = base + u * RPL + rr;
-      valid[u] = j < j1;
-      const size_t off = (size_t)(valid[u] ? j : j0) * DH + sub * EPC;
-      kraw[u] = *reinterpret_cast<const uint4*>(K + off);
-      vraw[u] = *reinterpret_cast<const uint4*>(V + off);
-    }
+    uint4 knext[U], vnext[U];
+    const int nb = base + RPL * U;
+    if (nb < j1) attend_issue<T, DH>(K, V, nb, j0, j1, knext, vnext);
     float s[U];
     float mx = m;
 #pragma unroll
@@ -102,7 +119,7 @@ __device__ __forceinline__ void wave_attend(const float* q, const T* __restrict_
       for (int e = 0; e < EPC; ++e) dot = fmaf(q[e], kf[e], dot);
 #pragma unroll
       for (int o = LPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, kWave);
-      s[u] = valid[u] ? dot : kNegBig;
+      s[u] = (base + u * RPL + rr < j1) ? dot : kNegBig;
       mx = fmaxf(mx, s[u]);
     }
     const float scale = __expf(m - mx);
@@ -111,7 +128,7 @@ __device__ __forceinline__ void wave_attend(const float* q, const T* __restrict_
     for (int e = 0; e < EPC; ++e) acc[e] *= scale;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const float p = valid[u] ? __expf(s[u] - mx) : 0.f;
+      const float p = (base + u * RPL + rr < j1) ? __expf(s[u] - mx) : 0.f;
       float vf[EPC];
       Chunk<T>::unpack(vraw[u], vf);
       l += p;
@@ -119,6 +136,10 @@ __device__ __forceinline__ void wave_attend(const float* q, const T* __restrict_
       for (int e = 0; e < EPC; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
     }
     m = mx;
+    if (nb < j1) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) { kraw[u] = knext[u]; vraw[u] = vnext[u]; }
+    }
   }
   // merge the RPL slots (lanes that share `sub`)
 #pragma unroll
@@ -172,9 +193,16 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(PartialSrc q
   const int sub = lane % LPR;
   T* K = Kc + (size_t)bh * n_cap * DH;
   T* V = Vc + (size_t)bh * n_cap * DH;
+  // the cached rows of this wave: their first batch of loads goes out before anything else
+  const int per = (n_old + NW - 1) / NW;
+  const int j0 = min(wave * per, n_old), j1 = min(j0 + per, n_old);
+  uint4 kraw[kAttnU], vraw[kAttnU];
+  if (j0 < j1) attend_issue<T, DH>(K, V, j0, j0, j1, kraw, vraw);
 
   // q, k, v of this head: sum the pieces, rotate q and k at position n_old, append k and v
   const int d = threadIdx.x;
+  float2 cs = make_float2(1.f, 0.f);
+  if (d < rot) cs = rope[(size_t)n_old * half + (d < half ? d : d - half)];
   if (d < DH) {
     const size_t base = (size_t)b * 3 * D + h * DH + d;
     s_q[d] = partial_value(qkv, base, h * DH + d);
@@ -187,8 +215,6 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(PartialSrc q
     qd = s_q[d];
     kd = s_k[d];
     if (d < rot) {
-      const int t = d < half ? d : d - half;
-      const float2 cs = rope[(size_t)n_old * half + t];
       if (d < half) { qd = qd * cs.x - s_q[d + half] * cs.y; kd = kd * cs.x - s_k[d + half] * cs.y; }
       else          { qd = qd * cs.x + s_q[d - half] * cs.y; kd = kd * cs.x + s_k[d - half] * cs.y; }
     }
@@ -213,10 +239,8 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(PartialSrc q
 #pragma unroll
   for (int e = 0; e < EPC; ++e) q[e] = s_q[sub * EPC + e];
 
-  const int per = (n_old + NW - 1) / NW;
-  const int j0 = min(wave * per, n_old), j1 = min(j0 + per, n_old);
   float m, l, acc[EPC];
-  wave_attend<T, DH>(q, K, V, j0, j1, m, l, acc);
+  wave_attend<T, DH>(q, K, V, j0, j1, kraw, vraw, m, l, acc);
   if (lane < LPR) {
     if (lane == 0) { s_m[wave] = m; s_l[wave] = l; }
 #pragma unroll
@@ -264,7 +288,9 @@ __global__ __launch_bounds__(256) void attn_block_prefill_kernel(const float* __
   const T* K = Kc + (size_t)bh * n_cap * DH;
   const T* V = Vc + (size_t)bh * n_cap * DH;
   float m, l, acc[EPC];
-  wave_attend<T, DH>(q, K, V, 0, i + 1, m, l, acc);
+  uint4 kraw[kAttnU], vraw[kAttnU];
+  attend_issue<T, DH>(K, V, 0, 0, i + 1, kraw, vraw);
+  wave_attend<T, DH>(q, K, V, 0, i + 1, kraw, vraw, m, l, acc);
   if (lane < LPR) {
     const float inv = 1.0f / l;
     float o[EPC];

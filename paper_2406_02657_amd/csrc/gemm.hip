@@ -436,7 +436,7 @@ static hipError_t launch_kslice(GemmGroup& g, size_t lds, hipStream_t s) {
   static bool attr_set = false;
   auto kern = gemm_kslice_kernel<KF, NT, MC, HL>;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
@@ -488,7 +488,7 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
       for (int i = 0; i < n_probs; ++i)
         if (probs[i].K % (32 * plan.kf * plan.splits[i])) return hipErrorInvalidValue;
       const size_t lds = kslice_lds_bytes(probs[0].M, plan.kf, hl);
-      if (lds > 96 * 1024) return hipErrorInvalidValue;
+      if (lds > 160 * 1024) return hipErrorInvalidValue;
       hipError_t e;
       switch (plan.kf * 2 + (hl ? 1 : 0)) {
         case 4:  e = launch_kslice_kf<2, false>(g, plan.nt, plan.mc, lds, s); break;
