@@ -176,6 +176,17 @@ def main():
             "avg_launch_us": st.attn_block_ms * 1e3 / st.attn_block_launches,
             "avg_bytes_per_launch": st.attn_block_bytes / st.attn_block_launches,
         }
+    roofline_gemm = None
+    if st.gemm_decode_launches > 0 and st.gemm_decode_ms > 0:
+        ach = st.gemm_decode_bytes / (st.gemm_decode_ms * 1e-3) / 1e9
+        roofline_gemm = {
+            "kernel": "gemm_kslice_kernel (grouped projection GEMMs of the decode steps: QKV + MLP-up, O + MLP-down)",
+            "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+            "launches": int(st.gemm_decode_launches),
+            "avg_launch_us": st.gemm_decode_ms * 1e3 / st.gemm_decode_launches,
+            "avg_bytes_per_launch": st.gemm_decode_bytes / st.gemm_decode_launches,
+            "note": "algorithmic bytes = weight bytes, each read once; by time this is the largest kernel of the step",
+        }
     # whole decode step against the HBM roofline: algorithmic bytes per step (weights + block KV)
     D, F, V, esz = cfg.d_model, cfg.d_ff, cfg.vocab, (2 if cfg.dtype == "bf16" else 4)
     p_layer = 12 * D * D + 13 * D
@@ -200,7 +211,7 @@ def main():
                    "block_len": cfg.block_len, "d_model": cfg.d_model, "layers": [cfg.n_block_layers, cfg.n_token_layers],
                    "prefix_len": cfg.prefix_len, "vocab": cfg.vocab},
         "prefill_ms": prefill_ms, "decode_ms_per_token_step": decode_ms / cfg.gen_len,
-        "roofline": roofline, "decode_step_roofline": step_roof,
+        "roofline": roofline, "roofline_gemm": roofline_gemm, "decode_step_roofline": step_roof,
     }
     model.close()
     del model

@@ -118,6 +118,11 @@ typedef struct {
   double  attn_block_ms;
   int64_t attn_block_launches;
   int64_t attn_block_bytes;    /* algorithmic K+V bytes those launches streamed */
+  /* same for the grouped projection GEMM launches of the decode steps (QKV+MLP-up, O+MLP-down;
+   * parallel-residual wiring, bf16 mode) */
+  double  gemm_decode_ms;
+  int64_t gemm_decode_launches;
+  int64_t gemm_decode_bytes;   /* weight bytes those launches read (each weight once) */
 } bt_stats;
 
 typedef struct bt_model bt_model;
@@ -177,7 +182,9 @@ int bt_get_context(bt_model *m, void *ctx_dev);
 int bt_set_context(bt_model *m, const void *ctx_dev);
 
 /* Profiling: when on, HIP events bracket every block-decoder decode attention
- * launch; bt_get_stats (which then synchronises the stream) reports their sum.
+ * launch and every grouped projection GEMM launch of the decode steps, and the
+ * steps are launched eagerly (no graph replay); bt_get_stats (which then
+ * synchronises the stream) reports the sums.
  * bt_reset_profile clears the sums. */
 int bt_set_profile(bt_model *m, int32_t on);
 int bt_reset_profile(bt_model *m);

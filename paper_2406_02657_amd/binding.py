@@ -48,7 +48,9 @@ class bt_stats(C.Structure):
                 ("block_kv_rows_read", C.c_int64), ("block_kv_bytes_read", C.c_int64),
                 ("n_blocks", C.c_int32), ("r", C.c_int32), ("batch", C.c_int32),
                 ("local_kv_high_water", C.c_int32), ("attn_block_ms", C.c_double),
-                ("attn_block_launches", C.c_int64), ("attn_block_bytes", C.c_int64)]
+                ("attn_block_launches", C.c_int64), ("attn_block_bytes", C.c_int64),
+                ("gemm_decode_ms", C.c_double), ("gemm_decode_launches", C.c_int64),
+                ("gemm_decode_bytes", C.c_int64)]
 
 
 _P = C.c_void_p

@@ -114,6 +114,7 @@ struct bt_model {
   bt_stats st;
   bool profile;
   std::vector<hipEvent_t> ev;      // pairs (start, stop)
+  std::vector<int> ev_tag;         // per pair: 0 = block-decoder decode attention, 1 = decode-step GEMM
   size_t ev_used;
   std::string err;
   struct StepGraph { hipGraphExec_t exec = nullptr; int seen = 0; };
@@ -143,6 +144,26 @@ void drop_graphs(bt_model* m) {
     g.exec = nullptr;
     g.seen = 0;
   }
+}
+
+// Profiling: a pair of HIP events around one launch, tagged by kind (bt_set_profile).
+int prof_begin(bt_model* m, int tag) {
+  if (m->ev_used + 2 > m->ev.size()) {
+    hipEvent_t n0, n1;
+    BT_HIP(m, hipEventCreate(&n0));
+    BT_HIP(m, hipEventCreate(&n1));
+    m->ev.push_back(n0);
+    m->ev.push_back(n1);
+    m->ev_tag.push_back(tag);
+  }
+  m->ev_tag[m->ev_used / 2] = tag;
+  BT_HIP(m, hipEventRecord(m->ev[m->ev_used], m->stream));
+  return BT_OK;
+}
+int prof_end(bt_model* m) {
+  BT_HIP(m, hipEventRecord(m->ev[m->ev_used + 1], m->stream));
+  m->ev_used += 2;
+  return BT_OK;
 }
 
 enum Mode { MODE_BLOCK_PREFILL, MODE_BLOCK_DECODE, MODE_TOKEN };
@@ -264,24 +285,12 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
       BT_HIP(m, launch_attn_block_prefill(dt, qkv, Kc, Vc, ao, loD, a.batch, H, dh, a.rows, c.max_blocks, s));
     } else {
       const int n_old = a.pos0;
-      hipEvent_t e0 = nullptr, e1 = nullptr;
-      if (m->profile) {
-        if (m->ev_used + 2 > m->ev.size()) {
-          hipEvent_t n0, n1;
-          BT_HIP(m, hipEventCreate(&n0));
-          BT_HIP(m, hipEventCreate(&n1));
-          m->ev.push_back(n0);
-          m->ev.push_back(n1);
-        }
-        e0 = m->ev[m->ev_used];
-        e1 = m->ev[m->ev_used + 1];
-        m->ev_used += 2;
-        BT_HIP(m, hipEventRecord(e0, s));
-      }
+      int prc;
+      if (m->profile && (prc = prof_begin(m, 0))) return prc;
       BT_HIP(m, launch_attn_block_decode(dt, qsrc, Kc, Vc, rope, c.rotary_dims, ao, loD, a.batch, H, dh, n_old,
                                          m->at<int>(L.state), c.max_blocks, gelu, s));
       if (m->profile) {
-        BT_HIP(m, hipEventRecord(e1, s));
+        if ((prc = prof_end(m))) return prc;
         m->st.attn_block_launches += 1;
         m->st.attn_block_bytes += (int64_t)2 * (n_old + 1) * D * L.esz * a.batch;
       }
@@ -305,11 +314,24 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
       GemmProblem p[2] = {pq, pu};
       p[0].W = lw[l].W_qkv; p[1].W = lw[l].W_up;
       if (!pieces) { p[0].bias = (const float*)lw[l].b_qkv; p[1].bias = (const float*)lw[l].b_up; }
+      const bool prof_gemm = m->profile && pieces;
+      if (prof_gemm && (rc = prof_begin(m, 1))) return rc;
       BT_HIP(m, launch_gemm(dt, p, 2, plan_in, s));
+      if (prof_gemm) {
+        if ((rc = prof_end(m))) return rc;
+        m->st.gemm_decode_launches += 1;
+        m->st.gemm_decode_bytes += (int64_t)(3 * D + F) * D * L.esz;
+      }
       if ((rc = attention(l, gelu_job(l)))) return rc;
       p[0] = po; p[0].W = lw[l].W_o;
       p[1] = pd; p[1].W = lw[l].W_down;
+      if (prof_gemm && (rc = prof_begin(m, 1))) return rc;
       BT_HIP(m, launch_gemm(dt, p, 2, plan_out, s));
+      if (prof_gemm) {
+        if ((rc = prof_end(m))) return rc;
+        m->st.gemm_decode_launches += 1;
+        m->st.gemm_decode_bytes += (int64_t)(D + F) * D * L.esz;
+      }
       if (l + 1 < n_layers) {
         if ((rc = ln(part_o, (const float*)lw[l].b_o, sO, part_d, (const float*)lw[l].b_down, sD,
                      lw[l + 1].ln1_g, lw[l + 1].ln1_b, lw[l + 1].ln2_g, lw[l + 1].ln2_b))) return rc;
@@ -633,6 +655,9 @@ int bt_reset_profile(bt_model* m) {
   m->st.attn_block_ms = 0.0;
   m->st.attn_block_launches = 0;
   m->st.attn_block_bytes = 0;
+  m->st.gemm_decode_ms = 0.0;
+  m->st.gemm_decode_launches = 0;
+  m->st.gemm_decode_bytes = 0;
   return BT_OK;
 }
 
@@ -640,13 +665,14 @@ int bt_get_stats(bt_model* m, bt_stats* out) {
   if (!m || !out) return BT_ERR_ARG;
   if (m->ev_used > 0) {
     BT_HIP(m, hipStreamSynchronize(m->stream));
-    double ms = 0.0;
+    double ms[2] = {0.0, 0.0};
     for (size_t i = 0; i + 1 < m->ev_used; i += 2) {
       float t = 0.f;
       BT_HIP(m, hipEventElapsedTime(&t, m->ev[i], m->ev[i + 1]));
-      ms += t;
+      ms[m->ev_tag[i / 2] & 1] += t;
     }
-    m->st.attn_block_ms = ms;
+    m->st.attn_block_ms = ms[0];
+    m->st.gemm_decode_ms = ms[1];
   }
   m->st.n_blocks = m->n_blocks;
   m->st.r = m->r;
