@@ -40,10 +40,7 @@ __device__ __forceinline__ void gelu_reduce_block(const GeluJob& j, int blk, int
       const float4 p = *reinterpret_cast<const float4*>(j.src.base + (size_t)s * j.src.stride + idx);
       v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
     }
-    store_act<T>(out, idx, j.out_lo_off, gelu_erf_f(v.x));
-    store_act<T>(out, idx + 1, j.out_lo_off, gelu_erf_f(v.y));
-    store_act<T>(out, idx + 2, j.out_lo_off, gelu_erf_f(v.z));
-    store_act<T>(out, idx + 3, j.out_lo_off, gelu_erf_f(v.w));
+    store_act4<T>(out, idx, j.out_lo_off, gelu_erf_f(v.x), gelu_erf_f(v.y), gelu_erf_f(v.z), gelu_erf_f(v.w));
   }
 }
 
@@ -53,7 +50,7 @@ __global__ __launch_bounds__(256) void gelu_reduce_kernel(GeluJob j) { gelu_redu
 __host__ inline int gelu_blocks(const GeluJob& j) {
   if (j.rows <= 0) return 0;
   const size_t groups = (size_t)j.rows * j.cols / 4;
-  size_t b = (groups + 1023) / 1024;          // about four 16-byte groups per thread
+  size_t b = (groups + 255) / 256;            // one group of four activations per thread
   return (int)(b < 1 ? 1 : (b > 1024 ? 1024 : b));
 }
 

@@ -66,6 +66,24 @@ __device__ __forceinline__ void store_act(T* p, size_t i, size_t lo_off, float v
   if (lo_off) p[i + lo_off] = from_float<T>(v - to_float<T>(hi));
 }
 
+// Four consecutive activations at once (i a multiple of 4): one 8- or 16-byte store per plane.
+template <class T>
+__device__ __forceinline__ void store_act4(T* p, size_t i, size_t lo_off, float a, float b, float c, float d);
+template <>
+__device__ __forceinline__ void store_act4<float>(float* p, size_t i, size_t, float a, float b, float c, float d) {
+  *reinterpret_cast<float4*>(p + i) = make_float4(a, b, c, d);
+}
+template <>
+__device__ __forceinline__ void store_act4<bf16_t>(bf16_t* p, size_t i, size_t lo_off, float a, float b, float c, float d) {
+  const uint32_t ha = float_to_bf16_bits(a), hb = float_to_bf16_bits(b), hc = float_to_bf16_bits(c), hd = float_to_bf16_bits(d);
+  *reinterpret_cast<uint2*>(p + i) = make_uint2(ha | (hb << 16), hc | (hd << 16));
+  if (lo_off) {
+    const uint32_t la = float_to_bf16_bits(a - bf16_bits_to_float(ha)), lb = float_to_bf16_bits(b - bf16_bits_to_float(hb));
+    const uint32_t lc = float_to_bf16_bits(c - bf16_bits_to_float(hc)), ld = float_to_bf16_bits(d - bf16_bits_to_float(hd));
+    *reinterpret_cast<uint2*>(p + i + lo_off) = make_uint2(la | (lb << 16), lc | (ld << 16));
+  }
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

@@ -158,14 +158,12 @@ __global__ __launch_bounds__(kLnThreads) void resid_ln_kernel(ResidLnArgs a) {
       if (a.u1_f32) {
         *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.u1) + o) = make_float4(o1[0], o1[1], o1[2], o1[3]);
       } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) store_act<T>(reinterpret_cast<T*>(a.u1), o + e, a.lo_off, o1[e]);
+        store_act4<T>(reinterpret_cast<T*>(a.u1), o, a.lo_off, o1[0], o1[1], o1[2], o1[3]);
       }
       if (a.g2) {
         const float4 g2 = *reinterpret_cast<const float4*>(a.g2 + 4 * g), b2 = *reinterpret_cast<const float4*>(a.b2 + 4 * g);
         const float o2[4] = {n[0] * g2.x + b2.x, n[1] * g2.y + b2.y, n[2] * g2.z + b2.z, n[3] * g2.w + b2.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) store_act<T>(reinterpret_cast<T*>(a.u2), o + e, a.lo_off, o2[e]);
+        store_act4<T>(reinterpret_cast<T*>(a.u2), o, a.lo_off, o2[0], o2[1], o2[2], o2[3]);
       }
     }
   }
