@@ -23,7 +23,7 @@ constexpr int kSkinnyRows = 256;     // GEMMs with at most this many rows may sp
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct Layout {
-  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cur, state, total;
+  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cur, state, frag, total;
   size_t blk_layer_stride, loc_layer_stride;   // bytes between layers (K then V inside)
   size_t part_elems;                           // floats in each of part_o, part_d
   size_t qkv_elems, part_u_elems;              // floats in qkv (may hold split-K pieces) and part_u
@@ -97,6 +97,15 @@ void make_layout(const bt_config& c, Layout& L) {
   L.logits = take(B * (size_t)c.vocab * 4);
   L.cur = take(B * c.block_len * 4);
   L.state = take(256);
+  // bf16 mode: a second copy of every GEMM weight in MFMA fragment order, read by the decode GEMMs
+  L.frag = off;
+  if (c.dtype == BT_BF16) {
+    const size_t per_layer = align_up(gemm_packed_elems(3 * (int)D, (int)D) * 2) + align_up(gemm_packed_elems((int)D, (int)D) * 2) +
+                             align_up(gemm_packed_elems((int)F, (int)D) * 2) + align_up(gemm_packed_elems((int)D, (int)F) * 2);
+    take(per_layer * (c.n_block_layers + c.n_token_layers));
+    take(gemm_packed_elems(c.vocab, (int)D) * 2);
+    if (c.prefix_len > 0) take(gemm_packed_elems(c.prefix_len * (int)D, (int)D) * 2);
+  }
   L.total = off;
 }
 
@@ -106,6 +115,10 @@ struct bt_model {
   bt_config cfg;
   bt_weights w;
   std::vector<bt_layer_weights> blk, tok;
+  // bf16 mode: the GEMM weights once more, in MFMA fragment order (inside the workspace)
+  struct FragLayer { const void *qkv, *o, *up, *down; };
+  std::vector<FragLayer> blk_frag, tok_frag;
+  const void *head_frag, *prefix_frag;
   Layout L;
   char* ws;
   hipStream_t stream;
@@ -213,6 +226,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
   const float2* rope = m->at<float2>(L.rope);
   hipStream_t s = m->stream;
   const int M = a.M;
+  const bt_model::FragLayer* fw = lw == m->blk.data() ? m->blk_frag.data() : m->tok_frag.data();
   if (n_layers == 0)
     return final_ln(m, a, nullptr, nullptr, 0, nullptr, nullptr, 0, fin_g, fin_b, fin_out, fin_f32, fin_n, fin_mul, fin_off);
 
@@ -313,6 +327,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     for (int l = 0; l < n_layers; ++l) {
       GemmProblem p[2] = {pq, pu};
       p[0].W = lw[l].W_qkv; p[1].W = lw[l].W_up;
+      p[0].W_frag = fw[l].qkv; p[1].W_frag = fw[l].up;
       if (!pieces) { p[0].bias = (const float*)lw[l].b_qkv; p[1].bias = (const float*)lw[l].b_up; }
       const bool prof_gemm = m->profile && pieces;
       if (prof_gemm && (rc = prof_begin(m, 1))) return rc;
@@ -323,8 +338,8 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
         m->st.gemm_decode_bytes += (int64_t)(3 * D + F) * D * L.esz;
       }
       if ((rc = attention(l, gelu_job(l)))) return rc;
-      p[0] = po; p[0].W = lw[l].W_o;
-      p[1] = pd; p[1].W = lw[l].W_down;
+      p[0] = po; p[0].W = lw[l].W_o; p[0].W_frag = fw[l].o;
+      p[1] = pd; p[1].W = lw[l].W_down; p[1].W_frag = fw[l].down;
       if (prof_gemm && (rc = prof_begin(m, 1))) return rc;
       BT_HIP(m, launch_gemm(dt, p, 2, plan_out, s));
       if (prof_gemm) {
@@ -344,18 +359,18 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     if ((rc = ln(nullptr, nullptr, 0, nullptr, nullptr, 0, lw[0].ln1_g, lw[0].ln1_b, nullptr, nullptr))) return rc;
     for (int l = 0; l < n_layers; ++l) {
       GemmProblem p = pq;
-      p.W = lw[l].W_qkv;
+      p.W = lw[l].W_qkv; p.W_frag = fw[l].qkv;
       if (!pieces) p.bias = (const float*)lw[l].b_qkv;
       BT_HIP(m, launch_gemm(dt, &p, 1, plan_q, s));
       if ((rc = attention(l, no_job))) return rc;
-      p = po; p.W = lw[l].W_o;
+      p = po; p.W = lw[l].W_o; p.W_frag = fw[l].o;
       BT_HIP(m, launch_gemm(dt, &p, 1, plan_o, s));
       if ((rc = ln(part_o, (const float*)lw[l].b_o, sO, nullptr, nullptr, 0, lw[l].ln2_g, lw[l].ln2_b, nullptr, nullptr))) return rc;
-      p = pu; p.W = lw[l].W_up;
+      p = pu; p.W = lw[l].W_up; p.W_frag = fw[l].up;
       if (!pieces) p.bias = (const float*)lw[l].b_up;
       BT_HIP(m, launch_gemm(dt, &p, 1, plan_u, s));
       BT_HIP(m, launch_gelu_reduce(dt, gelu_job(l), s));
-      p = pd; p.W = lw[l].W_down;
+      p = pd; p.W = lw[l].W_down; p.W_frag = fw[l].down;
       BT_HIP(m, launch_gemm(dt, &p, 1, plan_d, s));
       if (l + 1 < n_layers) {
         if ((rc = ln(nullptr, nullptr, 0, part_d, (const float*)lw[l].b_down, sD, lw[l + 1].ln1_g, lw[l + 1].ln1_b, nullptr, nullptr))) return rc;
@@ -422,6 +437,35 @@ int bt_create(const bt_config* cfg, const bt_weights* w, void* workspace_dev, si
   m->ev_used = 0;
   m->graphs.assign(cfg->block_len + 1, bt_model::StepGraph());
   m->graphs_ok = true;
+
+  m->blk_frag.assign(cfg->n_block_layers, bt_model::FragLayer{nullptr, nullptr, nullptr, nullptr});
+  m->tok_frag.assign(cfg->n_token_layers, bt_model::FragLayer{nullptr, nullptr, nullptr, nullptr});
+  m->head_frag = nullptr; m->prefix_frag = nullptr;
+  if (cfg->dtype == BT_BF16) {
+    const int D = cfg->d_model, F = cfg->d_ff;
+    size_t off = L.frag;
+    hipError_t e = hipSuccess;
+    auto pack = [&](const void* W, int N, int K) -> const void* {
+      void* dst = m->ws + off;
+      off = align_up(off + gemm_packed_elems(N, K) * 2);
+      if (e == hipSuccess) e = gemm_pack_weights(W, dst, N, K, m->stream);
+      return dst;
+    };
+    auto pack_layers = [&](const std::vector<bt_layer_weights>& lw, std::vector<bt_model::FragLayer>& fw) {
+      for (size_t i = 0; i < lw.size(); ++i) {
+        fw[i].qkv = pack(lw[i].W_qkv, 3 * D, D);
+        fw[i].o = pack(lw[i].W_o, D, D);
+        fw[i].up = pack(lw[i].W_up, F, D);
+        fw[i].down = pack(lw[i].W_down, D, F);
+      }
+    };
+    pack_layers(m->blk, m->blk_frag);
+    pack_layers(m->tok, m->tok_frag);
+    m->head_frag = pack(w->W_head, cfg->vocab, D);
+    if (cfg->prefix_len > 0) m->prefix_frag = pack(w->W_prefix, cfg->prefix_len * D, D);
+    if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+    if (e != hipSuccess || off > L.total) { delete m; return BT_ERR_HIP; }
+  }
 
   // rotary table: (cos, sin) of pos * 10000^(-2t/rot), computed in double on the host
   const int half = cfg->rotary_dims / 2;
@@ -501,7 +545,7 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
     }
     if (c.prefix_len > 0) {
       GemmProblem p{m->ws + L.ctx, m->w.W_prefix, (const float*)m->w.b_prefix, x, B, c.prefix_len * D, D, D,
-                    c.prefix_len * D, EPI_F32, fin_lo ? m->ws + L.ctx + fin_lo * 2 : nullptr, 0};
+                    c.prefix_len * D, EPI_F32, fin_lo ? m->ws + L.ctx + fin_lo * 2 : nullptr, 0, m->prefix_frag};
       GemmPlan pl{};
       BT_HIP(m, gemm_plan(c.dtype, &p, 1, &pl));
       BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));
@@ -520,7 +564,7 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
                      m->ws + L.hfin, 0, B, rows, rows - 1);
   if (rc) return rc;
   GemmProblem p{m->ws + L.hfin, m->w.W_head, nullptr, m->ws + L.logits, B, c.vocab, D, D, c.vocab, EPI_F32,
-                fin_lo ? m->ws + L.hfin + fin_lo * 2 : nullptr, 0};
+                fin_lo ? m->ws + L.hfin + fin_lo * 2 : nullptr, 0, m->head_frag};
   GemmPlan pl{};
   BT_HIP(m, gemm_plan(c.dtype, &p, 1, &pl));
   BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));

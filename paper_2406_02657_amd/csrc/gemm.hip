@@ -21,6 +21,7 @@ struct GemmDesc {
   int M, N, K, lda, ldo, epi, splits;
   const void* A_lo;      // bf16 remainder plane of A (null: none)
   size_t out_lo_off;     // EPI_GELU: != 0 writes the output as hi / remainder planes
+  const void* W_frag;    // W in MFMA fragment order (K-slice kernel)
   int tiles_m, tiles_n, tile_begin;   // tiles of this problem occupy blocks [tile_begin, tile_begin + tiles_m*tiles_n*splits)
 };
 struct GemmGroup {
@@ -237,8 +238,9 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
   const int n0 = tn * 64 * NT + wave * 16 * NT;
   const int Mpad = (d.M + 15) & ~15;
   const int k_iters = d.K / KS / d.splits;
+  const int kblocks = d.K >> 5, last_tile = ((d.N + 15) >> 4) - 1;
   const uint16_t* A = reinterpret_cast<const uint16_t*>(d.A);
-  const uint16_t* W = reinterpret_cast<const uint16_t*>(d.W);
+  const uint16_t* Wf = reinterpret_cast<const uint16_t*>(d.W_frag);
   const ptrdiff_t lo_delta = HL ? reinterpret_cast<const uint16_t*>(d.A_lo) - A : 0;
 
   f32x4_t acc[MC][NT][4];
@@ -252,13 +254,16 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
   const int total = Mpad * CPR;                 // 16-byte chunks of one plane of the slice
   for (int it = 0; it < k_iters; ++it) {
     const int kbase = (split * k_iters + it) * KS;
-    // weight fragments of this wave: issued first, they come from HBM
+    // weight fragments of this wave: issued first, they come from HBM.  In fragment order the KF
+    // fragments of one 16-column tile are KF consecutive KB.  Tiles past N repeat the last tile;
+    // their products are never stored.
     bf16x8_t wf[NT][KF];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      const uint16_t* wp = W + (size_t)min(n0 + nt * 16 + (lane & 15), d.N - 1) * d.K + kbase + (lane >> 4) * 8;
+      const int tile = min((n0 >> 4) + nt, last_tile);
+      const uint16_t* wp = Wf + ((size_t)tile * kblocks + (kbase >> 5)) * 512 + lane * 8;
 #pragma unroll
-      for (int kf = 0; kf < KF; ++kf) wf[nt][kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wp + kf * 32));
+      for (int kf = 0; kf < KF; ++kf) wf[nt][kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wp + kf * 512));
     }
     // activation slice -> LDS.  No branches here: chunk indices past the end are clamped to the
     // last chunk (which is then loaded and stored more than once, with the same bytes), so the
@@ -283,27 +288,31 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
       }
     }
     __syncthreads();
+    // Row tiles past the last one re-use its LDS rows (clamped, never stored), which keeps the
+    // loops free of branches: the 4 * NT accumulator chains of a 64-row chunk interleave.
 #pragma unroll
     for (int mc = 0; mc < MC; ++mc) {
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
-        const int row0 = mc * 64 + mt * 16;
-        if (row0 < Mpad) {
-          const uint16_t* sp = &sA[(row0 + (lane & 15)) * LDK + (lane >> 4) * 8];
-          bf16x8_t af[KF], al[HL ? KF : 1];
+      for (int kf = 0; kf < KF; ++kf) {
+        bf16x8_t af[4], al[HL ? 4 : 1];
 #pragma unroll
-          for (int kf = 0; kf < KF; ++kf) {
-            af[kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(sp + kf * 32));
-            if constexpr (HL) al[kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(sp + Mpad * LDK + kf * 32));
-          }
+        for (int mt = 0; mt < 4; ++mt) {
+          const int row = min(mc * 64 + mt * 16 + (lane & 15), Mpad - 1);
+          const uint16_t* sp = &sA[row * LDK + (lane >> 4) * 8 + kf * 32];
+          af[mt] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(sp));
+          if constexpr (HL) al[mt] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(sp + Mpad * LDK));
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt)
+            acc[mc][nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[mt], wf[nt][kf], acc[mc][nt][mt], 0, 0, 0);
+        if constexpr (HL) {
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int kf = 0; kf < KF; ++kf) {
-              acc[mc][nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[kf], wf[nt][kf], acc[mc][nt][mt], 0, 0, 0);
-              if constexpr (HL)
-                acc[mc][nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[kf], wf[nt][kf], acc[mc][nt][mt], 0, 0, 0);
-            }
+            for (int mt = 0; mt < 4; ++mt)
+              acc[mc][nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[mt], wf[nt][kf], acc[mc][nt][mt], 0, 0, 0);
         }
       }
     }
@@ -320,6 +329,20 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) epilogue_store<bf16_t>(d, split, row0 + r, col, acc[mc][nt][mt][r]);
       }
+}
+
+// W[N, K] -> fragment order, one thread per 16-byte chunk.
+__global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ Wf, int N, int K, size_t n_chunks) {
+  const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= n_chunks) return;
+  const int lane = (int)(c & 63);
+  const size_t tile_kb = c >> 6;
+  const int kblocks = K >> 5;
+  const int kb = (int)(tile_kb % kblocks), tile = (int)(tile_kb / kblocks);
+  const int n = tile * 16 + (lane & 15), k = kb * 32 + (lane >> 4) * 8;
+  uint4 v = make_uint4(0u, 0u, 0u, 0u);
+  if (n < N) v = *reinterpret_cast<const uint4*>(W + (size_t)n * K + k);
+  *reinterpret_cast<uint4*>(Wf + c * 8) = v;
 }
 
 // ---------------------------------------------------------------------------
@@ -348,6 +371,16 @@ size_t kslice_lds_bytes(int M, int kf, bool hl) {
   return (size_t)Mpad * (32 * kf + 8) * 2 * (hl ? 2 : 1);
 }
 }  // namespace
+
+size_t gemm_packed_elems(int N, int K) { return (size_t)((N + 15) & ~15) * K; }
+
+hipError_t gemm_pack_weights(const void* W, void* W_frag, int N, int K, hipStream_t s) {
+  if (!W || !W_frag || N <= 0 || K <= 0 || K % 32) return hipErrorInvalidValue;
+  const size_t n_chunks = gemm_packed_elems(N, K) / 8;
+  pack_weights_kernel<<<(unsigned)((n_chunks + 255) / 256), 256, 0, s>>>(
+      reinterpret_cast<const uint16_t*>(W), reinterpret_cast<uint16_t*>(W_frag), N, K, n_chunks);
+  return hipGetLastError();
+}
 
 hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan* plan) {
   if (n_probs < 1 || n_probs > 2 || !plan) return hipErrorInvalidValue;
@@ -386,8 +419,10 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
   }
   plan->kf = kf;
   // Columns per workgroup (64*nt) and K-slices per workgroup (q): minimise the bytes a launch
-  // moves besides W (activation re-reads + partial sums written and read back) while keeping
-  // every CU busy.  Problems that must finish their own epilogue keep all slices in one workgroup.
+  // moves (weights once, activation slices once per workgroup, partial sums written and read
+  // back), stretched when there are too few workgroups to overlap each other's load, multiply
+  // and store phases (measured: below about 1.75 workgroups per CU a launch is latency-bound).
+  // Problems that must finish their own epilogue keep all slices in one workgroup.
   double best_cost = 1e300;
   for (int nt : {4, 2, 1}) {
     if (nt * plan->mc > 8) continue;                       // accumulator registers
@@ -404,10 +439,11 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
           spl[i] = slices / qi;
         }
         wgs += tiles * spl[i];
+        cost += (double)p.N * p.K * 2;                                     // weights
         cost += (double)tiles * p.M * p.K * (hl ? 4 : 2);                  // activation reads
         if (p.epi == EPI_PARTIAL) cost += (double)spl[i] * p.M * p.N * 8;  // partials out and back
       }
-      if (wgs < kNumCU) cost *= (double)kNumCU / wgs;      // idle CUs stretch the launch
+      if (wgs * 4 < kNumCU * 7) cost *= (double)kNumCU * 7 / (wgs * 4);
       if (cost < best_cost) {
         best_cost = cost;
         plan->nt = nt;
@@ -471,7 +507,7 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
     g.p[i].A = p.A; g.p[i].W = p.W; g.p[i].bias = p.bias; g.p[i].out = p.out;
     g.p[i].M = p.M; g.p[i].N = p.N; g.p[i].K = p.K; g.p[i].lda = p.lda; g.p[i].ldo = p.ldo;
     g.p[i].epi = p.epi; g.p[i].splits = sp;
-    g.p[i].A_lo = p.A_lo; g.p[i].out_lo_off = p.out_lo_off;
+    g.p[i].A_lo = p.A_lo; g.p[i].out_lo_off = p.out_lo_off; g.p[i].W_frag = p.W_frag;
     if ((p.A_lo != nullptr) != (probs[0].A_lo != nullptr)) return hipErrorInvalidValue;
   }
   const bool hl = probs[0].A_lo != nullptr;
@@ -486,7 +522,7 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
       break;
     case KIND_KSLICE: {
       for (int i = 0; i < n_probs; ++i)
-        if (probs[i].K % (32 * plan.kf * plan.splits[i])) return hipErrorInvalidValue;
+        if (probs[i].K % (32 * plan.kf * plan.splits[i]) || !probs[i].W_frag) return hipErrorInvalidValue;
       const size_t lds = kslice_lds_bytes(probs[0].M, plan.kf, hl);
       if (lds > 160 * 1024) return hipErrorInvalidValue;
       hipError_t e;

@@ -64,6 +64,8 @@ enum { EPI_F32 = 0,        // out float [M, ldo]: acc + bias
 // lda / K contiguous.
 // A_lo (optional, bf16 mode): remainder plane of A, so that the product uses A + A_lo.
 // out_lo_off (EPI_GELU, bf16 mode): != 0 stores the output as hi / remainder planes.
+// W_frag (bf16 mode, required when M <= 256): the same weights in MFMA fragment order
+// (see gemm_pack_weights); the decode kernel reads only this copy.
 struct GemmProblem {
   const void* A;
   const void* W;
@@ -72,7 +74,15 @@ struct GemmProblem {
   int M, N, K, lda, ldo, epi;
   const void* A_lo;
   size_t out_lo_off;
+  const void* W_frag;
 };
+// bf16 weights W[N, K] (K % 32 == 0) re-ordered for the decode GEMM: tiles of 16 rows x 32 k,
+// tile (i, j) at element offset (i * K/32 + j) * 512; inside a tile lane l (0..63) owns the 8
+// consecutive elements W[16 i + (l & 15)][32 j + 8 (l >> 4) ...], i.e. exactly the B operand of
+// one 16x16x32 MFMA, so a wavefront fetches a fragment as 1 KB of consecutive bytes.
+// Rows past N (N rounded up to 16) are zero.
+size_t gemm_packed_elems(int N, int K);
+hipError_t gemm_pack_weights(const void* W, void* W_frag, int N, int K, hipStream_t s);
 // Which kernel serves a group of up to two problems, and into how many equal K
 // parts each EPI_PARTIAL problem is split (others: 1).  Depends on shapes only.
 struct GemmPlan {
