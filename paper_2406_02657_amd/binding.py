@@ -12,7 +12,7 @@ import os
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-lib_path = os.path.join(HERE, "libbt.so")
+lib_path = os.environ.get("BT_LIB", os.path.join(HERE, "libbt.so"))   # BT_LIB: debugging override
 if not os.path.exists(lib_path):
     raise ImportError(
         f"{lib_path} is missing: build it first (python -m paper_2406_02657_amd.build, "

@@ -454,6 +454,138 @@ __global__ void attn_local_kernel(PartialSrc qkv, T* __restrict__ Kl, T* __restr
 }
 
 // ---------------------------------------------------------------------------
+// Token decoder local attention with at most MAXJ keys per query (the usual case:
+// prefix tokens + block length is small).  One wave per (b, h), everything in
+// registers: lane owns dims d = lane + 64 c of q, of the new k, v and of every
+// cached row, so scores are lane-local products plus one wave reduction, and the
+// rotary partner comes from a shuffle.  All global loads of a row (cached rows,
+// the split-K pieces of q, k, v, the rotary pair) are issued before the first use:
+// one trip to memory per launch.  Same arithmetic as attn_local_kernel except
+// that the softmax is taken over all scores at once instead of online.
+// ---------------------------------------------------------------------------
+template <int DPL>
+__device__ __forceinline__ float shuffle_dim(const float* x, int p) {      // element p of a vector spread as x[c] = dim lane + 64 c
+  float r = 0.f;
+#pragma unroll
+  for (int c = 0; c < DPL; ++c) {
+    const float t = __shfl(x[c], p & 63, kWave);
+    if ((p >> 6) == c) r = t;
+  }
+  return r;
+}
+
+template <class T, int DH, int MAXJ>
+__global__ __launch_bounds__(256) void attn_local_reg_kernel(PartialSrc qkv, T* __restrict__ Kl, T* __restrict__ Vl,
+                                                             const float2* __restrict__ rope, T* __restrict__ out,
+                                                             size_t out_lo_off, int n_pairs, int n_heads, int rot, int rows,
+                                                             int pos0, int l_cap, int n_attn_blocks, GeluJob gelu) {
+  if ((int)blockIdx.x >= n_attn_blocks) {
+    gelu_reduce_block<T>(gelu, blockIdx.x - n_attn_blocks, gridDim.x - n_attn_blocks);
+    return;
+  }
+  constexpr int DPL = (DH + 63) / 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int pair_raw = blockIdx.x * (blockDim.x >> 6) + wave;
+  const bool active = pair_raw < n_pairs;
+  const int pair = active ? pair_raw : n_pairs - 1;     // idle waves shadow a valid pair, write nothing
+  const int b = pair / n_heads, h = pair - b * n_heads;
+  const int D = n_heads * DH, half = rot / 2;
+  T* Kg = Kl + (size_t)pair * l_cap * DH;
+  T* Vg = Vl + (size_t)pair * l_cap * DH;
+  const float sc = rsqrtf((float)DH);
+  int dcl[DPL];
+#pragma unroll
+  for (int c = 0; c < DPL; ++c) dcl[c] = min(lane + 64 * c, DH - 1);        // clamped dim: loads need no branch
+
+  // cached rows [0, pos0); slots past pos0 are zero until a new row lands there
+  float Kr[MAXJ][DPL], Vr[MAXJ][DPL];
+#pragma unroll
+  for (int j = 0; j < MAXJ; ++j) {
+    const int jc = min(j, max(pos0 - 1, 0));
+#pragma unroll
+    for (int c = 0; c < DPL; ++c) {
+      const float kx = to_float<T>(Kg[jc * DH + dcl[c]]), vx = to_float<T>(Vg[jc * DH + dcl[c]]);
+      Kr[j][c] = j < pos0 ? kx : 0.f;          // never-written cache memory may hold NaN patterns
+      Vr[j][c] = j < pos0 ? vx : 0.f;
+    }
+  }
+  for (int i = 0; i < rows; ++i) {
+    const int pos = pos0 + i;
+    const size_t row = (size_t)b * rows + i;
+    float q[DPL], k[DPL], v[DPL];
+    float2 cs[DPL];
+#pragma unroll
+    for (int c = 0; c < DPL; ++c) {
+      const int d = dcl[c];
+      const size_t src = row * 3 * D + h * DH + d;
+      q[c] = qkv.bias ? qkv.bias[h * DH + d] : 0.f;
+      k[c] = qkv.bias ? qkv.bias[D + h * DH + d] : 0.f;
+      v[c] = qkv.bias ? qkv.bias[2 * D + h * DH + d] : 0.f;
+      cs[c] = rope[(size_t)pos * half + (d < rot ? (d < half ? d : d - half) : 0)];
+      for (int s0 = 0; s0 < qkv.splits; s0 += 4) {
+        float t[3][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float* pb = qkv.base + (size_t)min(s0 + u, qkv.splits - 1) * qkv.stride + src;
+          t[0][u] = pb[0]; t[1][u] = pb[D]; t[2][u] = pb[2 * D];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float m = s0 + u < qkv.splits ? 1.f : 0.f;
+          q[c] += m * t[0][u]; k[c] += m * t[1][u]; v[c] += m * t[2][u];
+        }
+      }
+    }
+    float qv[DPL];
+#pragma unroll
+    for (int c = 0; c < DPL; ++c) {
+      const int d = lane + 64 * c;
+      float qd = q[c], kd = k[c];
+      const int partner = d < half ? d + half : d - half;
+      const float qp = shuffle_dim<DPL>(q, partner & (64 * DPL - 1)), kp = shuffle_dim<DPL>(k, partner & (64 * DPL - 1));
+      if (d < rot) {
+        if (d < half) { qd = qd * cs[c].x - qp * cs[c].y; kd = kd * cs[c].x - kp * cs[c].y; }
+        else          { qd = qd * cs[c].x + qp * cs[c].y; kd = kd * cs[c].x + kp * cs[c].y; }
+      }
+      qv[c] = d < DH ? qd * sc : 0.f;
+      const T kt = from_float<T>(kd), vt = from_float<T>(v[c]);
+      if (active && d < DH) { Kg[pos * DH + d] = kt; Vg[pos * DH + d] = vt; }
+      const float kf = to_float<T>(kt), vf = to_float<T>(vt);
+#pragma unroll
+      for (int j = 0; j < MAXJ; ++j)
+        if (j == pos) { Kr[j][c] = kf; Vr[j][c] = vf; }
+    }
+    float sj[MAXJ], m = kNegBig;
+#pragma unroll
+    for (int j = 0; j < MAXJ; ++j) {
+      float dot = 0.f;
+#pragma unroll
+      for (int c = 0; c < DPL; ++c) dot = fmaf(qv[c], Kr[j][c], dot);
+      dot = wave_sum(dot);
+      sj[j] = j <= pos ? dot : kNegBig;
+      m = fmaxf(m, sj[j]);
+    }
+    float l = 0.f, acc[DPL];
+#pragma unroll
+    for (int c = 0; c < DPL; ++c) acc[c] = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXJ; ++j) {
+      const float pj = j <= pos ? __expf(sj[j] - m) : 0.f;
+      l += pj;
+#pragma unroll
+      for (int c = 0; c < DPL; ++c) acc[c] = fmaf(pj, Vr[j][c], acc[c]);
+    }
+    if (active) {
+#pragma unroll
+      for (int c = 0; c < DPL; ++c) {
+        const int d = lane + 64 * c;
+        if (d < DH) store_act<T>(out, row * D + h * DH + d, out_lo_off, acc[c] / l);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 #define BT_DISPATCH_DH(DHV, ...)                         \
@@ -526,6 +658,21 @@ hipError_t launch_attn_local(int dtype, const PartialSrc& qkv, void* Kl, void* V
   if (rows < 1 || pos0 < 0 || pos0 + rows > l_cap) return hipErrorInvalidValue;
   if (gelu.rows > 0 && gelu.cols % 4) return hipErrorInvalidValue;
   const int n_pairs = batch * n_heads;
+  // few keys (the usual case): register kernel, sized by the number of keys this launch can see
+  const int n_keys = pos0 + rows;
+  if (n_keys <= 16) {
+    const int n_attn = (n_pairs + 3) / 4;
+    const int grid = n_attn + gelu_blocks(gelu);
+#define BT_LOCAL_REG(TT, MAXJ) BT_DISPATCH_DH(d_head, (attn_local_reg_kernel<TT, DH, MAXJ><<<grid, 256, 0, s>>>( \
+        qkv, (TT*)Kl, (TT*)Vl, rope, (TT*)out, dtype == BT_F32 ? 0 : out_lo_off, n_pairs, n_heads, rot, rows, pos0, l_cap, n_attn, gelu)))
+    if (dtype == BT_F32) {
+      if (n_keys <= 4) { BT_LOCAL_REG(float, 4); } else if (n_keys <= 8) { BT_LOCAL_REG(float, 8); } else { BT_LOCAL_REG(float, 16); }
+    } else {
+      if (n_keys <= 4) { BT_LOCAL_REG(bf16_t, 4); } else if (n_keys <= 8) { BT_LOCAL_REG(bf16_t, 8); } else { BT_LOCAL_REG(bf16_t, 16); }
+    }
+#undef BT_LOCAL_REG
+    return hipGetLastError();
+  }
   const size_t per_wave = (size_t)(2 * l_cap + 2) * d_head * sizeof(float);
   int nw = 4;
   while (nw > 1 && per_wave * nw > 60 * 1024) nw >>= 1;

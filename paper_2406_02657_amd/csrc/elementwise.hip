@@ -71,7 +71,7 @@ hipError_t launch_token_embed(int dtype, const void* E_tok, const int32_t* cur, 
 // Residual update + LayerNorm.  One workgroup (256 threads) per row; a thread
 // owns VPT groups of four consecutive floats, kept in registers (D <= 1024*VPT).
 // The split-K partial sums of the two producing GEMMs are added in a fixed order
-// (deterministic); their loads are issued eight at a time without branches.
+// (deterministic); all loads of a thread are issued together, without branches.
 // Mean and biased variance are taken in two passes over the registers, as the
 // definition states them.
 // ---------------------------------------------------------------------------
@@ -88,43 +88,54 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
 
 __device__ __forceinline__ void add4(float4& a, const float4& b) { a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; }
 
-// acc += sum over s < splits of part[s * stride + off .. off+3], eight loads in flight
-__device__ __forceinline__ void add_partials(float4& acc, const float* part, int splits, size_t stride, size_t off) {
-  for (int s0 = 0; s0 < splits; s0 += 8) {
-    float4 v[8];
+// acc += sum over the splits of partA, then of partB, of the float4 at element offset off.
+// The two lists are walked as one, kLnBatch loads in flight at a time and no branch around
+// them: indices past the end are clamped (the value is then multiplied by zero).
+constexpr int kLnBatch = 24;
+__device__ __forceinline__ void add_partials(float4& acc, const float* partA, int nA, const float* partB, int nB,
+                                             size_t stride, size_t off) {
+  const int n = nA + nB;
+  for (int s0 = 0; s0 < n; s0 += kLnBatch) {
+    float4 v[kLnBatch];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int s = min(s0 + u, splits - 1);
-      v[u] = *reinterpret_cast<const float4*>(part + (size_t)s * stride + off);
+    for (int u = 0; u < kLnBatch; ++u) {
+      const int s = min(s0 + u, n - 1);
+      const float* p = s < nA ? partA + (size_t)s * stride : partB + (size_t)(s - nA) * stride;
+      v[u] = *reinterpret_cast<const float4*>(p + off);
     }
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const float k = (s0 + u < splits) ? 1.f : 0.f;
+    for (int u = 0; u < kLnBatch; ++u) {
+      const float k = (s0 + u < n) ? 1.f : 0.f;
       acc.x += k * v[u].x; acc.y += k * v[u].y; acc.z += k * v[u].z; acc.w += k * v[u].w;
     }
   }
 }
 
 template <class T, int VPT>
-__global__ __launch_bounds__(kLnThreads) void resid_ln_kernel(ResidLnArgs a) {
+__global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void resid_ln_kernel(ResidLnArgs a) {
   __shared__ float red[4];
   const int i = blockIdx.x;
   const size_t row = (size_t)i * a.in_mul + a.in_off;
   const int D = a.D, G = D >> 2;
-  float4 v[VPT];
+  constexpr bool kEarly = VPT == 1;           // one group per thread: gamma / beta ride along the first trip to memory
+  float4 v[VPT], g1e, b1e, g2e, b2e;
   float* xr = a.x + row * D;
+  const int nA = a.partA ? a.splitsA : 0, nB = a.partB ? a.splitsB : 0;
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  // Every load of the kernel is issued here, before the first reduction: one trip to memory.
 #pragma unroll
   for (int c = 0; c < VPT; ++c) {
     const int g = min((int)threadIdx.x + c * kLnThreads, G - 1);     // clamped: no branch around the loads
+    if constexpr (kEarly) {
+      g1e = *reinterpret_cast<const float4*>(a.g1 + 4 * g);
+      b1e = *reinterpret_cast<const float4*>(a.b1 + 4 * g);
+      g2e = a.g2 ? *reinterpret_cast<const float4*>(a.g2 + 4 * g) : zero;
+      b2e = a.g2 ? *reinterpret_cast<const float4*>(a.b2 + 4 * g) : zero;
+    }
     float4 acc = *reinterpret_cast<const float4*>(xr + 4 * g);
-    if (a.partA) {
-      if (a.biasA) add4(acc, *reinterpret_cast<const float4*>(a.biasA + 4 * g));
-      add_partials(acc, a.partA, a.splitsA, a.part_stride, row * D + 4 * g);
-    }
-    if (a.partB) {
-      if (a.biasB) add4(acc, *reinterpret_cast<const float4*>(a.biasB + 4 * g));
-      add_partials(acc, a.partB, a.splitsB, a.part_stride, row * D + 4 * g);
-    }
+    if (nA && a.biasA) add4(acc, *reinterpret_cast<const float4*>(a.biasA + 4 * g));
+    if (nB && a.biasB) add4(acc, *reinterpret_cast<const float4*>(a.biasB + 4 * g));
+    if (nA + nB) add_partials(acc, a.partA, nA, a.partB, nB, a.part_stride, row * D + 4 * g);
     v[c] = acc;
   }
   float sum = 0.f;
@@ -152,7 +163,9 @@ __global__ __launch_bounds__(kLnThreads) void resid_ln_kernel(ResidLnArgs a) {
     const int g = threadIdx.x + c * kLnThreads;
     if (g < G) {
       const float n[4] = {(v[c].x - mean) * rstd, (v[c].y - mean) * rstd, (v[c].z - mean) * rstd, (v[c].w - mean) * rstd};
-      const float4 g1 = *reinterpret_cast<const float4*>(a.g1 + 4 * g), b1 = *reinterpret_cast<const float4*>(a.b1 + 4 * g);
+      float4 g1, b1;
+      if constexpr (kEarly) { g1 = g1e; b1 = b1e; }
+      else { g1 = *reinterpret_cast<const float4*>(a.g1 + 4 * g); b1 = *reinterpret_cast<const float4*>(a.b1 + 4 * g); }
       const float o1[4] = {n[0] * g1.x + b1.x, n[1] * g1.y + b1.y, n[2] * g1.z + b1.z, n[3] * g1.w + b1.w};
       const size_t o = (size_t)i * D + 4 * g;
       if (a.u1_f32) {
@@ -161,7 +174,9 @@ __global__ __launch_bounds__(kLnThreads) void resid_ln_kernel(ResidLnArgs a) {
         store_act4<T>(reinterpret_cast<T*>(a.u1), o, a.lo_off, o1[0], o1[1], o1[2], o1[3]);
       }
       if (a.g2) {
-        const float4 g2 = *reinterpret_cast<const float4*>(a.g2 + 4 * g), b2 = *reinterpret_cast<const float4*>(a.b2 + 4 * g);
+        float4 g2, b2;
+        if constexpr (kEarly) { g2 = g2e; b2 = b2e; }
+        else { g2 = *reinterpret_cast<const float4*>(a.g2 + 4 * g); b2 = *reinterpret_cast<const float4*>(a.b2 + 4 * g); }
         const float o2[4] = {n[0] * g2.x + b2.x, n[1] * g2.y + b2.y, n[2] * g2.z + b2.z, n[3] * g2.w + b2.w};
         store_act4<T>(reinterpret_cast<T*>(a.u2), o, a.lo_off, o2[0], o2[1], o2[2], o2[3]);
       }

@@ -231,7 +231,10 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
   constexpr int KS = 32 * KF, LDK = KS + 8, CPR = KS / 8, PL = HL ? 2 : 1;
   extern __shared__ __attribute__((aligned(16))) uint16_t sA[];
   const int bid = blockIdx.x;
-  const GemmDesc& d = (g.n > 1 && bid >= g.p[1].tile_begin) ? g.p[1] : g.p[0];
+  // The descriptor is copied into registers at once: every field the epilogue needs is then
+  // already there instead of being fetched from the argument block after the multiply.
+  GemmDesc d = g.p[0];
+  if (g.n > 1 && bid >= g.p[1].tile_begin) d = g.p[1];
   const int t = bid - d.tile_begin;
   const int split = t / d.tiles_n, tn = t - split * d.tiles_n;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -317,6 +320,22 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
       }
     }
     __syncthreads();
+  }
+  if (d.epi == EPI_PARTIAL) {
+    float* outp = reinterpret_cast<float*>(d.out) + (size_t)split * d.M * d.N;
+#pragma unroll
+    for (int mc = 0; mc < MC; ++mc)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const int col = n0 + nt * 16 + (lane & 15);
+          const int row0 = mc * 64 + mt * 16 + (lane >> 4) * 4;
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (row0 + r < d.M && col < d.N) outp[(size_t)(row0 + r) * d.N + col] = acc[mc][nt][mt][r];
+        }
+    return;
   }
 #pragma unroll
   for (int mc = 0; mc < MC; ++mc)
