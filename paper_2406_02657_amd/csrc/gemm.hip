@@ -61,10 +61,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmGroup g) {
   __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LDS];
 
   const int bid = blockIdx.x;
-  const GemmDesc& d = (g.n > 1 && bid >= g.p[1].tile_begin) ? g.p[1] : g.p[0];
+  GemmDesc d = g.p[0];
+  if (g.n > 1 && bid >= g.p[1].tile_begin) d = g.p[1];
   int t = bid - d.tile_begin;
-  const int split = t / (d.tiles_m * d.tiles_n);
-  t -= split * d.tiles_m * d.tiles_n;
+  const int T = d.tiles_m * d.tiles_n;
+  const int split = t / T;
+  t -= split * T;
+  // Tile order.  Workgroups are dealt to the 8 XCDs round-robin and each XCD has its own L2, so
+  // XCD x takes a contiguous run of the tile list (t -> start(x) + t / 8); the list itself walks
+  // kGroupM row tiles down, then one column tile across.  The workgroups resident on an XCD at
+  // one time thus cover a compact patch of the output and share their A and W tiles in its L2.
+  {
+    constexpr int kXcd = 8, kGroupM = 8;
+    const int x = t % kXcd, q = T / kXcd, rem = T % kXcd;
+    t = x * q + min(x, rem) + t / kXcd;
+    const int per_group = kGroupM * d.tiles_n;
+    const int grp = t / per_group, within = t - grp * per_group;
+    const int gm = min(kGroupM, d.tiles_m - grp * kGroupM);
+    t = (grp * kGroupM + within % gm) + (within / gm) * d.tiles_m;      // = tm + tn * tiles_m
+  }
   const int tm_idx = t % d.tiles_m, tn_idx = t / d.tiles_m;
   const int m0 = tm_idx * BM, n0 = tn_idx * BN;
   const int Ks = d.K / d.splits;
@@ -175,7 +190,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmGroup g) {
   __shared__ float sA[BK][BM + 4];
   __shared__ float sB[BK][BN + 4];
   const int bid = blockIdx.x;
-  const GemmDesc& d = (g.n > 1 && bid >= g.p[1].tile_begin) ? g.p[1] : g.p[0];
+  GemmDesc d = g.p[0];
+  if (g.n > 1 && bid >= g.p[1].tile_begin) d = g.p[1];
   int t = bid - d.tile_begin;
   const int split = t / (d.tiles_m * d.tiles_n);
   t -= split * d.tiles_m * d.tiles_n;
