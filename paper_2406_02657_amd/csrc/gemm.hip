@@ -12,6 +12,9 @@ namespace bt {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+// 16 bytes in flight between global memory and LDS.  A native vector, not HIP's uint4 struct:
+// arrays of the struct that live across loop iterations end up in private memory.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 struct GemmDesc {
   const void* A;
@@ -31,8 +34,19 @@ struct GemmGroup {
 
 __device__ __forceinline__ float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
 
+// What an epilogue needs from the descriptor, as plain values (kept in registers).
+struct EpiArgs {
+  void* out;
+  const float* bias;
+  int M, N, ldo, epi;
+  size_t out_lo_off;
+};
+__device__ __forceinline__ EpiArgs epi_args(const GemmDesc& d) {
+  return EpiArgs{d.out, d.bias, d.M, d.N, d.ldo, d.epi, d.out_lo_off};
+}
+
 template <class T>
-__device__ __forceinline__ void epilogue_store(const GemmDesc& d, int split, int row, int col, float acc) {
+__device__ __forceinline__ void epilogue_store(const EpiArgs& d, int split, int row, int col, float acc) {
   if (row >= d.M || col >= d.N) return;
   if (d.epi == EPI_PARTIAL) {
     reinterpret_cast<float*>(d.out)[((size_t)split * d.M + row) * d.N + col] = acc;
@@ -63,6 +77,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmGroup g) {
   const int bid = blockIdx.x;
   GemmDesc d = g.p[0];
   if (g.n > 1 && bid >= g.p[1].tile_begin) d = g.p[1];
+  const EpiArgs ea = epi_args(d);
   int t = bid - d.tile_begin;
   const int T = d.tiles_m * d.tiles_n;
   const int split = t / T;
@@ -117,33 +132,35 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmGroup g) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  uint4 ra[A_CH], rb[B_CH], rl[HL ? A_CH : 1];
+  u32x4_t ra[A_CH], rb[B_CH], rl[HL ? A_CH : 1];
 #pragma unroll
   for (int i = 0; i < A_CH; ++i) {
-    ra[i] = *reinterpret_cast<const uint4*>(a_ptr[i]);
-    if constexpr (HL) rl[i] = *reinterpret_cast<const uint4*>(a_ptr[i] + lo_delta);
+    ra[i] = *reinterpret_cast<const u32x4_t*>(a_ptr[i]);
+    if constexpr (HL) rl[i] = *reinterpret_cast<const u32x4_t*>(a_ptr[i] + lo_delta);
   }
 #pragma unroll
-  for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_ptr[i]);
+  for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const u32x4_t*>(b_ptr[i]);
 
   const int frag_row = lane & 15, frag_k = (lane >> 4) * 8;
   for (int kt = 0; kt < KT; ++kt) {
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
-      *reinterpret_cast<uint4*>(&sA[a_lds[i]]) = ra[i];
-      if constexpr (HL) *reinterpret_cast<uint4*>(&sAl[a_lds[i]]) = rl[i];
+      *reinterpret_cast<u32x4_t*>(&sA[a_lds[i]]) = ra[i];
+      if constexpr (HL) *reinterpret_cast<u32x4_t*>(&sAl[a_lds[i]]) = rl[i];
     }
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4*>(&sB[b_lds[i]]) = rb[i];
+    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4_t*>(&sB[b_lds[i]]) = rb[i];
     __syncthreads();
-    if (kt + 1 < KT) {
+    {
+      // next stage (the last iteration re-reads its own stage: no branch around the loads)
+      const size_t ko = (size_t)min(kt + 1, KT - 1) * BK;
 #pragma unroll
       for (int i = 0; i < A_CH; ++i) {
-        ra[i] = *reinterpret_cast<const uint4*>(a_ptr[i] + (size_t)(kt + 1) * BK);
-        if constexpr (HL) rl[i] = *reinterpret_cast<const uint4*>(a_ptr[i] + lo_delta + (size_t)(kt + 1) * BK);
+        ra[i] = *reinterpret_cast<const u32x4_t*>(a_ptr[i] + ko);
+        if constexpr (HL) rl[i] = *reinterpret_cast<const u32x4_t*>(a_ptr[i] + lo_delta + ko);
       }
 #pragma unroll
-      for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_ptr[i] + (size_t)(kt + 1) * BK);
+      for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const u32x4_t*>(b_ptr[i] + ko);
     }
 #pragma unroll
     for (int ks = 0; ks < BK / 32; ++ks) {
@@ -178,7 +195,124 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmGroup g) {
       const int col = n0 + wn * (BN / WN) + j * 16 + (lane & 15);
       const int row0 = m0 + wm * (BM / WM) + i * 16 + (lane >> 4) * 4;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) epilogue_store<bf16_t>(d, split, row0 + r, col, acc[i][j][r]);
+      for (int r = 0; r < 4; ++r) epilogue_store<bf16_t>(ea, split, row0 + r, col, acc[i][j][r]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// bf16 MFMA kernel for large M and N: 256 x 256 tile, BK = 64, 512 threads =
+// 8 waves laid out 2 (rows) x 4 (columns), each wave a 128 x 64 patch
+// (8 x 4 MFMA tiles).  A CU takes in operand bytes far more slowly than its
+// matrix cores consume them, so the tile is as large as the register file
+// allows: per byte loaded it does twice the work of the 128 x 128 tile.
+// Global -> registers -> LDS, next stage in flight during the multiply.
+// ---------------------------------------------------------------------------
+template <bool HL>
+__global__ __launch_bounds__(512) void gemm_bf16_big_kernel(GemmGroup g) {
+  constexpr int BM = 256, BN = 256, BK = 64, LDS = BK + 8;
+  constexpr int CH = BM * (BK / 8) / 512;       // 16-byte chunks per thread and operand plane (= 4)
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  uint16_t* sA = smem;
+  uint16_t* sB = smem + BM * LDS;
+  uint16_t* sAl = smem + (BM + BN) * LDS;       // only with HL
+
+  const int bid = blockIdx.x;
+  GemmDesc d = g.p[0];
+  if (g.n > 1 && bid >= g.p[1].tile_begin) d = g.p[1];
+  const EpiArgs ea = epi_args(d);
+  int t = bid - d.tile_begin;
+  const int T = d.tiles_m * d.tiles_n;
+  const int split = t / T;
+  t -= split * T;
+  {   // same tile order as the 128 x 128 kernel: a contiguous run per XCD, 4 row tiles down then across
+    constexpr int kXcd = 8, kGroupM = 4;
+    const int x = t % kXcd, q = T / kXcd, rem = T % kXcd;
+    t = x * q + min(x, rem) + t / kXcd;
+    const int per_group = kGroupM * d.tiles_n;
+    const int grp = t / per_group, within = t - grp * per_group;
+    const int gm = min(kGroupM, d.tiles_m - grp * kGroupM);
+    t = (grp * kGroupM + within % gm) + (within / gm) * d.tiles_m;
+  }
+  const int m0 = (t % d.tiles_m) * BM, n0 = (t / d.tiles_m) * BN;
+  const int Ks = d.K / d.splits, k_begin = split * Ks, KT = Ks / BK;
+  const uint16_t* A = reinterpret_cast<const uint16_t*>(d.A);
+  const uint16_t* W = reinterpret_cast<const uint16_t*>(d.W);
+  const ptrdiff_t lo_delta = HL ? reinterpret_cast<const uint16_t*>(d.A_lo) - A : 0;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+
+  // chunk c = tid + i * 512 -> row c >> 3, k-chunk c & 7 (rows 64 apart for consecutive i)
+  const int ld_row = tid >> 3, ld_kc = tid & 7;
+  const uint16_t* a_ptr[CH];
+  const uint16_t* b_ptr[CH];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    a_ptr[i] = A + (size_t)min(m0 + ld_row + 64 * i, d.M - 1) * d.lda + k_begin + ld_kc * 8;
+    b_ptr[i] = W + (size_t)min(n0 + ld_row + 64 * i, d.N - 1) * d.K + k_begin + ld_kc * 8;
+  }
+  const int lds_st = ld_row * LDS + ld_kc * 8;
+
+  f32x4_t acc[8][4];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  u32x4_t ra[CH], rb[CH], rl[HL ? CH : 1];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    ra[i] = *reinterpret_cast<const u32x4_t*>(a_ptr[i]);
+    if constexpr (HL) rl[i] = *reinterpret_cast<const u32x4_t*>(a_ptr[i] + lo_delta);
+    rb[i] = *reinterpret_cast<const u32x4_t*>(b_ptr[i]);
+  }
+  const int frag_row = lane & 15, frag_k = (lane >> 4) * 8;
+  const uint16_t* fa_base = sA + (wm * 128 + frag_row) * LDS + frag_k;
+  const uint16_t* fb_base = sB + (wn * 64 + frag_row) * LDS + frag_k;
+  for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      *reinterpret_cast<u32x4_t*>(&sA[lds_st + 64 * i * LDS]) = ra[i];
+      if constexpr (HL) *reinterpret_cast<u32x4_t*>(&sAl[lds_st + 64 * i * LDS]) = rl[i];
+      *reinterpret_cast<u32x4_t*>(&sB[lds_st + 64 * i * LDS]) = rb[i];
+    }
+    __syncthreads();
+    {
+      const size_t ko = (size_t)min(kt + 1, KT - 1) * BK;     // last iteration re-reads its own stage: no branch
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        ra[i] = *reinterpret_cast<const u32x4_t*>(a_ptr[i] + ko);
+        if constexpr (HL) rl[i] = *reinterpret_cast<const u32x4_t*>(a_ptr[i] + lo_delta + ko);
+        rb[i] = *reinterpret_cast<const u32x4_t*>(b_ptr[i] + ko);
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < BK / 32; ++ks) {
+      bf16x8_t fb[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        fb[j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(fb_base + j * 16 * LDS + ks * 32));
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const bf16x8_t fa = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(fa_base + i * 16 * LDS + ks * 32));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb[j], acc[i][j], 0, 0, 0);
+        if constexpr (HL) {
+          const bf16x8_t fl = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(fa_base + (BM + BN) * LDS + i * 16 * LDS + ks * 32));
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fl, fb[j], acc[i][j], 0, 0, 0);
+        }
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int col = n0 + wn * 64 + j * 16 + (lane & 15);
+      const int row0 = m0 + wm * 128 + i * 16 + (lane >> 4) * 4;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) epilogue_store<bf16_t>(ea, split, row0 + r, col, acc[i][j][r]);
     }
 }
 
@@ -192,6 +326,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmGroup g) {
   const int bid = blockIdx.x;
   GemmDesc d = g.p[0];
   if (g.n > 1 && bid >= g.p[1].tile_begin) d = g.p[1];
+  const EpiArgs ea = epi_args(d);
   int t = bid - d.tile_begin;
   const int split = t / (d.tiles_m * d.tiles_n);
   t -= split * d.tiles_m * d.tiles_n;
@@ -228,7 +363,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmGroup g) {
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) epilogue_store<float>(d, split, m0 + ty * 4 + i, n0 + tx * 4 + j, acc[i][j]);
+    for (int j = 0; j < 4; ++j) epilogue_store<float>(ea, split, m0 + ty * 4 + i, n0 + tx * 4 + j, acc[i][j]);
 }
 
 // ---------------------------------------------------------------------------
@@ -251,6 +386,7 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
   // already there instead of being fetched from the argument block after the multiply.
   GemmDesc d = g.p[0];
   if (g.n > 1 && bid >= g.p[1].tile_begin) d = g.p[1];
+  const EpiArgs ea = epi_args(d);
   const int t = bid - d.tile_begin;
   const int split = t / d.tiles_n, tn = t - split * d.tiles_n;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -362,7 +498,7 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
         const int col = n0 + nt * 16 + (lane & 15);
         const int row0 = mc * 64 + mt * 16 + (lane >> 4) * 4;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) epilogue_store<bf16_t>(d, split, row0 + r, col, acc[mc][nt][mt][r]);
+        for (int r = 0; r < 4; ++r) epilogue_store<bf16_t>(ea, split, row0 + r, col, acc[mc][nt][mt][r]);
       }
 }
 
@@ -384,7 +520,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t* __res
 // host side
 // ---------------------------------------------------------------------------
 namespace {
-enum { KIND_F32 = 0, KIND_TILE128 = 1, KIND_KSLICE = 2 };
+enum { KIND_F32 = 0, KIND_TILE128 = 1, KIND_KSLICE = 2, KIND_TILE256 = 3 };
 constexpr int kMaxSkinnyRows = 256;
 constexpr int kNumCU = 256;
 
@@ -439,7 +575,13 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
         if (probs[i].epi == EPI_PARTIAL) plan->splits[i] = f32_splits(probs[i].N, probs[i].K);
     return hipSuccess;
   }
-  if (max_m > kMaxSkinnyRows) { plan->kind = KIND_TILE128; return hipSuccess; }
+  if (max_m > kMaxSkinnyRows) {
+    // 256 x 256 tiles when they still fill the GPU; otherwise 128 x 128
+    long tiles256 = 0;
+    for (int i = 0; i < n_probs; ++i) tiles256 += (long)((probs[i].M + 255) / 256) * ((probs[i].N + 255) / 256);
+    plan->kind = tiles256 >= kNumCU ? KIND_TILE256 : KIND_TILE128;
+    return hipSuccess;
+  }
 
   // K-slice kernel.  Slice length: the longest of 256/192/128/64 that divides every K and keeps
   // the staged activation slice within 64 KB of LDS (at least two workgroups per CU).
@@ -555,6 +697,19 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
       if (hl) gemm_bf16_kernel<128, 128, 2, 2, true><<<fill_tiles<128, 128>(g), 256, 0, s>>>(g);
       else gemm_bf16_kernel<128, 128, 2, 2, false><<<fill_tiles<128, 128>(g), 256, 0, s>>>(g);
       break;
+    case KIND_TILE256: {
+      const size_t lds = (size_t)(512 + (hl ? 256 : 0)) * 72 * 2;
+      static bool attr_set[2] = {false, false};
+      const void* fn = hl ? reinterpret_cast<const void*>(gemm_bf16_big_kernel<true>) : reinterpret_cast<const void*>(gemm_bf16_big_kernel<false>);
+      if (!attr_set[hl]) {
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set[hl] = true;
+      }
+      if (hl) gemm_bf16_big_kernel<true><<<fill_tiles<256, 256>(g), 512, lds, s>>>(g);
+      else gemm_bf16_big_kernel<false><<<fill_tiles<256, 256>(g), 512, lds, s>>>(g);
+      break;
+    }
     case KIND_KSLICE: {
       for (int i = 0; i < n_probs; ++i)
         if (probs[i].K % (32 * plan.kf * plan.splits[i]) || !probs[i].W_frag) return hipErrorInvalidValue;
