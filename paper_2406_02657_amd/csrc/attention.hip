@@ -307,6 +307,164 @@ __global__ __launch_bounds__(256) void attn_block_prefill_kernel(const float* __
 }
 
 // ---------------------------------------------------------------------------
+// Block decoder, prefill, bf16 mode with many queries: causal attention as two
+// dense contractions on the matrix cores (v_mfma_f32_16x16x32_bf16).
+// Workgroup = one (b, h) x 64 consecutive queries, wave = 16 of them.  Keys are
+// walked in blocks of 32 up to the diagonal:
+//   S = Q K^T   A operand = q (scaled by 1/sqrt(d_h), split into bf16 hi + remainder,
+//               two MFMAs), B operand = a K row chunk straight from the cache;
+//   online softmax on S in the MFMA result layout (a lane holds 4 queries x 1 key per
+//               16-key tile; row max / sum by shuffles over the 16 lanes of a row);
+//   O += P V    P goes through LDS to become an A operand (hi + remainder again), V is
+//               staged transposed in LDS ([d][key]) so that a B fragment (8 consecutive
+//               keys of one d) is one 16-byte read.
+// Results match the plain kernel to fp32 rounding: every bf16 operand is either an exact
+// stored value (K, V) or carried as hi + remainder (q, p).
+// ---------------------------------------------------------------------------
+typedef __bf16 abf16x8_t __attribute__((ext_vector_type(8)));
+typedef float af32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void split8(const float* x, abf16x8_t& hi, abf16x8_t& lo) {
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const uint32_t h0 = float_to_bf16_bits(x[2 * e]), h1 = float_to_bf16_bits(x[2 * e + 1]);
+    const uint32_t l0 = float_to_bf16_bits(x[2 * e] - bf16_bits_to_float(h0));
+    const uint32_t l1 = float_to_bf16_bits(x[2 * e + 1] - bf16_bits_to_float(h1));
+    h[e] = h0 | (h1 << 16);
+    l[e] = l0 | (l1 << 16);
+  }
+  hi = __builtin_bit_cast(abf16x8_t, make_uint4(h[0], h[1], h[2], h[3]));
+  lo = __builtin_bit_cast(abf16x8_t, make_uint4(l[0], l[1], l[2], l[3]));
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_block_prefill_mfma_kernel(const float* __restrict__ qkv, const bf16_t* __restrict__ Kc,
+                                                                      const bf16_t* __restrict__ Vc, bf16_t* __restrict__ out,
+                                                                      size_t out_lo_off, int n_heads, int n_q, int n_cap) {
+  constexpr int KB = 32;                 // keys per block
+  constexpr int KP = KB + 8;             // padded key stride of the LDS tiles (elements)
+  constexpr int NC = DH / 32;            // 32-dim chunks of a head
+  constexpr int ND = DH / 16;            // 16-dim tiles of the output
+  __shared__ __attribute__((aligned(16))) uint16_t sVt[DH * KP];          // V block, transposed: [d][key]
+  __shared__ __attribute__((aligned(16))) uint16_t sP[4][2][16 * KP];     // per wave: p hi / remainder, [query][key]
+
+  const int bh = blockIdx.y;
+  const int b = bh / n_heads, h = bh - b * n_heads;
+  const int D = n_heads * DH;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int n_tiles = (n_q + 63) / 64;
+  const int q_wg = (n_tiles - 1 - (int)blockIdx.x) * 64;      // long rows first
+  const int q_w = q_wg + wave * 16;                           // first query of this wave
+  const bf16_t* K = Kc + (size_t)bh * n_cap * DH;
+  const bf16_t* V = Vc + (size_t)bh * n_cap * DH;
+
+  // A operand: q of query q_w + lr, dims 32 c + 8 lg .. + 8, scaled, as hi + remainder
+  abf16x8_t qh[NC], ql[NC];
+  {
+    const int qi = min(q_w + lr, n_q - 1);
+    const float* qp = qkv + ((size_t)b * n_q + qi) * 3 * D + h * DH + lg * 8;
+    const float sc = rsqrtf((float)DH);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const float4 a = *reinterpret_cast<const float4*>(qp + c * 32), bq = *reinterpret_cast<const float4*>(qp + c * 32 + 4);
+      const float x[8] = {a.x * sc, a.y * sc, a.z * sc, a.w * sc, bq.x * sc, bq.y * sc, bq.z * sc, bq.w * sc};
+      split8(x, qh[c], ql[c]);
+    }
+  }
+  af32x4_t o[ND];
+#pragma unroll
+  for (int t = 0; t < ND; ++t) o[t] = af32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m[4], l[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) { m[r] = kNegBig; l[r] = 0.f; }
+
+  const int last_key_wg = min(q_wg + 63, n_q - 1);
+  const int last_key_w = min(q_w + 15, n_q - 1);
+  for (int k0 = 0; k0 <= last_key_wg; k0 += KB) {
+    // V block -> LDS, transposed.  Thread t: key t / (DH/8), dims 8 (t % (DH/8)) .. + 8.
+    __syncthreads();                       // the previous block's fragments have been read
+    for (int c = tid; c < KB * (DH / 8); c += 256) {
+      const int key = c / (DH / 8), dc = c - key * (DH / 8);
+      uint4 v = *reinterpret_cast<const uint4*>(V + (size_t)min(k0 + key, n_cap - 1) * DH + dc * 8);
+      if (k0 + key >= n_q) v = make_uint4(0u, 0u, 0u, 0u);     // never-written rows may hold NaN patterns: 0 * NaN
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sVt[(dc * 8 + e) * KP + key] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+    }
+    __syncthreads();
+    if (k0 <= last_key_w) {                // blocks entirely above this wave's diagonal contribute nothing
+      // S = Q K^T for two 16-key tiles
+      af32x4_t sacc[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        sacc[t] = af32x4_t{0.f, 0.f, 0.f, 0.f};
+        const bf16_t* kp = K + (size_t)min(k0 + t * 16 + lr, n_cap - 1) * DH + lg * 8;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+          const abf16x8_t kf = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(kp + c * 32));
+          sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qh[c], kf, sacc[t], 0, 0, 0);
+          sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ql[c], kf, sacc[t], 0, 0, 0);
+        }
+      }
+      // lane holds S[query q_w + 4 lg + r][key k0 + 16 t + lr]
+      float alpha[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int qi = q_w + 4 * lg + r;
+        float s0 = (k0 + lr <= qi) ? sacc[0][r] : kNegBig;
+        float s1 = (k0 + 16 + lr <= qi) ? sacc[1][r] : kNegBig;
+        float mx = fmaxf(s0, s1);
+#pragma unroll
+        for (int off = 8; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+        const float mn = fmaxf(m[r], mx);
+        const float p0 = (k0 + lr <= qi) ? __expf(s0 - mn) : 0.f;
+        const float p1 = (k0 + 16 + lr <= qi) ? __expf(s1 - mn) : 0.f;
+        float ps = p0 + p1;
+#pragma unroll
+        for (int off = 8; off > 0; off >>= 1) ps += __shfl_xor(ps, off, kWave);
+        alpha[r] = __expf(m[r] - mn);
+        l[r] = l[r] * alpha[r] + ps;
+        m[r] = mn;
+        // p -> LDS as hi + remainder, [query][key]
+        const uint16_t h0 = float_to_bf16_bits(p0), h1 = float_to_bf16_bits(p1);
+        sP[wave][0][(4 * lg + r) * KP + lr] = h0;
+        sP[wave][0][(4 * lg + r) * KP + 16 + lr] = h1;
+        sP[wave][1][(4 * lg + r) * KP + lr] = float_to_bf16_bits(p0 - bf16_bits_to_float(h0));
+        sP[wave][1][(4 * lg + r) * KP + 16 + lr] = float_to_bf16_bits(p1 - bf16_bits_to_float(h1));
+      }
+#pragma unroll
+      for (int t = 0; t < ND; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[t][r] *= alpha[r];
+      __builtin_amdgcn_wave_barrier();
+      // O += P V: A = p of query q_w + lr, keys 8 lg .. + 8; B = V^T rows d = 16 t + lr, the same keys
+      const abf16x8_t ph = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(&sP[wave][0][lr * KP + lg * 8]));
+      const abf16x8_t pl = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(&sP[wave][1][lr * KP + lg * 8]));
+#pragma unroll
+      for (int t = 0; t < ND; ++t) {
+        const abf16x8_t vf = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(&sVt[(t * 16 + lr) * KP + lg * 8]));
+        o[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ph, vf, o[t], 0, 0, 0);
+        o[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pl, vf, o[t], 0, 0, 0);
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+  // lane holds O[query q_w + 4 lg + r][d = 16 t + lr]
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int qi = q_w + 4 * lg + r;
+    if (qi < n_q) {
+      const float inv = 1.0f / l[r];
+      const size_t row = (size_t)b * n_q + qi;
+#pragma unroll
+      for (int t = 0; t < ND; ++t) store_act<bf16_t>(out, row * D + h * DH + t * 16 + lr, out_lo_off, o[t][r] * inv);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Block decoder: rotary on q (in place) and k, append k, v to the block cache.
 // One workgroup per row.
 // ---------------------------------------------------------------------------
@@ -645,6 +803,11 @@ hipError_t launch_attn_block_prefill(int dtype, const float* qkv, const void* Kc
   if (dtype == BT_F32) {
     BT_DISPATCH_DH(d_head, (attn_block_prefill_kernel<float, DH><<<grid, 256, 0, s>>>(
         qkv, (const float*)Kc, (const float*)Vc, (float*)out, 0, n_heads, n_q, n_cap)));
+  } else if (n_q >= 64) {
+    // many queries per sequence: dense contractions on the matrix cores
+    const dim3 grid_m((n_q + 63) / 64, batch * n_heads);
+    BT_DISPATCH_DH(d_head, (attn_block_prefill_mfma_kernel<DH><<<grid_m, 256, 0, s>>>(
+        qkv, (const bf16_t*)Kc, (const bf16_t*)Vc, (bf16_t*)out, out_lo_off, n_heads, n_q, n_cap)));
   } else {
     BT_DISPATCH_DH(d_head, (attn_block_prefill_kernel<bf16_t, DH><<<grid, 256, 0, s>>>(
         qkv, (const bf16_t*)Kc, (const bf16_t*)Vc, (bf16_t*)out, out_lo_off, n_heads, n_q, n_cap)));

@@ -100,7 +100,8 @@ def compare_sampled_with_oracle(cfg, weights, prompts_np, gpu_ids, gpu_logits, s
     for t in steps:
         i, k = (T_p + t) // L, (T_p + t) % L
         ref = tf[i][:, k]
-        worst = max(worst, float(np.max(np.abs(gpu_logits[t].astype(np.float64) - ref))))
+        dmax = float(np.max(np.abs(gpu_logits[t].astype(np.float64) - ref)))
+        worst = max(worst, dmax) if np.isfinite(dmax) else float("inf")      # a NaN logit fails the tolerance
         srt = np.sort(ref, axis=-1)
         o_margin = srt[:, -1] - srt[:, -2]
         mism = gpu_ids[seqs, t] != np.argmax(ref, axis=-1)

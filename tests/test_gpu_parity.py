@@ -108,6 +108,15 @@ def test_bf16_streaming_gemm_shapes(amd, d, h, f, b, p, lb):
     run_case(amd, cfg, 2 * lb + 1, batch=b)
 
 
+@pytest.mark.parametrize("d,h,blocks", [(128, 4, 80), (256, 4, 145), (256, 2, 64), (128, 1, 97)])
+def test_bf16_prefill_attention_on_matrix_cores(amd, d, h, blocks):
+    """Prompts of at least 64 blocks take the MFMA causal-attention kernel of the block decoder's
+    prefill: head sizes 32 / 64 / 128, query counts that leave ragged 64-query and 32-key tiles."""
+    cfg = tiny_cfg(dtype="bf16", block_len=2, prefix_len=1, d_model=d, n_heads=h, d_ff=2 * d, vocab=200,
+                   prompt_len=2 * blocks, n_block_layers=2, n_token_layers=1)
+    run_case(amd, cfg, 3, batch=3)
+
+
 def test_bf16_prefill_large_tiles_ragged(amd):
     """Prefill big enough for the 256 x 256 MFMA tiles (>= 256 tiles) with a ragged last row tile
     (3300 = 12 * 256 + 228 block rows) and column tiles that do not fill the 4 x 8 tile blocks."""
