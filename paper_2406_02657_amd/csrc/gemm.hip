@@ -584,13 +584,16 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
   }
 
   // K-slice kernel.  Slice length: the longest of 256/192/128/64 that divides every K and keeps
-  // the staged activation slice within 64 KB of LDS (at least two workgroups per CU).
+  // the staged activation slice within the LDS budget below.
   plan->kind = KIND_KSLICE;
   plan->mc = (max_m + 63) / 64;
   if (plan->mc == 3) plan->mc = 4;
+  // Up to 128 rows the slice stays within 64 KB (two workgroups per CU overlap their phases); with
+  // more rows the multiply dominates and a longer slice (one workgroup per CU) pays.
+  const size_t lds_cap = max_m <= 128 ? 64 * 1024 : 144 * 1024;
   int kf = 2;
   for (int c : {8, 6, 4, 2}) {
-    bool ok = kslice_lds_bytes(max_m, c, hl) <= 64 * 1024;
+    bool ok = kslice_lds_bytes(max_m, c, hl) <= lds_cap;
     for (int i = 0; i < n_probs && ok; ++i) ok = probs[i].K % (32 * c) == 0;
     if (ok) { kf = c; break; }
   }
@@ -620,7 +623,9 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
         cost += (double)tiles * p.M * p.K * (hl ? 4 : 2);                  // activation reads
         if (p.epi == EPI_PARTIAL) cost += (double)spl[i] * p.M * p.N * 8;  // partials out and back
       }
-      if (wgs * 4 < kNumCU * 7) cost *= (double)kNumCU * 7 / (wgs * 4);
+      // workgroups wanted: 1.75 per CU, or one per CU when the slice leaves room for only one
+      const double want = kslice_lds_bytes(max_m, kf, hl) > 80 * 1024 ? kNumCU : kNumCU * 1.75;
+      if (wgs < want) cost *= want / wgs;
       if (cost < best_cost) {
         best_cost = cost;
         plan->nt = nt;
