@@ -17,7 +17,8 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+HBM_PEAK_GBS = 8000.0               # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 
 
 def log(*a):
@@ -178,14 +179,26 @@ def main():
         }
     roofline_gemm = None
     if st.gemm_decode_launches > 0 and st.gemm_decode_ms > 0:
-        ach = st.gemm_decode_bytes / (st.gemm_decode_ms * 1e-3) / 1e9
+        # Weight bytes are read once per launch; every weight meets batch rows x activation planes
+        # (bf16 hi + remainder) in the matrix cores.  Which roof is nearer depends on the batch.
+        planes = 2 if cfg.dtype == "bf16" else 1
+        secs = st.gemm_decode_ms * 1e-3
+        gbs = st.gemm_decode_bytes / secs / 1e9
+        esz_w = 2 if cfg.dtype == "bf16" else 4
+        tflops = 2.0 * (st.gemm_decode_bytes / esz_w) * cfg.batch * planes / secs / 1e12
+        f_hbm, f_mfma = gbs / HBM_PEAK_GBS, tflops / MFMA_BF16_PEAK_TFLOPS
+        by_mfma = cfg.dtype == "bf16" and f_mfma > f_hbm
         roofline_gemm = {
             "kernel": "gemm_kslice_kernel (grouped projection GEMMs of the decode steps: QKV + MLP-up, O + MLP-down)",
-            "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+            "bound": "mfma" if by_mfma else "hbm",
+            "achieved": tflops if by_mfma else gbs, "peak": MFMA_BF16_PEAK_TFLOPS if by_mfma else HBM_PEAK_GBS,
+            "unit": "TFLOP/s" if by_mfma else "GB/s", "frac": f_mfma if by_mfma else f_hbm,
+            "frac_of_hbm_peak": f_hbm, "frac_of_mfma_peak": f_mfma if cfg.dtype == "bf16" else None,
             "launches": int(st.gemm_decode_launches),
             "avg_launch_us": st.gemm_decode_ms * 1e3 / st.gemm_decode_launches,
             "avg_bytes_per_launch": st.gemm_decode_bytes / st.gemm_decode_launches,
-            "note": "algorithmic bytes = weight bytes, each read once; by time this is the largest kernel of the step",
+            "note": "bytes = weight bytes, each read once; flops = 2 x weights x batch rows x activation planes "
+                    "(the multiplies the matrix cores execute); by time this is the largest kernel of the step",
         }
     # whole decode step against the HBM roofline: algorithmic bytes per step (weights + block KV)
     D, F, V, esz = cfg.d_model, cfg.d_ff, cfg.vocab, (2 if cfg.dtype == "bf16" else 4)
