@@ -502,6 +502,147 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
       }
 }
 
+// ---------------------------------------------------------------------------
+// The same kernel for workgroups that walk several K-slices (k_iters >= 2): the
+// loads of slice it + 1 (weight fragments and the thread's share of the activation
+// slice, all into registers) are issued right after slice it has been handed to
+// LDS, so they travel while slice it is multiplied.  hi + remainder planes only;
+// MC * KF <= 8 (registers: the whole next slice is held by the 256 threads).
+// ---------------------------------------------------------------------------
+template <int KF, int NT, int MC>
+__global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(GemmGroup g) {
+  constexpr int KS = 32 * KF, LDK = KS + 8, CPR = KS / 8, NCH = MC * KF;
+  extern __shared__ __attribute__((aligned(16))) uint16_t sA[];
+  const int bid = blockIdx.x;
+  GemmDesc d = g.p[0];
+  if (g.n > 1 && bid >= g.p[1].tile_begin) d = g.p[1];
+  const EpiArgs ea = epi_args(d);
+  const int t = bid - d.tile_begin;
+  const int split = t / d.tiles_n, tn = t - split * d.tiles_n;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n0 = tn * 64 * NT + wave * 16 * NT;
+  const int Mpad = (d.M + 15) & ~15;
+  const int k_iters = d.K / KS / d.splits;
+  const int kblocks = d.K >> 5, last_tile = ((d.N + 15) >> 4) - 1;
+  const uint16_t* A = reinterpret_cast<const uint16_t*>(d.A);
+  const uint16_t* Wf = reinterpret_cast<const uint16_t*>(d.W_frag);
+  const ptrdiff_t lo_delta = reinterpret_cast<const uint16_t*>(d.A_lo) - A;
+
+  f32x4_t acc[MC][NT][4];
+#pragma unroll
+  for (int mc = 0; mc < MC; ++mc)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) acc[mc][nt][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  // this thread's chunks of a slice: global offset (without the slice's k base) and LDS offset
+  const int total = Mpad * CPR;
+  int a_off[NCH], lds_off[NCH];
+#pragma unroll
+  for (int u = 0; u < NCH; ++u) {
+    const int c = min(u * 256 + tid, total - 1);          // clamped: duplicates carry the same bytes
+    const int row = c / CPR, kc = c - row * CPR;
+    a_off[u] = min(row, d.M - 1) * d.lda + kc * 8;
+    lds_off[u] = row * LDK + kc * 8;
+  }
+  const uint16_t* w_base[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt)
+    w_base[nt] = Wf + (size_t)min((n0 >> 4) + nt, last_tile) * kblocks * 512 + lane * 8;
+
+  u32x4_t wn[NT][KF], ah[NCH], al[NCH];
+  {
+    const int kbase = split * k_iters * KS;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int kf = 0; kf < KF; ++kf) wn[nt][kf] = *reinterpret_cast<const u32x4_t*>(w_base[nt] + (size_t)((kbase >> 5) + kf) * 512);
+#pragma unroll
+    for (int u = 0; u < NCH; ++u) {
+      ah[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kbase);
+      al[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kbase + lo_delta);
+    }
+  }
+  for (int it = 0; it < k_iters; ++it) {
+    bf16x8_t wf[NT][KF];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int kf = 0; kf < KF; ++kf) wf[nt][kf] = __builtin_bit_cast(bf16x8_t, wn[nt][kf]);
+#pragma unroll
+    for (int u = 0; u < NCH; ++u) {
+      *reinterpret_cast<u32x4_t*>(&sA[lds_off[u]]) = ah[u];
+      *reinterpret_cast<u32x4_t*>(&sA[Mpad * LDK + lds_off[u]]) = al[u];
+    }
+    __syncthreads();
+    if (it + 1 < k_iters) {                       // uniform: the next slice starts its trip now
+      const int kbase = (split * k_iters + it + 1) * KS;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int kf = 0; kf < KF; ++kf) wn[nt][kf] = *reinterpret_cast<const u32x4_t*>(w_base[nt] + (size_t)((kbase >> 5) + kf) * 512);
+#pragma unroll
+      for (int u = 0; u < NCH; ++u) {
+        ah[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kbase);
+        al[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kbase + lo_delta);
+      }
+    }
+#pragma unroll
+    for (int mc = 0; mc < MC; ++mc) {
+#pragma unroll
+      for (int kf = 0; kf < KF; ++kf) {
+        bf16x8_t af[4], afl[4];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const int row = min(mc * 64 + mt * 16 + (lane & 15), Mpad - 1);
+          const uint16_t* sp = &sA[row * LDK + (lane >> 4) * 8 + kf * 32];
+          af[mt] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(sp));
+          afl[mt] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(sp + Mpad * LDK));
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt)
+            acc[mc][nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[mt], wf[nt][kf], acc[mc][nt][mt], 0, 0, 0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt)
+            acc[mc][nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afl[mt], wf[nt][kf], acc[mc][nt][mt], 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  }
+  if (d.epi == EPI_PARTIAL) {
+    float* outp = reinterpret_cast<float*>(d.out) + (size_t)split * d.M * d.N;
+#pragma unroll
+    for (int mc = 0; mc < MC; ++mc)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const int col = n0 + nt * 16 + (lane & 15);
+          const int row0 = mc * 64 + mt * 16 + (lane >> 4) * 4;
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (row0 + r < d.M && col < d.N) outp[(size_t)(row0 + r) * d.N + col] = acc[mc][nt][mt][r];
+        }
+    return;
+  }
+#pragma unroll
+  for (int mc = 0; mc < MC; ++mc)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        const int col = n0 + nt * 16 + (lane & 15);
+        const int row0 = mc * 64 + mt * 16 + (lane >> 4) * 4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) epilogue_store<bf16_t>(ea, split, row0 + r, col, acc[mc][nt][mt][r]);
+      }
+}
+
 // W[N, K] -> fragment order, one thread per 16-byte chunk.
 __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ Wf, int N, int K, size_t n_chunks) {
   const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -588,12 +729,13 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
   plan->kind = KIND_KSLICE;
   plan->mc = (max_m + 63) / 64;
   if (plan->mc == 3) plan->mc = 4;
-  // Up to 128 rows the slice stays within 64 KB (two workgroups per CU overlap their phases); with
-  // more rows the multiply dominates and a longer slice (one workgroup per CU) pays.
+  // Up to 128 rows the slice stays within 64 KB (two workgroups per CU overlap their phases).
+  // With more rows the multiply dominates and one workgroup per CU walks many slices; it then
+  // overlaps load and multiply itself (pipelined kernel), which needs mc * kf <= 8.
   const size_t lds_cap = max_m <= 128 ? 64 * 1024 : 144 * 1024;
   int kf = 2;
   for (int c : {8, 6, 4, 2}) {
-    bool ok = kslice_lds_bytes(max_m, c, hl) <= lds_cap;
+    bool ok = kslice_lds_bytes(max_m, c, hl) <= lds_cap && (max_m <= 128 || !hl || plan->mc * c <= 8);
     for (int i = 0; i < n_probs && ok; ++i) ok = probs[i].K % (32 * c) == 0;
     if (ok) { kf = c; break; }
   }
@@ -623,8 +765,8 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
         cost += (double)tiles * p.M * p.K * (hl ? 4 : 2);                  // activation reads
         if (p.epi == EPI_PARTIAL) cost += (double)spl[i] * p.M * p.N * 8;  // partials out and back
       }
-      // workgroups wanted: 1.75 per CU, or one per CU when the slice leaves room for only one
-      const double want = kslice_lds_bytes(max_m, kf, hl) > 80 * 1024 ? kNumCU : kNumCU * 1.75;
+      // workgroups wanted: 1.75 per CU, or one per CU when LDS or registers leave room for only one
+      const double want = (kslice_lds_bytes(max_m, kf, hl) > 80 * 1024 || plan->mc >= 4) ? kNumCU : kNumCU * 1.75;
       if (wgs < want) cost *= want / wgs;
       if (cost < best_cost) {
         best_cost = cost;
@@ -660,6 +802,40 @@ static hipError_t launch_kslice(GemmGroup& g, size_t lds, hipStream_t s) {
   }
   kern<<<fill_tiles<1 << 30, 64 * NT>(g), 256, lds, s>>>(g);
   return hipSuccess;
+}
+
+template <int KF, int NT, int MC>
+static hipError_t launch_kslice_pipe(GemmGroup& g, size_t lds, hipStream_t s) {
+  static bool attr_set = false;
+  auto kern = gemm_kslice_pipe_kernel<KF, NT, MC>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  kern<<<fill_tiles<1 << 30, 64 * NT>(g), 256, lds, s>>>(g);
+  return hipSuccess;
+}
+
+// The pipelined variant exists for these (kf, nt, mc); returns false when there is none.
+static bool launch_kslice_pipe_any(GemmGroup& g, int kf, int nt, int mc, size_t lds, hipStream_t s, hipError_t* e) {
+  switch (kf * 100 + nt * 10 + mc) {
+    case 211: *e = launch_kslice_pipe<2, 1, 1>(g, lds, s); return true;
+    case 221: *e = launch_kslice_pipe<2, 2, 1>(g, lds, s); return true;
+    case 212: *e = launch_kslice_pipe<2, 1, 2>(g, lds, s); return true;
+    case 222: *e = launch_kslice_pipe<2, 2, 2>(g, lds, s); return true;
+    case 214: *e = launch_kslice_pipe<2, 1, 4>(g, lds, s); return true;
+    case 224: *e = launch_kslice_pipe<2, 2, 4>(g, lds, s); return true;
+    case 411: *e = launch_kslice_pipe<4, 1, 1>(g, lds, s); return true;
+    case 421: *e = launch_kslice_pipe<4, 2, 1>(g, lds, s); return true;
+    case 412: *e = launch_kslice_pipe<4, 1, 2>(g, lds, s); return true;
+    case 422: *e = launch_kslice_pipe<4, 2, 2>(g, lds, s); return true;
+    case 611: *e = launch_kslice_pipe<6, 1, 1>(g, lds, s); return true;
+    case 621: *e = launch_kslice_pipe<6, 2, 1>(g, lds, s); return true;
+    case 811: *e = launch_kslice_pipe<8, 1, 1>(g, lds, s); return true;
+    case 821: *e = launch_kslice_pipe<8, 2, 1>(g, lds, s); return true;
+    default: return false;
+  }
 }
 
 template <int KF, bool HL>
@@ -721,6 +897,12 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
       const size_t lds = kslice_lds_bytes(probs[0].M, plan.kf, hl);
       if (lds > 160 * 1024) return hipErrorInvalidValue;
       hipError_t e;
+      bool several_slices = false;
+      for (int i = 0; i < n_probs; ++i) several_slices |= probs[i].K / (32 * plan.kf * plan.splits[i]) >= 2;
+      if (hl && several_slices && launch_kslice_pipe_any(g, plan.kf, plan.nt, plan.mc, lds, s, &e)) {
+        if (e != hipSuccess) return e;
+        break;
+      }
       switch (plan.kf * 2 + (hl ? 1 : 0)) {
         case 4:  e = launch_kslice_kf<2, false>(g, plan.nt, plan.mc, lds, s); break;
         case 5:  e = launch_kslice_kf<2, true>(g, plan.nt, plan.mc, lds, s); break;
