@@ -820,20 +820,8 @@ static hipError_t launch_kslice_pipe(GemmGroup& g, size_t lds, hipStream_t s) {
 // The pipelined variant exists for these (kf, nt, mc); returns false when there is none.
 static bool launch_kslice_pipe_any(GemmGroup& g, int kf, int nt, int mc, size_t lds, hipStream_t s, hipError_t* e) {
   switch (kf * 100 + nt * 10 + mc) {
-    case 211: *e = launch_kslice_pipe<2, 1, 1>(g, lds, s); return true;
-    case 221: *e = launch_kslice_pipe<2, 2, 1>(g, lds, s); return true;
-    case 212: *e = launch_kslice_pipe<2, 1, 2>(g, lds, s); return true;
-    case 222: *e = launch_kslice_pipe<2, 2, 2>(g, lds, s); return true;
     case 214: *e = launch_kslice_pipe<2, 1, 4>(g, lds, s); return true;
     case 224: *e = launch_kslice_pipe<2, 2, 4>(g, lds, s); return true;
-    case 411: *e = launch_kslice_pipe<4, 1, 1>(g, lds, s); return true;
-    case 421: *e = launch_kslice_pipe<4, 2, 1>(g, lds, s); return true;
-    case 412: *e = launch_kslice_pipe<4, 1, 2>(g, lds, s); return true;
-    case 422: *e = launch_kslice_pipe<4, 2, 2>(g, lds, s); return true;
-    case 611: *e = launch_kslice_pipe<6, 1, 1>(g, lds, s); return true;
-    case 621: *e = launch_kslice_pipe<6, 2, 1>(g, lds, s); return true;
-    case 811: *e = launch_kslice_pipe<8, 1, 1>(g, lds, s); return true;
-    case 821: *e = launch_kslice_pipe<8, 2, 1>(g, lds, s); return true;
     default: return false;
   }
 }
@@ -899,7 +887,10 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
       hipError_t e;
       bool several_slices = false;
       for (int i = 0; i < n_probs; ++i) several_slices |= probs[i].K / (32 * plan.kf * plan.splits[i]) >= 2;
-      if (hl && several_slices && launch_kslice_pipe_any(g, plan.kf, plan.nt, plan.mc, lds, s, &e)) {
+      // With few rows several workgroups share a CU and overlap each other's phases better than one
+      // pipelined workgroup does (LM head at 64 rows: 24 us against 27 us), so the pipelined
+      // variant serves the shapes that leave room for one workgroup per CU only.
+      if (hl && several_slices && plan.mc >= 4 && launch_kslice_pipe_any(g, plan.kf, plan.nt, plan.mc, lds, s, &e)) {
         if (e != hipSuccess) return e;
         break;
       }

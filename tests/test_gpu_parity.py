@@ -98,6 +98,31 @@ def test_bf16_small(amd, lb, p, par):
     run_case(amd, cfg, 3 * lb + 2, batch=5)
 
 
+@pytest.mark.parametrize("act_split", [0, 1])
+def test_bf16_single_plane_activations(amd, act_split):
+    """act_split = 0 / 1: GEMM operands as one bf16 plane (everywhere / in prefill only).  Less
+    accurate than the default hi + remainder planes, still inside the bar at this size."""
+    cfg = tiny_cfg(dtype="bf16", block_len=4, prefix_len=1, d_model=256, n_heads=4, d_ff=512, vocab=300,
+                   prompt_len=24, n_block_layers=2, n_token_layers=2)
+    W = make_weights(cfg)
+    prompts = make_prompts(cfg, batch=5)
+    m = amd.Model(cfg, W, max_batch=5, max_blocks=12, act_split=act_split)
+    ids, lgs = gpu_generate(m, prompts, 10)
+    m.close()
+    rep = compare_with_oracle(cfg, W, prompts, ids, lgs, TOL_BF16)
+    print(act_split, rep)
+    assert_parity(rep)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_local_attention_with_many_keys(amd, dtype):
+    """Block length 16 with 2 prefix rows: up to 17 local keys, past what the register kernel of the
+    token decoder's attention holds, so the LDS kernel serves the later positions of a block."""
+    cfg = tiny_cfg(dtype=dtype, block_len=16, prefix_len=2, d_model=128, n_heads=2, d_ff=256, vocab=200,
+                   prompt_len=32, n_block_layers=1, n_token_layers=2)
+    run_case(amd, cfg, 35, batch=3)
+
+
 @pytest.mark.parametrize("d,h,f,b,p,lb", [(256, 4, 1024, 5, 1, 4), (768, 12, 3072, 70, 2, 4), (512, 4, 2048, 33, 1, 2),
                                            (1024, 8, 4096, 17, 1, 1)])
 def test_bf16_streaming_gemm_shapes(amd, d, h, f, b, p, lb):
