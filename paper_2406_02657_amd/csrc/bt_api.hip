@@ -23,7 +23,7 @@ constexpr int kSkinnyRows = 256;     // GEMMs with at most this many rows may sp
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct Layout {
-  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cur, state, frag, total;
+  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cand, cur, state, frag, total;
   size_t blk_layer_stride, loc_layer_stride;   // bytes between layers (K then V inside)
   size_t part_elems;                           // floats in each of part_o, part_d
   size_t qkv_elems, part_u_elems;              // floats in qkv (may hold split-K pieces) and part_u
@@ -95,6 +95,7 @@ void make_layout(const bt_config& c, Layout& L) {
   L.ctx = take(B * D * 4);
   L.hfin = take(B * D * 4);
   L.logits = take(B * (size_t)c.vocab * 4);
+  L.cand = take(B * (size_t)((c.vocab + 63) / 64) * sizeof(float2));   // per-tile argmax candidates of the LM head
   L.cur = take(B * c.block_len * 4);
   L.state = take(256);
   // bf16 mode: a second copy of every GEMM weight in MFMA fragment order, read by the decode GEMMs
@@ -567,8 +568,15 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
                 fin_lo ? m->ws + L.hfin + fin_lo * 2 : nullptr, 0, m->head_frag};
   GemmPlan pl{};
   BT_HIP(m, gemm_plan(c.dtype, &p, 1, &pl));
+  // Greedy argmax: where the head's kernel can, it leaves per-tile (max, column) candidates per row
+  // and a small kernel picks among them; otherwise one workgroup per row scans the logits.
+  const int cand_tiles = gemm_row_max_tiles(p, pl);
+  if (cand_tiles > 0) p.row_max = m->at<float2>(L.cand);
   BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));
-  BT_HIP(m, launch_argmax(m->at<float>(L.logits), B, c.vocab, ids_out, cur, c.block_len, r, s));
+  if (cand_tiles > 0)
+    BT_HIP(m, launch_argmax_candidates(m->at<float2>(L.cand), cand_tiles, B, ids_out, cur, c.block_len, r, s));
+  else
+    BT_HIP(m, launch_argmax(m->at<float>(L.logits), B, c.vocab, ids_out, cur, c.block_len, r, s));
   return BT_OK;
 }
 

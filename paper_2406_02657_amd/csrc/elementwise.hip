@@ -252,6 +252,37 @@ hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* nex
   return hipGetLastError();
 }
 
+// Greedy argmax from per-tile candidates: one wave per sequence scans cand[b * n_tiles + tile].
+__global__ __launch_bounds__(64) void argmax_candidates_kernel(const float2* __restrict__ cand, int n_tiles, int batch,
+                                                               int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
+                                                               int block_len, int r) {
+  const int b = blockIdx.x;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int t = threadIdx.x; t < n_tiles; t += 64) {
+    const float2 c = cand[(size_t)b * n_tiles + t];
+    argmax_take(c.x, __float_as_int(c.y), best, bi);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(best, o, kWave);
+    const int oi = __shfl_xor(bi, o, kWave);
+    argmax_take(ov, oi, best, bi);
+  }
+  if (threadIdx.x == 0) {
+    if (bi == 0x7fffffff) bi = 0;           // every logit was NaN or -inf
+    if (next_ids) next_ids[b] = bi;
+    cur[b * block_len + r] = bi;
+  }
+}
+
+hipError_t launch_argmax_candidates(const float2* cand, int n_tiles, int batch, int32_t* next_ids,
+                                    int32_t* cur, int block_len, int r, hipStream_t s) {
+  if (n_tiles < 1) return hipErrorInvalidValue;
+  argmax_candidates_kernel<<<batch, 64, 0, s>>>(cand, n_tiles, batch, next_ids, cur, block_len, r);
+  return hipGetLastError();
+}
+
 __global__ void scatter_ids_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ cur, int batch,
                                    int block_len, int r) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;

@@ -25,6 +25,7 @@ struct GemmDesc {
   const void* A_lo;      // bf16 remainder plane of A (null: none)
   size_t out_lo_off;     // EPI_GELU: != 0 writes the output as hi / remainder planes
   const void* W_frag;    // W in MFMA fragment order (K-slice kernel)
+  float2* row_max;       // per (column tile, row) candidates for argmax, or null
   int tiles_m, tiles_n, tile_begin;   // tiles of this problem occupy blocks [tile_begin, tile_begin + tiles_m*tiles_n*splits)
 };
 struct GemmGroup {
@@ -211,10 +212,10 @@ template <bool HL>
 __global__ __launch_bounds__(512) void gemm_bf16_big_kernel(GemmGroup g) {
   constexpr int BM = 256, BN = 256, BK = 64, LDS = BK + 8;
   constexpr int CH = BM * (BK / 8) / 512;       // 16-byte chunks per thread and operand plane (= 4)
-  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  uint16_t* sA = smem;
-  uint16_t* sB = smem + BM * LDS;
-  uint16_t* sAl = smem + (BM + BN) * LDS;       // only with HL
+  extern __shared__ __attribute__((aligned(16))) uint16_t sbig[];
+  uint16_t* sA = sbig;
+  uint16_t* sB = sbig + BM * LDS;
+  uint16_t* sAl = sbig + (BM + BN) * LDS;       // only with HL
 
   const int bid = blockIdx.x;
   GemmDesc d = g.p[0];
@@ -377,6 +378,18 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmGroup g) {
 // writes raw partial sums [split][M][N]; the consumer adds bias / activation.
 // With one split the usual epilogue (bias, GELU) is applied here.
 // ---------------------------------------------------------------------------
+// All-reduce over the 16 lanes of a DPP row by rotations (0x120 + n = rotate right by n inside
+// the row): after steps 8, 4, 2, 1 every lane holds the result.  Register to register; a shuffle
+// would go through the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ float row_max_step(float v) {
+  return fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false)));
+}
+template <int CTRL>
+__device__ __forceinline__ int row_min_step(int v) {
+  return min(v, __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false));
+}
+
 template <int KF, int NT, int MC, bool HL>
 __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
   constexpr int KS = 32 * KF, LDK = KS + 8, CPR = KS / 8, PL = HL ? 2 : 1;
@@ -386,7 +399,6 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
   // already there instead of being fetched from the argument block after the multiply.
   GemmDesc d = g.p[0];
   if (g.n > 1 && bid >= g.p[1].tile_begin) d = g.p[1];
-  const EpiArgs ea = epi_args(d);
   const int t = bid - d.tile_begin;
   const int split = t / d.tiles_n, tn = t - split * d.tiles_n;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -489,20 +501,82 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
         }
     return;
   }
+  // Candidates first: the barrier inside would otherwise wait for the logit stores to drain.
+  if (d.row_max) {
+    // Per row: best (value, column) of this workgroup's 64*NT columns, lowest column on ties.
+    // A lane holds rows 4 (lane >> 4) + r of each 16-row tile and one column per 16-column tile:
+    // first over its own columns, then over the 16 lanes that share the rows, then over the waves.
+    float bcol[NT];
 #pragma unroll
-  for (int mc = 0; mc < MC; ++mc)
+    for (int nt = 0; nt < NT; ++nt) {
+      const int col = n0 + nt * 16 + (lane & 15);
+      bcol[nt] = (d.bias && col < d.N) ? d.bias[col] : 0.f;
+    }
+    float* red_v = reinterpret_cast<float*>(sA);            // [4 waves][64 MC rows]; the slice is no longer needed
+    int* red_i = reinterpret_cast<int*>(sA) + 4 * 64 * MC;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+    for (int mc = 0; mc < MC; ++mc)
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
-        const int col = n0 + nt * 16 + (lane & 15);
-        const int row0 = mc * 64 + mt * 16 + (lane >> 4) * 4;
+      for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) epilogue_store<bf16_t>(ea, split, row0 + r, col, acc[mc][nt][mt][r]);
+        for (int r = 0; r < 4; ++r) {
+          // own columns first (ascending, so the lowest column wins ties), then the row's maximum
+          // over the 16 lanes, then the lowest column among the lanes that hold it
+          float bv = -INFINITY;
+          int bi = 0x7fffffff;
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            const int col = n0 + nt * 16 + (lane & 15);
+            const float v = acc[mc][nt][mt][r] + bcol[nt];
+            const bool take = (col < d.N) & (v > bv);
+            bv = take ? v : bv;
+            bi = take ? col : bi;
+          }
+          float mx = bv;
+          mx = row_max_step<0x128>(mx); mx = row_max_step<0x124>(mx); mx = row_max_step<0x122>(mx); mx = row_max_step<0x121>(mx);
+          bi = (bv == mx) ? bi : 0x7fffffff;
+          bi = row_min_step<0x128>(bi); bi = row_min_step<0x124>(bi); bi = row_min_step<0x122>(bi); bi = row_min_step<0x121>(bi);
+          bv = mx;
+          if ((lane & 15) == 0) {
+            const int row = mc * 64 + mt * 16 + (lane >> 4) * 4 + r;
+            red_v[wave * 64 * MC + row] = bv;
+            red_i[wave * 64 * MC + row] = bi;
+          }
+        }
+    __syncthreads();
+    for (int row = tid; row < d.M; row += 256) {
+      float bv = red_v[row];
+      int bi = red_i[row];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) {
+        const float ov = red_v[w * 64 * MC + row];
+        const int oi = red_i[w * 64 * MC + row];
+        const bool take = (ov > bv) | ((ov == bv) & (oi < bi));
+        bv = take ? ov : bv;
+        bi = take ? oi : bi;
       }
+      d.row_max[(size_t)row * d.tiles_n + tn] = make_float2(bv, __int_as_float(bi));
+    }
+  }
+  // EPI_F32 (the launcher admits nothing else here): out = acc + bias, float
+  {
+    float* outp = reinterpret_cast<float*>(d.out);
+#pragma unroll
+    for (int mc = 0; mc < MC; ++mc)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const int col = n0 + nt * 16 + (lane & 15);
+          const int row0 = mc * 64 + mt * 16 + (lane >> 4) * 4;
+          const float bcol = (d.bias && col < d.N) ? d.bias[col] : 0.f;
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (row0 + r < d.M && col < d.N) outp[(size_t)(row0 + r) * d.ldo + col] = acc[mc][nt][mt][r] + bcol;
+        }
+  }
 }
 
-// ---------------------------------------------------------------------------
 // The same kernel for workgroups that walk several K-slices (k_iters >= 2): the
 // loads of slice it + 1 (weight fragments and the thread's share of the activation
 // slice, all into registers) are issued right after slice it has been handed to
@@ -516,7 +590,6 @@ __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(GemmGroup g) {
   const int bid = blockIdx.x;
   GemmDesc d = g.p[0];
   if (g.n > 1 && bid >= g.p[1].tile_begin) d = g.p[1];
-  const EpiArgs ea = epi_args(d);
   const int t = bid - d.tile_begin;
   const int split = t / d.tiles_n, tn = t - split * d.tiles_n;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -630,17 +703,23 @@ __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(GemmGroup g) {
         }
     return;
   }
+  // EPI_F32 (the launcher admits nothing else here): out = acc + bias, float
+  {
+    float* outp = reinterpret_cast<float*>(d.out);
 #pragma unroll
-  for (int mc = 0; mc < MC; ++mc)
+    for (int mc = 0; mc < MC; ++mc)
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+      for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
-        const int col = n0 + nt * 16 + (lane & 15);
-        const int row0 = mc * 64 + mt * 16 + (lane >> 4) * 4;
+        for (int mt = 0; mt < 4; ++mt) {
+          const int col = n0 + nt * 16 + (lane & 15);
+          const int row0 = mc * 64 + mt * 16 + (lane >> 4) * 4;
+          const float bcol = (d.bias && col < d.N) ? d.bias[col] : 0.f;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) epilogue_store<bf16_t>(ea, split, row0 + r, col, acc[mc][nt][mt][r]);
-      }
+          for (int r = 0; r < 4; ++r)
+            if (row0 + r < d.M && col < d.N) outp[(size_t)(row0 + r) * d.ldo + col] = acc[mc][nt][mt][r] + bcol;
+        }
+  }
 }
 
 // W[N, K] -> fragment order, one thread per 16-byte chunk.
@@ -683,6 +762,13 @@ size_t kslice_lds_bytes(int M, int kf, bool hl) {
   return (size_t)Mpad * (32 * kf + 8) * 2 * (hl ? 2 : 1);
 }
 }  // namespace
+
+int gemm_row_max_tiles(const GemmProblem& p, const GemmPlan& plan) {
+  // candidates come from the plain K-slice kernel only: every row of a workgroup in one 64*MC chunk
+  // set, one K-split, final values in the epilogue
+  if (plan.kind != KIND_KSLICE || plan.splits[0] != 1 || p.epi != EPI_F32 || plan.mc >= 4) return 0;
+  return (p.N + 64 * plan.nt - 1) / (64 * plan.nt);
+}
 
 size_t gemm_packed_elems(int N, int K) { return (size_t)((N + 15) & ~15) * K; }
 
@@ -853,7 +939,7 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
     g.p[i].A = p.A; g.p[i].W = p.W; g.p[i].bias = p.bias; g.p[i].out = p.out;
     g.p[i].M = p.M; g.p[i].N = p.N; g.p[i].K = p.K; g.p[i].lda = p.lda; g.p[i].ldo = p.ldo;
     g.p[i].epi = p.epi; g.p[i].splits = sp;
-    g.p[i].A_lo = p.A_lo; g.p[i].out_lo_off = p.out_lo_off; g.p[i].W_frag = p.W_frag;
+    g.p[i].A_lo = p.A_lo; g.p[i].out_lo_off = p.out_lo_off; g.p[i].W_frag = p.W_frag; g.p[i].row_max = p.row_max;
     if ((p.A_lo != nullptr) != (probs[0].A_lo != nullptr)) return hipErrorInvalidValue;
   }
   const bool hl = probs[0].A_lo != nullptr;
@@ -881,7 +967,7 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
     }
     case KIND_KSLICE: {
       for (int i = 0; i < n_probs; ++i)
-        if (probs[i].K % (32 * plan.kf * plan.splits[i]) || !probs[i].W_frag) return hipErrorInvalidValue;
+        if (probs[i].K % (32 * plan.kf * plan.splits[i]) || !probs[i].W_frag || probs[i].epi == EPI_GELU) return hipErrorInvalidValue;
       const size_t lds = kslice_lds_bytes(probs[0].M, plan.kf, hl);
       if (lds > 160 * 1024) return hipErrorInvalidValue;
       hipError_t e;

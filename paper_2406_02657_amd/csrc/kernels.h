@@ -46,6 +46,9 @@ hipError_t launch_resid_ln(int dtype, const ResidLnArgs& a, hipStream_t s);
 // next_ids[b] (if non-null) and cur[b*L_B + r].
 hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next_ids,
                          int32_t* cur, int block_len, int r, hipStream_t s);
+// The same from per-tile candidates cand[b * n_tiles + tile] = (value, column as int bits).
+hipError_t launch_argmax_candidates(const float2* cand, int n_tiles, int batch, int32_t* next_ids,
+                                    int32_t* cur, int block_len, int r, hipStream_t s);
 
 hipError_t launch_scatter_ids(const int32_t* ids, int32_t* cur, int batch, int block_len, int r, hipStream_t s);
 // out[b] = cur[b*L_B + r]
@@ -75,6 +78,11 @@ struct GemmProblem {
   const void* A_lo;
   size_t out_lo_off;
   const void* W_frag;
+  // EPI_F32 on the decode kernel (M <= 192, one K-split): when non-null, every workgroup also
+  // writes, per row, the largest value of its columns and that column (lowest on ties) to
+  // row_max[row * tiles + tile]; gemm_row_max_tiles() gives the tile count.  Greedy argmax then reads
+  // these candidates instead of the whole logits row.
+  float2* row_max;
 };
 // bf16 weights W[N, K] (K % 32 == 0) re-ordered for the decode GEMM: tiles of 16 rows x 32 k,
 // tile (i, j) at element offset (i * K/32 + j) * 512; inside a tile lane l (0..63) owns the 8
@@ -90,6 +98,8 @@ struct GemmPlan {
   int splits[2];
 };
 hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan* plan);
+// Number of candidate tiles the launch writes per row (0: this plan does not produce them).
+int gemm_row_max_tiles(const GemmProblem& p, const GemmPlan& plan);
 // Up to two independent problems in one launch.
 hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const GemmPlan& plan, hipStream_t s);
 
