@@ -65,6 +65,7 @@ def main():
     ap.add_argument("--workload", default="cfg1", help="cfg1 (decode-heavy, the headline), cfg2, cfg3, cfg4, cfg4v, cfg0")
     ap.add_argument("--gen-len", type=int, default=0, help="override the number of generated tokens (0 = the workload's)")
     ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--prompt-len", type=int, default=0, help="override the prompt length (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attn-events", action="store_true", help="skip the profiled pass that brackets the "
                     "block-attention launches with HIP events (no roofline object)")
@@ -101,6 +102,8 @@ def main():
         cfg = cfg.with_(gen_len=args.gen_len)
     if args.batch:
         cfg = cfg.with_(batch=args.batch)
+    if args.prompt_len:
+        cfg = cfg.with_(prompt_len=args.prompt_len)
     log(f"workload {cfg.name}: B={cfg.batch} prompt={cfg.prompt_len} gen={cfg.gen_len} L_B={cfg.block_len} "
         f"D={cfg.d_model} layers={cfg.n_block_layers}+{cfg.n_token_layers} P={cfg.prefix_len} dtype={cfg.dtype}")
     t0 = time.perf_counter()
@@ -156,15 +159,18 @@ def main():
     decode_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
     value = cfg.batch * cfg.gen_len / (ms_per_step / 1e3)
 
-    # HBM traffic of that kernel relative to its algorithmic bytes, from the committed rocprofv3
-    # --pmc summary (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size)
-    traffic_ratio = None
+    # HBM traffic of that kernel per launch, from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    # WRITE_SIZE, each scaled by a plain copy of known size): K/V bytes are fetched `kv` times, and
+    # the launch reads / writes a constant amount besides (q, k, v and MLP pieces in; GELU, output out)
+    pmc = {}
     try:
         for line in open(os.path.join(ROOT, "profiles", "cfg1_hbm_traffic_pmc.txt")):
-            if line.startswith("traffic_over_algorithmic="):
-                traffic_ratio = float(line.split("=")[1])
+            for key in ("kv_read_over_algorithmic", "other_read_bytes", "write_bytes"):
+                if line.startswith(key + "="):
+                    pmc[key] = float(line.split("=")[1])
     except OSError:
         pass
+    pmc_ok = len(pmc) == 3 and cfg.name == "cfg1" and not args.batch
     roofline = None
     if st.attn_block_launches > 0 and st.attn_block_ms > 0:
         ach = st.attn_block_bytes / (st.attn_block_ms * 1e-3) / 1e9
@@ -173,9 +179,11 @@ def main():
                       "also finishes q/k/v of the new block, appends them, and carries the MLP GELU as extra workgroups)",
             "events": "inside the timed steps" if in_region else "one extra job of the same workload after the timed steps",
             "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-            "traffic": (traffic_ratio * st.attn_block_bytes / st.attn_block_launches) if traffic_ratio else None,
-            "traffic_note": "HBM bytes per launch = measured traffic/algorithmic ratio of profiles/cfg1_hbm_traffic_pmc.txt "
-                            "(rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE) x this run's algorithmic bytes per launch",
+            "traffic": (pmc["kv_read_over_algorithmic"] * st.attn_block_bytes / st.attn_block_launches
+                        + pmc["other_read_bytes"] + pmc["write_bytes"]) if pmc_ok else None,
+            "traffic_note": "HBM bytes per launch from profiles/cfg1_hbm_traffic_pmc.txt (rocprofv3 --pmc FETCH_SIZE, "
+                            "WRITE_SIZE at two cache lengths): 1.015 x this run's K/V bytes per launch + 5.44 MB of other "
+                            "inputs (split-K pieces of q, k, v and of the MLP up-projection) + 1.18 MB written",
             "launches": int(st.attn_block_launches),
             "avg_launch_us": st.attn_block_ms * 1e3 / st.attn_block_launches,
             "avg_bytes_per_launch": st.attn_block_bytes / st.attn_block_launches,
