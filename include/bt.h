@@ -128,14 +128,19 @@ typedef struct {
 typedef struct bt_model bt_model;
 
 /* Bytes of device workspace bt_create needs for this config (block KV cache,
- * local KV cache, activations, split-K partials, logits).  host out pointer. */
+ * local KV cache, activations, split-K partials, logits, argmax candidates and,
+ * in bf16 mode, a second copy of every GEMM weight matrix in the order the
+ * decode GEMMs fetch it: about the size of the model again).  host out pointer. */
 int bt_workspace_bytes(const bt_config *cfg, size_t *bytes);
 
 /* Build a model.  cfg, w: host structs (copied).  workspace_dev: device memory
  * of at least bt_workspace_bytes, 256-byte aligned, owned by the caller.
  * hip_stream: a hipStream_t (NULL = the default stream).  *out receives the
- * handle.  Errors: BT_ERR_ARG (bad config / null), BT_ERR_CAPACITY (workspace
- * too small), BT_ERR_HIP. */
+ * handle.  In bf16 mode the call reads every GEMM weight matrix once (a small
+ * kernel writes the re-ordered copy into the workspace) and synchronises the
+ * stream; weights changed afterwards are not seen by the decode steps.
+ * Errors: BT_ERR_ARG (bad config / null), BT_ERR_CAPACITY (workspace too
+ * small), BT_ERR_HIP. */
 int bt_create(const bt_config *cfg, const bt_weights *w, void *workspace_dev,
               size_t workspace_bytes, void *hip_stream, bt_model **out);
 

@@ -1,7 +1,9 @@
 // GEMMs of the projections (QKV, O, MLP up/down, prefix, LM head):
 //   out[M, N] = A[M, K] * W[N, K]^T  (+ bias, GELU, or split-K partial sums)
-// bf16 mode: MFMA (v_mfma_f32_16x16x32_bf16) with LDS-staged tiles, fp32
-// accumulation.  fp32 mode: an LDS-tiled VALU kernel (small models only).
+// bf16 mode: MFMA (v_mfma_f32_16x16x32_bf16), fp32 accumulation.  Prefill (many
+// rows): 256 x 256 or 128 x 128 tiles staged through LDS.  Decode (<= 256 rows):
+// K-slice kernels that stream the weights once, from a copy in fragment order.
+// fp32 mode: an LDS-tiled VALU kernel (small models only).
 // Both operands are K-contiguous, so a lane's MFMA fragment (8 consecutive k of
 // one row) is one 16-byte load.  Up to two independent problems share a launch.
 #include "common.h"

@@ -72,3 +72,13 @@ def test_create_rejects_null_and_small_workspace(B):
     assert B.lib.bt_decode_step(None, 1, None) == B.BT_ERR_ARG
     assert B.lib.bt_last_error(None) == b"null model"
     B.lib.bt_destroy(None)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N > 1 exits with a message before touching any GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
