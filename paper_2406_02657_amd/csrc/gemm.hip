@@ -853,9 +853,15 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
         cost += (double)tiles * p.M * p.K * (hl ? 4 : 2);                  // activation reads
         if (p.epi == EPI_PARTIAL) cost += (double)spl[i] * p.M * p.N * 8;  // partials out and back
       }
-      // workgroups wanted: 1.75 per CU, or one per CU when LDS or registers leave room for only one
-      const double want = (kslice_lds_bytes(max_m, kf, hl) > 80 * 1024 || plan->mc >= 4) ? kNumCU : kNumCU * 1.75;
-      if (wgs < want) cost *= want / wgs;
+      // workgroups wanted: 1.75 per CU, so that they overlap each other's phases.  Where LDS or
+      // registers leave room for one workgroup per CU, the launch runs in rounds of one per CU and
+      // what counts is how full the last round is.
+      if (kslice_lds_bytes(max_m, kf, hl) > 80 * 1024 || plan->mc >= 4) {
+        const int rounds = (wgs + kNumCU - 1) / kNumCU;
+        cost *= (double)rounds * kNumCU / wgs;
+      } else if (wgs < kNumCU * 1.75) {
+        cost *= kNumCU * 1.75 / wgs;
+      }
       if (cost < best_cost) {
         best_cost = cost;
         plan->nt = nt;
