@@ -812,6 +812,13 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
     return hipSuccess;
   }
 
+  // A wide problem that finishes its own epilogue (the LM head) at more than 192 rows: the K-slice
+  // kernel would pull the whole activation matrix through L2 once per 128 columns (4 x the weight
+  // bytes at 256 rows); 256 x 256 tiles halve that (137 us against 204 us at 256 x 50304 x 2048).
+  if (n_probs == 1 && probs[0].epi != EPI_PARTIAL && max_m > 192 && probs[0].N >= 4096) {
+    plan->kind = KIND_TILE256;
+    return hipSuccess;
+  }
   // K-slice kernel.  Slice length: the longest of 256/192/128/64 that divides every K and keeps
   // the staged activation slice within the LDS budget below.
   plan->kind = KIND_KSLICE;
