@@ -189,6 +189,13 @@ struct StackArgs {
   int b0;          // first sequence (cache offset)
   int rows;        // rows per sequence (prefill: N_p; decode: 1; token: P or 1)
   int pos0;        // first position of the new rows
+  // Optional: the first LayerNorm launch of the stack reads its rows from an embedding table
+  // (row i = table[ids[i * stride + off]]) and writes them into the residual stream.
+  const void* emb_table = nullptr;
+  const int32_t* emb_ids = nullptr;
+  int emb_stride = 0, emb_off = 0;
+  // Optional: the stack's final LayerNorm launch bumps this device counter by one.
+  int* counter_inc = nullptr;
 };
 
 // Final LayerNorm of a stack on row (i*in_mul + in_off) of x, for i < n.
@@ -205,6 +212,7 @@ int final_ln(bt_model* m, const StackArgs& a, const float* pendO, const float* b
   r.g2 = nullptr; r.b2 = nullptr; r.u2 = nullptr;
   r.n_rows = n; r.D = m->cfg.d_model; r.in_mul = in_mul; r.in_off = in_off; r.write_x = 0;
   r.eps = m->cfg.ln_eps;
+  r.counter_inc = a.counter_inc;
   BT_HIP(m, launch_resid_ln(m->cfg.dtype, r, m->stream));
   return BT_OK;
 }
@@ -275,6 +283,10 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     r.n_rows = M; r.D = D; r.in_mul = 1; r.in_off = 0; r.write_x = (pO || pD) ? 1 : 0;
     r.eps = c.ln_eps;
     r.lo_off = loD;
+    if (!pO && !pD && a.emb_table) {        // first launch of the stack: rows come from the table
+      r.emb_table = a.emb_table; r.emb_ids = a.emb_ids; r.emb_stride = a.emb_stride; r.emb_off = a.emb_off;
+      r.write_x = 1;
+    }
     BT_HIP(m, launch_resid_ln(dt, r, s));
     return BT_OK;
   };
@@ -539,10 +551,10 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
     if (with_block) {
       BT_HIP(m, launch_embed_concat(c.dtype, m->w.E_emb, cur, x, B, c.block_len, D / c.block_len, s));
       StackArgs a{MODE_BLOCK_DECODE, B, B, 0, 1, m->n_blocks};
+      a.counter_inc = m->at<int>(L.state);     // the final LayerNorm launch counts the new block in
       int rc = run_stack(m, m->blk.data(), c.n_block_layers, a, m->w.blk_lnf_g, m->w.blk_lnf_b,
                          m->ws + L.ctx, ctx_f32, B, 1, 0);
       if (rc) return rc;
-      BT_HIP(m, launch_state_add(m->at<int>(L.state), 1, s));
     }
     if (c.prefix_len > 0) {
       GemmProblem p{m->ws + L.ctx, m->w.W_prefix, (const float*)m->w.b_prefix, x, B, c.prefix_len * D, D, D,
@@ -556,11 +568,14 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
     rows = L.n_pref;
     pos0 = 0;
   } else {
-    BT_HIP(m, launch_token_embed(c.dtype, m->w.E_tok, cur, x, B, c.block_len, r - 1, D, s));
+    // the token's embedding row is read by the first LayerNorm launch of the stack; without
+    // layers there is no such launch
+    if (c.n_token_layers == 0) BT_HIP(m, launch_token_embed(c.dtype, m->w.E_tok, cur, x, B, c.block_len, r - 1, D, s));
     rows = 1;
     pos0 = L.n_pref + r - 1;
   }
   StackArgs a{MODE_TOKEN, B * rows, B, 0, rows, pos0};
+  if (r != 0 && c.n_token_layers > 0) { a.emb_table = m->w.E_tok; a.emb_ids = cur; a.emb_stride = c.block_len; a.emb_off = r - 1; }
   int rc = run_stack(m, m->tok.data(), c.n_token_layers, a, m->w.tok_lnf_g, m->w.tok_lnf_b,
                      m->ws + L.hfin, 0, B, rows, rows - 1);
   if (rc) return rc;

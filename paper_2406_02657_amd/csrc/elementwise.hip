@@ -132,12 +132,19 @@ __global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2
       g2e = a.g2 ? *reinterpret_cast<const float4*>(a.g2 + 4 * g) : zero;
       b2e = a.g2 ? *reinterpret_cast<const float4*>(a.b2 + 4 * g) : zero;
     }
-    float4 acc = *reinterpret_cast<const float4*>(xr + 4 * g);
+    float4 acc;
+    if (a.emb_table) {
+      const T* er = reinterpret_cast<const T*>(a.emb_table) + (size_t)a.emb_ids[(size_t)i * a.emb_stride + a.emb_off] * D + 4 * g;
+      acc = make_float4(to_float<T>(er[0]), to_float<T>(er[1]), to_float<T>(er[2]), to_float<T>(er[3]));
+    } else {
+      acc = *reinterpret_cast<const float4*>(xr + 4 * g);
+    }
     if (nA && a.biasA) add4(acc, *reinterpret_cast<const float4*>(a.biasA + 4 * g));
     if (nB && a.biasB) add4(acc, *reinterpret_cast<const float4*>(a.biasB + 4 * g));
     if (nA + nB) add_partials(acc, a.partA, nA, a.partB, nB, a.part_stride, row * D + 4 * g);
     v[c] = acc;
   }
+  if (a.counter_inc && blockIdx.x == 0 && threadIdx.x == 0) *a.counter_inc += 1;
   float sum = 0.f;
 #pragma unroll
   for (int c = 0; c < VPT; ++c) {

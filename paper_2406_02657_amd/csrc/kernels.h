@@ -39,6 +39,13 @@ struct ResidLnArgs {
   int n_rows, D, in_mul, in_off, write_x;
   float eps;
   size_t lo_off;         // != 0: u1 / u2 also get the bf16 remainder plane at +lo_off elements
+  // Optional: the rows do not come from x but from an embedding table (storage dtype, [*, D]):
+  // row i = emb_table[emb_ids[i * emb_stride + emb_off]]; with write_x the residual stream gets them.
+  const void* emb_table;
+  const int32_t* emb_ids;
+  int emb_stride, emb_off;
+  // Optional: one thread adds 1 to *counter_inc (the device-side count of cached blocks).
+  int* counter_inc;
 };
 hipError_t launch_resid_ln(int dtype, const ResidLnArgs& a, hipStream_t s);
 
