@@ -77,8 +77,8 @@ def main():
                          "WRITE_SIZE this gives the factor between the counters and real HBM bytes")
     args = ap.parse_args()
     if args.gpus != 1:
-        log("bench.py: this build runs on ONE GPU only (the path shards by batch with no exchange; "
-            "see DESIGN.md); --gpus must be 1")
+        log("bench.py: this build runs on ONE GPU only (the path would shard by batch, with no exchange "
+            "between GPUs during generation); --gpus must be 1")
         sys.exit(2)
 
     import numpy as np
