@@ -98,6 +98,25 @@ def test_bf16_small(amd, lb, p, par):
     run_case(amd, cfg, 3 * lb + 2, batch=5)
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4, 5, 6, 7])
+def test_bf16_seeded_random_shapes(amd, seed):
+    """Seeded draws of width, heads, block length, prefix length, batch (up to 250 rows: every
+    row-chunk count of the decode GEMM), vocabulary (ragged column tiles) and residual wiring."""
+    rng = np.random.default_rng(9000 + seed)
+    dh = int(rng.choice([32, 64, 128]))
+    heads = int(rng.choice([1, 2, 4] if dh < 128 else [1, 2]))
+    d = dh * heads
+    lb = int(rng.choice([x for x in (1, 2, 4, 8) if d % x == 0 and (d // x) % 8 == 0]))
+    p = int(rng.integers(1, 4)) if lb > 1 else int(rng.integers(0, 2))
+    batch = int(rng.choice([1, 3, 17, 64, 65, 130, 200, 250]))
+    cfg = tiny_cfg(dtype="bf16", block_len=lb, prefix_len=p, d_model=d, n_heads=heads, d_ff=int(rng.choice([2, 4])) * d,
+                   vocab=int(rng.integers(20, 700)), prompt_len=lb * int(rng.integers(1, 6)),
+                   n_block_layers=int(rng.integers(1, 3)), n_token_layers=int(rng.integers(1, 3)),
+                   parallel_residual=int(rng.integers(0, 2)), weights_seed=100 + seed, prompt_seed=200 + seed)
+    print(seed, cfg, "batch", batch)
+    run_case(amd, cfg, 2 * lb + 1, batch=batch, seqs=[0, batch - 1] if batch > 8 else None)
+
+
 @pytest.mark.parametrize("act_split", [0, 1])
 def test_bf16_single_plane_activations(amd, act_split):
     """act_split = 0 / 1: GEMM operands as one bf16 plane (everywhere / in prefill only).  Less
