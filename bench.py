@@ -218,7 +218,7 @@ def main():
     w_blk = cfg.n_block_layers * p_layer * esz
     w_head = V * D * esz
     n_block_steps = -(-cfg.gen_len // cfg.block_len) - 1
-    n_p = cfg.prompt_len // cfg.block_len
+    n_p = cfg.n_prompt_blocks
     kv_total = sum((n_p + k + 1) for k in range(n_block_steps)) * cfg.batch * cfg.n_block_layers * 2 * D * esz
     alg_bytes_decode = cfg.gen_len * (w_tok + w_head) + n_block_steps * w_blk + kv_total
     step_roof = {

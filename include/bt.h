@@ -77,6 +77,9 @@ typedef struct {
                                (about 16 mantissa bits): 0 never, 1 in decode steps, 2 also in prefill */
   int32_t use_graphs;       /* 1: decode steps are captured into HIP graphs (one per position in the
                                block) and replayed; 0: every launch is issued eagerly */
+  int32_t pad_id;           /* token id that fills, from the left, the first block of a prompt whose
+                               length is not a multiple of L_B (App. "Random length padding"; the
+                               paper does not name the id); 0 <= pad_id < vocab */
   float   ln_eps;
 } bt_config;
 
@@ -145,13 +148,18 @@ int bt_create(const bt_config *cfg, const bt_weights *w, void *workspace_dev,
               size_t workspace_bytes, void *hip_stream, bt_model **out);
 
 /* Prefill (Fig. 1; Sec. 2.4; App. C): run the embedder and the block decoder
- * over all prompt blocks, fill the block KV cache with prompt_len/L_B entries
- * per sequence and keep the context embedding for the first generated block.
- * The token decoder is not run.  Resets all sequence state (re-entrant).
+ * over all prompt blocks, fill the block KV cache with ceil(prompt_len/L_B)
+ * entries per sequence and keep the context embedding for the first generated
+ * block.  The token decoder is not run.  Resets all sequence state
+ * (re-entrant).  A prompt_len that is not a multiple of L_B (App. "Random
+ * length padding"; footnote of the zero-shot table, Sec. 3) counts as the
+ * prompt preceded by (-prompt_len mod L_B) copies of cfg.pad_id: the pads are
+ * embedded into the first block like any other token; the caller's buffer
+ * holds the unpadded ids only.  prompt_len == 1 is the paper's setting
+ * without an input sequence (L_B - 1 pads and one token).
  * tokens_dev: int32 [batch, prompt_len] row-major, device; ids are not
- * range-checked.  Errors: BT_ERR_ARG if batch < 1, batch > max_batch,
- * prompt_len < L_B or prompt_len % L_B != 0; BT_ERR_CAPACITY if
- * prompt_len/L_B > max_blocks. */
+ * range-checked.  Errors: BT_ERR_ARG if batch < 1, batch > max_batch or
+ * prompt_len < 1; BT_ERR_CAPACITY if ceil(prompt_len/L_B) > max_blocks. */
 int bt_prefill(bt_model *m, const int32_t *tokens_dev, int32_t batch, int32_t prompt_len);
 
 /* One decode step (Sec. 2.1): emits exactly one token per sequence.  At the

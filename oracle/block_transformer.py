@@ -27,7 +27,11 @@ Readings taken where the paper is silent (each also listed in the design notes):
     LayerNorm; exact (erf) GELU; biased variance, eps inside the square root;
     LM head has no bias; greedy argmax, lowest index on ties;
   * prefix_len == 0 (only with block_len == 1): the context embedding itself is
-    the token decoder's single input row.
+    the token decoder's single input row;
+  * a prompt whose length is not a multiple of L_B gets the fewest pad tokens
+    (0 .. L_B-1 of cfg.pad_id) in FRONT of its first block; the pads are
+    embedded like any token (App. "Random length padding", footnote of the
+    zero-shot table in Sec. 3).
 All arithmetic is float64 on the stored weight values (bf16 bit patterns are
 widened exactly); nothing else is rounded.
 
@@ -232,6 +236,21 @@ def greedy(logits):
     return np.argmax(logits, axis=-1).astype(np.int32)
 
 
+def left_pad(cfg, prompts):
+    """Fill the first block of prompts [B, T], T >= 1, from the left (App. "Random length padding").
+
+    Returns [B, ceil(T/L_B)*L_B]: (-T mod L_B) copies of cfg.pad_id, then the prompt.  The
+    pads are ordinary tokens from here on: the embedder looks them up and concatenates them
+    into the first block's embedding.  A prompt of one token is the paper's setting without
+    an input sequence (App. on batch sizes and context lengths): L_B - 1 pads and that token.
+    """
+    prompts = np.asarray(prompts, dtype=np.int64)
+    B, T = prompts.shape
+    assert T >= 1
+    k = (-T) % cfg.block_len
+    return np.concatenate([np.full((B, k), cfg.pad_id, dtype=np.int64), prompts], axis=1)
+
+
 # ----------------------------------------------------------------------------
 # mode "full": the plain definition, no caches
 # ----------------------------------------------------------------------------
@@ -286,7 +305,7 @@ def teacher_forced_logits(P, cfg, tokens, blocks):
 
 def generate_full(P, cfg, prompts, n_new):
     """Greedy generation by full recomputation.  Returns (ids [B, n_new], logits [B, n_new, V])."""
-    hist = np.array(prompts, dtype=np.int64)
+    hist = left_pad(cfg, prompts)
     ids, lgs = [], []
     for _ in range(n_new):
         lg = next_token_logits_full(P, cfg, hist)
@@ -329,7 +348,7 @@ class CachedGenerator:
 
     def prefill(self, prompts):
         cfg = self.cfg
-        prompts = np.asarray(prompts, dtype=np.int64)
+        prompts = left_pad(cfg, prompts)
         B, T = prompts.shape
         assert B == self.B and T >= cfg.block_len and T % cfg.block_len == 0
         for c in self.blk + self.loc:
@@ -381,7 +400,7 @@ def generate_cached(P, cfg, prompts, n_new, forced=None):
     """Greedy (or teacher-forced on `forced` [B, n_new]) generation in cached mode."""
     prompts = np.asarray(prompts)
     B, T = prompts.shape
-    gen = CachedGenerator(P, cfg, B, (T + n_new) // cfg.block_len + 1)
+    gen = CachedGenerator(P, cfg, B, (T + n_new) // cfg.block_len + 2)
     gen.prefill(prompts)
     ids, lgs = [], []
     for t in range(n_new):

@@ -27,7 +27,7 @@ class bt_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "vocab", "block_len", "d_model", "n_heads", "d_ff", "n_block_layers", "n_token_layers",
         "prefix_len", "dtype", "max_batch", "max_blocks", "rotary_dims", "parallel_residual",
-        "prefill_rows", "act_split", "use_graphs")] + [("ln_eps", C.c_float)]
+        "prefill_rows", "act_split", "use_graphs", "pad_id")] + [("ln_eps", C.c_float)]
 
 
 _LAYER_FIELDS = ("ln1_g", "ln1_b", "W_qkv", "b_qkv", "W_o", "b_o", "ln2_g", "ln2_b", "W_up", "b_up", "W_down", "b_down")
@@ -95,7 +95,7 @@ def make_config(cfg, max_batch=None, max_blocks=None, prefill_rows=0, act_split=
         rotary_dims=cfg.rot, parallel_residual=cfg.parallel_residual, prefill_rows=prefill_rows,
         act_split=DEFAULT_ACT_SPLIT if act_split is None else act_split,
         use_graphs=int(use_graphs) if "BT_USE_GRAPHS" not in os.environ else int(os.environ["BT_USE_GRAPHS"]),
-        ln_eps=cfg.ln_eps)
+        pad_id=getattr(cfg, "pad_id", 0), ln_eps=cfg.ln_eps)
 
 
 class Model:

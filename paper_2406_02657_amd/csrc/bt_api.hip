@@ -49,6 +49,7 @@ int check_config(const bt_config& c, std::string* why) {
   if (c.prefill_rows < 0) return bad("prefill_rows < 0");
   if (c.act_split < 0 || c.act_split > 2) return bad("act_split must be 0, 1 or 2");
   if (c.use_graphs < 0 || c.use_graphs > 1) return bad("use_graphs must be 0 or 1");
+  if (c.pad_id < 0 || c.pad_id >= c.vocab) return bad("pad_id outside the vocabulary");
   if (!(c.ln_eps >= 0.f)) return bad("ln_eps < 0");
   const int l_cap = (c.prefix_len > 0 ? c.prefix_len : 1) + c.block_len;
   if ((size_t)(2 * l_cap + 2) * dh * sizeof(float) > 60 * 1024) return bad("prefix_len + block_len too large for the local-attention kernel");
@@ -502,8 +503,9 @@ int bt_prefill(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t pr
   const bt_config& c = m->cfg;
   if (!tokens_dev) return fail(m, BT_ERR_ARG, "tokens_dev is null");
   if (batch < 1 || batch > c.max_batch) return fail(m, BT_ERR_ARG, "batch out of range");
-  if (prompt_len < c.block_len || prompt_len % c.block_len) return fail(m, BT_ERR_ARG, "prompt_len must be a positive multiple of block_len");
-  const int n_p = prompt_len / c.block_len;
+  if (prompt_len < 1) return fail(m, BT_ERR_ARG, "prompt_len < 1");
+  // a first block that the prompt does not fill is completed from the left with pad_id
+  const int n_p = (prompt_len + c.block_len - 1) / c.block_len;
   if (n_p > c.max_blocks) return fail(m, BT_ERR_CAPACITY, "prompt needs more block slots than max_blocks");
   const Layout& L = m->L;
   int per = L.m_rows / n_p;
@@ -513,7 +515,7 @@ int bt_prefill(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t pr
   for (int b0 = 0; b0 < batch; b0 += per) {
     const int bc = batch - b0 < per ? batch - b0 : per;
     BT_HIP(m, launch_embed_concat(c.dtype, m->w.E_emb, tokens_dev + (size_t)b0 * prompt_len, m->at<float>(L.x),
-                                  bc * n_p, c.block_len, c.d_model / c.block_len, m->stream));
+                                  bc, n_p, c.block_len, c.d_model / c.block_len, prompt_len, c.pad_id, m->stream));
     StackArgs a{MODE_BLOCK_PREFILL, bc * n_p, bc, b0, n_p, 0};
     int rc = run_stack(m, m->blk.data(), c.n_block_layers, a, m->w.blk_lnf_g, m->w.blk_lnf_b,
                        m->ws + L.ctx + (size_t)b0 * c.d_model * ctx_esz, ctx_f32, bc, n_p, n_p - 1);
@@ -549,7 +551,7 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
   int rows, pos0;
   if (r == 0) {
     if (with_block) {
-      BT_HIP(m, launch_embed_concat(c.dtype, m->w.E_emb, cur, x, B, c.block_len, D / c.block_len, s));
+      BT_HIP(m, launch_embed_concat(c.dtype, m->w.E_emb, cur, x, B, 1, c.block_len, D / c.block_len, c.block_len, 0, s));
       StackArgs a{MODE_BLOCK_DECODE, B, B, 0, 1, m->n_blocks};
       a.counter_inc = m->at<int>(L.state);     // the final LayerNorm launch counts the new block in
       int rc = run_stack(m, m->blk.data(), c.n_block_layers, a, m->w.blk_lnf_g, m->w.blk_lnf_b,
@@ -665,8 +667,8 @@ int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
 int bt_embed(bt_model* m, const int32_t* tokens_dev, int32_t n_rows, float* out_dev) {
   if (!m) return BT_ERR_ARG;
   if (!tokens_dev || !out_dev || n_rows < 0) return fail(m, BT_ERR_ARG, "bt_embed: null pointer or negative n_rows");
-  BT_HIP(m, launch_embed_concat(m->cfg.dtype, m->w.E_emb, tokens_dev, out_dev, n_rows, m->cfg.block_len,
-                                m->cfg.d_model / m->cfg.block_len, m->stream));
+  BT_HIP(m, launch_embed_concat(m->cfg.dtype, m->w.E_emb, tokens_dev, out_dev, n_rows, 1, m->cfg.block_len,
+                                m->cfg.d_model / m->cfg.block_len, m->cfg.block_len, 0, m->stream));
   return BT_OK;
 }
 

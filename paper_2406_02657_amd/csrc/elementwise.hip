@@ -12,15 +12,18 @@ namespace bt {
 // ---------------------------------------------------------------------------
 template <class T>
 __global__ __launch_bounds__(256) void embed_concat_kernel(const T* __restrict__ E, const int32_t* __restrict__ tokens,
-                                                           float* __restrict__ x, int block_len, int d_emb) {
+                                                           float* __restrict__ x, int block_len, int d_emb,
+                                                           int blocks_per_seq, int seq_len, int pad, int pad_id) {
   constexpr int EPC = Chunk<T>::EPC;
   const int m = blockIdx.x;
+  const int b = m / blocks_per_seq, blk = m - b * blocks_per_seq;
   const int chunks_per_tok = d_emb / EPC;
   const int n_chunks = block_len * chunks_per_tok;
   float* xr = x + (size_t)m * block_len * d_emb;
   for (int c = threadIdx.x; c < n_chunks; c += blockDim.x) {
     const int j = c / chunks_per_tok, cc = c - j * chunks_per_tok;
-    const int tok = tokens[(size_t)m * block_len + j];
+    const int t = blk * block_len + j - pad;           // index into the unpadded sequence
+    const int tok = t < 0 ? pad_id : tokens[(size_t)b * seq_len + t];
     const uint4 raw = *reinterpret_cast<const uint4*>(E + (size_t)tok * d_emb + cc * EPC);
     float f[EPC];
     Chunk<T>::unpack(raw, f);
@@ -32,12 +35,18 @@ __global__ __launch_bounds__(256) void embed_concat_kernel(const T* __restrict__
 }
 
 hipError_t launch_embed_concat(int dtype, const void* E_emb, const int32_t* tokens, float* x,
-                               int n_rows, int block_len, int d_emb, hipStream_t s) {
+                               int n_seqs, int blocks_per_seq, int block_len, int d_emb,
+                               int seq_len, int pad_id, hipStream_t s) {
+  const int n_rows = n_seqs * blocks_per_seq;
   if (n_rows <= 0) return hipSuccess;
+  const int pad = blocks_per_seq * block_len - seq_len;
+  if (pad < 0 || pad >= block_len) return hipErrorInvalidValue;
   if (dtype == BT_F32)
-    embed_concat_kernel<float><<<n_rows, 256, 0, s>>>((const float*)E_emb, tokens, x, block_len, d_emb);
+    embed_concat_kernel<float><<<n_rows, 256, 0, s>>>((const float*)E_emb, tokens, x, block_len, d_emb,
+                                                      blocks_per_seq, seq_len, pad, pad_id);
   else
-    embed_concat_kernel<bf16_t><<<n_rows, 256, 0, s>>>((const bf16_t*)E_emb, tokens, x, block_len, d_emb);
+    embed_concat_kernel<bf16_t><<<n_rows, 256, 0, s>>>((const bf16_t*)E_emb, tokens, x, block_len, d_emb,
+                                                       blocks_per_seq, seq_len, pad, pad_id);
   return hipGetLastError();
 }
 

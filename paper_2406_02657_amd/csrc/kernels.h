@@ -9,9 +9,13 @@
 namespace bt {
 
 // ---------------------------------------------------------------- elementwise
-// Embedder (Sec. 2.2): x[m, j*d_emb + e] = E_emb[tokens[m*L_B + j], e], float out.
+// Embedder (Sec. 2.2): row m = b * blocks_per_seq + i of x is the concatenation of the table rows
+// of block i of sequence b, float out.  tokens [n_seqs, seq_len]; when seq_len is not a multiple
+// of L_B the sequence counts as left-padded with pad_id up to blocks_per_seq * L_B tokens
+// (App. "Random length padding"); blocks_per_seq * L_B - seq_len must lie in [0, L_B).
 hipError_t launch_embed_concat(int dtype, const void* E_emb, const int32_t* tokens, float* x,
-                               int n_rows, int block_len, int d_emb, hipStream_t s);
+                               int n_seqs, int blocks_per_seq, int block_len, int d_emb,
+                               int seq_len, int pad_id, hipStream_t s);
 
 // Token-decoder input row: x[b, :] = E_tok[cur[b*L_B + r_prev], :], float out.
 hipError_t launch_token_embed(int dtype, const void* E_tok, const int32_t* cur, float* x,

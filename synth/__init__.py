@@ -54,6 +54,7 @@ class BTConfig:
     rotary_dims: int = -1   # per head; -1 -> d_head // 4
     parallel_residual: int = 1
     ln_eps: float = 1e-5
+    pad_id: int = 0         # fills the first block of a prompt whose length is not a multiple of L_B
 
     @property
     def d_emb(self) -> int:
@@ -68,8 +69,12 @@ class BTConfig:
         return self.d_head // 4 if self.rotary_dims < 0 else self.rotary_dims
 
     @property
+    def n_prompt_blocks(self) -> int:
+        return -(-self.prompt_len // self.block_len)
+
+    @property
     def max_blocks(self) -> int:
-        return (self.prompt_len + self.gen_len) // self.block_len
+        return self.n_prompt_blocks + self.gen_len // self.block_len
 
     @property
     def n_prefix_rows(self) -> int:

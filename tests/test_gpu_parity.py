@@ -42,7 +42,7 @@ def run_case(amd, cfg, n_new, batch=None, prompt_len=None, tol=None, seqs=None):
 def test_cfg0_every_sequence_every_step(amd):
     cfg = CONFIGS["cfg0"]
     rep, st, ids, _ = run_case(amd, cfg, cfg.gen_len)
-    n_p = cfg.prompt_len // cfg.block_len
+    n_p = cfg.n_prompt_blocks
     assert st.block_passes == n_p + -(-cfg.gen_len // cfg.block_len) - 1
     assert st.token_passes == cfg.gen_len
     assert st.local_kv_high_water == cfg.prefix_len + cfg.block_len - 1
@@ -287,9 +287,9 @@ def test_errors_on_device(amd):
     assert lib.bt_decode_step(h, 2, ids.data_ptr()) == -2                      # decode before prefill
     toks = torch.zeros(2, 8, dtype=torch.int32, device="cuda")
     assert lib.bt_prefill(h, toks.data_ptr(), 3, 8) == -1                      # batch > max_batch
-    assert lib.bt_prefill(h, toks.data_ptr(), 2, 6) == -1                      # not a multiple of L_B
-    assert lib.bt_prefill(h, toks.data_ptr(), 2, 2) == -1                      # shorter than a block
+    assert lib.bt_prefill(h, toks.data_ptr(), 2, 0) == -1                      # empty prompt
     assert lib.bt_prefill(h, toks.data_ptr(), 2, 16) == -3                     # more blocks than capacity
+    assert lib.bt_prefill(h, toks.data_ptr(), 2, 13) == -3                     # padded to 4 blocks: also too many
     assert lib.bt_prefill(h, toks.data_ptr(), 2, 8) == 0
     assert lib.bt_decode_step(h, 1, ids.data_ptr()) == -2                      # batch mismatch
     for _ in range(8):                                                          # 2 blocks fit (slots 2 of 3 used + 1)
@@ -298,3 +298,26 @@ def test_errors_on_device(amd):
     assert b"full" in lib.bt_last_error(h)
     torch.cuda.synchronize()
     m.close()
+
+
+@pytest.mark.parametrize("dtype,lb,p,T", [("fp32", 4, 1, 1), ("fp32", 4, 2, 6), ("fp32", 8, 1, 19), ("fp32", 2, 1, 5),
+                                          ("bf16", 4, 1, 1), ("bf16", 4, 1, 127), ("bf16", 8, 2, 45), ("bf16", 4, 2, 270)])
+def test_prompt_length_not_a_multiple_of_block_length(amd, dtype, lb, p, T):
+    """The first block is completed from the left with pad_id, pads embedded like tokens
+    (App. "Random length padding"); T == 1 is the setting without an input sequence."""
+    cfg = tiny_cfg(dtype=dtype, block_len=lb, prefix_len=p, d_model=128, n_heads=4, d_ff=256, vocab=211,
+                   prompt_len=T, n_block_layers=2, n_token_layers=2).with_(pad_id=3)
+    n_new = 2 * lb + 3
+    rep, st, _, _ = run_case(amd, cfg, n_new, batch=5)
+    assert st.block_passes == -(-T // lb) + -(-n_new // lb) - 1
+    assert st.n_blocks == st.block_passes
+
+
+def test_pad_id_reaches_the_embedder(amd):
+    """Same ragged prompt, two pad ids: the GPU logits differ, and each matches its own oracle run."""
+    base = tiny_cfg(d_model=64, n_heads=2, d_ff=128, vocab=64, block_len=4, prefix_len=1, prompt_len=6)
+    first = []
+    for pad in (0, 17):
+        rep, _, _, lgs = run_case(amd, base.with_(pad_id=pad), 2)
+        first.append(lgs[:, 0])
+    assert np.abs(first[0] - first[1]).max() > 1e-4

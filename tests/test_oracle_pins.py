@@ -490,3 +490,53 @@ def test_layernorm_gelu_values():
     assert abs(O.gelu(np.array([0.0]))[0]) == 0.0
     assert abs(O.gelu(np.array([1.0]))[0] - 0.8413447460685429) < 1e-15   # Phi(1)
     assert abs(O.gelu(np.array([-2.0]))[0] + 2 * 0.022750131948179195) < 1e-15
+
+
+# --------------------------------------------------------------------------
+# prompts whose length is not a multiple of L_B (App. "Random length padding";
+# footnote of the zero-shot table, Sec. 3)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("lb", [1, 2, 4, 8])
+def test_left_pad_count_and_place(lb):
+    cfg = tiny_cfg(block_len=lb, prefix_len=1, d_model=32, n_heads=2).with_(pad_id=7)
+    for T in range(1, 2 * lb + 2):
+        toks = 100 + np.arange(2 * T).reshape(2, T)
+        out = O.left_pad(cfg, toks)
+        assert out.shape[1] % lb == 0 and 0 <= out.shape[1] - T < lb      # fewest pads that fill the block
+        assert np.array_equal(out[:, out.shape[1] - T:], toks)            # prompt keeps its order, at the end
+        assert np.all(out[:, :out.shape[1] - T] == 7)                     # pads in front
+    assert O.left_pad(cfg, np.array([[3]])).shape[1] == lb                # one token: L_B - 1 pads (footnote)
+
+
+@pytest.mark.parametrize("lb,T", [(4, 1), (4, 6), (4, 7), (2, 5), (8, 3)])
+def test_ragged_prompt_equals_hand_padded_prompt(lb, T):
+    """Full and cached generation from T tokens == generation from the block-aligned prompt
+    written out by hand, and differs from padding on the right."""
+    cfg = tiny_cfg(block_len=lb, prefix_len=1, d_model=32, n_heads=2, prompt_len=T).with_(pad_id=5)
+    P = build(cfg)
+    toks = make_prompts(cfg, batch=2)
+    k = -(-T // lb) * lb - T
+    by_hand = np.array([[5] * k + [int(t) for t in row] for row in toks])
+    ids_a, lg_a = O.generate_full(P, cfg, toks, lb + 2)
+    ids_b, lg_b = O.generate_full(P, cfg, by_hand, lb + 2)
+    assert np.array_equal(lg_a, lg_b) and np.array_equal(ids_a, ids_b)
+    ids_c, lg_c, gen = O.generate_cached(P, cfg, toks, lb + 2)
+    assert np.array_equal(ids_c, ids_a) and np.abs(lg_c - lg_a).max() < 1e-11
+    assert gen.blk[0].n == (T + k) // lb + 1
+    right = np.array([[int(t) for t in row] + [5] * k for row in toks])
+    assert np.abs(O.generate_full(P, cfg, right, 1)[1] - lg_a[:, :1]).max() > 1e-6
+
+
+def test_pad_tokens_enter_the_first_block_embedding():
+    """Unlike masked pads of a vanilla transformer, the pad id's embedding is part of the first
+    block's input: the row is the concatenation of table rows, pads included."""
+    cfg = tiny_cfg(block_len=4, prefix_len=1, d_model=32, n_heads=2, prompt_len=6).with_(pad_id=9)
+    W = make_weights(cfg)
+    P = O.Params(W)
+    toks = make_prompts(cfg, batch=1)
+    e = O.embedder(P, cfg, O.left_pad(cfg, toks))
+    E = W["E_emb"].astype(np.float64)
+    want = np.concatenate([E[9], E[9], E[int(toks[0, 0])], E[int(toks[0, 1])]])
+    assert np.array_equal(e[0, 0], want)
+    other = O.generate_full(P, cfg.with_(pad_id=10), toks, 1)[1]
+    assert np.abs(other - O.generate_full(P, cfg, toks, 1)[1]).max() > 1e-6
