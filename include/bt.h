@@ -80,6 +80,10 @@ typedef struct {
   int32_t pad_id;           /* token id that fills, from the left, the first block of a prompt whose
                                length is not a multiple of L_B (App. "Random length padding"; the
                                paper does not name the id); 0 <= pad_id < vocab */
+  int32_t eos_id;           /* -1: none.  Otherwise a sequence that has emitted this id emits it at
+                               every later step as well (the paper generates a fixed number of
+                               tokens and states no stopping rule; the batch is static, so a finished
+                               sequence still occupies its rows) */
   float   ln_eps;
 } bt_config;
 
@@ -162,6 +166,22 @@ int bt_create(const bt_config *cfg, const bt_weights *w, void *workspace_dev,
  * prompt_len < 1; BT_ERR_CAPACITY if ceil(prompt_len/L_B) > max_blocks. */
 int bt_prefill(bt_model *m, const int32_t *tokens_dev, int32_t batch, int32_t prompt_len);
 
+/* Prefill of prompts of different lengths in one batch (same passages as
+ * bt_prefill).  tokens_dev: int32 [batch, max_len] row-major, device; sequence
+ * b holds its lens_host[b] ids at the start of row b, the rest of the row is
+ * not read.  lens_host: host array [batch], 1 <= lens_host[b] <= max_len, read
+ * before the call returns (the call synchronises the stream once to upload
+ * it).  Every sequence is left-padded with cfg.pad_id to whole blocks on its
+ * own, exactly as bt_prefill would pad it alone, so all sequences end on a
+ * block boundary and the decode steps run in lockstep; sequence b starts with
+ * ceil(lens_host[b]/L_B) cached blocks.  Results per sequence equal those of a
+ * batch of that sequence alone.  The per-sequence counters of bt_stats
+ * (n_blocks, block_passes, block_kv_rows_read) then describe the longest
+ * sequence; the byte counters sum over the batch.
+ * Errors: as bt_prefill; BT_ERR_ARG if a length lies outside [1, max_len]. */
+int bt_prefill_ragged(bt_model *m, const int32_t *tokens_dev, const int32_t *lens_host,
+                      int32_t batch, int32_t max_len);
+
 /* One decode step (Sec. 2.1): emits exactly one token per sequence.  At the
  * first step of a block the finished block is embedded and pushed through the
  * block decoder (attention over the whole block KV cache), its context
@@ -173,6 +193,14 @@ int bt_prefill(bt_model *m, const int32_t *tokens_dev, int32_t batch, int32_t pr
  * Errors: BT_ERR_STATE before prefill or if batch differs from the prefill's;
  * BT_ERR_CAPACITY if the step needs a block slot >= max_blocks. */
 int bt_decode_step(bt_model *m, int32_t batch, int32_t *next_ids_dev);
+
+/* End-of-sequence flags (for callers that stop early; no passage of the paper:
+ * it times a fixed number of generated tokens).  flags_dev: int32 [batch],
+ * device; flags_dev[b] = 1 once sequence b has emitted cfg.eos_id at some
+ * step since the last prefill, else 0 (always 0 when eos_id == -1).  Enqueued
+ * on the model's stream like every other call.  Errors: BT_ERR_ARG (null),
+ * BT_ERR_STATE (no prefill yet). */
+int bt_get_finished(bt_model *m, int32_t *flags_dev);
 
 /* Embedder alone (Sec. 2.2; App. D.1 "Lookup"): out_dev[m, j*d_emb + e] =
  * E_emb[tokens_dev[m*L_B + j], e] widened to float.  tokens_dev: int32

@@ -31,7 +31,11 @@ Readings taken where the paper is silent (each also listed in the design notes):
   * a prompt whose length is not a multiple of L_B gets the fewest pad tokens
     (0 .. L_B-1 of cfg.pad_id) in FRONT of its first block; the pads are
     embedded like any token (App. "Random length padding", footnote of the
-    zero-shot table in Sec. 3).
+    zero-shot table in Sec. 3);
+  * stopping is not part of the paper (it generates a fixed number of tokens):
+    with cfg.eos_id >= 0 a sequence that has emitted eos_id emits eos_id at
+    every later step; the batch stays static and the other sequences are
+    unaffected.
 All arithmetic is float64 on the stored weight values (bf16 bit patterns are
 widened exactly); nothing else is rounded.
 
@@ -345,6 +349,7 @@ class CachedGenerator:
         self.token_rows = 0             # rows pushed through the token decoder
         self.block_kv_rows_read = 0     # cached block entries attended, summed over decode steps
         self.local_kv_high_water = 0
+        self.finished = np.zeros(batch, dtype=bool)   # has emitted cfg.eos_id (only when eos_id >= 0)
 
     def prefill(self, prompts):
         cfg = self.cfg
@@ -360,6 +365,7 @@ class CachedGenerator:
         self.r = 0
         self.token_passes = self.token_rows = self.block_kv_rows_read = 0
         self.local_kv_high_water = 0
+        self.finished[:] = False
 
     def step(self, forced_ids=None):
         """One decode step.  Returns (logits [B, V], ids [B]).
@@ -390,6 +396,10 @@ class CachedGenerator:
             self.local_kv_high_water = max(self.local_kv_high_water, self.loc[0].n)
         logits = lm_head(P, g[:, -1])
         ids = greedy(logits)
+        eos = getattr(cfg, "eos_id", -1)
+        if eos >= 0:
+            ids = np.where(self.finished, eos, ids).astype(np.int32)
+            self.finished |= ids == eos
         fed = ids if forced_ids is None else np.asarray(forced_ids)
         self.cur[:, self.r] = fed
         self.r = (self.r + 1) % cfg.block_len
@@ -408,3 +418,20 @@ def generate_cached(P, cfg, prompts, n_new, forced=None):
         ids.append(nxt)
         lgs.append(lg)
     return np.stack(ids, axis=1), np.stack(lgs, axis=1), gen
+
+
+def generate_ragged(P, cfg, prompts, n_new, forced=None):
+    """Prompts of different lengths in one batch: a list of 1-D id arrays, each of length >= 1.
+
+    Sequences never interact (every attention and every table lookup is per sequence), so the
+    batch is defined as each sequence generated alone, left-padded on its own (left_pad).
+    forced: optional [B, n_new] ids fed back in place of the greedy choice.
+    Returns (ids [B, n_new], logits [B, n_new, V]).
+    """
+    ids, lgs = [], []
+    for b, p in enumerate(prompts):
+        i, l, _ = generate_cached(P, cfg, np.asarray(p)[None, :], n_new,
+                                  None if forced is None else np.asarray(forced)[b:b + 1])
+        ids.append(i[0])
+        lgs.append(l[0])
+    return np.stack(ids), np.stack(lgs)

@@ -27,7 +27,7 @@ class bt_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "vocab", "block_len", "d_model", "n_heads", "d_ff", "n_block_layers", "n_token_layers",
         "prefix_len", "dtype", "max_batch", "max_blocks", "rotary_dims", "parallel_residual",
-        "prefill_rows", "act_split", "use_graphs", "pad_id")] + [("ln_eps", C.c_float)]
+        "prefill_rows", "act_split", "use_graphs", "pad_id", "eos_id")] + [("ln_eps", C.c_float)]
 
 
 _LAYER_FIELDS = ("ln1_g", "ln1_b", "W_qkv", "b_qkv", "W_o", "b_o", "ln2_g", "ln2_b", "W_up", "b_up", "W_down", "b_down")
@@ -57,8 +57,10 @@ _P = C.c_void_p
 lib.bt_workspace_bytes.argtypes = [C.POINTER(bt_config), C.POINTER(C.c_size_t)]
 lib.bt_create.argtypes = [C.POINTER(bt_config), C.POINTER(bt_weights), _P, C.c_size_t, _P, C.POINTER(_P)]
 lib.bt_prefill.argtypes = [_P, _P, C.c_int32, C.c_int32]
+lib.bt_prefill_ragged.argtypes = [_P, _P, C.POINTER(C.c_int32), C.c_int32, C.c_int32]
 lib.bt_decode_step.argtypes = [_P, C.c_int32, _P]
 lib.bt_get_logits.argtypes = [_P, _P]
+lib.bt_get_finished.argtypes = [_P, _P]
 lib.bt_force_last_ids.argtypes = [_P, _P]
 lib.bt_get_context.argtypes = [_P, _P]
 lib.bt_set_context.argtypes = [_P, _P]
@@ -70,7 +72,8 @@ lib.bt_last_error.restype = C.c_char_p
 lib.bt_destroy.argtypes = [_P]
 lib.bt_destroy.restype = None
 lib.bt_embed.argtypes = [_P, _P, C.c_int32, _P]
-for _f in ("bt_workspace_bytes", "bt_create", "bt_prefill", "bt_decode_step", "bt_get_logits", "bt_force_last_ids",
+for _f in ("bt_workspace_bytes", "bt_create", "bt_prefill", "bt_prefill_ragged", "bt_decode_step", "bt_get_logits",
+           "bt_get_finished", "bt_force_last_ids",
            "bt_get_context", "bt_set_context", "bt_set_profile", "bt_reset_profile", "bt_get_stats", "bt_embed"):
     getattr(lib, _f).restype = C.c_int
 
@@ -95,7 +98,7 @@ def make_config(cfg, max_batch=None, max_blocks=None, prefill_rows=0, act_split=
         rotary_dims=cfg.rot, parallel_residual=cfg.parallel_residual, prefill_rows=prefill_rows,
         act_split=DEFAULT_ACT_SPLIT if act_split is None else act_split,
         use_graphs=int(use_graphs) if "BT_USE_GRAPHS" not in os.environ else int(os.environ["BT_USE_GRAPHS"]),
-        pad_id=getattr(cfg, "pad_id", 0), ln_eps=cfg.ln_eps)
+        pad_id=getattr(cfg, "pad_id", 0), eos_id=getattr(cfg, "eos_id", -1), ln_eps=cfg.ln_eps)
 
 
 class Model:
@@ -150,7 +153,18 @@ class Model:
         """tokens: int32 cuda tensor [batch, prompt_len]."""
         assert tokens.dtype == self.torch.int32 and tokens.is_cuda and tokens.is_contiguous()
         self._chk(lib.bt_prefill(self.h, tokens.data_ptr(), tokens.shape[0], tokens.shape[1]))
-        self.batch = tokens.shape[0]
+        self._after_prefill(tokens.shape[0])
+
+    def bt_prefill_ragged(self, tokens, lens):
+        """tokens: int32 cuda tensor [batch, max_len]; lens: host sequence of batch prompt lengths."""
+        assert tokens.dtype == self.torch.int32 and tokens.is_cuda and tokens.is_contiguous()
+        assert len(lens) == tokens.shape[0]
+        arr = (C.c_int32 * len(lens))(*[int(v) for v in lens])
+        self._chk(lib.bt_prefill_ragged(self.h, tokens.data_ptr(), arr, tokens.shape[0], tokens.shape[1]))
+        self._after_prefill(tokens.shape[0])
+
+    def _after_prefill(self, batch):
+        self.batch = batch
         self._ids = self.torch.empty(self.batch, dtype=self.torch.int32, device=self.device)
 
     def bt_decode_step(self, out=None):
@@ -162,6 +176,11 @@ class Model:
         lg = self.torch.empty(self.batch, self.cfg.vocab, dtype=self.torch.float32, device=self.device)
         self._chk(lib.bt_get_logits(self.h, lg.data_ptr()))
         return lg
+
+    def bt_get_finished(self):
+        fl = self.torch.empty(self.batch, dtype=self.torch.int32, device=self.device)
+        self._chk(lib.bt_get_finished(self.h, fl.data_ptr()))
+        return fl
 
     def bt_force_last_ids(self, ids):
         assert ids.dtype == self.torch.int32 and ids.is_cuda

@@ -182,9 +182,9 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(PartialSrc q
   }
   // the number of cached blocks may live in device memory, so that a captured graph of the
   // step stays valid while the cache grows
-  const int n_old = n_dev ? min(*n_dev, n_cap - 1) : n_old_arg;
   const int bh = blockIdx.x;
   const int b = bh / n_heads, h = bh - b * n_heads;
+  const int n_old = n_dev ? min(n_dev[b], n_cap - 1) : n_old_arg;
   const int D = n_heads * DH, half = rot / 2;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR;
@@ -470,14 +470,13 @@ __global__ __launch_bounds__(256) void attn_block_prefill_mfma_kernel(const floa
 // ---------------------------------------------------------------------------
 template <class T>
 __global__ __launch_bounds__(256) void rope_append_kernel(PartialSrc src, T* __restrict__ Kc, T* __restrict__ Vc,
-                                                          const float2* __restrict__ rope, int n_new, int pos0_arg,
-                                                          const int* __restrict__ n_dev, int n_heads, int DH, int rot,
+                                                          const float2* __restrict__ rope, int n_new, int pos0,
+                                                          int n_heads, int DH, int rot,
                                                           int n_cap, int n_rows, GeluJob gelu) {
   if ((int)blockIdx.x >= n_rows) {
     gelu_reduce_block<T>(gelu, blockIdx.x - n_rows, gridDim.x - n_rows);
     return;
   }
-  const int pos0 = n_dev ? min(*n_dev, n_cap - 1) : pos0_arg;
   const int m = blockIdx.x;
   const int b = m / n_new, pos = pos0 + (m - b * n_new);
   const int D = n_heads * DH, half = rot / 2;
@@ -755,16 +754,15 @@ __global__ __launch_bounds__(256) void attn_local_reg_kernel(PartialSrc qkv, T* 
   }
 
 hipError_t launch_rope_append(int dtype, const PartialSrc& src, void* Kc, void* Vc, const float2* rope,
-                              int n_rows, int n_new, int pos0, const int* n_dev, int n_heads, int d_head, int rot,
+                              int n_rows, int n_new, int pos0, int n_heads, int d_head, int rot,
                               int n_cap, const GeluJob& gelu, hipStream_t s) {
   if (n_rows <= 0) return hipSuccess;
-  if (n_dev && n_new != 1) return hipErrorInvalidValue;
   if (gelu.rows > 0 && gelu.cols % 4) return hipErrorInvalidValue;
   const int grid = n_rows + gelu_blocks(gelu);
   if (dtype == BT_F32)
-    rope_append_kernel<float><<<grid, 256, 0, s>>>(src, (float*)Kc, (float*)Vc, rope, n_new, pos0, n_dev, n_heads, d_head, rot, n_cap, n_rows, gelu);
+    rope_append_kernel<float><<<grid, 256, 0, s>>>(src, (float*)Kc, (float*)Vc, rope, n_new, pos0, n_heads, d_head, rot, n_cap, n_rows, gelu);
   else
-    rope_append_kernel<bf16_t><<<grid, 256, 0, s>>>(src, (bf16_t*)Kc, (bf16_t*)Vc, rope, n_new, pos0, n_dev, n_heads, d_head, rot, n_cap, n_rows, gelu);
+    rope_append_kernel<bf16_t><<<grid, 256, 0, s>>>(src, (bf16_t*)Kc, (bf16_t*)Vc, rope, n_new, pos0, n_heads, d_head, rot, n_cap, n_rows, gelu);
   return hipGetLastError();
 }
 

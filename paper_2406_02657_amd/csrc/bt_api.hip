@@ -23,7 +23,7 @@ constexpr int kSkinnyRows = 256;     // GEMMs with at most this many rows may sp
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct Layout {
-  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cand, cur, state, frag, total;
+  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cand, cur, state, lens, fin, frag, total;
   size_t blk_layer_stride, loc_layer_stride;   // bytes between layers (K then V inside)
   size_t part_elems;                           // floats in each of part_o, part_d
   size_t qkv_elems, part_u_elems;              // floats in qkv (may hold split-K pieces) and part_u
@@ -50,6 +50,7 @@ int check_config(const bt_config& c, std::string* why) {
   if (c.act_split < 0 || c.act_split > 2) return bad("act_split must be 0, 1 or 2");
   if (c.use_graphs < 0 || c.use_graphs > 1) return bad("use_graphs must be 0 or 1");
   if (c.pad_id < 0 || c.pad_id >= c.vocab) return bad("pad_id outside the vocabulary");
+  if (c.eos_id < -1 || c.eos_id >= c.vocab) return bad("eos_id must be -1 (none) or a vocabulary id");
   if (!(c.ln_eps >= 0.f)) return bad("ln_eps < 0");
   const int l_cap = (c.prefix_len > 0 ? c.prefix_len : 1) + c.block_len;
   if ((size_t)(2 * l_cap + 2) * dh * sizeof(float) > 60 * 1024) return bad("prefix_len + block_len too large for the local-attention kernel");
@@ -98,7 +99,9 @@ void make_layout(const bt_config& c, Layout& L) {
   L.logits = take(B * (size_t)c.vocab * 4);
   L.cand = take(B * (size_t)((c.vocab + 63) / 64) * sizeof(float2));   // per-tile argmax candidates of the LM head
   L.cur = take(B * c.block_len * 4);
-  L.state = take(256);
+  L.state = take(B * 4);       // cached blocks per sequence (device-side counters)
+  L.lens = take(B * 4);        // prompt lengths of the last prefill
+  L.fin = take(B * 4);         // per sequence: has emitted eos_id
   // bf16 mode: a second copy of every GEMM weight in MFMA fragment order, read by the decode GEMMs
   L.frag = off;
   if (c.dtype == BT_BF16) {
@@ -124,7 +127,8 @@ struct bt_model {
   Layout L;
   char* ws;
   hipStream_t stream;
-  int batch, n_blocks, r;
+  int batch, n_blocks, r;          // n_blocks: cached blocks of the longest sequence
+  int64_t blocks_sum;              // cached blocks summed over the batch
   bool have_context, stepped;
   bt_stats st;
   bool profile;
@@ -195,8 +199,10 @@ struct StackArgs {
   const void* emb_table = nullptr;
   const int32_t* emb_ids = nullptr;
   int emb_stride = 0, emb_off = 0;
-  // Optional: the stack's final LayerNorm launch bumps this device counter by one.
+  // Optional: the stack's final LayerNorm launch adds one to counter_inc[i] for its row i.
   int* counter_inc = nullptr;
+  // Optional: the final LayerNorm's row i is i * in_mul + fin_off_dev[i] - 1 (device memory).
+  const int* fin_off_dev = nullptr;
 };
 
 // Final LayerNorm of a stack on row (i*in_mul + in_off) of x, for i < n.
@@ -214,6 +220,7 @@ int final_ln(bt_model* m, const StackArgs& a, const float* pendO, const float* b
   r.n_rows = n; r.D = m->cfg.d_model; r.in_mul = in_mul; r.in_off = in_off; r.write_x = 0;
   r.eps = m->cfg.ln_eps;
   r.counter_inc = a.counter_inc;
+  r.in_off_dev = a.fin_off_dev;
   BT_HIP(m, launch_resid_ln(m->cfg.dtype, r, m->stream));
   return BT_OK;
 }
@@ -308,7 +315,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     char* Kc = base + seq;
     char* Vc = base + half + seq;
     if (a.mode == MODE_BLOCK_PREFILL) {
-      BT_HIP(m, launch_rope_append(dt, qsrc, Kc, Vc, rope, M, a.rows, a.pos0, nullptr, H, dh, c.rotary_dims,
+      BT_HIP(m, launch_rope_append(dt, qsrc, Kc, Vc, rope, M, a.rows, a.pos0, H, dh, c.rotary_dims,
                                    c.max_blocks, gelu, s));
       BT_HIP(m, launch_attn_block_prefill(dt, qkv, Kc, Vc, ao, loD, a.batch, H, dh, a.rows, c.max_blocks, s));
     } else {
@@ -320,7 +327,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
       if (m->profile) {
         if ((prc = prof_end(m))) return prc;
         m->st.attn_block_launches += 1;
-        m->st.attn_block_bytes += (int64_t)2 * (n_old + 1) * D * L.esz * a.batch;
+        m->st.attn_block_bytes += (int64_t)2 * (m->blocks_sum + a.batch) * D * L.esz;
       }
     }
     return BT_OK;
@@ -444,7 +451,7 @@ int bt_create(const bt_config* cfg, const bt_weights* w, void* workspace_dev, si
   m->L = L;
   m->ws = reinterpret_cast<char*>(workspace_dev);
   m->stream = reinterpret_cast<hipStream_t>(hip_stream);
-  m->batch = 0; m->n_blocks = 0; m->r = 0;
+  m->batch = 0; m->n_blocks = 0; m->blocks_sum = 0; m->r = 0;
   m->have_context = false; m->stepped = false;
   std::memset(&m->st, 0, sizeof(m->st));
   m->profile = false;
@@ -498,33 +505,49 @@ int bt_create(const bt_config* cfg, const bt_weights* w, void* workspace_dev, si
   return BT_OK;
 }
 
-int bt_prefill(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t prompt_len) {
-  if (!m) return BT_ERR_ARG;
+// Prefill of `batch` prompts held in rows of `row_stride` ids.  lens_host null: every prompt has
+// max_len ids; else sequence b has lens_host[b] <= max_len.  Every sequence is left-padded to
+// whole blocks on its own, so all of them end on a block boundary and decode in lockstep; the
+// shorter ones simply hold fewer cached blocks.
+static int prefill_impl(bt_model* m, const int32_t* tokens_dev, int batch, int row_stride, int max_len,
+                        const int32_t* lens_host) {
   const bt_config& c = m->cfg;
-  if (!tokens_dev) return fail(m, BT_ERR_ARG, "tokens_dev is null");
-  if (batch < 1 || batch > c.max_batch) return fail(m, BT_ERR_ARG, "batch out of range");
-  if (prompt_len < 1) return fail(m, BT_ERR_ARG, "prompt_len < 1");
-  // a first block that the prompt does not fill is completed from the left with pad_id
-  const int n_p = (prompt_len + c.block_len - 1) / c.block_len;
+  const int n_p = (max_len + c.block_len - 1) / c.block_len;     // blocks of the longest prompt
   if (n_p > c.max_blocks) return fail(m, BT_ERR_CAPACITY, "prompt needs more block slots than max_blocks");
   const Layout& L = m->L;
   int per = L.m_rows / n_p;
   if (per < 1) return fail(m, BT_ERR_CAPACITY, "workspace rows < prompt blocks");
+  int* seq_n = m->at<int>(L.state);
+  int* seq_len = m->at<int>(L.lens);
+  int64_t blocks_sum = (int64_t)batch * n_p;
+  if (lens_host) {
+    blocks_sum = 0;
+    for (int b = 0; b < batch; ++b) blocks_sum += (lens_host[b] + c.block_len - 1) / c.block_len;
+    BT_HIP(m, hipMemcpyAsync(seq_len, lens_host, (size_t)batch * sizeof(int32_t), hipMemcpyHostToDevice, m->stream));
+    BT_HIP(m, hipStreamSynchronize(m->stream));                  // the caller's array is free again on return
+    BT_HIP(m, launch_seq_blocks(seq_len, seq_n, c.block_len, batch, m->stream));
+  } else {
+    BT_HIP(m, launch_state_set(seq_len, max_len, batch, m->stream));
+    BT_HIP(m, launch_state_set(seq_n, n_p, batch, m->stream));
+  }
+  BT_HIP(m, launch_state_set(m->at<int>(L.fin), 0, c.max_batch, m->stream));
   const bool ctx_f32 = c.prefix_len == 0;
   const size_t ctx_esz = ctx_f32 ? 4 : L.esz;
   for (int b0 = 0; b0 < batch; b0 += per) {
     const int bc = batch - b0 < per ? batch - b0 : per;
-    BT_HIP(m, launch_embed_concat(c.dtype, m->w.E_emb, tokens_dev + (size_t)b0 * prompt_len, m->at<float>(L.x),
-                                  bc, n_p, c.block_len, c.d_model / c.block_len, prompt_len, c.pad_id, m->stream));
+    BT_HIP(m, launch_embed_concat(c.dtype, m->w.E_emb, tokens_dev + (size_t)b0 * row_stride, m->at<float>(L.x),
+                                  bc, n_p, c.block_len, c.d_model / c.block_len, row_stride, max_len, seq_len + b0,
+                                  c.pad_id, m->stream));
     StackArgs a{MODE_BLOCK_PREFILL, bc * n_p, bc, b0, n_p, 0};
+    a.fin_off_dev = seq_n + b0;             // the context embedding is the row of each sequence's own last block
     int rc = run_stack(m, m->blk.data(), c.n_block_layers, a, m->w.blk_lnf_g, m->w.blk_lnf_b,
                        m->ws + L.ctx + (size_t)b0 * c.d_model * ctx_esz, ctx_f32, bc, n_p, n_p - 1);
     if (rc) return rc;
   }
-  BT_HIP(m, launch_state_set(m->at<int>(L.state), n_p, m->stream));
   if (batch != m->batch) drop_graphs(m);      // captured launches are sized for one batch
   m->batch = batch;
   m->n_blocks = n_p;
+  m->blocks_sum = blocks_sum;
   m->r = 0;
   m->have_context = true;
   m->stepped = false;
@@ -533,6 +556,27 @@ int bt_prefill(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t pr
   st.token_passes = st.token_rows = st.block_kv_rows_read = st.block_kv_bytes_read = 0;
   st.local_kv_high_water = 0;
   return BT_OK;
+}
+
+int bt_prefill(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t prompt_len) {
+  if (!m) return BT_ERR_ARG;
+  if (!tokens_dev) return fail(m, BT_ERR_ARG, "tokens_dev is null");
+  if (batch < 1 || batch > m->cfg.max_batch) return fail(m, BT_ERR_ARG, "batch out of range");
+  if (prompt_len < 1) return fail(m, BT_ERR_ARG, "prompt_len < 1");
+  return prefill_impl(m, tokens_dev, batch, prompt_len, prompt_len, nullptr);
+}
+
+int bt_prefill_ragged(bt_model* m, const int32_t* tokens_dev, const int32_t* lens_host, int32_t batch, int32_t max_len) {
+  if (!m) return BT_ERR_ARG;
+  if (!tokens_dev || !lens_host) return fail(m, BT_ERR_ARG, "tokens_dev or lens_host is null");
+  if (batch < 1 || batch > m->cfg.max_batch) return fail(m, BT_ERR_ARG, "batch out of range");
+  if (max_len < 1) return fail(m, BT_ERR_ARG, "max_len < 1");
+  int longest = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (lens_host[b] < 1 || lens_host[b] > max_len) return fail(m, BT_ERR_ARG, "a prompt length lies outside [1, max_len]");
+    if (lens_host[b] > longest) longest = lens_host[b];
+  }
+  return prefill_impl(m, tokens_dev, batch, max_len, longest, lens_host);
 }
 
 // Enqueue every launch of one decode step.  with_block: embed the finished block and run the
@@ -551,7 +595,8 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
   int rows, pos0;
   if (r == 0) {
     if (with_block) {
-      BT_HIP(m, launch_embed_concat(c.dtype, m->w.E_emb, cur, x, B, 1, c.block_len, D / c.block_len, c.block_len, 0, s));
+      BT_HIP(m, launch_embed_concat(c.dtype, m->w.E_emb, cur, x, B, 1, c.block_len, D / c.block_len, c.block_len,
+                                    c.block_len, nullptr, c.pad_id, s));
       StackArgs a{MODE_BLOCK_DECODE, B, B, 0, 1, m->n_blocks};
       a.counter_inc = m->at<int>(L.state);     // the final LayerNorm launch counts the new block in
       int rc = run_stack(m, m->blk.data(), c.n_block_layers, a, m->w.blk_lnf_g, m->w.blk_lnf_b,
@@ -591,9 +636,11 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
   if (cand_tiles > 0) p.row_max = m->at<float2>(L.cand);
   BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));
   if (cand_tiles > 0)
-    BT_HIP(m, launch_argmax_candidates(m->at<float2>(L.cand), cand_tiles, B, ids_out, cur, c.block_len, r, s));
+    BT_HIP(m, launch_argmax_candidates(m->at<float2>(L.cand), cand_tiles, B, ids_out, cur, c.block_len, r, c.eos_id,
+                                       m->at<int32_t>(L.fin), s));
   else
-    BT_HIP(m, launch_argmax(m->at<float>(L.logits), B, c.vocab, ids_out, cur, c.block_len, r, s));
+    BT_HIP(m, launch_argmax(m->at<float>(L.logits), B, c.vocab, ids_out, cur, c.block_len, r, c.eos_id,
+                            m->at<int32_t>(L.fin), s));
   return BT_OK;
 }
 
@@ -652,8 +699,9 @@ int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
   if (with_block) {
     m->st.block_passes += 1;
     m->st.block_kv_rows_read += m->n_blocks + 1;
-    m->st.block_kv_bytes_read += (int64_t)(m->n_blocks + 1) * batch * c.n_block_layers * 2 * c.d_model * L.esz;
+    m->st.block_kv_bytes_read += (m->blocks_sum + batch) * c.n_block_layers * 2 * c.d_model * L.esz;
     m->n_blocks += 1;
+    m->blocks_sum += batch;
   }
   if (r == 0) m->have_context = false;
   m->st.token_passes += 1;
@@ -668,7 +716,16 @@ int bt_embed(bt_model* m, const int32_t* tokens_dev, int32_t n_rows, float* out_
   if (!m) return BT_ERR_ARG;
   if (!tokens_dev || !out_dev || n_rows < 0) return fail(m, BT_ERR_ARG, "bt_embed: null pointer or negative n_rows");
   BT_HIP(m, launch_embed_concat(m->cfg.dtype, m->w.E_emb, tokens_dev, out_dev, n_rows, 1, m->cfg.block_len,
-                                m->cfg.d_model / m->cfg.block_len, m->cfg.block_len, 0, m->stream));
+                                m->cfg.d_model / m->cfg.block_len, m->cfg.block_len, m->cfg.block_len, nullptr,
+                                m->cfg.pad_id, m->stream));
+  return BT_OK;
+}
+
+int bt_get_finished(bt_model* m, int32_t* flags_dev) {
+  if (!m) return BT_ERR_ARG;
+  if (!flags_dev) return fail(m, BT_ERR_ARG, "flags_dev is null");
+  if (m->batch == 0) return fail(m, BT_ERR_STATE, "no prefill yet");
+  BT_HIP(m, launch_gather_ids(m->at<int32_t>(m->L.fin), flags_dev, m->batch, 1, 0, m->stream));
   return BT_OK;
 }
 

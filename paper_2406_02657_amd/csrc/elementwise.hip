@@ -13,17 +13,21 @@ namespace bt {
 template <class T>
 __global__ __launch_bounds__(256) void embed_concat_kernel(const T* __restrict__ E, const int32_t* __restrict__ tokens,
                                                            float* __restrict__ x, int block_len, int d_emb,
-                                                           int blocks_per_seq, int seq_len, int pad, int pad_id) {
+                                                           int blocks_per_seq, int row_stride, int seq_len_arg,
+                                                           const int* __restrict__ seq_lens, int pad_id) {
   constexpr int EPC = Chunk<T>::EPC;
   const int m = blockIdx.x;
   const int b = m / blocks_per_seq, blk = m - b * blocks_per_seq;
+  const int len = seq_lens ? seq_lens[b] : seq_len_arg;
+  const int pad = (len + block_len - 1) / block_len * block_len - len;   // pads in front of the sequence's first block
   const int chunks_per_tok = d_emb / EPC;
   const int n_chunks = block_len * chunks_per_tok;
   float* xr = x + (size_t)m * block_len * d_emb;
   for (int c = threadIdx.x; c < n_chunks; c += blockDim.x) {
     const int j = c / chunks_per_tok, cc = c - j * chunks_per_tok;
     const int t = blk * block_len + j - pad;           // index into the unpadded sequence
-    const int tok = t < 0 ? pad_id : tokens[(size_t)b * seq_len + t];
+    // t >= len: a block past the end of a shorter sequence of the batch; its row is never used
+    const int tok = (t < 0 || t >= len) ? pad_id : tokens[(size_t)b * row_stride + t];
     const uint4 raw = *reinterpret_cast<const uint4*>(E + (size_t)tok * d_emb + cc * EPC);
     float f[EPC];
     Chunk<T>::unpack(raw, f);
@@ -36,17 +40,16 @@ __global__ __launch_bounds__(256) void embed_concat_kernel(const T* __restrict__
 
 hipError_t launch_embed_concat(int dtype, const void* E_emb, const int32_t* tokens, float* x,
                                int n_seqs, int blocks_per_seq, int block_len, int d_emb,
-                               int seq_len, int pad_id, hipStream_t s) {
+                               int row_stride, int seq_len, const int* seq_lens, int pad_id, hipStream_t s) {
   const int n_rows = n_seqs * blocks_per_seq;
   if (n_rows <= 0) return hipSuccess;
-  const int pad = blocks_per_seq * block_len - seq_len;
-  if (pad < 0 || pad >= block_len) return hipErrorInvalidValue;
+  if (!seq_lens && (seq_len < 1 || seq_len > row_stride || seq_len > blocks_per_seq * block_len)) return hipErrorInvalidValue;
   if (dtype == BT_F32)
     embed_concat_kernel<float><<<n_rows, 256, 0, s>>>((const float*)E_emb, tokens, x, block_len, d_emb,
-                                                      blocks_per_seq, seq_len, pad, pad_id);
+                                                      blocks_per_seq, row_stride, seq_len, seq_lens, pad_id);
   else
     embed_concat_kernel<bf16_t><<<n_rows, 256, 0, s>>>((const bf16_t*)E_emb, tokens, x, block_len, d_emb,
-                                                       blocks_per_seq, seq_len, pad, pad_id);
+                                                       blocks_per_seq, row_stride, seq_len, seq_lens, pad_id);
   return hipGetLastError();
 }
 
@@ -120,11 +123,12 @@ __device__ __forceinline__ void add_partials(float4& acc, const float* partA, in
   }
 }
 
-template <class T, int VPT>
+// SEL: the row offset inside each group of in_mul rows comes from device memory (in_off_dev).
+template <class T, int VPT, bool SEL>
 __global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void resid_ln_kernel(ResidLnArgs a) {
   __shared__ float red[4];
   const int i = blockIdx.x;
-  const size_t row = (size_t)i * a.in_mul + a.in_off;
+  const size_t row = (size_t)i * a.in_mul + (SEL ? a.in_off_dev[i] - 1 : a.in_off);
   const int D = a.D, G = D >> 2;
   constexpr bool kEarly = VPT == 1;           // one group per thread: gamma / beta ride along the first trip to memory
   float4 v[VPT], g1e, b1e, g2e, b2e;
@@ -153,7 +157,7 @@ __global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2
     if (nA + nB) add_partials(acc, a.partA, nA, a.partB, nB, a.part_stride, row * D + 4 * g);
     v[c] = acc;
   }
-  if (a.counter_inc && blockIdx.x == 0 && threadIdx.x == 0) *a.counter_inc += 1;
+  if (a.counter_inc && threadIdx.x == 0) a.counter_inc[i] += 1;
   float sum = 0.f;
 #pragma unroll
   for (int c = 0; c < VPT; ++c) {
@@ -203,10 +207,16 @@ __global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2
 template <class T>
 static hipError_t launch_resid_ln_t(const ResidLnArgs& a, hipStream_t s) {
   const int G = a.D / 4;
-  if (G <= kLnThreads) resid_ln_kernel<T, 1><<<a.n_rows, kLnThreads, 0, s>>>(a);
-  else if (G <= 2 * kLnThreads) resid_ln_kernel<T, 2><<<a.n_rows, kLnThreads, 0, s>>>(a);
-  else if (G <= 4 * kLnThreads) resid_ln_kernel<T, 4><<<a.n_rows, kLnThreads, 0, s>>>(a);
-  else return hipErrorInvalidValue;
+  if (G > 4 * kLnThreads) return hipErrorInvalidValue;
+  if (a.in_off_dev) {
+    if (G <= kLnThreads) resid_ln_kernel<T, 1, true><<<a.n_rows, kLnThreads, 0, s>>>(a);
+    else if (G <= 2 * kLnThreads) resid_ln_kernel<T, 2, true><<<a.n_rows, kLnThreads, 0, s>>>(a);
+    else resid_ln_kernel<T, 4, true><<<a.n_rows, kLnThreads, 0, s>>>(a);
+  } else {
+    if (G <= kLnThreads) resid_ln_kernel<T, 1, false><<<a.n_rows, kLnThreads, 0, s>>>(a);
+    else if (G <= 2 * kLnThreads) resid_ln_kernel<T, 2, false><<<a.n_rows, kLnThreads, 0, s>>>(a);
+    else resid_ln_kernel<T, 4, false><<<a.n_rows, kLnThreads, 0, s>>>(a);
+  }
   return hipGetLastError();
 }
 
@@ -225,9 +235,17 @@ __device__ __forceinline__ void argmax_take(float v, int i, float& best, int& bi
   if (v > best || (v == best && i < bi)) { best = v; bi = i; }
 }
 
+// End-of-sequence rule (eos_id >= 0): a sequence that has emitted eos_id emits eos_id from then on.
+__device__ __forceinline__ int apply_eos(int id, int eos_id, int32_t* finished, int b) {
+  if (eos_id < 0) return id;
+  if (finished[b]) return eos_id;
+  if (id == eos_id) finished[b] = 1;
+  return id;
+}
+
 __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int vocab,
                                                       int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
-                                                      int block_len, int r) {
+                                                      int block_len, int r, int eos_id, int32_t* __restrict__ finished) {
   __shared__ float sv[16];
   __shared__ int si[16];
   const int b = blockIdx.x;
@@ -257,21 +275,23 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
   if (threadIdx.x == 0) {
     for (int w = 1; w < 16; ++w) argmax_take(sv[w], si[w], best, bi);
     if (bi == 0x7fffffff) bi = 0;           // every logit was NaN or -inf
+    bi = apply_eos(bi, eos_id, finished, b);
     if (next_ids) next_ids[b] = bi;
     cur[b * block_len + r] = bi;
   }
 }
 
 hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next_ids,
-                         int32_t* cur, int block_len, int r, hipStream_t s) {
-  argmax_kernel<<<batch, 1024, 0, s>>>(logits, vocab, next_ids, cur, block_len, r);
+                         int32_t* cur, int block_len, int r, int eos_id, int32_t* finished, hipStream_t s) {
+  argmax_kernel<<<batch, 1024, 0, s>>>(logits, vocab, next_ids, cur, block_len, r, eos_id, finished);
   return hipGetLastError();
 }
 
 // Greedy argmax from per-tile candidates: one wave per sequence scans cand[b * n_tiles + tile].
 __global__ __launch_bounds__(64) void argmax_candidates_kernel(const float2* __restrict__ cand, int n_tiles, int batch,
                                                                int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
-                                                               int block_len, int r) {
+                                                               int block_len, int r, int eos_id,
+                                                               int32_t* __restrict__ finished) {
   const int b = blockIdx.x;
   float best = -INFINITY;
   int bi = 0x7fffffff;
@@ -287,15 +307,16 @@ __global__ __launch_bounds__(64) void argmax_candidates_kernel(const float2* __r
   }
   if (threadIdx.x == 0) {
     if (bi == 0x7fffffff) bi = 0;           // every logit was NaN or -inf
+    bi = apply_eos(bi, eos_id, finished, b);
     if (next_ids) next_ids[b] = bi;
     cur[b * block_len + r] = bi;
   }
 }
 
 hipError_t launch_argmax_candidates(const float2* cand, int n_tiles, int batch, int32_t* next_ids,
-                                    int32_t* cur, int block_len, int r, hipStream_t s) {
+                                    int32_t* cur, int block_len, int r, int eos_id, int32_t* finished, hipStream_t s) {
   if (n_tiles < 1) return hipErrorInvalidValue;
-  argmax_candidates_kernel<<<batch, 64, 0, s>>>(cand, n_tiles, batch, next_ids, cur, block_len, r);
+  argmax_candidates_kernel<<<batch, 64, 0, s>>>(cand, n_tiles, batch, next_ids, cur, block_len, r, eos_id, finished);
   return hipGetLastError();
 }
 
@@ -321,15 +342,23 @@ hipError_t launch_gather_ids(const int32_t* cur, int32_t* out, int batch, int bl
   return hipGetLastError();
 }
 
-__global__ void state_set_kernel(int* p, int value) { *p = value; }
-__global__ void state_add_kernel(int* p, int delta) { *p += delta; }
+__global__ void state_set_kernel(int* p, int value, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = value;
+}
+__global__ void seq_blocks_kernel(const int* lens, int* n_blocks, int block_len, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) n_blocks[i] = (lens[i] + block_len - 1) / block_len;
+}
 
-hipError_t launch_state_set(int* p, int value, hipStream_t s) {
-  state_set_kernel<<<1, 1, 0, s>>>(p, value);
+hipError_t launch_state_set(int* p, int value, int n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  state_set_kernel<<<(n + 255) / 256, 256, 0, s>>>(p, value, n);
   return hipGetLastError();
 }
-hipError_t launch_state_add(int* p, int delta, hipStream_t s) {
-  state_add_kernel<<<1, 1, 0, s>>>(p, delta);
+hipError_t launch_seq_blocks(const int* lens, int* n_blocks, int block_len, int n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  seq_blocks_kernel<<<(n + 255) / 256, 256, 0, s>>>(lens, n_blocks, block_len, n);
   return hipGetLastError();
 }
 

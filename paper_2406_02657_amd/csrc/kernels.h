@@ -10,12 +10,13 @@ namespace bt {
 
 // ---------------------------------------------------------------- elementwise
 // Embedder (Sec. 2.2): row m = b * blocks_per_seq + i of x is the concatenation of the table rows
-// of block i of sequence b, float out.  tokens [n_seqs, seq_len]; when seq_len is not a multiple
-// of L_B the sequence counts as left-padded with pad_id up to blocks_per_seq * L_B tokens
-// (App. "Random length padding"); blocks_per_seq * L_B - seq_len must lie in [0, L_B).
+// of block i of sequence b, float out.  tokens [n_seqs, row_stride]; sequence b holds seq_lens[b]
+// ids (seq_lens null: seq_len for all) at the start of its row and counts as left-padded with
+// pad_id to the next multiple of L_B (App. "Random length padding").  Blocks past a sequence's
+// own end (shorter sequences of a batch) are filled with pad_id; their rows are never used.
 hipError_t launch_embed_concat(int dtype, const void* E_emb, const int32_t* tokens, float* x,
                                int n_seqs, int blocks_per_seq, int block_len, int d_emb,
-                               int seq_len, int pad_id, hipStream_t s);
+                               int row_stride, int seq_len, const int* seq_lens, int pad_id, hipStream_t s);
 
 // Token-decoder input row: x[b, :] = E_tok[cur[b*L_B + r_prev], :], float out.
 hipError_t launch_token_embed(int dtype, const void* E_tok, const int32_t* cur, float* x,
@@ -48,25 +49,30 @@ struct ResidLnArgs {
   const void* emb_table;
   const int32_t* emb_ids;
   int emb_stride, emb_off;
-  // Optional: one thread adds 1 to *counter_inc (the device-side count of cached blocks).
+  // Optional: row i adds 1 to counter_inc[i] (the device-side count of cached blocks of sequence i).
   int* counter_inc;
+  // Optional: row i takes in_off_dev[i] - 1 in place of in_off (device memory).  New fields go at
+  // the end: moving the offsets of the fields above measurably slows the decode-step launches.
+  const int* in_off_dev;
 };
 hipError_t launch_resid_ln(int dtype, const ResidLnArgs& a, hipStream_t s);
 
 // Greedy argmax over logits [batch, vocab] (lowest index on ties); writes
-// next_ids[b] (if non-null) and cur[b*L_B + r].
+// next_ids[b] (if non-null) and cur[b*L_B + r].  eos_id >= 0: once sequence b has emitted eos_id
+// (finished[b] is then set, device memory), every later id of b is eos_id.
 hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next_ids,
-                         int32_t* cur, int block_len, int r, hipStream_t s);
+                         int32_t* cur, int block_len, int r, int eos_id, int32_t* finished, hipStream_t s);
 // The same from per-tile candidates cand[b * n_tiles + tile] = (value, column as int bits).
 hipError_t launch_argmax_candidates(const float2* cand, int n_tiles, int batch, int32_t* next_ids,
-                                    int32_t* cur, int block_len, int r, hipStream_t s);
+                                    int32_t* cur, int block_len, int r, int eos_id, int32_t* finished, hipStream_t s);
 
 hipError_t launch_scatter_ids(const int32_t* ids, int32_t* cur, int batch, int block_len, int r, hipStream_t s);
 // out[b] = cur[b*L_B + r]
 hipError_t launch_gather_ids(const int32_t* cur, int32_t* out, int batch, int block_len, int r, hipStream_t s);
-// *p = value, or *p += delta (one thread): the device-side count of cached blocks
-hipError_t launch_state_set(int* p, int value, hipStream_t s);
-hipError_t launch_state_add(int* p, int delta, hipStream_t s);
+// p[i] = value for i < n: the device-side counts of cached blocks, one per sequence
+hipError_t launch_state_set(int* p, int value, int n, hipStream_t s);
+// n_blocks[i] = ceil(lens[i] / block_len) for i < n
+hipError_t launch_seq_blocks(const int* lens, int* n_blocks, int block_len, int n, hipStream_t s);
 
 // ----------------------------------------------------------------------- GEMM
 enum { EPI_F32 = 0,        // out float [M, ldo]: acc + bias
@@ -143,14 +149,15 @@ hipError_t launch_gelu_reduce(int dtype, const GeluJob& job, hipStream_t s);
 // qkv may arrive as split-K partials (src.splits > 1 and/or src.bias): the rotated q is then
 // written complete into plane 0 (src.base), which is what the attention kernels read.
 hipError_t launch_rope_append(int dtype, const PartialSrc& src, void* Kc, void* Vc, const float2* rope,
-                              int n_rows, int n_new, int pos0, const int* n_dev, int n_heads, int d_head, int rot,
+                              int n_rows, int n_new, int pos0, int n_heads, int d_head, int rot,
                               int n_cap, const GeluJob& gelu, hipStream_t s);
 
 // Block decoder decode step, fused: finish q, k, v of every (b, h) from the (possibly split-K)
 // QKV output, rotate q and k at position n_old, append k, v to the cache at slot n_old, and
 // attend the one query to cache rows [0, n_old].  out [B, D] storage dtype (out_lo_off != 0:
-// also the bf16 remainder plane).  n_dev: when non-null n_old is read from device memory
-// (*n_dev), so that a captured graph stays valid while the cache grows.  gelu: optional job
+// also the bf16 remainder plane).  n_dev: when non-null, sequence b reads its own n_old from
+// device memory (n_dev[b]): a captured graph stays valid while the caches grow, and the
+// sequences of a batch may hold different numbers of blocks.  gelu: optional job
 // done by extra workgroups of the same launch.
 hipError_t launch_attn_block_decode(int dtype, const PartialSrc& qkv, void* Kc, void* Vc, const float2* rope, int rot,
                                     void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_old,

@@ -55,6 +55,7 @@ class BTConfig:
     parallel_residual: int = 1
     ln_eps: float = 1e-5
     pad_id: int = 0         # fills the first block of a prompt whose length is not a multiple of L_B
+    eos_id: int = -1        # -1: none; else a sequence that emitted it keeps emitting it
 
     @property
     def d_emb(self) -> int:

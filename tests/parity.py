@@ -47,6 +47,39 @@ def compare_with_oracle(cfg, weights, prompts_np, gpu_ids, gpu_logits, tol, marg
     }
 
 
+def gpu_generate_ragged(model, prompts, n_new):
+    """prompts: list of 1-D id arrays of different lengths.  Returns (ids [B, n_new], logits [B, n_new, V])."""
+    import torch
+    lens = [len(p) for p in prompts]
+    buf = np.full((len(prompts), max(lens)), 1, dtype=np.int32)      # the tail of a shorter row must not be read
+    for b, p in enumerate(prompts):
+        buf[b, :lens[b]] = p
+    model.bt_prefill_ragged(torch.from_numpy(buf).to(model.device), lens)
+    ids, lgs = [], []
+    for _ in range(n_new):
+        ids.append(model.bt_decode_step().clone())
+        lgs.append(model.bt_get_logits())
+    torch.cuda.synchronize()
+    return torch.stack(ids, 1).cpu().numpy(), torch.stack(lgs, 1).cpu().numpy()
+
+
+def compare_ragged_with_oracle(cfg, weights, prompts, gpu_ids, gpu_logits, tol, margin=2e-2):
+    """As compare_with_oracle for a batch of prompts of different lengths."""
+    import oracle.block_transformer as O
+    _, o_logits = O.generate_ragged(O.Params(weights), cfg, prompts, gpu_ids.shape[1], forced=gpu_ids)
+    diff = np.abs(gpu_logits.astype(np.float64) - o_logits)
+    srt = np.sort(o_logits, axis=-1)
+    o_margin = srt[..., -1] - srt[..., -2]
+    mism = gpu_ids != np.argmax(o_logits, axis=-1)
+    return {
+        "max_abs_logit_diff": float(diff.max()),
+        "steps": int(mism.size),
+        "exempt_mismatches": int(np.sum(mism & (o_margin < margin))),
+        "true_mismatches": int(np.sum(mism & (o_margin >= margin))),
+        "tol": tol,
+    }
+
+
 def assert_parity(rep):
     assert rep["max_abs_logit_diff"] <= rep["tol"], rep
     assert rep["true_mismatches"] == 0, rep

@@ -7,7 +7,8 @@ import numpy as np
 import pytest
 
 from helpers import tiny_cfg
-from parity import assert_parity, compare_with_oracle, gpu_generate
+from parity import (assert_parity, compare_ragged_with_oracle, compare_with_oracle, gpu_generate,
+                    gpu_generate_ragged)
 from synth import CONFIGS, make_prompts, make_weights
 
 pytestmark = pytest.mark.gpu
@@ -321,3 +322,84 @@ def test_pad_id_reaches_the_embedder(amd):
         rep, _, _, lgs = run_case(amd, base.with_(pad_id=pad), 2)
         first.append(lgs[:, 0])
     assert np.abs(first[0] - first[1]).max() > 1e-4
+
+
+@pytest.mark.parametrize("dtype,lb,p,lens,prefill_rows", [
+    ("fp32", 4, 1, [11, 1, 8, 6, 4], 0),
+    ("fp32", 8, 2, [3, 40, 17, 16], 0),
+    ("bf16", 4, 1, [127, 1, 64, 30, 128, 5, 77], 0),
+    ("bf16", 4, 2, [300, 7, 256, 129], 0),           # longest prompt: 75 blocks, matrix-core prefill attention
+    ("bf16", 8, 1, [90, 33, 64, 1, 8, 250], 64),      # prefill in chunks of two sequences
+])
+def test_prompts_of_different_lengths_in_one_batch(amd, dtype, lb, p, lens, prefill_rows):
+    """Each sequence is left-padded on its own and keeps its own count of cached blocks; the result
+    per sequence is that of the sequence alone (App. "Random length padding")."""
+    cfg = tiny_cfg(dtype=dtype, block_len=lb, prefix_len=p, d_model=128, n_heads=4, d_ff=256, vocab=211,
+                   prompt_len=max(lens), n_block_layers=2, n_token_layers=2).with_(pad_id=3)
+    W = make_weights(cfg)
+    full = make_prompts(cfg, batch=len(lens))
+    prompts = [full[b, :n] for b, n in enumerate(lens)]
+    n_new = 3 * lb + 2                                   # the with-block step kind is replayed from its graph
+    m = amd.Model(cfg, W, max_batch=len(lens), max_blocks=-(-max(lens) // lb) + 4, prefill_rows=prefill_rows)
+    ids, lgs = gpu_generate_ragged(m, prompts, n_new)
+    st = m.bt_get_stats()
+    rep = compare_ragged_with_oracle(cfg, W, prompts, ids, lgs, TOL_F32 if dtype == "fp32" else TOL_BF16)
+    print(rep)
+    assert_parity(rep)
+    assert st.n_blocks == -(-max(lens) // lb) + 3
+    # the same model then serves an ordinary batch again
+    ids2, lgs2 = gpu_generate(m, full[:, :2 * lb], lb + 1)
+    m.close()
+    assert_parity(compare_with_oracle(cfg.with_(prompt_len=2 * lb), W, full[:, :2 * lb], ids2, lgs2,
+                                      TOL_F32 if dtype == "fp32" else TOL_BF16))
+
+
+def test_ragged_prefill_rejects_bad_lengths(amd):
+    import ctypes as C
+    import torch
+    cfg = tiny_cfg(d_model=64, n_heads=2, d_ff=128, vocab=64, block_len=4, prefix_len=1, prompt_len=8)
+    m = amd.Model(cfg, make_weights(cfg), max_batch=2, max_blocks=3)
+    toks = torch.zeros(2, 8, dtype=torch.int32, device="cuda")
+    lens = lambda *v: (C.c_int32 * len(v))(*v)
+    assert amd.lib.bt_prefill_ragged(m.h, toks.data_ptr(), lens(8, 0), 2, 8) == -1
+    assert amd.lib.bt_prefill_ragged(m.h, toks.data_ptr(), lens(9, 3), 2, 8) == -1
+    assert amd.lib.bt_prefill_ragged(m.h, toks.data_ptr(), None, 2, 8) == -1
+    assert amd.lib.bt_prefill_ragged(m.h, toks.data_ptr(), lens(8, 3), 3, 8) == -1
+    assert amd.lib.bt_prefill_ragged(m.h, toks.data_ptr(), lens(5, 3), 2, 8) == 0
+    torch.cuda.synchronize()
+    m.close()
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_eos_rule_on_device(amd, dtype):
+    """A sequence that has emitted eos_id emits it from then on and raises its flag; the others go on."""
+    import oracle.block_transformer as O
+    import torch
+    base = tiny_cfg(dtype=dtype, d_model=128, n_heads=4, d_ff=256, vocab=23, block_len=4, prefix_len=1, prompt_len=8)
+    W = make_weights(base)
+    prompts = make_prompts(base, batch=6)
+    n_new = 18
+    m = amd.Model(base, W, max_batch=6, max_blocks=8)
+    free, _ = gpu_generate(m, prompts, n_new)
+    m.close()
+    eos = int(free[0, 6])
+    cfg = base.with_(eos_id=eos)
+    m = amd.Model(cfg, W, max_batch=6, max_blocks=8)
+    ids, lgs = gpu_generate(m, prompts, n_new)
+    flags = m.bt_get_finished().cpu().numpy()
+    # the oracle with the same rule, teacher-forced on the GPU's ids
+    _, o_lgs, gen = O.generate_cached(O.Params(W), cfg, prompts, n_new, forced=ids)
+    assert np.abs(lgs - o_lgs).max() <= (TOL_F32 if dtype == "fp32" else TOL_BF16)
+    assert np.array_equal(flags.astype(bool), gen.finished)
+    for b in range(6):
+        where = np.nonzero(free[b] == eos)[0]
+        if len(where):
+            k = where[0]
+            assert np.array_equal(ids[b, :k + 1], free[b, :k + 1]) and np.all(ids[b, k:] == eos) and flags[b] == 1
+        else:
+            assert np.array_equal(ids[b], free[b]) and flags[b] == 0
+    assert flags[0] == 1
+    # a new prefill clears the flags
+    m.bt_prefill(torch.from_numpy(prompts).to(m.device))
+    assert int(m.bt_get_finished().sum()) == 0
+    m.close()

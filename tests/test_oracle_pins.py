@@ -540,3 +540,46 @@ def test_pad_tokens_enter_the_first_block_embedding():
     assert np.array_equal(e[0, 0], want)
     other = O.generate_full(P, cfg.with_(pad_id=10), toks, 1)[1]
     assert np.abs(other - O.generate_full(P, cfg, toks, 1)[1]).max() > 1e-6
+
+
+def test_ragged_batch_is_each_sequence_alone():
+    """A batch of prompts of different lengths == every sequence run by the no-cache definition on
+    its own hand-padded prompt; with equal lengths it is the ordinary batch."""
+    cfg = tiny_cfg(block_len=4, prefix_len=2, d_model=32, n_heads=2, prompt_len=11).with_(pad_id=2)
+    P = build(cfg)
+    full = make_prompts(cfg, batch=4)
+    lens = [11, 1, 8, 6]
+    prompts = [full[b, :n] for b, n in enumerate(lens)]
+    ids, lgs = O.generate_ragged(P, cfg, prompts, 6)
+    for b, n in enumerate(lens):
+        k = (-n) % 4
+        by_hand = np.array([[2] * k + [int(t) for t in prompts[b]]])
+        i1, l1 = O.generate_full(P, cfg, by_hand, 6)
+        assert np.array_equal(ids[b], i1[0]) and np.abs(lgs[b] - l1[0]).max() < 1e-11
+    same = [full[b, :8] for b in range(4)]
+    ids2, lgs2 = O.generate_ragged(P, cfg, same, 5)
+    ids3, lgs3, _ = O.generate_cached(P, cfg, full[:, :8], 5)
+    assert np.array_equal(ids2, ids3) and np.abs(lgs2 - lgs3).max() < 1e-11
+
+
+def test_eos_rule():
+    """eos_id = -1 changes nothing; with an eos id the ids equal the free run up to and including
+    each sequence's first eos and are eos afterwards; other sequences are untouched."""
+    cfg = tiny_cfg(block_len=4, prefix_len=1, d_model=32, n_heads=2, prompt_len=8, vocab=13)
+    P = build(cfg)
+    toks = make_prompts(cfg, batch=3)
+    free, lg_free, _ = O.generate_cached(P, cfg, toks, 14)
+    eos = int(free[0, 5])                                   # sequence 0 emits it at step <= 5
+    ids, lgs, gen = O.generate_cached(P, cfg.with_(eos_id=eos), toks, 14)
+    hits = 0
+    for b in range(3):
+        where = np.nonzero(free[b] == eos)[0]
+        if len(where) == 0:
+            assert np.array_equal(ids[b], free[b]) and not gen.finished[b]
+            continue
+        k = where[0]
+        hits += 1
+        assert np.array_equal(ids[b, :k + 1], free[b, :k + 1])
+        assert np.all(ids[b, k:] == eos) and gen.finished[b]
+        assert np.array_equal(lgs[b, :k + 1], lg_free[b, :k + 1])
+    assert hits >= 1 and np.all(ids[0, 5:] == eos)
