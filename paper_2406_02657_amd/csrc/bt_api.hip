@@ -220,8 +220,7 @@ int final_ln(bt_model* m, const StackArgs& a, const float* pendO, const float* b
   r.n_rows = n; r.D = m->cfg.d_model; r.in_mul = in_mul; r.in_off = in_off; r.write_x = 0;
   r.eps = m->cfg.ln_eps;
   r.counter_inc = a.counter_inc;
-  r.in_off_dev = a.fin_off_dev;
-  BT_HIP(m, launch_resid_ln(m->cfg.dtype, r, m->stream));
+  BT_HIP(m, launch_resid_ln(m->cfg.dtype, r, m->stream, a.fin_off_dev));
   return BT_OK;
 }
 

@@ -123,12 +123,11 @@ __device__ __forceinline__ void add_partials(float4& acc, const float* partA, in
   }
 }
 
-// SEL: the row offset inside each group of in_mul rows comes from device memory (in_off_dev).
-template <class T, int VPT, bool SEL>
-__global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void resid_ln_kernel(ResidLnArgs a) {
+template <class T, int VPT>
+__device__ __forceinline__ void resid_ln_body(const ResidLnArgs& a, int in_off) {
   __shared__ float red[4];
   const int i = blockIdx.x;
-  const size_t row = (size_t)i * a.in_mul + (SEL ? a.in_off_dev[i] - 1 : a.in_off);
+  const size_t row = (size_t)i * a.in_mul + in_off;
   const int D = a.D, G = D >> 2;
   constexpr bool kEarly = VPT == 1;           // one group per thread: gamma / beta ride along the first trip to memory
   float4 v[VPT], g1e, b1e, g2e, b2e;
@@ -204,26 +203,36 @@ __global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2
   }
 }
 
+template <class T, int VPT>
+__global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void resid_ln_kernel(ResidLnArgs a) {
+  resid_ln_body<T, VPT>(a, a.in_off);
+}
+// The row offset inside each group of in_mul rows comes from device memory.
+template <class T, int VPT>
+__global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void resid_ln_sel_kernel(ResidLnArgs a, const int* __restrict__ in_off_dev) {
+  resid_ln_body<T, VPT>(a, in_off_dev[blockIdx.x] - 1);
+}
+
 template <class T>
-static hipError_t launch_resid_ln_t(const ResidLnArgs& a, hipStream_t s) {
+static hipError_t launch_resid_ln_t(const ResidLnArgs& a, hipStream_t s, const int* in_off_dev) {
   const int G = a.D / 4;
   if (G > 4 * kLnThreads) return hipErrorInvalidValue;
-  if (a.in_off_dev) {
-    if (G <= kLnThreads) resid_ln_kernel<T, 1, true><<<a.n_rows, kLnThreads, 0, s>>>(a);
-    else if (G <= 2 * kLnThreads) resid_ln_kernel<T, 2, true><<<a.n_rows, kLnThreads, 0, s>>>(a);
-    else resid_ln_kernel<T, 4, true><<<a.n_rows, kLnThreads, 0, s>>>(a);
+  if (in_off_dev) {
+    if (G <= kLnThreads) resid_ln_sel_kernel<T, 1><<<a.n_rows, kLnThreads, 0, s>>>(a, in_off_dev);
+    else if (G <= 2 * kLnThreads) resid_ln_sel_kernel<T, 2><<<a.n_rows, kLnThreads, 0, s>>>(a, in_off_dev);
+    else resid_ln_sel_kernel<T, 4><<<a.n_rows, kLnThreads, 0, s>>>(a, in_off_dev);
   } else {
-    if (G <= kLnThreads) resid_ln_kernel<T, 1, false><<<a.n_rows, kLnThreads, 0, s>>>(a);
-    else if (G <= 2 * kLnThreads) resid_ln_kernel<T, 2, false><<<a.n_rows, kLnThreads, 0, s>>>(a);
-    else resid_ln_kernel<T, 4, false><<<a.n_rows, kLnThreads, 0, s>>>(a);
+    if (G <= kLnThreads) resid_ln_kernel<T, 1><<<a.n_rows, kLnThreads, 0, s>>>(a);
+    else if (G <= 2 * kLnThreads) resid_ln_kernel<T, 2><<<a.n_rows, kLnThreads, 0, s>>>(a);
+    else resid_ln_kernel<T, 4><<<a.n_rows, kLnThreads, 0, s>>>(a);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_resid_ln(int dtype, const ResidLnArgs& a, hipStream_t s) {
+hipError_t launch_resid_ln(int dtype, const ResidLnArgs& a, hipStream_t s, const int* in_off_dev) {
   if (a.n_rows <= 0) return hipSuccess;
   if (a.D % 4) return hipErrorInvalidValue;
-  return dtype == BT_F32 ? launch_resid_ln_t<float>(a, s) : launch_resid_ln_t<bf16_t>(a, s);
+  return dtype == BT_F32 ? launch_resid_ln_t<float>(a, s, in_off_dev) : launch_resid_ln_t<bf16_t>(a, s, in_off_dev);
 }
 
 // ---------------------------------------------------------------------------
@@ -243,9 +252,9 @@ __device__ __forceinline__ int apply_eos(int id, int eos_id, int32_t* finished, 
   return id;
 }
 
-__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int vocab,
-                                                      int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
-                                                      int block_len, int r, int eos_id, int32_t* __restrict__ finished) {
+__device__ __forceinline__ void argmax_body(const float* __restrict__ logits, int vocab,
+                                            int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
+                                            int block_len, int r, int eos_id, int32_t* __restrict__ finished) {
   __shared__ float sv[16];
   __shared__ int si[16];
   const int b = blockIdx.x;
@@ -281,17 +290,29 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
   }
 }
 
+// Two entry points each: the one without the end-of-sequence rule keeps the short argument list.
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int vocab,
+                                                      int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
+                                                      int block_len, int r) {
+  argmax_body(logits, vocab, next_ids, cur, block_len, r, -1, nullptr);
+}
+__global__ __launch_bounds__(1024) void argmax_eos_kernel(const float* __restrict__ logits, int vocab,
+                                                          int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
+                                                          int block_len, int r, int eos_id, int32_t* __restrict__ finished) {
+  argmax_body(logits, vocab, next_ids, cur, block_len, r, eos_id, finished);
+}
+
 hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next_ids,
                          int32_t* cur, int block_len, int r, int eos_id, int32_t* finished, hipStream_t s) {
-  argmax_kernel<<<batch, 1024, 0, s>>>(logits, vocab, next_ids, cur, block_len, r, eos_id, finished);
+  if (eos_id >= 0) argmax_eos_kernel<<<batch, 1024, 0, s>>>(logits, vocab, next_ids, cur, block_len, r, eos_id, finished);
+  else argmax_kernel<<<batch, 1024, 0, s>>>(logits, vocab, next_ids, cur, block_len, r);
   return hipGetLastError();
 }
 
 // Greedy argmax from per-tile candidates: one wave per sequence scans cand[b * n_tiles + tile].
-__global__ __launch_bounds__(64) void argmax_candidates_kernel(const float2* __restrict__ cand, int n_tiles, int batch,
-                                                               int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
-                                                               int block_len, int r, int eos_id,
-                                                               int32_t* __restrict__ finished) {
+__device__ __forceinline__ void argmax_candidates_body(const float2* __restrict__ cand, int n_tiles,
+                                                       int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
+                                                       int block_len, int r, int eos_id, int32_t* __restrict__ finished) {
   const int b = blockIdx.x;
   float best = -INFINITY;
   int bi = 0x7fffffff;
@@ -313,10 +334,23 @@ __global__ __launch_bounds__(64) void argmax_candidates_kernel(const float2* __r
   }
 }
 
+__global__ __launch_bounds__(64) void argmax_candidates_kernel(const float2* __restrict__ cand, int n_tiles, int batch,
+                                                               int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
+                                                               int block_len, int r) {
+  argmax_candidates_body(cand, n_tiles, next_ids, cur, block_len, r, -1, nullptr);
+}
+__global__ __launch_bounds__(64) void argmax_candidates_eos_kernel(const float2* __restrict__ cand, int n_tiles,
+                                                                   int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
+                                                                   int block_len, int r, int eos_id,
+                                                                   int32_t* __restrict__ finished) {
+  argmax_candidates_body(cand, n_tiles, next_ids, cur, block_len, r, eos_id, finished);
+}
+
 hipError_t launch_argmax_candidates(const float2* cand, int n_tiles, int batch, int32_t* next_ids,
                                     int32_t* cur, int block_len, int r, int eos_id, int32_t* finished, hipStream_t s) {
   if (n_tiles < 1) return hipErrorInvalidValue;
-  argmax_candidates_kernel<<<batch, 64, 0, s>>>(cand, n_tiles, batch, next_ids, cur, block_len, r, eos_id, finished);
+  if (eos_id >= 0) argmax_candidates_eos_kernel<<<batch, 64, 0, s>>>(cand, n_tiles, next_ids, cur, block_len, r, eos_id, finished);
+  else argmax_candidates_kernel<<<batch, 64, 0, s>>>(cand, n_tiles, batch, next_ids, cur, block_len, r);
   return hipGetLastError();
 }
 

@@ -35,6 +35,41 @@ struct GemmGroup {
   int n;
 };
 
+// The decode (K-slice) kernels take a compact form of the same description: one 64-byte cache line
+// per problem.  Every workgroup of a launch fetches its kernel arguments from memory before it can
+// issue anything else, and each further line of arguments measurably lengthens that first trip.
+// Implied: lda == K, ldo == N, tiles_n from N and the kernel's tile width; a missing second problem
+// has tile_begin == INT_MAX.
+struct alignas(64) KsDesc {
+  const void* A;
+  const void* W_frag;
+  void* out;
+  const float* bias;
+  float2* row_max;
+  int lo_delta;          // elements from A to its bf16 remainder plane (0: none)
+  int M, N, K;
+  int epi_splits;        // epi | splits << 8
+  int tile_begin;
+};
+static_assert(sizeof(KsDesc) == 64, "one cache line per problem");
+struct KsGroup {
+  KsDesc p[2];
+};
+// The fields the kernel bodies use, under the names of GemmDesc.
+struct KsView {
+  const void* A;
+  const void* A_lo;
+  const void* W_frag;
+  void* out;
+  const float* bias;
+  float2* row_max;
+  int M, N, K, lda, ldo, epi, splits, tiles_n, tile_begin;
+  __device__ __forceinline__ KsView(const KsDesc& c, int tile_cols)
+      : A(c.A), A_lo(reinterpret_cast<const uint16_t*>(c.A) + c.lo_delta), W_frag(c.W_frag), out(c.out), bias(c.bias),
+        row_max(c.row_max), M(c.M), N(c.N), K(c.K), lda(c.K), ldo(c.N), epi(c.epi_splits & 0xff),
+        splits(c.epi_splits >> 8), tiles_n((c.N + tile_cols - 1) / tile_cols), tile_begin(c.tile_begin) {}
+};
+
 __device__ __forceinline__ float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
 
 // What an epilogue needs from the descriptor, as plain values (kept in registers).
@@ -393,14 +428,15 @@ __device__ __forceinline__ int row_min_step(int v) {
 }
 
 template <int KF, int NT, int MC, bool HL>
-__global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
+__global__ __launch_bounds__(256) void gemm_kslice_kernel(KsGroup g) {
   constexpr int KS = 32 * KF, LDK = KS + 8, CPR = KS / 8, PL = HL ? 2 : 1;
   extern __shared__ __attribute__((aligned(16))) uint16_t sA[];
   const int bid = blockIdx.x;
   // The descriptor is copied into registers at once: every field the epilogue needs is then
   // already there instead of being fetched from the argument block after the multiply.
-  GemmDesc d = g.p[0];
-  if (g.n > 1 && bid >= g.p[1].tile_begin) d = g.p[1];
+  KsDesc c = g.p[0];
+  if (bid >= g.p[1].tile_begin) c = g.p[1];
+  const KsView d(c, 64 * NT);
   const int t = bid - d.tile_begin;
   const int split = t / d.tiles_n, tn = t - split * d.tiles_n;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -586,12 +622,13 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(GemmGroup g) {
 // MC * KF <= 8 (registers: the whole next slice is held by the 256 threads).
 // ---------------------------------------------------------------------------
 template <int KF, int NT, int MC>
-__global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(GemmGroup g) {
+__global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(KsGroup g) {
   constexpr int KS = 32 * KF, LDK = KS + 8, CPR = KS / 8, NCH = MC * KF;
   extern __shared__ __attribute__((aligned(16))) uint16_t sA[];
   const int bid = blockIdx.x;
-  GemmDesc d = g.p[0];
-  if (g.n > 1 && bid >= g.p[1].tile_begin) d = g.p[1];
+  KsDesc c = g.p[0];
+  if (bid >= g.p[1].tile_begin) c = g.p[1];
+  const KsView d(c, 64 * NT);
   const int t = bid - d.tile_begin;
   const int split = t / d.tiles_n, tn = t - split * d.tiles_n;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -892,6 +929,23 @@ static int fill_tiles(GemmGroup& g) {
   return begin;
 }
 
+// Compact form of the group for the K-slice kernels (tile width 64 * NT columns); returns the grid size.
+static int pack_kslice(const GemmGroup& g, int tile_cols, KsGroup& k) {
+  int begin = 0;
+  for (int i = 0; i < 2; ++i) {
+    KsDesc& c = k.p[i];
+    if (i >= g.n) { c = KsDesc{}; c.tile_begin = 0x7fffffff; continue; }
+    const GemmDesc& d = g.p[i];
+    c.A = d.A; c.W_frag = d.W_frag; c.out = d.out; c.bias = d.bias; c.row_max = d.row_max;
+    c.lo_delta = d.A_lo ? (int)(reinterpret_cast<const uint16_t*>(d.A_lo) - reinterpret_cast<const uint16_t*>(d.A)) : 0;
+    c.M = d.M; c.N = d.N; c.K = d.K;
+    c.epi_splits = d.epi | (d.splits << 8);
+    c.tile_begin = begin;
+    begin += (d.N + tile_cols - 1) / tile_cols * d.splits;
+  }
+  return begin;
+}
+
 template <int KF, int NT, int MC, bool HL>
 static hipError_t launch_kslice(GemmGroup& g, size_t lds, hipStream_t s) {
   static bool attr_set = false;
@@ -901,7 +955,9 @@ static hipError_t launch_kslice(GemmGroup& g, size_t lds, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  kern<<<fill_tiles<1 << 30, 64 * NT>(g), 256, lds, s>>>(g);
+  KsGroup k;
+  const int grid = pack_kslice(g, 64 * NT, k);
+  kern<<<grid, 256, lds, s>>>(k);
   return hipSuccess;
 }
 
@@ -914,7 +970,9 @@ static hipError_t launch_kslice_pipe(GemmGroup& g, size_t lds, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  kern<<<fill_tiles<1 << 30, 64 * NT>(g), 256, lds, s>>>(g);
+  KsGroup k;
+  const int grid = pack_kslice(g, 64 * NT, k);
+  kern<<<grid, 256, lds, s>>>(k);
   return hipSuccess;
 }
 
@@ -981,8 +1039,16 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
       break;
     }
     case KIND_KSLICE: {
-      for (int i = 0; i < n_probs; ++i)
-        if (probs[i].K % (32 * plan.kf * plan.splits[i]) || !probs[i].W_frag || probs[i].epi == EPI_GELU) return hipErrorInvalidValue;
+      for (int i = 0; i < n_probs; ++i) {
+        const GemmProblem& p = probs[i];
+        if (p.K % (32 * plan.kf * plan.splits[i]) || !p.W_frag || p.epi == EPI_GELU) return hipErrorInvalidValue;
+        // the compact argument form implies dense rows and a remainder plane within 2^31 elements
+        if (p.lda != p.K || (p.epi == EPI_F32 && p.ldo != p.N) || plan.splits[i] > 0xffff) return hipErrorInvalidValue;
+        if (p.A_lo) {
+          const ptrdiff_t delta = reinterpret_cast<const uint16_t*>(p.A_lo) - reinterpret_cast<const uint16_t*>(p.A);
+          if (delta <= 0 || delta > 0x7fffffff) return hipErrorInvalidValue;
+        }
+      }
       const size_t lds = kslice_lds_bytes(probs[0].M, plan.kf, hl);
       if (lds > 160 * 1024) return hipErrorInvalidValue;
       hipError_t e;

@@ -51,11 +51,11 @@ struct ResidLnArgs {
   int emb_stride, emb_off;
   // Optional: row i adds 1 to counter_inc[i] (the device-side count of cached blocks of sequence i).
   int* counter_inc;
-  // Optional: row i takes in_off_dev[i] - 1 in place of in_off (device memory).  New fields go at
-  // the end: moving the offsets of the fields above measurably slows the decode-step launches.
-  const int* in_off_dev;
 };
-hipError_t launch_resid_ln(int dtype, const ResidLnArgs& a, hipStream_t s);
+// in_off_dev (optional, device memory): row i takes in_off_dev[i] - 1 in place of a.in_off.  It is
+// a launch argument of its own, used by a separate instantiation: the size and field offsets of
+// ResidLnArgs measurably change the cost of the decode-step launches.
+hipError_t launch_resid_ln(int dtype, const ResidLnArgs& a, hipStream_t s, const int* in_off_dev = nullptr);
 
 // Greedy argmax over logits [batch, vocab] (lowest index on ties); writes
 // next_ids[b] (if non-null) and cur[b*L_B + r].  eos_id >= 0: once sequence b has emitted eos_id
