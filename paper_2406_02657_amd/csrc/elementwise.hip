@@ -123,16 +123,45 @@ __device__ __forceinline__ void add_partials(float4& acc, const float* partA, in
   }
 }
 
-template <class T, int VPT>
-__device__ __forceinline__ void resid_ln_body(const ResidLnArgs& a, int in_off) {
+// What the kernel receives.  Every workgroup fetches its kernel arguments from memory before it can
+// issue anything else, and each further 64-byte line of them lengthens that first trip, so the
+// fields every launch needs fit two lines (LnHot) and the rarely used ones (LnCold) are a second
+// argument that only the EXTRA instantiation touches.
+struct LnHot {
+  float* x;
+  const float *partA, *partB, *biasA, *biasB;
+  const float *g1, *b1, *g2, *b2;
+  void *u1, *u2;
+  size_t part_stride;
+  unsigned lo_off;
+  int D, in_mul, in_off;
+  float eps;
+  unsigned packed;       // splitsA | splitsB << 12 | u1_f32 << 24 | write_x << 25
+};
+static_assert(sizeof(LnHot) <= 128, "two cache lines");
+struct LnCold {
+  const void* emb_table;
+  const int32_t* emb_ids;
+  int* counter_inc;
+  const int* in_off_dev;
+  int emb_stride, emb_off;
+};
+
+template <class T, int VPT, bool EXTRA>
+__device__ __forceinline__ void resid_ln_body(const LnHot& a, const LnCold& cold) {
   __shared__ float red[4];
   const int i = blockIdx.x;
+  const int in_off = (EXTRA && cold.in_off_dev) ? cold.in_off_dev[i] - 1 : a.in_off;
   const size_t row = (size_t)i * a.in_mul + in_off;
   const int D = a.D, G = D >> 2;
+  const int splitsA = a.packed & 0xfff, splitsB = (a.packed >> 12) & 0xfff;
+  const bool u1_f32 = (a.packed >> 24) & 1, write_x = (a.packed >> 25) & 1;
+  const void* emb_table = EXTRA ? cold.emb_table : nullptr;
+  int* counter_inc = EXTRA ? cold.counter_inc : nullptr;
   constexpr bool kEarly = VPT == 1;           // one group per thread: gamma / beta ride along the first trip to memory
   float4 v[VPT], g1e, b1e, g2e, b2e;
   float* xr = a.x + row * D;
-  const int nA = a.partA ? a.splitsA : 0, nB = a.partB ? a.splitsB : 0;
+  const int nA = a.partA ? splitsA : 0, nB = a.partB ? splitsB : 0;
   const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
   // Every load of the kernel is issued here, before the first reduction: one trip to memory.
 #pragma unroll
@@ -145,8 +174,8 @@ __device__ __forceinline__ void resid_ln_body(const ResidLnArgs& a, int in_off) 
       b2e = a.g2 ? *reinterpret_cast<const float4*>(a.b2 + 4 * g) : zero;
     }
     float4 acc;
-    if (a.emb_table) {
-      const T* er = reinterpret_cast<const T*>(a.emb_table) + (size_t)a.emb_ids[(size_t)i * a.emb_stride + a.emb_off] * D + 4 * g;
+    if (emb_table) {
+      const T* er = reinterpret_cast<const T*>(emb_table) + (size_t)cold.emb_ids[(size_t)i * cold.emb_stride + cold.emb_off] * D + 4 * g;
       acc = make_float4(to_float<T>(er[0]), to_float<T>(er[1]), to_float<T>(er[2]), to_float<T>(er[3]));
     } else {
       acc = *reinterpret_cast<const float4*>(xr + 4 * g);
@@ -156,13 +185,13 @@ __device__ __forceinline__ void resid_ln_body(const ResidLnArgs& a, int in_off) 
     if (nA + nB) add_partials(acc, a.partA, nA, a.partB, nB, a.part_stride, row * D + 4 * g);
     v[c] = acc;
   }
-  if (a.counter_inc && threadIdx.x == 0) a.counter_inc[i] += 1;
+  if (counter_inc && threadIdx.x == 0) counter_inc[i] += 1;
   float sum = 0.f;
 #pragma unroll
   for (int c = 0; c < VPT; ++c) {
     const bool live = (int)threadIdx.x + c * kLnThreads < G;
     if (live) {
-      if (a.write_x) *reinterpret_cast<float4*>(xr + 4 * (threadIdx.x + c * kLnThreads)) = v[c];
+      if (write_x) *reinterpret_cast<float4*>(xr + 4 * (threadIdx.x + c * kLnThreads)) = v[c];
       sum += (v[c].x + v[c].y) + (v[c].z + v[c].w);
     }
   }
@@ -187,7 +216,7 @@ __device__ __forceinline__ void resid_ln_body(const ResidLnArgs& a, int in_off) 
       else { g1 = *reinterpret_cast<const float4*>(a.g1 + 4 * g); b1 = *reinterpret_cast<const float4*>(a.b1 + 4 * g); }
       const float o1[4] = {n[0] * g1.x + b1.x, n[1] * g1.y + b1.y, n[2] * g1.z + b1.z, n[3] * g1.w + b1.w};
       const size_t o = (size_t)i * D + 4 * g;
-      if (a.u1_f32) {
+      if (u1_f32) {
         *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.u1) + o) = make_float4(o1[0], o1[1], o1[2], o1[3]);
       } else {
         store_act4<T>(reinterpret_cast<T*>(a.u1), o, a.lo_off, o1[0], o1[1], o1[2], o1[3]);
@@ -204,27 +233,36 @@ __device__ __forceinline__ void resid_ln_body(const ResidLnArgs& a, int in_off) 
 }
 
 template <class T, int VPT>
-__global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void resid_ln_kernel(ResidLnArgs a) {
-  resid_ln_body<T, VPT>(a, a.in_off);
+__global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void resid_ln_kernel(LnHot a) {
+  resid_ln_body<T, VPT, false>(a, LnCold{});
 }
-// The row offset inside each group of in_mul rows comes from device memory.
+// With the rarely used inputs: rows gathered from an embedding table, the per-sequence block
+// counters, per-row offsets from device memory.
 template <class T, int VPT>
-__global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void resid_ln_sel_kernel(ResidLnArgs a, const int* __restrict__ in_off_dev) {
-  resid_ln_body<T, VPT>(a, in_off_dev[blockIdx.x] - 1);
+__global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2))) void resid_ln_extra_kernel(LnHot a, LnCold c) {
+  resid_ln_body<T, VPT, true>(a, c);
 }
 
 template <class T>
-static hipError_t launch_resid_ln_t(const ResidLnArgs& a, hipStream_t s, const int* in_off_dev) {
-  const int G = a.D / 4;
+static hipError_t launch_resid_ln_t(const ResidLnArgs& r, hipStream_t s, const int* in_off_dev) {
+  const int G = r.D / 4;
   if (G > 4 * kLnThreads) return hipErrorInvalidValue;
-  if (in_off_dev) {
-    if (G <= kLnThreads) resid_ln_sel_kernel<T, 1><<<a.n_rows, kLnThreads, 0, s>>>(a, in_off_dev);
-    else if (G <= 2 * kLnThreads) resid_ln_sel_kernel<T, 2><<<a.n_rows, kLnThreads, 0, s>>>(a, in_off_dev);
-    else resid_ln_sel_kernel<T, 4><<<a.n_rows, kLnThreads, 0, s>>>(a, in_off_dev);
+  if (r.splitsA < 0 || r.splitsA > 0xfff || r.splitsB < 0 || r.splitsB > 0xfff || r.lo_off > 0xffffffffu) return hipErrorInvalidValue;
+  LnHot a;
+  a.x = r.x; a.partA = r.partA; a.partB = r.partB; a.biasA = r.biasA; a.biasB = r.biasB;
+  a.g1 = r.g1; a.b1 = r.b1; a.g2 = r.g2; a.b2 = r.b2; a.u1 = r.u1; a.u2 = r.u2;
+  a.part_stride = r.part_stride; a.lo_off = (unsigned)r.lo_off; a.D = r.D; a.in_mul = r.in_mul; a.in_off = r.in_off;
+  a.eps = r.eps;
+  a.packed = (unsigned)r.splitsA | (unsigned)r.splitsB << 12 | (r.u1_f32 ? 1u << 24 : 0u) | (r.write_x ? 1u << 25 : 0u);
+  if (r.emb_table || r.counter_inc || in_off_dev) {
+    const LnCold c{r.emb_table, r.emb_ids, r.counter_inc, in_off_dev, r.emb_stride, r.emb_off};
+    if (G <= kLnThreads) resid_ln_extra_kernel<T, 1><<<r.n_rows, kLnThreads, 0, s>>>(a, c);
+    else if (G <= 2 * kLnThreads) resid_ln_extra_kernel<T, 2><<<r.n_rows, kLnThreads, 0, s>>>(a, c);
+    else resid_ln_extra_kernel<T, 4><<<r.n_rows, kLnThreads, 0, s>>>(a, c);
   } else {
-    if (G <= kLnThreads) resid_ln_kernel<T, 1><<<a.n_rows, kLnThreads, 0, s>>>(a);
-    else if (G <= 2 * kLnThreads) resid_ln_kernel<T, 2><<<a.n_rows, kLnThreads, 0, s>>>(a);
-    else resid_ln_kernel<T, 4><<<a.n_rows, kLnThreads, 0, s>>>(a);
+    if (G <= kLnThreads) resid_ln_kernel<T, 1><<<r.n_rows, kLnThreads, 0, s>>>(a);
+    else if (G <= 2 * kLnThreads) resid_ln_kernel<T, 2><<<r.n_rows, kLnThreads, 0, s>>>(a);
+    else resid_ln_kernel<T, 4><<<r.n_rows, kLnThreads, 0, s>>>(a);
   }
   return hipGetLastError();
 }
