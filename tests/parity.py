@@ -123,9 +123,11 @@ def compare_sampled_with_oracle(cfg, weights, prompts_np, gpu_ids, gpu_logits, s
     """Oracle logits (plain definition, teacher-forced on the GPU's history) at the sampled steps."""
     import oracle.block_transformer as O
     seqs = list(seqs)
-    L, T_p = cfg.block_len, prompts_np.shape[1]
+    L = cfg.block_len
     P = O.Params(weights, keep=False)
-    hist = np.concatenate([prompts_np[seqs], gpu_ids[seqs]], axis=1).astype(np.int64)
+    padded = O.left_pad(cfg, prompts_np[seqs])           # no-op for whole blocks
+    T_p = padded.shape[1]
+    hist = np.concatenate([padded, gpu_ids[seqs]], axis=1).astype(np.int64)
     steps = sorted(gpu_logits)
     blocks = sorted({(T_p + t) // L for t in steps})
     tf = O.teacher_forced_logits(P, cfg, hist, blocks)

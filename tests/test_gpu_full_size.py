@@ -37,7 +37,7 @@ def full_size_case(amd, cfg, n_new, seqs, batch=None, prompt_len=None):
     m.close()
     print(f"[{cfg.name}] gpu {time.time() - t0:.1f}s  B={B} T_p={T} n_new={n_new}", flush=True)
     assert ids.min() >= 0 and ids.max() < cfg.vocab
-    n_p = T // cfg.block_len
+    n_p = -(-T // cfg.block_len)
     assert st.block_passes == n_p + -(-n_new // cfg.block_len) - 1
     assert st.token_passes == n_new
     t0 = time.time()
@@ -73,3 +73,16 @@ def test_cfg4v_vanilla_equivalent(amd):
     token makes the full 256 x 4096 cache 206 GB; the oracle pass is the other bound)."""
     cfg = CONFIGS["cfg4v"]
     full_size_case(amd, cfg, 64, [7], batch=8, prompt_len=512)
+
+
+def test_cfg1_model_long_context(amd):
+    """8K-token prompts on cfg1's model (the long-context setting of the paper's appendix on
+    context lengths): 2048 cached blocks per sequence after prefill."""
+    cfg = CONFIGS["cfg1"]
+    full_size_case(amd, cfg, 24, [0, 15], batch=16, prompt_len=8192)
+
+
+def test_cfg1_model_unaligned_no_prompt(amd):
+    """Full batch, one-token prompts (the setting without an input sequence): L_B - 1 pads."""
+    cfg = CONFIGS["cfg1"]
+    full_size_case(amd, cfg, 64, [0, cfg.batch - 1], prompt_len=1)

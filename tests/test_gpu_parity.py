@@ -403,3 +403,13 @@ def test_eos_rule_on_device(amd, dtype):
     m.bt_prefill(torch.from_numpy(prompts).to(m.device))
     assert int(m.bt_get_finished().sum()) == 0
     m.close()
+
+
+@pytest.mark.parametrize("p,lb", [(4, 4), (8, 4), (8, 8), (4, 16)])
+def test_bf16_prefix_length_sweep(amd, p, lb):
+    """Longer prefixes (the paper's prefix-length ablation, P up to 8); P + L_B - 1 local keys: up to
+    15 in registers, 19 through the LDS kernel."""
+    cfg = tiny_cfg(dtype="bf16", block_len=lb, prefix_len=p, d_model=128, n_heads=4, d_ff=256, vocab=300,
+                   prompt_len=3 * lb, n_block_layers=2, n_token_layers=2)
+    rep, st, _, _ = run_case(amd, cfg, 2 * lb + 2, batch=3)
+    assert st.local_kv_high_water == p + lb - 1
