@@ -66,7 +66,8 @@ def main():
     ap.add_argument("--gen-len", type=int, default=0, help="override the number of generated tokens (0 = the workload's)")
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--prompt-len", type=int, default=0, help="override the prompt length (0 = the workload's)")
-    ap.add_argument("--prefix-len", type=int, default=0, help="override P, the prefix length of the token decoder")
+    ap.add_argument("--prefix-len", type=int, default=-1, help="override P, the prefix length of the token decoder "
+                    "(0 only together with --block-len 1: the vanilla-equivalent run)")
     ap.add_argument("--block-len", type=int, default=0, help="override L_B (must divide the model width)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attn-events", action="store_true", help="skip the profiled pass that brackets the "
@@ -106,7 +107,7 @@ def main():
         cfg = cfg.with_(batch=args.batch)
     if args.prompt_len:
         cfg = cfg.with_(prompt_len=args.prompt_len)
-    if args.prefix_len:
+    if args.prefix_len >= 0:
         cfg = cfg.with_(prefix_len=args.prefix_len)
     if args.block_len:
         cfg = cfg.with_(block_len=args.block_len)
