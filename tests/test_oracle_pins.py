@@ -583,3 +583,34 @@ def test_eos_rule():
         assert np.all(ids[b, k:] == eos) and gen.finished[b]
         assert np.array_equal(lgs[b, :k + 1], lg_free[b, :k + 1])
     assert hits >= 1 and np.all(ids[0, 5:] == eos)
+
+
+# --------------------------------------------------------------------------
+# teacher-forced scoring (Sec. 2.1: all blocks in parallel)
+# --------------------------------------------------------------------------
+def test_score_nll_against_stepwise_definition_and_closed_forms():
+    cfg = tiny_cfg(block_len=4, prefix_len=2, d_model=32, n_heads=2, prompt_len=12, vocab=19)
+    W = make_weights(cfg)
+    P = O.Params(W)
+    toks = make_prompts(cfg, batch=2)
+    nll = O.score_nll(P, cfg, toks)
+    assert nll.shape == (2, 12) and np.all(nll[:, :4] == 0.0) and np.all(nll[:, 4:] > 0.0)
+    # position by position from the one-step definition, softmax written out with math.log / math.exp
+    for t in (4, 5, 7, 8, 11):
+        lg = O.next_token_logits_full(P, cfg, toks[:, :t])
+        for b in range(2):
+            z = [float(v) for v in lg[b]]
+            den = sum(math.exp(v - max(z)) for v in z)
+            want = -(z[int(toks[b, t])] - max(z) - math.log(den))
+            assert abs(nll[b, t] - want) < 1e-12
+    # a head of zeros gives the uniform distribution: nll = log V everywhere
+    W0 = dict(W)
+    W0["W_head"] = np.zeros_like(W["W_head"])
+    assert np.allclose(O.score_nll(O.Params(W0), cfg, toks)[:, 4:], math.log(19), atol=1e-12)
+    # probabilities of one position sum to one when the target runs over the vocabulary
+    base = toks[:1].copy()
+    tot = 0.0
+    for v in range(19):
+        base[0, 6] = v
+        tot += math.exp(-O.score_nll(P, cfg, base)[0, 6])
+    assert abs(tot - 1.0) < 1e-12
