@@ -80,6 +80,9 @@ typedef struct {
   int32_t pad_id;           /* token id that fills, from the left, the first block of a prompt whose
                                length is not a multiple of L_B (App. "Random length padding"; the
                                paper does not name the id); 0 <= pad_id < vocab */
+  int32_t score_rows;       /* 0: no scoring support.  > 0: bt_score may be called; it runs the LM head
+                               over this many rows at a time (workspace: score_rows * vocab floats,
+                               plus local KV for every block of a prefill chunk) */
   int32_t eos_id;           /* -1: none.  Otherwise a sequence that has emitted this id emits it at
                                every later step as well (the paper generates a fixed number of
                                tokens and states no stopping rule; the batch is static, so a finished
@@ -193,6 +196,20 @@ int bt_prefill_ragged(bt_model *m, const int32_t *tokens_dev, const int32_t *len
  * Errors: BT_ERR_STATE before prefill or if batch differs from the prefill's;
  * BT_ERR_CAPACITY if the step needs a block slot >= max_blocks. */
 int bt_decode_step(bt_model *m, int32_t batch, int32_t *next_ids_dev);
+
+/* Teacher-forced scoring (Sec. 2.1, Fig. 1: block decoder and token decoder over
+ * all blocks of a sequence at once; the token decoder sees each block as an
+ * independent sequence of prefix_len + L_B - 1 rows).  tokens_dev: int32
+ * [batch, len] row-major, device; len a multiple of L_B, at least 2 L_B.
+ * nll_dev: float [batch, len], device; entry t >= L_B receives
+ * -log p(x_t | x_<t), the log-softmax of the logits the generation step would
+ * produce at that position given the same history; the first block has no
+ * context embedding and gets 0.  Needs cfg.score_rows > 0 and prefix_len >= 1.
+ * Overwrites the block KV cache: any generation in progress is lost (a new
+ * bt_prefill is needed before bt_decode_step).  Errors: BT_ERR_ARG (null,
+ * sizes), BT_ERR_STATE (score_rows == 0), BT_ERR_CAPACITY (len / L_B >
+ * max_blocks, or one sequence's rows exceed the workspace), BT_ERR_HIP. */
+int bt_score(bt_model *m, const int32_t *tokens_dev, int32_t batch, int32_t len, float *nll_dev);
 
 /* End-of-sequence flags (for callers that stop early; no passage of the paper:
  * it times a fixed number of generated tokens).  flags_dev: int32 [batch],

@@ -27,7 +27,7 @@ class bt_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "vocab", "block_len", "d_model", "n_heads", "d_ff", "n_block_layers", "n_token_layers",
         "prefix_len", "dtype", "max_batch", "max_blocks", "rotary_dims", "parallel_residual",
-        "prefill_rows", "act_split", "use_graphs", "pad_id", "eos_id")] + [("ln_eps", C.c_float)]
+        "prefill_rows", "act_split", "use_graphs", "pad_id", "score_rows", "eos_id")] + [("ln_eps", C.c_float)]
 
 
 _LAYER_FIELDS = ("ln1_g", "ln1_b", "W_qkv", "b_qkv", "W_o", "b_o", "ln2_g", "ln2_b", "W_up", "b_up", "W_down", "b_down")
@@ -61,6 +61,7 @@ lib.bt_prefill_ragged.argtypes = [_P, _P, C.POINTER(C.c_int32), C.c_int32, C.c_i
 lib.bt_decode_step.argtypes = [_P, C.c_int32, _P]
 lib.bt_get_logits.argtypes = [_P, _P]
 lib.bt_get_finished.argtypes = [_P, _P]
+lib.bt_score.argtypes = [_P, _P, C.c_int32, C.c_int32, _P]
 lib.bt_force_last_ids.argtypes = [_P, _P]
 lib.bt_get_context.argtypes = [_P, _P]
 lib.bt_set_context.argtypes = [_P, _P]
@@ -73,7 +74,7 @@ lib.bt_destroy.argtypes = [_P]
 lib.bt_destroy.restype = None
 lib.bt_embed.argtypes = [_P, _P, C.c_int32, _P]
 for _f in ("bt_workspace_bytes", "bt_create", "bt_prefill", "bt_prefill_ragged", "bt_decode_step", "bt_get_logits",
-           "bt_get_finished", "bt_force_last_ids",
+           "bt_get_finished", "bt_score", "bt_force_last_ids",
            "bt_get_context", "bt_set_context", "bt_set_profile", "bt_reset_profile", "bt_get_stats", "bt_embed"):
     getattr(lib, _f).restype = C.c_int
 
@@ -87,7 +88,8 @@ class BTError(RuntimeError):
 DEFAULT_ACT_SPLIT = int(os.environ.get("BT_ACT_SPLIT", "2"))
 
 
-def make_config(cfg, max_batch=None, max_blocks=None, prefill_rows=0, act_split=None, use_graphs=1) -> bt_config:
+def make_config(cfg, max_batch=None, max_blocks=None, prefill_rows=0, act_split=None, use_graphs=1,
+                score_rows=0) -> bt_config:
     """cfg: any object with the fields of synth.BTConfig."""
     return bt_config(
         vocab=cfg.vocab, block_len=cfg.block_len, d_model=cfg.d_model, n_heads=cfg.n_heads, d_ff=cfg.d_ff,
@@ -98,19 +100,19 @@ def make_config(cfg, max_batch=None, max_blocks=None, prefill_rows=0, act_split=
         rotary_dims=cfg.rot, parallel_residual=cfg.parallel_residual, prefill_rows=prefill_rows,
         act_split=DEFAULT_ACT_SPLIT if act_split is None else act_split,
         use_graphs=int(use_graphs) if "BT_USE_GRAPHS" not in os.environ else int(os.environ["BT_USE_GRAPHS"]),
-        pad_id=getattr(cfg, "pad_id", 0), eos_id=getattr(cfg, "eos_id", -1), ln_eps=cfg.ln_eps)
+        pad_id=getattr(cfg, "pad_id", 0), score_rows=score_rows, eos_id=getattr(cfg, "eos_id", -1), ln_eps=cfg.ln_eps)
 
 
 class Model:
     """Owns the device copies of the weights and the workspace; forwards to the C ABI."""
 
     def __init__(self, cfg, weights, max_batch=None, max_blocks=None, prefill_rows=0, act_split=None,
-                 use_graphs=1, device="cuda:0"):
+                 use_graphs=1, score_rows=0, device="cuda:0"):
         import torch
         self.torch = torch
         self.device = torch.device(device)
         self.cfg = cfg
-        self.c = make_config(cfg, max_batch, max_blocks, prefill_rows, act_split, use_graphs)
+        self.c = make_config(cfg, max_batch, max_blocks, prefill_rows, act_split, use_graphs, score_rows)
         self._keep = {}
         for name, arr in weights.items():
             a = np.ascontiguousarray(arr)
@@ -176,6 +178,13 @@ class Model:
         lg = self.torch.empty(self.batch, self.cfg.vocab, dtype=self.torch.float32, device=self.device)
         self._chk(lib.bt_get_logits(self.h, lg.data_ptr()))
         return lg
+
+    def bt_score(self, tokens):
+        """tokens: int32 cuda tensor [batch, len]; returns float32 [batch, len] negative log-likelihoods."""
+        assert tokens.dtype == self.torch.int32 and tokens.is_cuda and tokens.is_contiguous()
+        nll = self.torch.empty(tokens.shape, dtype=self.torch.float32, device=self.device)
+        self._chk(lib.bt_score(self.h, tokens.data_ptr(), tokens.shape[0], tokens.shape[1], nll.data_ptr()))
+        return nll
 
     def bt_get_finished(self):
         fl = self.torch.empty(self.batch, dtype=self.torch.int32, device=self.device)

@@ -23,7 +23,7 @@ constexpr int kSkinnyRows = 256;     // GEMMs with at most this many rows may sp
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct Layout {
-  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cand, cur, state, lens, fin, frag, total;
+  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cand, cur, state, lens, fin, score_kv, score_logits, frag, total;
   size_t blk_layer_stride, loc_layer_stride;   // bytes between layers (K then V inside)
   size_t part_elems;                           // floats in each of part_o, part_d
   size_t qkv_elems, part_u_elems;              // floats in qkv (may hold split-K pieces) and part_u
@@ -51,6 +51,7 @@ int check_config(const bt_config& c, std::string* why) {
   if (c.use_graphs < 0 || c.use_graphs > 1) return bad("use_graphs must be 0 or 1");
   if (c.pad_id < 0 || c.pad_id >= c.vocab) return bad("pad_id outside the vocabulary");
   if (c.eos_id < -1 || c.eos_id >= c.vocab) return bad("eos_id must be -1 (none) or a vocabulary id");
+  if (c.score_rows < 0) return bad("score_rows < 0");
   if (!(c.ln_eps >= 0.f)) return bad("ln_eps < 0");
   const int l_cap = (c.prefix_len > 0 ? c.prefix_len : 1) + c.block_len;
   if ((size_t)(2 * l_cap + 2) * dh * sizeof(float) > 60 * 1024) return bad("prefix_len + block_len too large for the local-attention kernel");
@@ -64,8 +65,11 @@ void make_layout(const bt_config& c, Layout& L) {
   L.l_cap = L.n_pref + c.block_len;
   L.rope_len = c.max_blocks > L.l_cap ? c.max_blocks : L.l_cap;
   size_t pr = c.prefill_rows > 0 ? c.prefill_rows : kDefaultPrefillRows;
-  if (pr < (size_t)c.max_blocks) pr = c.max_blocks;
-  if (pr > B * (size_t)c.max_blocks) pr = B * (size_t)c.max_blocks;
+  // rows one sequence needs at once: its blocks (prefill), times the token-decoder rows per block when
+  // the model also scores whole sequences
+  const size_t per_seq = (size_t)c.max_blocks * (c.score_rows > 0 ? L.n_pref + c.block_len - 1 : 1);
+  if (pr < per_seq) pr = per_seq;
+  if (pr > B * per_seq) pr = B * per_seq;
   size_t m_rows = pr;
   if (m_rows < B * L.n_pref) m_rows = B * L.n_pref;
   L.m_rows = (int)m_rows;
@@ -102,6 +106,14 @@ void make_layout(const bt_config& c, Layout& L) {
   L.state = take(B * 4);       // cached blocks per sequence (device-side counters)
   L.lens = take(B * 4);        // prompt lengths of the last prefill
   L.fin = take(B * 4);         // per sequence: has emitted eos_id
+  // teacher-forced scoring (score_rows > 0): the local KV of every block scored in one chunk (one
+  // layer's worth, re-used by all layers) and the logits of score_rows rows at a time
+  L.score_kv = L.score_logits = off;
+  if (c.score_rows > 0) {
+    const size_t lq = L.n_pref + c.block_len - 1;
+    L.score_kv = take(2 * (m_rows / lq + 1) * H * L.l_cap * dh * L.esz);
+    L.score_logits = take((size_t)c.score_rows * c.vocab * 4);
+  }
   // bf16 mode: a second copy of every GEMM weight in MFMA fragment order, read by the decode GEMMs
   L.frag = off;
   if (c.dtype == BT_BF16) {
@@ -203,6 +215,11 @@ struct StackArgs {
   int* counter_inc = nullptr;
   // Optional: the final LayerNorm's row i is i * in_mul + fin_off_dev[i] - 1 (device memory).
   const int* fin_off_dev = nullptr;
+  // Optional: where the final LayerNorm's remainder plane goes (elements after its output; 0: the default).
+  size_t fin_lo_off = 0;
+  // Optional (MODE_TOKEN): local K (then V at +loc_half bytes) of `batch` sequences, shared by all layers.
+  char* loc_base = nullptr;
+  size_t loc_half = 0;
 };
 
 // Final LayerNorm of a stack on row (i*in_mul + in_off) of x, for i < n.
@@ -210,7 +227,8 @@ int final_ln(bt_model* m, const StackArgs& a, const float* pendO, const float* b
              const float* pendD, const float* biasD, int sD, const void* g, const void* b,
              void* out, int out_f32, int n, int in_mul, int in_off) {
   ResidLnArgs r{};
-  r.lo_off = (!out_f32 && m->cfg.dtype == BT_BF16 && m->cfg.act_split >= 1) ? (size_t)m->cfg.max_batch * m->cfg.d_model : 0;
+  r.lo_off = (!out_f32 && m->cfg.dtype == BT_BF16 && m->cfg.act_split >= 1)
+                 ? (a.fin_lo_off ? a.fin_lo_off : (size_t)m->cfg.max_batch * m->cfg.d_model) : 0;
   r.x = m->at<float>(m->L.x);
   r.partA = pendO; r.biasA = biasO; r.splitsA = sO;
   r.partB = pendD; r.biasB = biasD; r.splitsB = sD;
@@ -302,8 +320,8 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
   auto attention = [&](int l, const GeluJob& gelu) -> int {
     const PartialSrc qsrc{qkv, pieces ? (const float*)lw[l].b_qkv : nullptr, sQ, (size_t)M * 3 * D};
     if (a.mode == MODE_TOKEN) {
-      char* base = m->ws + L.loc_kv + (size_t)l * L.loc_layer_stride;
-      const size_t half = (size_t)c.max_batch * H * L.l_cap * dh * L.esz;
+      char* base = a.loc_base ? a.loc_base : m->ws + L.loc_kv + (size_t)l * L.loc_layer_stride;
+      const size_t half = a.loc_base ? a.loc_half : (size_t)c.max_batch * H * L.l_cap * dh * L.esz;
       BT_HIP(m, launch_attn_local(dt, qsrc, base, base + half, rope, ao, loD, a.batch, H, dh, c.rotary_dims,
                                   a.rows, a.pos0, L.l_cap, gelu, s));
       return BT_OK;
@@ -717,6 +735,71 @@ int bt_embed(bt_model* m, const int32_t* tokens_dev, int32_t n_rows, float* out_
   BT_HIP(m, launch_embed_concat(m->cfg.dtype, m->w.E_emb, tokens_dev, out_dev, n_rows, 1, m->cfg.block_len,
                                 m->cfg.d_model / m->cfg.block_len, m->cfg.block_len, m->cfg.block_len, nullptr,
                                 m->cfg.pad_id, m->stream));
+  return BT_OK;
+}
+
+int bt_score(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t len, float* nll_dev) {
+  if (!m) return BT_ERR_ARG;
+  const bt_config& c = m->cfg;
+  const Layout& L = m->L;
+  if (!tokens_dev || !nll_dev) return fail(m, BT_ERR_ARG, "tokens_dev or nll_dev is null");
+  if (c.score_rows < 1) return fail(m, BT_ERR_STATE, "the model was created with score_rows == 0");
+  if (c.prefix_len < 1) return fail(m, BT_ERR_ARG, "scoring needs prefix_len >= 1");
+  if (c.d_ff < c.d_model) return fail(m, BT_ERR_ARG, "scoring needs d_ff >= d_model");   // the context rows borrow the MLP buffer
+  if (batch < 1 || batch > c.max_batch) return fail(m, BT_ERR_ARG, "batch out of range");
+  if (len < 2 * c.block_len || len % c.block_len) return fail(m, BT_ERR_ARG, "len must be a multiple of block_len, two blocks or more");
+  const int N = len / c.block_len, P = c.prefix_len, D = c.d_model, H = c.n_heads, dh = D / H;
+  if (N > c.max_blocks) return fail(m, BT_ERR_CAPACITY, "more blocks than max_blocks");
+  const int Lq = P + c.block_len - 1;
+  const int per = L.m_rows / (N * Lq);          // sequences per chunk: all their token-decoder rows fit the workspace
+  if (per < 1) return fail(m, BT_ERR_CAPACITY, "workspace rows < blocks * (prefix_len + block_len - 1)");
+  hipStream_t s = m->stream;
+  m->batch = 0;                                 // the block KV cache is overwritten: any generation state is gone
+  m->have_context = false;
+  drop_graphs(m);
+  BT_HIP(m, hipMemsetAsync(nll_dev, 0, (size_t)batch * len * sizeof(float), s));
+  const bool lo_planes = c.dtype == BT_BF16 && c.act_split >= 1;
+  const size_t loD = lo_planes ? (size_t)L.m_rows * D : 0;
+  float* x = m->at<float>(L.x);
+  char* ctx_all = m->ws + L.hmid;               // free once the block stack's last GEMM has read it
+  float* pref = m->at<float>(L.part_o);         // free after the stack's final LayerNorm
+  char* h_all = m->ws + L.u1;                   // final hidden rows of the token decoder
+  for (int b0 = 0; b0 < batch; b0 += per) {
+    const int bc = batch - b0 < per ? batch - b0 : per;
+    const int32_t* toks = tokens_dev + (size_t)b0 * len;
+    // block decoder over all blocks; its final LayerNorm keeps every row: context j serves block j + 1
+    BT_HIP(m, launch_embed_concat(c.dtype, m->w.E_emb, toks, x, bc, N, c.block_len, D / c.block_len, len, len, nullptr,
+                                  c.pad_id, s));
+    StackArgs ab{MODE_BLOCK_PREFILL, bc * N, bc, b0, N, 0};
+    ab.fin_lo_off = loD;
+    int rc = run_stack(m, m->blk.data(), c.n_block_layers, ab, m->w.blk_lnf_g, m->w.blk_lnf_b, ctx_all, 0, bc * N, 1, 0);
+    if (rc) return rc;
+    GemmProblem pp{ctx_all, m->w.W_prefix, (const float*)m->w.b_prefix, pref, bc * N, P * D, D, D, P * D, EPI_F32,
+                   lo_planes ? ctx_all + loD * 2 : nullptr, 0, m->prefix_frag};
+    GemmPlan pl{};
+    BT_HIP(m, gemm_plan(c.dtype, &pp, 1, &pl));
+    BT_HIP(m, launch_gemm(c.dtype, &pp, 1, pl, s));
+    // token decoder over bc * (N - 1) independent local sequences of Lq rows
+    BT_HIP(m, launch_score_assemble(c.dtype, pref, m->w.E_tok, toks, x, bc, N, len, D, P, c.block_len, s));
+    const int n_loc = bc * (N - 1), rows = n_loc * Lq;
+    StackArgs at{MODE_TOKEN, rows, n_loc, 0, Lq, 0};
+    at.fin_lo_off = loD;
+    at.loc_base = m->ws + L.score_kv;
+    at.loc_half = (size_t)n_loc * H * L.l_cap * dh * L.esz;
+    rc = run_stack(m, m->tok.data(), c.n_token_layers, at, m->w.tok_lnf_g, m->w.tok_lnf_b, h_all, 0, rows, 1, 0);
+    if (rc) return rc;
+    // LM head and log-softmax, score_rows rows at a time
+    for (int r0 = 0; r0 < rows; r0 += c.score_rows) {
+      const int rc_rows = rows - r0 < c.score_rows ? rows - r0 : c.score_rows;
+      GemmProblem ph{h_all + (size_t)r0 * D * L.esz, m->w.W_head, nullptr, m->ws + L.score_logits, rc_rows, c.vocab, D, D,
+                     c.vocab, EPI_F32, lo_planes ? h_all + (loD + (size_t)r0 * D) * 2 : nullptr, 0, m->head_frag};
+      GemmPlan ph_plan{};
+      BT_HIP(m, gemm_plan(c.dtype, &ph, 1, &ph_plan));
+      BT_HIP(m, launch_gemm(c.dtype, &ph, 1, ph_plan, s));
+      BT_HIP(m, launch_score_rows(m->at<float>(L.score_logits), rc_rows, c.vocab, r0, toks, nll_dev + (size_t)b0 * len,
+                                  P, c.block_len, N, len, s));
+    }
+  }
   return BT_OK;
 }
 

@@ -414,6 +414,85 @@ hipError_t launch_gather_ids(const int32_t* cur, int32_t* out, int batch, int bl
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Teacher-forced scoring (Sec. 2.1, all blocks in parallel).  Local sequence s = bl * (N - 1) + j
+// scores block j + 1 of sequence bl of the chunk from the context embedding of block j; it has
+// Lq = P + L_B - 1 rows: the P prefix rows, then the block's first L_B - 1 token embeddings.
+// ---------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(256) void score_assemble_kernel(const float* __restrict__ pref, const T* __restrict__ E_tok,
+                                                             const int32_t* __restrict__ tokens, float* __restrict__ x,
+                                                             int D, int P, int block_len, int n_blocks, int seq_len) {
+  const int Lq = P + block_len - 1;
+  const int row = blockIdx.x;
+  const int s = row / Lq, pos = row - s * Lq;
+  const int bl = s / (n_blocks - 1), j = s - bl * (n_blocks - 1);
+  float* dst = x + (size_t)row * D;
+  if (pos < P) {
+    const float* src = pref + ((size_t)(bl * n_blocks + j) * P + pos) * D;
+    for (int i = threadIdx.x * 4; i < D; i += 1024) *reinterpret_cast<float4*>(dst + i) = *reinterpret_cast<const float4*>(src + i);
+  } else {
+    const int tok = tokens[(size_t)bl * seq_len + (j + 1) * block_len + (pos - P)];
+    const T* src = E_tok + (size_t)tok * D;
+    for (int i = threadIdx.x * 4; i < D; i += 1024)
+      *reinterpret_cast<float4*>(dst + i) = make_float4(to_float<T>(src[i]), to_float<T>(src[i + 1]), to_float<T>(src[i + 2]), to_float<T>(src[i + 3]));
+  }
+}
+
+hipError_t launch_score_assemble(int dtype, const float* pref, const void* E_tok, const int32_t* tokens, float* x,
+                                 int n_seqs, int n_blocks, int seq_len, int D, int P, int block_len, hipStream_t s) {
+  const int rows = n_seqs * (n_blocks - 1) * (P + block_len - 1);
+  if (rows <= 0) return hipSuccess;
+  if (D % 4 || P < 1 || n_blocks < 2) return hipErrorInvalidValue;
+  if (dtype == BT_F32)
+    score_assemble_kernel<float><<<rows, 256, 0, s>>>(pref, (const float*)E_tok, tokens, x, D, P, block_len, n_blocks, seq_len);
+  else
+    score_assemble_kernel<bf16_t><<<rows, 256, 0, s>>>(pref, (const bf16_t*)E_tok, tokens, x, D, P, block_len, n_blocks, seq_len);
+  return hipGetLastError();
+}
+
+// One workgroup per logits row: nll = log(sum exp(z - max)) + max - z[target].  Rows at the first
+// P - 1 prefix positions predict nothing and are skipped.
+__global__ __launch_bounds__(1024) void score_rows_kernel(const float* __restrict__ logits, int vocab, int row0,
+                                                          const int32_t* __restrict__ tokens, float* __restrict__ nll,
+                                                          int P, int block_len, int n_blocks, int seq_len) {
+  __shared__ float red[16];
+  const int Lq = P + block_len - 1;
+  const int row = row0 + blockIdx.x;
+  const int s = row / Lq, pos = row - s * Lq;
+  if (pos < P - 1) return;
+  const int bl = s / (n_blocks - 1), j = s - bl * (n_blocks - 1);
+  const size_t t = (size_t)bl * seq_len + (j + 1) * block_len + (pos - (P - 1));
+  const float* z = logits + (size_t)blockIdx.x * vocab;
+  float mx = -INFINITY;
+  for (int v = threadIdx.x; v < vocab; v += 1024) mx = fmaxf(mx, z[v]);
+  mx = wave_max(mx);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  mx = red[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) mx = fmaxf(mx, red[w]);
+  __syncthreads();
+  float sum = 0.f;
+  for (int v = threadIdx.x; v < vocab; v += 1024) sum += expf(z[v] - mx);
+  sum = wave_sum(sum);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += red[w];
+    nll[t] = logf(tot) + mx - z[tokens[t]];
+  }
+}
+
+hipError_t launch_score_rows(const float* logits, int n_rows, int vocab, int row0, const int32_t* tokens, float* nll,
+                             int P, int block_len, int n_blocks, int seq_len, hipStream_t s) {
+  if (n_rows <= 0) return hipSuccess;
+  score_rows_kernel<<<n_rows, 1024, 0, s>>>(logits, vocab, row0, tokens, nll, P, block_len, n_blocks, seq_len);
+  return hipGetLastError();
+}
+
 __global__ void state_set_kernel(int* p, int value, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = value;

@@ -74,6 +74,19 @@ hipError_t launch_state_set(int* p, int value, int n, hipStream_t s);
 // n_blocks[i] = ceil(lens[i] / block_len) for i < n
 hipError_t launch_seq_blocks(const int* lens, int* n_blocks, int block_len, int n, hipStream_t s);
 
+// Teacher-forced scoring (Sec. 2.1: every block of a sequence at once).  A chunk holds n_seqs
+// sequences of n_blocks blocks; local sequence s = bl * (n_blocks - 1) + j scores block j + 1 of
+// sequence bl from the context embedding of block j and has Lq = P + L_B - 1 rows.
+// assemble: x[s * Lq + p] = pref[(bl * n_blocks + j), p * D ...] for p < P (prefix rows, float), then
+// E_tok[tokens[bl * seq_len + (j + 1) * L_B + k]] for k < L_B - 1.  tokens: the chunk's first row.
+hipError_t launch_score_assemble(int dtype, const float* pref, const void* E_tok, const int32_t* tokens, float* x,
+                                 int n_seqs, int n_blocks, int seq_len, int D, int P, int block_len, hipStream_t s);
+// logits [n_rows, vocab] of the chunk's rows row0 .. row0 + n_rows - 1 (row = s * Lq + pos).  Rows with
+// pos >= P - 1 predict token k = pos - (P - 1) of their block: nll[bl * seq_len + (j + 1) * L_B + k] =
+// log sum exp(logits) - logits[that token].  tokens, nll: the chunk's first row.
+hipError_t launch_score_rows(const float* logits, int n_rows, int vocab, int row0, const int32_t* tokens, float* nll,
+                             int P, int block_len, int n_blocks, int seq_len, hipStream_t s);
+
 // ----------------------------------------------------------------------- GEMM
 enum { EPI_F32 = 0,        // out float [M, ldo]: acc + bias
        EPI_GELU = 1,       // out storage dtype: gelu(acc + bias)

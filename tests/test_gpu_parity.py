@@ -413,3 +413,57 @@ def test_bf16_prefix_length_sweep(amd, p, lb):
                    prompt_len=3 * lb, n_block_layers=2, n_token_layers=2)
     rep, st, _, _ = run_case(amd, cfg, 2 * lb + 2, batch=3)
     assert st.local_kv_high_water == p + lb - 1
+
+
+@pytest.mark.parametrize("dtype,lb,p,T,B,score_rows", [
+    ("fp32", 4, 1, 12, 2, 7),            # skinny GEMMs, logits in chunks of 7 rows
+    ("fp32", 4, 2, 24, 3, 64),
+    ("bf16", 4, 1, 48, 5, 100),
+    ("bf16", 8, 2, 320, 4, 500),         # 40 blocks: tiled GEMMs in both decoders
+    ("bf16", 2, 1, 300, 3, 4096),        # 150 blocks: matrix-core prefill attention
+])
+def test_teacher_forced_scoring(amd, dtype, lb, p, T, B, score_rows):
+    """bt_score against the oracle's score_nll (Sec. 2.1: all blocks in parallel), and against the
+    log-softmax of the logits the generation path itself produces for the same history."""
+    import oracle.block_transformer as O
+    import torch
+    cfg = tiny_cfg(dtype=dtype, block_len=lb, prefix_len=p, d_model=128, n_heads=4, d_ff=256, vocab=211,
+                   prompt_len=T, n_block_layers=2, n_token_layers=2)
+    W = make_weights(cfg)
+    toks = make_prompts(cfg, batch=B)
+    m = amd.Model(cfg, W, max_batch=B, max_blocks=T // lb + 2, score_rows=score_rows)
+    nll = m.bt_score(torch.from_numpy(toks).to(m.device)).cpu().numpy()
+    want = O.score_nll(O.Params(W), cfg, toks)
+    tol = 2 * (TOL_F32 if dtype == "fp32" else TOL_BF16)     # |d lse| <= max |d logit|, plus the target's own logit
+    assert np.all(nll[:, :lb] == 0.0)
+    assert np.abs(nll - want).max() <= tol, np.abs(nll - want).max()
+    # scoring leaves no generation state behind; the model generates again after a prefill,
+    # and the last scored position equals the generation step's own distribution
+    ids = torch.zeros(B, dtype=torch.int32, device=m.device)
+    assert amd.lib.bt_decode_step(m.h, B, ids.data_ptr()) == -2
+    m.bt_prefill(torch.from_numpy(np.ascontiguousarray(toks[:, :T - lb])).to(m.device))
+    m.bt_decode_step()
+    lg = m.bt_get_logits().double().cpu().numpy()
+    lse = np.log(np.exp(lg - lg.max(axis=1, keepdims=True)).sum(axis=1)) + lg.max(axis=1)
+    step_nll = lse - lg[np.arange(B), toks[:, T - lb]]
+    assert np.abs(step_nll - nll[:, T - lb]).max() <= (1e-4 if dtype == "fp32" else 2e-2)
+    m.close()
+
+
+def test_scoring_needs_configuration(amd):
+    import torch
+    cfg = tiny_cfg(d_model=64, n_heads=2, d_ff=128, vocab=64, block_len=4, prefix_len=1, prompt_len=8)
+    W = make_weights(cfg)
+    toks = torch.zeros(2, 8, dtype=torch.int32, device="cuda")
+    out = torch.zeros(2, 8, dtype=torch.float32, device="cuda")
+    m = amd.Model(cfg, W, max_batch=2, max_blocks=3)
+    assert amd.lib.bt_score(m.h, toks.data_ptr(), 2, 8, out.data_ptr()) == -2          # score_rows == 0
+    m.close()
+    m = amd.Model(cfg, W, max_batch=2, max_blocks=3, score_rows=16)
+    assert amd.lib.bt_score(m.h, toks.data_ptr(), 2, 6, out.data_ptr()) == -1          # not whole blocks
+    assert amd.lib.bt_score(m.h, toks.data_ptr(), 2, 4, out.data_ptr()) == -1          # a single block: nothing to score
+    assert amd.lib.bt_score(m.h, toks.data_ptr(), 3, 8, out.data_ptr()) == -1          # batch > max_batch
+    assert amd.lib.bt_score(m.h, toks.data_ptr(), 2, 16, out.data_ptr()) == -3         # more blocks than max_blocks
+    assert amd.lib.bt_score(m.h, toks.data_ptr(), 2, 8, out.data_ptr()) == 0
+    torch.cuda.synchronize()
+    m.close()
