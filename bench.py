@@ -57,6 +57,79 @@ def cpu_baseline(cfg, W, prompts, budget_s=12.0):
     }
 
 
+def score_bench(args, cfg, W):
+    """Teacher-forced scoring of batch x (prompt_len + gen_len) tokens; one JSON line."""
+    import numpy as np
+    import torch
+    from synth import make_prompts
+    import paper_2406_02657_amd as amd
+    T = (cfg.prompt_len + cfg.gen_len) // cfg.block_len * cfg.block_len
+    toks_np = make_prompts(cfg, prompt_len=T)
+    model = amd.Model(cfg, W, max_blocks=T // cfg.block_len, score_rows=4096)
+    toks = torch.from_numpy(toks_np).cuda()
+    log(f"scoring {cfg.batch} x {T} tokens; workspace {model.workspace_bytes / 2**30:.2f} GiB")
+    for _ in range(args.warmup):
+        model.bt_score(toks)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        model.bt_score(toks)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    model.bt_set_profile(True)
+    model.bt_reset_profile()
+    nll = model.bt_score(toks)
+    torch.cuda.synchronize()
+    st = model.bt_get_stats()
+    model.bt_set_profile(False)
+    scored = cfg.batch * (T - cfg.block_len)
+    ms = wall * 1e3 / args.steps
+    planes = 2 if cfg.dtype == "bf16" else 1
+    flops = float(st.gemm_tiled_flops) * planes
+    tfl = flops / (st.gemm_tiled_ms * 1e-3) / 1e12 if st.gemm_tiled_ms > 0 else 0.0
+    peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else 157.3
+    res = {
+        "metric": "scored tokens/sec on 1 MI355X (teacher-forced)", "value": scored / (ms / 1e3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name} model, scoring", "batch": cfg.batch, "len": T, "block_len": cfg.block_len,
+                   "d_model": cfg.d_model, "layers": [cfg.n_block_layers, cfg.n_token_layers],
+                   "prefix_len": cfg.prefix_len, "vocab": cfg.vocab},
+        "mean_nll": float(nll[:, cfg.block_len:].mean()),
+        "roofline": {
+            "kernel": "tiled MFMA GEMM launches of the pass (gemm_bf16_big_kernel, 256 x 256 tiles: token-decoder layers "
+                      "and LM head; gemm_bf16_kernel<128,128>: block-decoder layers of a chunk)",
+            "events": "one extra pass after the timed ones", "bound": "mfma", "achieved": tfl, "peak": peak,
+            "unit": "TFLOP/s", "frac": tfl / peak, "traffic": None,
+            "launches": int(st.gemm_tiled_launches),
+            "avg_launch_us": st.gemm_tiled_ms * 1e3 / max(int(st.gemm_tiled_launches), 1),
+            "algorithmic_tflops": tfl / planes,
+            "note": "achieved = 2 x rows x N x K x activation planes (bf16 hi + remainder), the multiplies the matrix "
+                    "cores execute; algorithmic_tflops counts one plane",
+        },
+        "cpu_baseline": None,
+    }
+    model.close()
+    del model
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        import oracle.block_transformer as O
+        n_tok = min(T, 32 * cfg.block_len)
+        P = O.Params(W, keep=False)
+        t0 = time.perf_counter()
+        O.score_nll(P, cfg, toks_np[:1, :n_tok].astype(np.int64))
+        dt = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        res["cpu_baseline"] = {"value": (n_tok - cfg.block_len) / dt, "unit": "tokens/s", "cores": int(cores),
+                               "kind": "oracle", "sample": f"score_nll of one sequence of {n_tok} tokens ({dt:.1f} s, "
+                               "includes widening the weights to f64)"}
+    print(json.dumps(res))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,6 +142,9 @@ def main():
     ap.add_argument("--prefix-len", type=int, default=-1, help="override P, the prefix length of the token decoder "
                     "(0 only together with --block-len 1: the vanilla-equivalent run)")
     ap.add_argument("--block-len", type=int, default=0, help="override L_B (must divide the model width)")
+    ap.add_argument("--score", action="store_true",
+                    help="time teacher-forced scoring (bt_score) of batch x (prompt + generated) tokens instead of "
+                         "generation; a step is one scoring pass over the whole batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attn-events", action="store_true", help="skip the profiled pass that brackets the "
                     "block-attention launches with HIP events (no roofline object)")
@@ -115,6 +191,9 @@ def main():
         f"D={cfg.d_model} layers={cfg.n_block_layers}+{cfg.n_token_layers} P={cfg.prefix_len} dtype={cfg.dtype}")
     t0 = time.perf_counter()
     W = make_weights(cfg)
+    if args.score:
+        score_bench(args, cfg, W)
+        return
     prompts = make_prompts(cfg)
     log(f"inputs generated in {time.perf_counter() - t0:.1f} s")
     model = amd.Model(cfg, W)

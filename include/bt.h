@@ -133,6 +133,11 @@ typedef struct {
   double  gemm_decode_ms;
   int64_t gemm_decode_launches;
   int64_t gemm_decode_bytes;   /* weight bytes those launches read (each weight once) */
+  /* same for the GEMM launches that finish their own epilogue (more than 256 rows: prefill and
+   * bt_score; parallel-residual wiring): the grouped layer GEMMs and the LM head of bt_score */
+  double  gemm_tiled_ms;
+  int64_t gemm_tiled_launches;
+  int64_t gemm_tiled_flops;    /* 2 * rows * N * K summed over those launches (one activation plane) */
 } bt_stats;
 
 typedef struct bt_model bt_model;

@@ -50,7 +50,8 @@ class bt_stats(C.Structure):
                 ("local_kv_high_water", C.c_int32), ("attn_block_ms", C.c_double),
                 ("attn_block_launches", C.c_int64), ("attn_block_bytes", C.c_int64),
                 ("gemm_decode_ms", C.c_double), ("gemm_decode_launches", C.c_int64),
-                ("gemm_decode_bytes", C.c_int64)]
+                ("gemm_decode_bytes", C.c_int64), ("gemm_tiled_ms", C.c_double),
+                ("gemm_tiled_launches", C.c_int64), ("gemm_tiled_flops", C.c_int64)]
 
 
 _P = C.c_void_p

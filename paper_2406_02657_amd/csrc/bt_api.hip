@@ -367,23 +367,31 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
       p[0].W = lw[l].W_qkv; p[1].W = lw[l].W_up;
       p[0].W_frag = fw[l].qkv; p[1].W_frag = fw[l].up;
       if (!pieces) { p[0].bias = (const float*)lw[l].b_qkv; p[1].bias = (const float*)lw[l].b_up; }
-      const bool prof_gemm = m->profile && pieces;
-      if (prof_gemm && (rc = prof_begin(m, 1))) return rc;
+      const bool prof_gemm = m->profile && pieces, prof_tiled = m->profile && !pieces;
+      if (m->profile && (rc = prof_begin(m, pieces ? 1 : 2))) return rc;
       BT_HIP(m, launch_gemm(dt, p, 2, plan_in, s));
+      if (m->profile && (rc = prof_end(m))) return rc;
       if (prof_gemm) {
-        if ((rc = prof_end(m))) return rc;
         m->st.gemm_decode_launches += 1;
         m->st.gemm_decode_bytes += (int64_t)(3 * D + F) * D * L.esz;
+      }
+      if (prof_tiled) {
+        m->st.gemm_tiled_launches += 1;
+        m->st.gemm_tiled_flops += (int64_t)2 * M * (3 * D + F) * D;
       }
       if ((rc = attention(l, gelu_job(l)))) return rc;
       p[0] = po; p[0].W = lw[l].W_o; p[0].W_frag = fw[l].o;
       p[1] = pd; p[1].W = lw[l].W_down; p[1].W_frag = fw[l].down;
-      if (prof_gemm && (rc = prof_begin(m, 1))) return rc;
+      if (m->profile && (rc = prof_begin(m, pieces ? 1 : 2))) return rc;
       BT_HIP(m, launch_gemm(dt, p, 2, plan_out, s));
+      if (m->profile && (rc = prof_end(m))) return rc;
       if (prof_gemm) {
-        if ((rc = prof_end(m))) return rc;
         m->st.gemm_decode_launches += 1;
         m->st.gemm_decode_bytes += (int64_t)(D + F) * D * L.esz;
+      }
+      if (prof_tiled) {
+        m->st.gemm_tiled_launches += 1;
+        m->st.gemm_tiled_flops += (int64_t)2 * M * (D + F) * D;
       }
       if (l + 1 < n_layers) {
         if ((rc = ln(part_o, (const float*)lw[l].b_o, sO, part_d, (const float*)lw[l].b_down, sD,
@@ -795,7 +803,14 @@ int bt_score(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t len,
                      c.vocab, EPI_F32, lo_planes ? h_all + (loD + (size_t)r0 * D) * 2 : nullptr, 0, m->head_frag};
       GemmPlan ph_plan{};
       BT_HIP(m, gemm_plan(c.dtype, &ph, 1, &ph_plan));
+      int prc;
+      if (m->profile && (prc = prof_begin(m, 2))) return prc;
       BT_HIP(m, launch_gemm(c.dtype, &ph, 1, ph_plan, s));
+      if (m->profile) {
+        if ((prc = prof_end(m))) return prc;
+        m->st.gemm_tiled_launches += 1;
+        m->st.gemm_tiled_flops += (int64_t)2 * rc_rows * c.vocab * D;
+      }
       BT_HIP(m, launch_score_rows(m->at<float>(L.score_logits), rc_rows, c.vocab, r0, toks, nll_dev + (size_t)b0 * len,
                                   P, c.block_len, N, len, s));
     }
@@ -866,6 +881,9 @@ int bt_reset_profile(bt_model* m) {
   m->st.gemm_decode_ms = 0.0;
   m->st.gemm_decode_launches = 0;
   m->st.gemm_decode_bytes = 0;
+  m->st.gemm_tiled_ms = 0.0;
+  m->st.gemm_tiled_launches = 0;
+  m->st.gemm_tiled_flops = 0;
   return BT_OK;
 }
 
@@ -873,14 +891,16 @@ int bt_get_stats(bt_model* m, bt_stats* out) {
   if (!m || !out) return BT_ERR_ARG;
   if (m->ev_used > 0) {
     BT_HIP(m, hipStreamSynchronize(m->stream));
-    double ms[2] = {0.0, 0.0};
+    double ms[3] = {0.0, 0.0, 0.0};
     for (size_t i = 0; i + 1 < m->ev_used; i += 2) {
       float t = 0.f;
       BT_HIP(m, hipEventElapsedTime(&t, m->ev[i], m->ev[i + 1]));
-      ms[m->ev_tag[i / 2] & 1] += t;
+      const int tag = m->ev_tag[i / 2];
+      ms[tag >= 0 && tag <= 2 ? tag : 0] += t;
     }
     m->st.attn_block_ms = ms[0];
     m->st.gemm_decode_ms = ms[1];
+    m->st.gemm_tiled_ms = ms[2];
   }
   m->st.n_blocks = m->n_blocks;
   m->st.r = m->r;

@@ -86,3 +86,28 @@ def test_cfg1_model_unaligned_no_prompt(amd):
     """Full batch, one-token prompts (the setting without an input sequence): L_B - 1 pads."""
     cfg = CONFIGS["cfg1"]
     full_size_case(amd, cfg, 64, [0, cfg.batch - 1], prompt_len=1)
+
+
+def test_cfg1_model_scoring(amd):
+    """bt_score on cfg1's model: 16 sequences of 2176 tokens (cfg1's prompt + generation length), the
+    workspace's default row budget (several prefill chunks), checked on three blocks of two sequences."""
+    import oracle.block_transformer as O
+    import torch
+    cfg = CONFIGS["cfg1"]
+    T = cfg.prompt_len + cfg.gen_len
+    W = make_weights(cfg)
+    toks = make_prompts(cfg, batch=16, prompt_len=T)
+    m = amd.Model(cfg, W, max_batch=16, max_blocks=T // cfg.block_len, score_rows=4096)
+    nll = m.bt_score(torch.from_numpy(toks).to(m.device)).cpu().numpy()
+    m.close()
+    assert np.isfinite(nll).all() and np.all(nll[:, :cfg.block_len] == 0) and np.all(nll[:, cfg.block_len:] > 0)
+    seqs, blocks = [0, 15], [1, 271, T // cfg.block_len - 1]
+    lg = O.teacher_forced_logits(O.Params(W, keep=False), cfg, toks[seqs].astype(np.int64), blocks)
+    L = cfg.block_len
+    for i in blocks:
+        z = lg[i]
+        lse = z.max(axis=-1) + np.log(np.exp(z - z.max(axis=-1, keepdims=True)).sum(axis=-1))
+        want = lse - np.take_along_axis(z, toks[seqs, i * L:(i + 1) * L].astype(np.int64)[..., None], axis=-1)[..., 0]
+        got = nll[seqs, i * L:(i + 1) * L]
+        print(f"[cfg1 scoring] block {i}: max |d nll| {np.abs(got - want).max():.2e}", flush=True)
+        assert np.abs(got - want).max() <= 4e-2
