@@ -415,14 +415,15 @@ def test_bf16_prefix_length_sweep(amd, p, lb):
     assert st.local_kv_high_water == p + lb - 1
 
 
-@pytest.mark.parametrize("dtype,lb,p,T,B,score_rows", [
-    ("fp32", 4, 1, 12, 2, 7),            # skinny GEMMs, logits in chunks of 7 rows
-    ("fp32", 4, 2, 24, 3, 64),
-    ("bf16", 4, 1, 48, 5, 100),
-    ("bf16", 8, 2, 320, 4, 500),         # 40 blocks: tiled GEMMs in both decoders
-    ("bf16", 2, 1, 300, 3, 4096),        # 150 blocks: matrix-core prefill attention
+@pytest.mark.parametrize("dtype,lb,p,T,B,score_rows,prefill_rows", [
+    ("fp32", 4, 1, 12, 2, 7, 0),            # skinny GEMMs, logits in chunks of 7 rows
+    ("fp32", 4, 2, 24, 3, 64, 0),
+    ("bf16", 4, 1, 48, 5, 100, 0),
+    ("bf16", 8, 2, 320, 4, 500, 0),         # 40 blocks: tiled GEMMs in both decoders
+    ("bf16", 2, 1, 300, 3, 4096, 0),        # 150 blocks: matrix-core prefill attention
+    ("bf16", 4, 2, 64, 7, 33, 200),         # row budget for two sequences at a time: four chunks, the last of one
 ])
-def test_teacher_forced_scoring(amd, dtype, lb, p, T, B, score_rows):
+def test_teacher_forced_scoring(amd, dtype, lb, p, T, B, score_rows, prefill_rows):
     """bt_score against the oracle's score_nll (Sec. 2.1: all blocks in parallel), and against the
     log-softmax of the logits the generation path itself produces for the same history."""
     import oracle.block_transformer as O
@@ -431,7 +432,7 @@ def test_teacher_forced_scoring(amd, dtype, lb, p, T, B, score_rows):
                    prompt_len=T, n_block_layers=2, n_token_layers=2)
     W = make_weights(cfg)
     toks = make_prompts(cfg, batch=B)
-    m = amd.Model(cfg, W, max_batch=B, max_blocks=T // lb + 2, score_rows=score_rows)
+    m = amd.Model(cfg, W, max_batch=B, max_blocks=T // lb + 2, score_rows=score_rows, prefill_rows=prefill_rows)
     nll = m.bt_score(torch.from_numpy(toks).to(m.device)).cpu().numpy()
     want = O.score_nll(O.Params(W), cfg, toks)
     tol = 2 * (TOL_F32 if dtype == "fp32" else TOL_BF16)     # |d lse| <= max |d logit|, plus the target's own logit
@@ -467,3 +468,32 @@ def test_scoring_needs_configuration(amd):
     assert amd.lib.bt_score(m.h, toks.data_ptr(), 2, 8, out.data_ptr()) == 0
     torch.cuda.synchronize()
     m.close()
+
+
+def test_ragged_batch_with_eos(amd):
+    """Different prompt lengths and the end-of-sequence rule together, graphs on: per sequence the ids
+    equal the run without the rule up to the first eos."""
+    cfg = tiny_cfg(dtype="bf16", d_model=128, n_heads=4, d_ff=256, vocab=19, block_len=4, prefix_len=1, prompt_len=30)
+    W = make_weights(cfg)
+    full = make_prompts(cfg, batch=6)
+    lens = [30, 1, 17, 8, 5, 24]
+    prompts = [full[b, :n] for b, n in enumerate(lens)]
+    n_new = 22
+    m = amd.Model(cfg, W, max_batch=6, max_blocks=16)
+    free, _ = gpu_generate_ragged(m, prompts, n_new)
+    m.close()
+    eos = int(free[2, 9])
+    m = amd.Model(cfg.with_(eos_id=eos), W, max_batch=6, max_blocks=16)
+    ids, lgs = gpu_generate_ragged(m, prompts, n_new)
+    flags = m.bt_get_finished().cpu().numpy()
+    m.close()
+    rep = compare_ragged_with_oracle(cfg.with_(eos_id=eos), W, prompts, ids, lgs, TOL_BF16)
+    assert rep["max_abs_logit_diff"] <= TOL_BF16, rep       # logits are computed for finished rows as well
+    for b in range(6):
+        where = np.nonzero(free[b] == eos)[0]
+        if len(where):
+            k = where[0]
+            assert np.array_equal(ids[b, :k + 1], free[b, :k + 1]) and np.all(ids[b, k:] == eos) and flags[b] == 1
+        else:
+            assert np.array_equal(ids[b], free[b]) and flags[b] == 0
+    assert flags[2] == 1
