@@ -57,6 +57,37 @@ def cpu_baseline(cfg, W, prompts, budget_s=12.0):
     }
 
 
+def largest_batch(cfg, amd, torch):
+    """Largest multiple of 64 whose workspace (bt_workspace_bytes: a host-side computation) fits the free
+    device memory beside the weights, their bf16 storage and a margin for the id buffers."""
+    import ctypes as C
+    free, _ = torch.cuda.mem_get_info()
+    D, F, V = cfg.d_model, cfg.d_ff, cfg.vocab
+    esz = 2 if cfg.dtype == "bf16" else 4
+    w_bytes = ((cfg.n_block_layers + cfg.n_token_layers) * 12 * D * D + V * (D + D + D // cfg.block_len)
+               + cfg.prefix_len * D * D) * esz
+    budget = free - w_bytes - (2 << 30)
+
+    def fits(b):
+        c = amd.binding.make_config(cfg.with_(batch=b))
+        n = C.c_size_t(0)
+        return amd.lib.bt_workspace_bytes(C.byref(c), C.byref(n)) == 0 and n.value <= budget
+
+    lo, hi = 0, 64
+    while fits(hi) and hi < (1 << 20):
+        lo, hi = hi, hi * 2
+    while hi - lo > 64:
+        mid = (lo + hi) // 2 // 64 * 64
+        if fits(mid):
+            lo = mid
+        else:
+            hi = mid
+    if lo == 0:
+        raise SystemExit("bench.py: not even a batch of 64 fits the free device memory")
+    log(f"largest batch that fits: {lo} ({free / 2**30:.0f} GiB free, weights {w_bytes / 2**30:.1f} GiB)")
+    return lo
+
+
 def score_bench(args, cfg, W):
     """Teacher-forced scoring of batch x (prompt_len + gen_len) tokens; one JSON line."""
     import numpy as np
@@ -142,6 +173,9 @@ def main():
     ap.add_argument("--prefix-len", type=int, default=-1, help="override P, the prefix length of the token decoder "
                     "(0 only together with --block-len 1: the vanilla-equivalent run)")
     ap.add_argument("--block-len", type=int, default=0, help="override L_B (must divide the model width)")
+    ap.add_argument("--max-batch", action="store_true",
+                    help="use the largest batch (a multiple of 64) whose workspace plus weights fit the free device "
+                         "memory, the paper's maximum-throughput setting; overrides --batch")
     ap.add_argument("--score", action="store_true",
                     help="time teacher-forced scoring (bt_score) of batch x (prompt + generated) tokens instead of "
                          "generation; a step is one scoring pass over the whole batch")
@@ -187,6 +221,8 @@ def main():
         cfg = cfg.with_(prefix_len=args.prefix_len)
     if args.block_len:
         cfg = cfg.with_(block_len=args.block_len)
+    if args.max_batch:
+        cfg = cfg.with_(batch=largest_batch(cfg, amd, torch))
     log(f"workload {cfg.name}: B={cfg.batch} prompt={cfg.prompt_len} gen={cfg.gen_len} L_B={cfg.block_len} "
         f"D={cfg.d_model} layers={cfg.n_block_layers}+{cfg.n_token_layers} P={cfg.prefix_len} dtype={cfg.dtype}")
     t0 = time.perf_counter()
