@@ -110,6 +110,67 @@ __device__ __forceinline__ void epilogue_store(const EpiArgs& d, int split, int 
   }
 }
 
+// Four consecutive columns of one row (col a multiple of 4): one 16-byte store for float outputs,
+// 8 bytes per plane for bf16.  The tiled kernels multiply with the weight fragment as the MFMA's
+// first operand, so that a lane's four accumulator values are four neighbouring columns of one
+// output row rather than four rows of one column: a quarter of the store instructions, and the
+// bias arrives as one float4.  Needs N and ldo to be multiples of 4 (else the callers store
+// element by element).
+template <class T, int EPI>
+__device__ __forceinline__ void epilogue_store4(const EpiArgs& d, int split, int row, int col, f32x4_t v) {
+  if (row >= d.M || col >= d.N) return;
+  if constexpr (EPI == EPI_PARTIAL) {
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(d.out) + ((size_t)split * d.M + row) * d.N + col) = make_float4(v[0], v[1], v[2], v[3]);
+  } else {
+    if (d.bias) {
+      const float4 b = *reinterpret_cast<const float4*>(d.bias + col);
+      v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
+    }
+    const size_t o = (size_t)row * d.ldo + col;
+    if constexpr (EPI == EPI_F32) *reinterpret_cast<float4*>(reinterpret_cast<float*>(d.out) + o) = make_float4(v[0], v[1], v[2], v[3]);
+    else store_act4<T>(reinterpret_cast<T*>(d.out), o, d.out_lo_off, gelu_for<T>(v[0]), gelu_for<T>(v[1]), gelu_for<T>(v[2]), gelu_for<T>(v[3]));
+  }
+}
+
+// The accumulator tiles of one wave, TM x TN MFMA results whose lane layout is (row lane%16, columns
+// 4*(lane/16) + 0..3) relative to (row_base + 16 i, col_base + 16 j).  The epilogue kind is resolved
+// once, outside the unrolled loops, so that each copy of the loop body stays small (a large body
+// keeps the compiler from unrolling, and the accumulators then land in scratch memory).
+template <class T, int TM, int TN>
+__device__ __forceinline__ void epilogue_tiles(const EpiArgs& ea, int split, int row_base, int col_base, int lane,
+                                               const f32x4_t (&acc)[TM][TN]) {
+  const int row_l = lane & 15, col_l = (lane >> 4) * 4;
+  if (((ea.N | ea.ldo) & 3) != 0) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          epilogue_store<T>(ea, split, row_base + i * 16 + row_l, col_base + j * 16 + col_l + r, acc[i][j][r]);
+    return;
+  }
+  if (ea.epi == EPI_PARTIAL) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        epilogue_store4<T, EPI_PARTIAL>(ea, split, row_base + i * 16 + row_l, col_base + j * 16 + col_l, acc[i][j]);
+  } else if (ea.epi == EPI_F32) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        epilogue_store4<T, EPI_F32>(ea, split, row_base + i * 16 + row_l, col_base + j * 16 + col_l, acc[i][j]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        epilogue_store4<T, EPI_GELU>(ea, split, row_base + i * 16 + row_l, col_base + j * 16 + col_l, acc[i][j]);
+  }
+}
+
 // ---------------------------------------------------------------------------
 // bf16 MFMA kernel.  256 threads = 4 waves laid out WM x WN over a BM x BN tile,
 // BK = 64 per stage.  Global -> registers -> LDS with the next stage's loads in
@@ -233,23 +294,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmGroup g) {
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-          if constexpr (HL) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fl[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+          if constexpr (HL) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fl[i], acc[i][j], 0, 0, 0);
         }
     }
     __syncthreads();
   }
 
-  // C layout of the 16x16 MFMA: lane holds column lane%16, rows 4*(lane/16) + 0..3
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = n0 + wn * (BN / WN) + j * 16 + (lane & 15);
-      const int row0 = m0 + wm * (BM / WM) + i * 16 + (lane >> 4) * 4;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) epilogue_store<bf16_t>(ea, split, row0 + r, col, acc[i][j][r]);
-    }
+  // The weight fragment is the MFMA's first operand: the 16 x 16 result is the tile transposed, and a
+  // lane holds output row lane%16, columns 4*(lane/16) + 0..3
+  epilogue_tiles<bf16_t, TM, TN>(ea, split, m0 + wm * (BM / WM), n0 + wn * (BN / WN), lane, acc);
 }
 
 // ---------------------------------------------------------------------------
@@ -348,25 +402,18 @@ __global__ __launch_bounds__(512) void gemm_bf16_big_kernel(GemmGroup g) {
       for (int i = 0; i < 8; ++i) {
         const bf16x8_t fa = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(fa_base + i * 16 * LDS + ks * 32));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa, acc[i][j], 0, 0, 0);
         if constexpr (HL) {
           const bf16x8_t fl = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(fa_base + (BM + BN) * LDS + i * 16 * LDS + ks * 32));
 #pragma unroll
-          for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fl, fb[j], acc[i][j], 0, 0, 0);
+          for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fl, acc[i][j], 0, 0, 0);
         }
       }
     }
     __syncthreads();
   }
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int col = n0 + wn * 64 + j * 16 + (lane & 15);
-      const int row0 = m0 + wm * 128 + i * 16 + (lane >> 4) * 4;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) epilogue_store<bf16_t>(ea, split, row0 + r, col, acc[i][j][r]);
-    }
+  // weight fragment first: a lane holds output row lane%16, columns 4*(lane/16) + 0..3 of each MFMA tile
+  epilogue_tiles<bf16_t, 8, 4>(ea, split, m0 + wm * 128, n0 + wn * 64, lane, acc);
 }
 
 // ---------------------------------------------------------------------------
