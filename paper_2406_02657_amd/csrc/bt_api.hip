@@ -27,6 +27,7 @@ struct Layout {
   size_t blk_layer_stride, loc_layer_stride;   // bytes between layers (K then V inside)
   size_t part_elems;                           // floats in each of part_o, part_d
   size_t qkv_elems, part_u_elems;              // floats in qkv (may hold split-K pieces) and part_u
+  size_t score_target_cap = 0;                 // rows of a chunk whose targets fit the scoring buffer
   int m_rows, l_cap, n_pref, rope_len, esz;
 };
 
@@ -113,6 +114,9 @@ void make_layout(const bt_config& c, Layout& L) {
     const size_t lq = L.n_pref + c.block_len - 1;
     L.score_kv = take(2 * (m_rows / lq + 1) * H * L.l_cap * dh * L.esz);
     L.score_logits = take((size_t)c.score_rows * c.vocab * 4);
+    // the same buffer, when the head's GEMM keeps the logits to itself: stats, target logits, then targets
+    const size_t fixed = (size_t)c.score_rows * ((c.vocab + 63) / 64) * 8 + (size_t)c.score_rows * 4;
+    L.score_target_cap = (size_t)c.score_rows * c.vocab * 4 > fixed ? ((size_t)c.score_rows * c.vocab * 4 - fixed) / 4 : 0;
   }
   // bf16 mode: a second copy of every GEMM weight in MFMA fragment order, read by the decode GEMMs
   L.frag = off;
@@ -796,13 +800,32 @@ int bt_score(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t len,
     at.loc_half = (size_t)n_loc * H * L.l_cap * dh * L.esz;
     rc = run_stack(m, m->tok.data(), c.n_token_layers, at, m->w.tok_lnf_g, m->w.tok_lnf_b, h_all, 0, rows, 1, 0);
     if (rc) return rc;
-    // LM head and log-softmax, score_rows rows at a time
+    // LM head and log-softmax, score_rows rows at a time.  Where the tiled MFMA kernel serves the
+    // head it leaves (max, sum of exponentials) per 64 columns and the target's logit instead of
+    // the logits themselves; otherwise the logits go through memory and a kernel reduces each row.
+    // The logits buffer holds, for the first form: stats | target logits | targets of the chunk.
+    const int groups = (c.vocab + 63) / 64;
+    float2* stats = m->at<float2>(L.score_logits);
+    float* tgt_logit = reinterpret_cast<float*>(stats + (size_t)c.score_rows * groups);
+    int32_t* targets = reinterpret_cast<int32_t*>(tgt_logit + c.score_rows);
+    bool targets_made = false;
     for (int r0 = 0; r0 < rows; r0 += c.score_rows) {
       const int rc_rows = rows - r0 < c.score_rows ? rows - r0 : c.score_rows;
       GemmProblem ph{h_all + (size_t)r0 * D * L.esz, m->w.W_head, nullptr, m->ws + L.score_logits, rc_rows, c.vocab, D, D,
                      c.vocab, EPI_F32, lo_planes ? h_all + (loD + (size_t)r0 * D) * 2 : nullptr, 0, m->head_frag};
       GemmPlan ph_plan{};
       BT_HIP(m, gemm_plan(c.dtype, &ph, 1, &ph_plan));
+      const bool fused = gemm_has_lse_epilogue(ph_plan) && (size_t)rows <= L.score_target_cap;
+      if (fused) {
+        if (!targets_made) {
+          BT_HIP(m, launch_score_targets(toks, targets, rows, P, c.block_len, N, len, s));
+          targets_made = true;
+        }
+        ph.epi = EPI_LSE;
+        ph.out = stats;
+        ph.lse_targets = targets + r0;
+        ph.lse_target_out = tgt_logit;
+      }
       int prc;
       if (m->profile && (prc = prof_begin(m, 2))) return prc;
       BT_HIP(m, launch_gemm(c.dtype, &ph, 1, ph_plan, s));
@@ -811,8 +834,12 @@ int bt_score(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t len,
         m->st.gemm_tiled_launches += 1;
         m->st.gemm_tiled_flops += (int64_t)2 * rc_rows * c.vocab * D;
       }
-      BT_HIP(m, launch_score_rows(m->at<float>(L.score_logits), rc_rows, c.vocab, r0, toks, nll_dev + (size_t)b0 * len,
-                                  P, c.block_len, N, len, s));
+      if (fused)
+        BT_HIP(m, launch_score_combine(stats, groups, tgt_logit, rc_rows, r0, nll_dev + (size_t)b0 * len, P, c.block_len,
+                                       N, len, s));
+      else
+        BT_HIP(m, launch_score_rows(m->at<float>(L.score_logits), rc_rows, c.vocab, r0, toks, nll_dev + (size_t)b0 * len,
+                                    P, c.block_len, N, len, s));
     }
   }
   return BT_OK;

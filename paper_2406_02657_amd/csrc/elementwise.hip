@@ -486,6 +486,61 @@ __global__ __launch_bounds__(1024) void score_rows_kernel(const float* __restric
   }
 }
 
+// Target column per token-decoder row of a chunk (row = s * Lq + pos as above): the token the row
+// predicts, or -1 for the first P - 1 prefix positions.
+__global__ void score_targets_kernel(const int32_t* __restrict__ tokens, int32_t* __restrict__ targets, int n_rows,
+                                     int P, int block_len, int n_blocks, int seq_len) {
+  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= n_rows) return;
+  const int Lq = P + block_len - 1;
+  const int s = row / Lq, pos = row - s * Lq;
+  const int bl = s / (n_blocks - 1), j = s - bl * (n_blocks - 1);
+  targets[row] = pos < P - 1 ? -1 : tokens[(size_t)bl * seq_len + (j + 1) * block_len + (pos - (P - 1))];
+}
+
+hipError_t launch_score_targets(const int32_t* tokens, int32_t* targets, int n_rows, int P, int block_len,
+                                int n_blocks, int seq_len, hipStream_t s) {
+  if (n_rows <= 0) return hipSuccess;
+  score_targets_kernel<<<(n_rows + 255) / 256, 256, 0, s>>>(tokens, targets, n_rows, P, block_len, n_blocks, seq_len);
+  return hipGetLastError();
+}
+
+// nll from the pieces a GEMM with the log-sum-exp epilogue left: one wave per row combines the
+// (max, sum of exponentials) of its column groups.
+__global__ __launch_bounds__(256) void score_combine_kernel(const float2* __restrict__ stats, int groups,
+                                                            const float* __restrict__ target_logit, int n_rows, int row0,
+                                                            float* __restrict__ nll, int P, int block_len, int n_blocks,
+                                                            int seq_len) {
+  const int lane = threadIdx.x & 63;
+  const int local = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (local >= n_rows) return;
+  const int Lq = P + block_len - 1;
+  const int row = row0 + local;
+  const int s = row / Lq, pos = row - s * Lq;
+  if (pos < P - 1) return;
+  const int bl = s / (n_blocks - 1), j = s - bl * (n_blocks - 1);
+  const size_t t = (size_t)bl * seq_len + (j + 1) * block_len + (pos - (P - 1));
+  const float2* st = stats + (size_t)local * groups;
+  float m = -INFINITY;
+  for (int g = lane; g < groups; g += 64) m = fmaxf(m, st[g].x);
+  m = wave_max(m);
+  float sum = 0.f;
+  for (int g = lane; g < groups; g += 64) {
+    const float2 p = st[g];
+    sum += p.y > 0.f ? p.y * __expf(p.x - m) : 0.f;
+  }
+  sum = wave_sum(sum);
+  if (lane == 0) nll[t] = logf(sum) + m - target_logit[local];
+}
+
+hipError_t launch_score_combine(const float2* stats, int groups, const float* target_logit, int n_rows, int row0,
+                                float* nll, int P, int block_len, int n_blocks, int seq_len, hipStream_t s) {
+  if (n_rows <= 0) return hipSuccess;
+  score_combine_kernel<<<(n_rows + 3) / 4, 256, 0, s>>>(stats, groups, target_logit, n_rows, row0, nll, P, block_len,
+                                                         n_blocks, seq_len);
+  return hipGetLastError();
+}
+
 hipError_t launch_score_rows(const float* logits, int n_rows, int vocab, int row0, const int32_t* tokens, float* nll,
                              int P, int block_len, int n_blocks, int seq_len, hipStream_t s) {
   if (n_rows <= 0) return hipSuccess;

@@ -28,6 +28,8 @@ struct GemmDesc {
   size_t out_lo_off;     // EPI_GELU: != 0 writes the output as hi / remainder planes
   const void* W_frag;    // W in MFMA fragment order (K-slice kernel)
   float2* row_max;       // per (column tile, row) candidates for argmax, or null
+  const int32_t* lse_targets;   // EPI_LSE: per row the column whose value goes to lse_target_out
+  float* lse_target_out;
   int tiles_m, tiles_n, tile_begin;   // tiles of this problem occupy blocks [tile_begin, tile_begin + tiles_m*tiles_n*splits)
 };
 struct GemmGroup {
@@ -93,9 +95,11 @@ struct EpiArgs {
   const float* bias;
   int M, N, ldo, epi;
   size_t out_lo_off;
+  const int32_t* lse_targets;
+  float* lse_target_out;
 };
 __device__ __forceinline__ EpiArgs epi_args(const GemmDesc& d) {
-  return EpiArgs{d.out, d.bias, d.M, d.N, d.ldo, d.epi, d.out_lo_off};
+  return EpiArgs{d.out, d.bias, d.M, d.N, d.ldo, d.epi, d.out_lo_off, d.lse_targets, d.lse_target_out};
 }
 
 template <class T>
@@ -140,6 +144,41 @@ template <class T, int TM, int TN>
 __device__ __forceinline__ void epilogue_tiles(const EpiArgs& ea, int split, int row_base, int col_base, int lane,
                                                const f32x4_t (&acc)[TM][TN]) {
   const int row_l = lane & 15, col_l = (lane >> 4) * 4;
+  if (ea.epi == EPI_LSE) {
+    // Log-sum-exp pieces instead of the values: this wave holds, for each of its 16 * TM rows, 16 * TN
+    // consecutive columns (one group when TN == 4); the four lanes that share a row combine by shuffles.
+    static_assert(TN == 4, "a wave covers one 64-column group");
+    float2* stats = reinterpret_cast<float2*>(ea.out);
+    const int groups = (ea.N + 63) >> 6, group = col_base >> 6;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int row = row_base + i * 16 + row_l;
+      const int tgt = (row < ea.M && ea.lse_targets) ? ea.lse_targets[row] : -1;
+      float v[TN][4];
+      float m = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int col = col_base + j * 16 + col_l + r;
+          const float x = acc[i][j][r] + ((ea.bias && col < ea.N) ? ea.bias[col] : 0.f);
+          v[j][r] = col < ea.N ? x : -INFINITY;
+          m = fmaxf(m, v[j][r]);
+          if (col == tgt) ea.lse_target_out[row] = x;
+        }
+      m = fmaxf(m, __shfl_xor(m, 16, kWave));
+      m = fmaxf(m, __shfl_xor(m, 32, kWave));
+      float ssum = 0.f;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ssum += v[j][r] > -INFINITY ? __expf(v[j][r] - m) : 0.f;
+      ssum += __shfl_xor(ssum, 16, kWave);
+      ssum += __shfl_xor(ssum, 32, kWave);
+      if (lane < 16 && row < ea.M && group < groups) stats[(size_t)row * groups + group] = make_float2(m, ssum);
+    }
+    return;
+  }
   if (((ea.N | ea.ldo) & 3) != 0) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -864,6 +903,8 @@ size_t kslice_lds_bytes(int M, int kf, bool hl) {
 }
 }  // namespace
 
+bool gemm_has_lse_epilogue(const GemmPlan& plan) { return plan.kind == KIND_TILE256 || plan.kind == KIND_TILE128; }
+
 int gemm_row_max_tiles(const GemmProblem& p, const GemmPlan& plan) {
   // candidates come from the plain K-slice kernel only: every row of a workgroup in one 64*MC chunk
   // set, one K-split, final values in the epilogue
@@ -1075,6 +1116,8 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
     g.p[i].M = p.M; g.p[i].N = p.N; g.p[i].K = p.K; g.p[i].lda = p.lda; g.p[i].ldo = p.ldo;
     g.p[i].epi = p.epi; g.p[i].splits = sp;
     g.p[i].A_lo = p.A_lo; g.p[i].out_lo_off = p.out_lo_off; g.p[i].W_frag = p.W_frag; g.p[i].row_max = p.row_max;
+    g.p[i].lse_targets = p.lse_targets; g.p[i].lse_target_out = p.lse_target_out;
+    if (p.epi == EPI_LSE && ((plan.kind != KIND_TILE256 && plan.kind != KIND_TILE128) || sp != 1 || !p.lse_target_out)) return hipErrorInvalidValue;
     if ((p.A_lo != nullptr) != (probs[0].A_lo != nullptr)) return hipErrorInvalidValue;
   }
   const bool hl = probs[0].A_lo != nullptr;

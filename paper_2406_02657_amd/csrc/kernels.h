@@ -87,11 +87,23 @@ hipError_t launch_score_assemble(int dtype, const float* pref, const void* E_tok
 hipError_t launch_score_rows(const float* logits, int n_rows, int vocab, int row0, const int32_t* tokens, float* nll,
                              int P, int block_len, int n_blocks, int seq_len, hipStream_t s);
 
+// The same without the logits: targets[row] = the token row `row` of the chunk predicts (-1: none), for a
+// GEMM with the EPI_LSE epilogue; and the combination of what that GEMM leaves for rows row0 .. row0 +
+// n_rows - 1: stats [n_rows][groups] (max, sum of exponentials), target_logit [n_rows].
+hipError_t launch_score_targets(const int32_t* tokens, int32_t* targets, int n_rows, int P, int block_len,
+                                int n_blocks, int seq_len, hipStream_t s);
+hipError_t launch_score_combine(const float2* stats, int groups, const float* target_logit, int n_rows, int row0,
+                                float* nll, int P, int block_len, int n_blocks, int seq_len, hipStream_t s);
+
 // ----------------------------------------------------------------------- GEMM
 enum { EPI_F32 = 0,        // out float [M, ldo]: acc + bias
        EPI_GELU = 1,       // out storage dtype: gelu(acc + bias)
-       EPI_PARTIAL = 2 };  // out float [splits][M][N]: raw partial sums (no bias); the consumer
+       EPI_PARTIAL = 2,    // out float [splits][M][N]: raw partial sums (no bias); the consumer
                            // sums the splits in order and applies bias / activation
+       EPI_LSE = 3 };      // tiled bf16 kernels only: the values acc + bias are not stored; out is
+                           // float2 [M][ceil(N/64)]: per row and group of 64 columns (max, sum of
+                           // exp(value - max)), and the value at column lse_targets[row] goes to
+                           // lse_target_out[row] (rows whose target is negative write nothing)
 
 // out[M, N] = A[M, K] * W[N, K]^T (+ bias).  A, W in the storage dtype, row-major,
 // lda / K contiguous.
@@ -113,6 +125,9 @@ struct GemmProblem {
   // row_max[row * tiles + tile]; gemm_row_max_tiles() gives the tile count.  Greedy argmax then reads
   // these candidates instead of the whole logits row.
   float2* row_max;
+  // EPI_LSE only
+  const int32_t* lse_targets;
+  float* lse_target_out;
 };
 // bf16 weights W[N, K] (K % 32 == 0) re-ordered for the decode GEMM: tiles of 16 rows x 32 k,
 // tile (i, j) at element offset (i * K/32 + j) * 512; inside a tile lane l (0..63) owns the 8
@@ -128,6 +143,8 @@ struct GemmPlan {
   int splits[2];
 };
 hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan* plan);
+// Whether the kernel this plan selects implements EPI_LSE.
+bool gemm_has_lse_epilogue(const GemmPlan& plan);
 // Number of candidate tiles the launch writes per row (0: this plan does not produce them).
 int gemm_row_max_tiles(const GemmProblem& p, const GemmPlan& plan);
 // Up to two independent problems in one launch.
