@@ -243,6 +243,14 @@ __global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2
   resid_ln_body<T, VPT, true>(a, c);
 }
 
+// Many rows (prefill, scoring, large batches): the same body without the occupancy cap.  The cap buys
+// the 64-row decode launches registers for their loads; with thousands of rows it is resident
+// workgroups, not registers, that keep enough bytes in flight.
+template <class T, int VPT>
+__global__ __launch_bounds__(kLnThreads) void resid_ln_many_kernel(LnHot a) {
+  resid_ln_body<T, VPT, false>(a, LnCold{});
+}
+
 template <class T>
 static hipError_t launch_resid_ln_t(const ResidLnArgs& r, hipStream_t s, const int* in_off_dev) {
   const int G = r.D / 4;
@@ -259,6 +267,10 @@ static hipError_t launch_resid_ln_t(const ResidLnArgs& r, hipStream_t s, const i
     if (G <= kLnThreads) resid_ln_extra_kernel<T, 1><<<r.n_rows, kLnThreads, 0, s>>>(a, c);
     else if (G <= 2 * kLnThreads) resid_ln_extra_kernel<T, 2><<<r.n_rows, kLnThreads, 0, s>>>(a, c);
     else resid_ln_extra_kernel<T, 4><<<r.n_rows, kLnThreads, 0, s>>>(a, c);
+  } else if (r.n_rows >= 1024) {
+    if (G <= kLnThreads) resid_ln_many_kernel<T, 1><<<r.n_rows, kLnThreads, 0, s>>>(a);
+    else if (G <= 2 * kLnThreads) resid_ln_many_kernel<T, 2><<<r.n_rows, kLnThreads, 0, s>>>(a);
+    else resid_ln_many_kernel<T, 4><<<r.n_rows, kLnThreads, 0, s>>>(a);
   } else {
     if (G <= kLnThreads) resid_ln_kernel<T, 1><<<r.n_rows, kLnThreads, 0, s>>>(a);
     else if (G <= 2 * kLnThreads) resid_ln_kernel<T, 2><<<r.n_rows, kLnThreads, 0, s>>>(a);
