@@ -97,9 +97,10 @@ struct EpiArgs {
   size_t out_lo_off;
   const int32_t* lse_targets;
   float* lse_target_out;
+  float2* row_max;
 };
 __device__ __forceinline__ EpiArgs epi_args(const GemmDesc& d) {
-  return EpiArgs{d.out, d.bias, d.M, d.N, d.ldo, d.epi, d.out_lo_off, d.lse_targets, d.lse_target_out};
+  return EpiArgs{d.out, d.bias, d.M, d.N, d.ldo, d.epi, d.out_lo_off, d.lse_targets, d.lse_target_out, d.row_max};
 }
 
 template <class T>
@@ -201,6 +202,37 @@ __device__ __forceinline__ void epilogue_tiles(const EpiArgs& ea, int split, int
 #pragma unroll
       for (int j = 0; j < TN; ++j)
         epilogue_store4<T, EPI_F32>(ea, split, row_base + i * 16 + row_l, col_base + j * 16 + col_l, acc[i][j]);
+    if (ea.row_max) {
+      // argmax candidates: per row the largest value of this wave's 64 columns and its column, the
+      // lowest on ties: own 16 values first (ascending columns), then the four lanes that share the row
+      static_assert(TN == 4, "a wave covers one 64-column group");
+      const int groups = (ea.N + 63) >> 6, group = col_base >> 6;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = row_base + i * 16 + row_l;
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int col = col_base + j * 16 + col_l + r;
+            const float x = acc[i][j][r] + ((ea.bias && col < ea.N) ? ea.bias[col] : 0.f);
+            const bool take = (col < ea.N) & (x > bv);
+            bv = take ? x : bv;
+            bi = take ? col : bi;
+          }
+#pragma unroll
+        for (int o = 16; o <= 32; o <<= 1) {
+          const float ov = __shfl_xor(bv, o, kWave);
+          const int oi = __shfl_xor(bi, o, kWave);
+          const bool take = (ov > bv) | ((ov == bv) & (oi < bi));
+          bv = take ? ov : bv;
+          bi = take ? oi : bi;
+        }
+        if (lane < 16 && row < ea.M && group < groups) ea.row_max[(size_t)row * groups + group] = make_float2(bv, __int_as_float(bi));
+      }
+    }
   } else {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -908,7 +940,10 @@ bool gemm_has_lse_epilogue(const GemmPlan& plan) { return plan.kind == KIND_TILE
 int gemm_row_max_tiles(const GemmProblem& p, const GemmPlan& plan) {
   // candidates come from the plain K-slice kernel only: every row of a workgroup in one 64*MC chunk
   // set, one K-split, final values in the epilogue
-  if (plan.kind != KIND_KSLICE || plan.splits[0] != 1 || p.epi != EPI_F32 || plan.mc >= 4) return 0;
+  if (p.epi != EPI_F32 || plan.splits[0] != 1) return 0;
+  // the tiled MFMA kernels: one candidate per row and 64 columns (N a multiple of 4: their vector epilogue)
+  if (plan.kind == KIND_TILE256 || plan.kind == KIND_TILE128) return (p.N & 3) || (p.ldo & 3) ? 0 : (p.N + 63) / 64;
+  if (plan.kind != KIND_KSLICE || plan.mc >= 4) return 0;
   return (p.N + 64 * plan.nt - 1) / (64 * plan.nt);
 }
 

@@ -120,10 +120,10 @@ struct GemmProblem {
   const void* A_lo;
   size_t out_lo_off;
   const void* W_frag;
-  // EPI_F32 on the decode kernel (M <= 192, one K-split): when non-null, every workgroup also
-  // writes, per row, the largest value of its columns and that column (lowest on ties) to
-  // row_max[row * tiles + tile]; gemm_row_max_tiles() gives the tile count.  Greedy argmax then reads
-  // these candidates instead of the whole logits row.
+  // EPI_F32, one K-split: when non-null, every workgroup (decode kernel, M <= 192) or wavefront (tiled
+  // kernels: one per 64 columns) also writes, per row, the largest value of its columns and that column
+  // (lowest on ties) to row_max[row * tiles + tile]; gemm_row_max_tiles() gives the tile count (0: this
+  // plan cannot).  Greedy argmax then reads these candidates instead of the whole logits row.
   float2* row_max;
   // EPI_LSE only
   const int32_t* lse_targets;
