@@ -104,19 +104,20 @@ __device__ __forceinline__ void add4(float4& a, const float4& b) { a.x += b.x; a
 // The two lists are walked as one, kLnBatch loads in flight at a time and no branch around
 // them: indices past the end are clamped (the value is then multiplied by zero).
 constexpr int kLnBatch = 24;
+template <int BATCH>
 __device__ __forceinline__ void add_partials(float4& acc, const float* partA, int nA, const float* partB, int nB,
                                              size_t stride, size_t off) {
   const int n = nA + nB;
-  for (int s0 = 0; s0 < n; s0 += kLnBatch) {
-    float4 v[kLnBatch];
+  for (int s0 = 0; s0 < n; s0 += BATCH) {
+    float4 v[BATCH];
 #pragma unroll
-    for (int u = 0; u < kLnBatch; ++u) {
+    for (int u = 0; u < BATCH; ++u) {
       const int s = min(s0 + u, n - 1);
       const float* p = s < nA ? partA + (size_t)s * stride : partB + (size_t)(s - nA) * stride;
       v[u] = *reinterpret_cast<const float4*>(p + off);
     }
 #pragma unroll
-    for (int u = 0; u < kLnBatch; ++u) {
+    for (int u = 0; u < BATCH; ++u) {
       const float k = (s0 + u < n) ? 1.f : 0.f;
       acc.x += k * v[u].x; acc.y += k * v[u].y; acc.z += k * v[u].z; acc.w += k * v[u].w;
     }
@@ -147,7 +148,7 @@ struct LnCold {
   int emb_stride, emb_off;
 };
 
-template <class T, int VPT, bool EXTRA>
+template <class T, int VPT, bool EXTRA, int BATCH = kLnBatch>
 __device__ __forceinline__ void resid_ln_body(const LnHot& a, const LnCold& cold) {
   __shared__ float red[4];
   const int i = blockIdx.x;
@@ -182,7 +183,7 @@ __device__ __forceinline__ void resid_ln_body(const LnHot& a, const LnCold& cold
     }
     if (nA && a.biasA) add4(acc, *reinterpret_cast<const float4*>(a.biasA + 4 * g));
     if (nB && a.biasB) add4(acc, *reinterpret_cast<const float4*>(a.biasB + 4 * g));
-    if (nA + nB) add_partials(acc, a.partA, nA, a.partB, nB, a.part_stride, row * D + 4 * g);
+    if (nA + nB) add_partials<BATCH>(acc, a.partA, nA, a.partB, nB, a.part_stride, row * D + 4 * g);
     v[c] = acc;
   }
   if (counter_inc && threadIdx.x == 0) counter_inc[i] += 1;
@@ -243,12 +244,13 @@ __global__ __launch_bounds__(kLnThreads) __attribute__((amdgpu_waves_per_eu(1, 2
   resid_ln_body<T, VPT, true>(a, c);
 }
 
-// Many rows (prefill, scoring, large batches): the same body without the occupancy cap.  The cap buys
-// the 64-row decode launches registers for their loads; with thousands of rows it is resident
-// workgroups, not registers, that keep enough bytes in flight.
+// Many rows (prefill, scoring, large batches): the same body without the occupancy cap and with
+// the partial sums taken four at a time (such launches have two pieces, not twenty).  The cap and
+// the deep batch buy the 64-row decode launches registers for their loads; with thousands of rows
+// it is resident workgroups, not registers, that keep enough bytes in flight.
 template <class T, int VPT>
 __global__ __launch_bounds__(kLnThreads) void resid_ln_many_kernel(LnHot a) {
-  resid_ln_body<T, VPT, false>(a, LnCold{});
+  resid_ln_body<T, VPT, false, 4>(a, LnCold{});
 }
 
 template <class T>
