@@ -145,7 +145,9 @@ typedef struct bt_model bt_model;
 /* Bytes of device workspace bt_create needs for this config (block KV cache,
  * local KV cache, activations, split-K partials, logits, argmax candidates and,
  * in bf16 mode, a second copy of every GEMM weight matrix in the order the
- * decode GEMMs fetch it: about the size of the model again).  host out pointer. */
+ * decode GEMMs fetch it: about the size of the model again; with
+ * score_rows > 0 also the scoring buffers, and activation rows for one
+ * sequence's blocks times prefix_len + L_B - 1).  host out pointer. */
 int bt_workspace_bytes(const bt_config *cfg, size_t *bytes);
 
 /* Build a model.  cfg, w: host structs (copied).  workspace_dev: device memory
