@@ -207,14 +207,15 @@ int bt_decode_step(bt_model *m, int32_t batch, int32_t *next_ids_dev);
 /* Teacher-forced scoring (Sec. 2.1, Fig. 1: block decoder and token decoder over
  * all blocks of a sequence at once; the token decoder sees each block as an
  * independent sequence of prefix_len + L_B - 1 rows).  tokens_dev: int32
- * [batch, len] row-major, device; len a multiple of L_B, at least 2 L_B.
- * nll_dev: float [batch, len], device; entry t >= L_B receives
+ * [batch, len] row-major, device; len > L_B.  A len that is not a multiple of
+ * L_B counts as left-padded with cfg.pad_id, as in bt_prefill.
+ * nll_dev: float [batch, len], device; entry t receives
  * -log p(x_t | x_<t), the log-softmax of the logits the generation step would
- * produce at that position given the same history; the first block has no
- * context embedding and gets 0.  Needs cfg.score_rows > 0 and prefix_len >= 1.
+ * produce at that position given the same history; the tokens of the first
+ * block (the first L_B - pads of them) have no context embedding and get 0.  Needs cfg.score_rows > 0 and prefix_len >= 1.
  * Overwrites the block KV cache: any generation in progress is lost (a new
  * bt_prefill is needed before bt_decode_step).  Errors: BT_ERR_ARG (null,
- * sizes), BT_ERR_STATE (score_rows == 0), BT_ERR_CAPACITY (len / L_B >
+ * sizes), BT_ERR_STATE (score_rows == 0), BT_ERR_CAPACITY (ceil(len / L_B) >
  * max_blocks, or one sequence's rows exceed the workspace), BT_ERR_HIP. */
 int bt_score(bt_model *m, const int32_t *tokens_dev, int32_t batch, int32_t len, float *nll_dev);
 

@@ -309,26 +309,29 @@ def teacher_forced_logits(P, cfg, tokens, blocks):
 
 def score_nll(P, cfg, tokens):
     """Teacher-forced scoring (the training-time forward of Sec. 2.1 / Fig. 1: both decoders over all
-    blocks at once).  tokens [B, T], T a multiple of L_B with at least two blocks.
+    blocks at once).  tokens [B, T], any T that spans two blocks or more once its first block has been
+    completed from the left (left_pad).
 
-    Returns [B, T] float64: entry t >= L_B is -log p(x_t | x_<t), the softmax of the logits that
-    next_token_logits_full defines for that position; the first block has no context embedding
-    and is not scored (zeros).
+    Returns [B, T] float64: entry t is -log p(x_t | x_<t), the softmax of the logits that
+    next_token_logits_full defines for that position; the tokens of the first block have no context
+    embedding and are not scored (zeros).
     """
     tokens = np.asarray(tokens, dtype=np.int64)
     B, T = tokens.shape
     L_B = cfg.block_len
-    assert T % L_B == 0 and T >= 2 * L_B
-    n = T // L_B
-    lg = teacher_forced_logits(P, cfg, tokens, range(1, n))
-    out = np.zeros((B, T))
+    padded = left_pad(cfg, tokens)
+    pad = padded.shape[1] - T
+    n = padded.shape[1] // L_B
+    assert n >= 2
+    lg = teacher_forced_logits(P, cfg, padded, range(1, n))
+    out = np.zeros((B, padded.shape[1]))
     for i in range(1, n):
         z = lg[i]                                               # [B, L_B, V]
         zmax = z.max(axis=-1, keepdims=True)
         lse = zmax[..., 0] + np.log(np.exp(z - zmax).sum(axis=-1))
-        tgt = tokens[:, i * L_B:(i + 1) * L_B]
+        tgt = padded[:, i * L_B:(i + 1) * L_B]
         out[:, i * L_B:(i + 1) * L_B] = lse - np.take_along_axis(z, tgt[..., None], axis=-1)[..., 0]
-    return out
+    return out[:, pad:]
 
 
 def generate_full(P, cfg, prompts, n_new):

@@ -759,8 +759,8 @@ int bt_score(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t len,
   if (c.prefix_len < 1) return fail(m, BT_ERR_ARG, "scoring needs prefix_len >= 1");
   if (c.d_ff < c.d_model) return fail(m, BT_ERR_ARG, "scoring needs d_ff >= d_model");   // the context rows borrow the MLP buffer
   if (batch < 1 || batch > c.max_batch) return fail(m, BT_ERR_ARG, "batch out of range");
-  if (len < 2 * c.block_len || len % c.block_len) return fail(m, BT_ERR_ARG, "len must be a multiple of block_len, two blocks or more");
-  const int N = len / c.block_len, P = c.prefix_len, D = c.d_model, H = c.n_heads, dh = D / H;
+  if (len <= c.block_len) return fail(m, BT_ERR_ARG, "len must exceed block_len (two blocks or more after left padding)");
+  const int N = (len + c.block_len - 1) / c.block_len, P = c.prefix_len, D = c.d_model, H = c.n_heads, dh = D / H;
   if (N > c.max_blocks) return fail(m, BT_ERR_CAPACITY, "more blocks than max_blocks");
   const int Lq = P + c.block_len - 1;
   const int per = L.m_rows / (N * Lq);          // sequences per chunk: all their token-decoder rows fit the workspace

@@ -438,6 +438,7 @@ __global__ __launch_bounds__(256) void score_assemble_kernel(const float* __rest
                                                              const int32_t* __restrict__ tokens, float* __restrict__ x,
                                                              int D, int P, int block_len, int n_blocks, int seq_len) {
   const int Lq = P + block_len - 1;
+  const int pad = n_blocks * block_len - seq_len;      // the first block was completed from the left
   const int row = blockIdx.x;
   const int s = row / Lq, pos = row - s * Lq;
   const int bl = s / (n_blocks - 1), j = s - bl * (n_blocks - 1);
@@ -446,7 +447,7 @@ __global__ __launch_bounds__(256) void score_assemble_kernel(const float* __rest
     const float* src = pref + ((size_t)(bl * n_blocks + j) * P + pos) * D;
     for (int i = threadIdx.x * 4; i < D; i += 1024) *reinterpret_cast<float4*>(dst + i) = *reinterpret_cast<const float4*>(src + i);
   } else {
-    const int tok = tokens[(size_t)bl * seq_len + (j + 1) * block_len + (pos - P)];
+    const int tok = tokens[(size_t)bl * seq_len + (j + 1) * block_len + (pos - P) - pad];
     const T* src = E_tok + (size_t)tok * D;
     for (int i = threadIdx.x * 4; i < D; i += 1024)
       *reinterpret_cast<float4*>(dst + i) = make_float4(to_float<T>(src[i]), to_float<T>(src[i + 1]), to_float<T>(src[i + 2]), to_float<T>(src[i + 3]));
@@ -476,7 +477,7 @@ __global__ __launch_bounds__(1024) void score_rows_kernel(const float* __restric
   const int s = row / Lq, pos = row - s * Lq;
   if (pos < P - 1) return;
   const int bl = s / (n_blocks - 1), j = s - bl * (n_blocks - 1);
-  const size_t t = (size_t)bl * seq_len + (j + 1) * block_len + (pos - (P - 1));
+  const size_t t = (size_t)bl * seq_len + (j + 1) * block_len + (pos - (P - 1)) - (n_blocks * block_len - seq_len);
   const float* z = logits + (size_t)blockIdx.x * vocab;
   float mx = -INFINITY;
   for (int v = threadIdx.x; v < vocab; v += 1024) mx = fmaxf(mx, z[v]);
@@ -509,7 +510,7 @@ __global__ void score_targets_kernel(const int32_t* __restrict__ tokens, int32_t
   const int Lq = P + block_len - 1;
   const int s = row / Lq, pos = row - s * Lq;
   const int bl = s / (n_blocks - 1), j = s - bl * (n_blocks - 1);
-  targets[row] = pos < P - 1 ? -1 : tokens[(size_t)bl * seq_len + (j + 1) * block_len + (pos - (P - 1))];
+  targets[row] = pos < P - 1 ? -1 : tokens[(size_t)bl * seq_len + (j + 1) * block_len + (pos - (P - 1)) - (n_blocks * block_len - seq_len)];
 }
 
 hipError_t launch_score_targets(const int32_t* tokens, int32_t* targets, int n_rows, int P, int block_len,
@@ -533,7 +534,7 @@ __global__ __launch_bounds__(256) void score_combine_kernel(const float2* __rest
   const int s = row / Lq, pos = row - s * Lq;
   if (pos < P - 1) return;
   const int bl = s / (n_blocks - 1), j = s - bl * (n_blocks - 1);
-  const size_t t = (size_t)bl * seq_len + (j + 1) * block_len + (pos - (P - 1));
+  const size_t t = (size_t)bl * seq_len + (j + 1) * block_len + (pos - (P - 1)) - (n_blocks * block_len - seq_len);
   const float2* st = stats + (size_t)local * groups;
   float m = -INFINITY;
   for (int g = lane; g < groups; g += 64) m = fmaxf(m, st[g].x);

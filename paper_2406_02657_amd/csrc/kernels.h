@@ -75,7 +75,8 @@ hipError_t launch_state_set(int* p, int value, int n, hipStream_t s);
 hipError_t launch_seq_blocks(const int* lens, int* n_blocks, int block_len, int n, hipStream_t s);
 
 // Teacher-forced scoring (Sec. 2.1: every block of a sequence at once).  A chunk holds n_seqs
-// sequences of n_blocks blocks; local sequence s = bl * (n_blocks - 1) + j scores block j + 1 of
+// sequences of seq_len tokens = n_blocks blocks once the first block is completed from the left with
+// n_blocks * L_B - seq_len pads (token indices below count the pads); local sequence s = bl * (n_blocks - 1) + j scores block j + 1 of
 // sequence bl from the context embedding of block j and has Lq = P + L_B - 1 rows.
 // assemble: x[s * Lq + p] = pref[(bl * n_blocks + j), p * D ...] for p < P (prefix rows, float), then
 // E_tok[tokens[bl * seq_len + (j + 1) * L_B + k]] for k < L_B - 1.  tokens: the chunk's first row.

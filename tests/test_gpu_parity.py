@@ -422,6 +422,9 @@ def test_bf16_prefix_length_sweep(amd, p, lb):
     ("bf16", 8, 2, 320, 4, 500, 0),         # 40 blocks: tiled GEMMs in both decoders
     ("bf16", 2, 1, 300, 3, 4096, 0),        # 150 blocks: matrix-core prefill attention
     ("bf16", 4, 2, 64, 7, 33, 200),         # row budget for two sequences at a time: four chunks, the last of one
+    ("fp32", 4, 1, 13, 2, 7, 0),            # lengths that are not whole blocks: the first block is left-padded
+    ("bf16", 4, 2, 61, 3, 100, 0),
+    ("bf16", 8, 1, 323, 4, 500, 0),
 ])
 def test_teacher_forced_scoring(amd, dtype, lb, p, T, B, score_rows, prefill_rows):
     """bt_score against the oracle's score_nll (Sec. 2.1: all blocks in parallel), and against the
@@ -432,11 +435,12 @@ def test_teacher_forced_scoring(amd, dtype, lb, p, T, B, score_rows, prefill_row
                    prompt_len=T, n_block_layers=2, n_token_layers=2)
     W = make_weights(cfg)
     toks = make_prompts(cfg, batch=B)
-    m = amd.Model(cfg, W, max_batch=B, max_blocks=T // lb + 2, score_rows=score_rows, prefill_rows=prefill_rows)
+    m = amd.Model(cfg, W, max_batch=B, max_blocks=-(-T // lb) + 2, score_rows=score_rows, prefill_rows=prefill_rows)
     nll = m.bt_score(torch.from_numpy(toks).to(m.device)).cpu().numpy()
     want = O.score_nll(O.Params(W), cfg, toks)
     tol = 2 * (TOL_F32 if dtype == "fp32" else TOL_BF16)     # |d lse| <= max |d logit|, plus the target's own logit
-    assert np.all(nll[:, :lb] == 0.0)
+    first = lb - (-T) % lb                                  # tokens of the (left-padded) first block: not scored
+    assert np.all(nll[:, :first] == 0.0) and np.all(nll[:, first:] > 0.0)
     assert np.abs(nll - want).max() <= tol, np.abs(nll - want).max()
     # scoring leaves no generation state behind; the model generates again after a prefill,
     # and the last scored position equals the generation step's own distribution
@@ -461,8 +465,9 @@ def test_scoring_needs_configuration(amd):
     assert amd.lib.bt_score(m.h, toks.data_ptr(), 2, 8, out.data_ptr()) == -2          # score_rows == 0
     m.close()
     m = amd.Model(cfg, W, max_batch=2, max_blocks=3, score_rows=16)
-    assert amd.lib.bt_score(m.h, toks.data_ptr(), 2, 6, out.data_ptr()) == -1          # not whole blocks
     assert amd.lib.bt_score(m.h, toks.data_ptr(), 2, 4, out.data_ptr()) == -1          # a single block: nothing to score
+    assert amd.lib.bt_score(m.h, toks.data_ptr(), 2, 3, out.data_ptr()) == -1
+    assert amd.lib.bt_score(m.h, toks.data_ptr(), 2, 6, out.data_ptr()) == 0           # two blocks after left padding
     assert amd.lib.bt_score(m.h, toks.data_ptr(), 3, 8, out.data_ptr()) == -1          # batch > max_batch
     assert amd.lib.bt_score(m.h, toks.data_ptr(), 2, 16, out.data_ptr()) == -3         # more blocks than max_blocks
     assert amd.lib.bt_score(m.h, toks.data_ptr(), 2, 8, out.data_ptr()) == 0

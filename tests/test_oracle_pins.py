@@ -614,3 +614,15 @@ def test_score_nll_against_stepwise_definition_and_closed_forms():
         base[0, 6] = v
         tot += math.exp(-O.score_nll(P, cfg, base)[0, 6])
     assert abs(tot - 1.0) < 1e-12
+
+
+def test_score_nll_of_a_length_that_is_not_whole_blocks():
+    """Scoring T tokens == scoring the hand-padded sequence and dropping the pads' entries."""
+    cfg = tiny_cfg(block_len=4, prefix_len=1, d_model=32, n_heads=2, prompt_len=10, vocab=19).with_(pad_id=6)
+    P = build(cfg)
+    toks = make_prompts(cfg, batch=2)
+    by_hand = np.array([[6, 6] + [int(t) for t in row] for row in toks])
+    a = O.score_nll(P, cfg, toks)
+    b = O.score_nll(P, cfg, by_hand)
+    assert a.shape == (2, 10) and np.array_equal(a, b[:, 2:])
+    assert np.all(a[:, :2] == 0.0) and np.all(a[:, 2:] > 0.0)      # first block = 2 pads + 2 tokens: those 2 are not scored
