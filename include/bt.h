@@ -51,6 +51,7 @@ typedef enum {
 } bt_status;
 
 enum { BT_F32 = 0, BT_BF16 = 1 };
+enum { BT_MIX_PREFIX = 0, BT_MIX_SUM = 1 };
 
 /* Model and capacity description (plain data, filled by the caller).
  * Shape limits: d_model % n_heads == 0; d_head = d_model/n_heads in
@@ -59,6 +60,9 @@ enum { BT_F32 = 0, BT_BF16 = 1 };
  * block_len == 1 (then the context embedding itself is the token decoder's
  * single input row).  In bf16 mode d_model and d_ff must be multiples of 64. */
 typedef struct {
+  int32_t struct_size;      /* sizeof(bt_config) as the caller compiled it; the library rejects any
+                               other value (BT_ERR_ARG), so a caller built against an older or newer
+                               header fails at bt_create instead of being misread */
   int32_t vocab;
   int32_t block_len;        /* L_B */
   int32_t d_model;          /* D, both decoders */
@@ -76,7 +80,9 @@ typedef struct {
   int32_t act_split;        /* bf16 mode only: activations enter the MFMA GEMMs as hi + lo bf16 pairs
                                (about 16 mantissa bits): 0 never, 1 in decode steps, 2 also in prefill */
   int32_t use_graphs;       /* 1: decode steps are captured into HIP graphs (one per position in the
-                               block) and replayed; 0: every launch is issued eagerly */
+                               block) and replayed; 0: every launch is issued eagerly.  Capture needs
+                               a stream other than the default (NULL) stream; with the default stream
+                               the steps run eagerly and bt_stats.graph_fallback is set */
   int32_t pad_id;           /* token id that fills, from the left, the first block of a prompt whose
                                length is not a multiple of L_B (App. "Random length padding"; the
                                paper does not name the id); 0 <= pad_id < vocab */
@@ -87,6 +93,19 @@ typedef struct {
                                every later step as well (the paper generates a fixed number of
                                tokens and states no stopping rule; the batch is static, so a finished
                                sequence still occupies its rows) */
+  int32_t keep_logits;      /* 1: every decode step stores its float logits [batch, vocab] for
+                               bt_get_logits.  0: the LM head skips that store wherever greedy argmax
+                               works from the per-tile candidates the head leaves (bf16 mode);
+                               bt_get_logits then returns BT_ERR_STATE */
+  int32_t token_mix;        /* how the context embedding enters the token decoder (App. D.2):
+                               BT_MIX_PREFIX: projected to prefix_len prefix tokens (the paper's design);
+                               BT_MIX_SUM: projected to L_B vectors of dimension D, vector k added to the
+                               token decoder's input at local position k ("Summation").  The paper does
+                               not say what stands under vector 0, the position that predicts the
+                               block's first token: here nothing does (input 0 is vector 0 alone), and
+                               position k >= 1 holds E_tok[token k-1 of the block] + vector k.
+                               W_prefix is then [L_B*D, D]; prefix_len must be 1 (it only sizes nothing);
+                               bt_score is not available */
   float   ln_eps;
 } bt_config;
 
@@ -138,6 +157,12 @@ typedef struct {
   double  gemm_tiled_ms;
   int64_t gemm_tiled_launches;
   int64_t gemm_tiled_flops;    /* 2 * rows * N * K summed over those launches (one activation plane) */
+  /* HIP-graph state of the decode steps (cfg.use_graphs) */
+  int64_t graph_launches;      /* decode steps that ran as a graph replay since bt_create */
+  int32_t graph_captures;      /* step kinds captured and instantiated so far */
+  int32_t graph_fallback;      /* 1: capture or instantiation failed (or the stream is the default
+                                  stream) and every later step is launched eagerly; the reason is in
+                                  bt_last_error */
 } bt_stats;
 
 typedef struct bt_model bt_model;
@@ -234,12 +259,15 @@ int bt_get_finished(bt_model *m, int32_t *flags_dev);
 int bt_embed(bt_model *m, const int32_t *tokens_dev, int32_t n_rows, float *out_dev);
 
 /* Copy the float logits [batch, vocab] of the last decode step to logits_dev
- * (device), on the model's stream.  For parity checks. */
+ * (device), on the model's stream.  For parity checks.  Errors: BT_ERR_STATE if
+ * no decode step has run since the last prefill, or cfg.keep_logits == 0. */
 int bt_get_logits(bt_model *m, float *logits_dev);
 
 /* Replace the token that the last decode step appended to each sequence's
  * history (teacher forcing for parity checks).  ids_dev: int32 [batch], device.
- * Must follow a bt_decode_step and precede the next one. */
+ * Must follow a bt_decode_step and precede the next one (else BT_ERR_STATE).
+ * With cfg.eos_id >= 0 a forced eos_id marks the sequence finished, as an
+ * emitted one does. */
 int bt_force_last_ids(bt_model *m, const int32_t *ids_dev);
 
 /* Copy the current context embedding [batch, D] (model dtype) out / in, on the

@@ -12,7 +12,7 @@ import os
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-lib_path = os.environ.get("BT_LIB", os.path.join(HERE, "libbt.so"))   # BT_LIB: debugging override
+lib_path = os.path.join(HERE, "libbt.so")
 if not os.path.exists(lib_path):
     raise ImportError(
         f"{lib_path} is missing: build it first (python -m paper_2406_02657_amd.build, "
@@ -20,14 +20,16 @@ if not os.path.exists(lib_path):
 lib = C.CDLL(lib_path)
 
 BT_F32, BT_BF16 = 0, 1
+BT_MIX_PREFIX, BT_MIX_SUM = 0, 1
 BT_OK, BT_ERR_ARG, BT_ERR_STATE, BT_ERR_CAPACITY, BT_ERR_HIP = 0, -1, -2, -3, -4
 
 
 class bt_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
-        "vocab", "block_len", "d_model", "n_heads", "d_ff", "n_block_layers", "n_token_layers",
+        "struct_size", "vocab", "block_len", "d_model", "n_heads", "d_ff", "n_block_layers", "n_token_layers",
         "prefix_len", "dtype", "max_batch", "max_blocks", "rotary_dims", "parallel_residual",
-        "prefill_rows", "act_split", "use_graphs", "pad_id", "score_rows", "eos_id")] + [("ln_eps", C.c_float)]
+        "prefill_rows", "act_split", "use_graphs", "pad_id", "score_rows", "eos_id", "keep_logits",
+        "token_mix")] + [("ln_eps", C.c_float)]
 
 
 _LAYER_FIELDS = ("ln1_g", "ln1_b", "W_qkv", "b_qkv", "W_o", "b_o", "ln2_g", "ln2_b", "W_up", "b_up", "W_down", "b_down")
@@ -51,7 +53,8 @@ class bt_stats(C.Structure):
                 ("attn_block_launches", C.c_int64), ("attn_block_bytes", C.c_int64),
                 ("gemm_decode_ms", C.c_double), ("gemm_decode_launches", C.c_int64),
                 ("gemm_decode_bytes", C.c_int64), ("gemm_tiled_ms", C.c_double),
-                ("gemm_tiled_launches", C.c_int64), ("gemm_tiled_flops", C.c_int64)]
+                ("gemm_tiled_launches", C.c_int64), ("gemm_tiled_flops", C.c_int64),
+                ("graph_launches", C.c_int64), ("graph_captures", C.c_int32), ("graph_fallback", C.c_int32)]
 
 
 _P = C.c_void_p
@@ -86,34 +89,58 @@ class BTError(RuntimeError):
         self.code = code
 
 
-DEFAULT_ACT_SPLIT = int(os.environ.get("BT_ACT_SPLIT", "2"))
+DEFAULT_ACT_SPLIT = 2
 
 
 def make_config(cfg, max_batch=None, max_blocks=None, prefill_rows=0, act_split=None, use_graphs=1,
-                score_rows=0) -> bt_config:
+                score_rows=0, keep_logits=1) -> bt_config:
     """cfg: any object with the fields of synth.BTConfig."""
     return bt_config(
-        vocab=cfg.vocab, block_len=cfg.block_len, d_model=cfg.d_model, n_heads=cfg.n_heads, d_ff=cfg.d_ff,
+        struct_size=C.sizeof(bt_config), vocab=cfg.vocab, block_len=cfg.block_len, d_model=cfg.d_model, n_heads=cfg.n_heads, d_ff=cfg.d_ff,
         n_block_layers=cfg.n_block_layers, n_token_layers=cfg.n_token_layers, prefix_len=cfg.prefix_len,
         dtype=BT_BF16 if cfg.dtype == "bf16" else BT_F32,
         max_batch=cfg.batch if max_batch is None else max_batch,
         max_blocks=cfg.max_blocks if max_blocks is None else max_blocks,
         rotary_dims=cfg.rot, parallel_residual=cfg.parallel_residual, prefill_rows=prefill_rows,
         act_split=DEFAULT_ACT_SPLIT if act_split is None else act_split,
-        use_graphs=int(use_graphs) if "BT_USE_GRAPHS" not in os.environ else int(os.environ["BT_USE_GRAPHS"]),
-        pad_id=getattr(cfg, "pad_id", 0), score_rows=score_rows, eos_id=getattr(cfg, "eos_id", -1), ln_eps=cfg.ln_eps)
+        use_graphs=int(use_graphs),
+        pad_id=getattr(cfg, "pad_id", 0), score_rows=score_rows, eos_id=getattr(cfg, "eos_id", -1),
+        keep_logits=int(keep_logits),
+        token_mix=BT_MIX_SUM if getattr(cfg, "token_mix", "prefix") == "sum" else BT_MIX_PREFIX, ln_eps=cfg.ln_eps)
+
+
+class _Ordered:
+    """Orders one library call (enqueued on `stream`) against torch's current stream."""
+
+    def __init__(self, torch, device, stream):
+        self.cur = torch.cuda.current_stream(device)
+        self.stream = stream
+
+    def __enter__(self):
+        if self.cur != self.stream:
+            self.stream.wait_stream(self.cur)
+
+    def __exit__(self, *exc):
+        if self.cur != self.stream:
+            self.cur.wait_stream(self.stream)
+        return False
 
 
 class Model:
     """Owns the device copies of the weights and the workspace; forwards to the C ABI."""
 
     def __init__(self, cfg, weights, max_batch=None, max_blocks=None, prefill_rows=0, act_split=None,
-                 use_graphs=1, score_rows=0, device="cuda:0"):
+                 use_graphs=1, score_rows=0, keep_logits=1, device="cuda:0", stream=None):
         import torch
         self.torch = torch
         self.device = torch.device(device)
         self.cfg = cfg
-        self.c = make_config(cfg, max_batch, max_blocks, prefill_rows, act_split, use_graphs, score_rows)
+        self.c = make_config(cfg, max_batch, max_blocks, prefill_rows, act_split, use_graphs, score_rows, keep_logits)
+        # The library enqueues everything on one HIP stream.  HIP graphs cannot be captured on the
+        # default stream, so the model brings a stream of its own (default priority).  Callers
+        # that make it current (`with model.on_stream():`) pay nothing; from any other stream
+        # every call is bracketed by the two stream waits that keep the order.
+        self.stream = torch.cuda.Stream(self.device) if stream is None else stream
         self._keep = {}
         for name, arr in weights.items():
             a = np.ascontiguousarray(arr)
@@ -142,11 +169,19 @@ class Model:
         self.workspace = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=self.device)
         base = (self.workspace.data_ptr() + 255) // 256 * 256
         self.h = _P()
-        stream = torch.cuda.current_stream(self.device).cuda_stream
-        rc = lib.bt_create(C.byref(self.c), C.byref(self.w), base, nbytes.value, stream, C.byref(self.h))
+        with self._ordered():
+            rc = lib.bt_create(C.byref(self.c), C.byref(self.w), base, nbytes.value, self.stream.cuda_stream,
+                               C.byref(self.h))
         if rc:
             raise BTError(rc, "bt_create")
         self.batch = 0
+
+    def on_stream(self):
+        """Context manager that makes the model's stream torch's current stream."""
+        return self.torch.cuda.stream(self.stream)
+
+    def _ordered(self):
+        return _Ordered(self.torch, self.device, self.stream)
 
     def _chk(self, rc):
         if rc:
@@ -155,7 +190,8 @@ class Model:
     def bt_prefill(self, tokens):
         """tokens: int32 cuda tensor [batch, prompt_len]."""
         assert tokens.dtype == self.torch.int32 and tokens.is_cuda and tokens.is_contiguous()
-        self._chk(lib.bt_prefill(self.h, tokens.data_ptr(), tokens.shape[0], tokens.shape[1]))
+        with self._ordered():
+            self._chk(lib.bt_prefill(self.h, tokens.data_ptr(), tokens.shape[0], tokens.shape[1]))
         self._after_prefill(tokens.shape[0])
 
     def bt_prefill_ragged(self, tokens, lens):
@@ -163,7 +199,8 @@ class Model:
         assert tokens.dtype == self.torch.int32 and tokens.is_cuda and tokens.is_contiguous()
         assert len(lens) == tokens.shape[0]
         arr = (C.c_int32 * len(lens))(*[int(v) for v in lens])
-        self._chk(lib.bt_prefill_ragged(self.h, tokens.data_ptr(), arr, tokens.shape[0], tokens.shape[1]))
+        with self._ordered():
+            self._chk(lib.bt_prefill_ragged(self.h, tokens.data_ptr(), arr, tokens.shape[0], tokens.shape[1]))
         self._after_prefill(tokens.shape[0])
 
     def _after_prefill(self, batch):
@@ -172,29 +209,34 @@ class Model:
 
     def bt_decode_step(self, out=None):
         ids = self._ids if out is None else out
-        self._chk(lib.bt_decode_step(self.h, self.batch, ids.data_ptr()))
+        with self._ordered():
+            self._chk(lib.bt_decode_step(self.h, self.batch, ids.data_ptr()))
         return ids
 
     def bt_get_logits(self):
         lg = self.torch.empty(self.batch, self.cfg.vocab, dtype=self.torch.float32, device=self.device)
-        self._chk(lib.bt_get_logits(self.h, lg.data_ptr()))
+        with self._ordered():
+            self._chk(lib.bt_get_logits(self.h, lg.data_ptr()))
         return lg
 
     def bt_score(self, tokens):
         """tokens: int32 cuda tensor [batch, len]; returns float32 [batch, len] negative log-likelihoods."""
         assert tokens.dtype == self.torch.int32 and tokens.is_cuda and tokens.is_contiguous()
         nll = self.torch.empty(tokens.shape, dtype=self.torch.float32, device=self.device)
-        self._chk(lib.bt_score(self.h, tokens.data_ptr(), tokens.shape[0], tokens.shape[1], nll.data_ptr()))
+        with self._ordered():
+            self._chk(lib.bt_score(self.h, tokens.data_ptr(), tokens.shape[0], tokens.shape[1], nll.data_ptr()))
         return nll
 
     def bt_get_finished(self):
         fl = self.torch.empty(self.batch, dtype=self.torch.int32, device=self.device)
-        self._chk(lib.bt_get_finished(self.h, fl.data_ptr()))
+        with self._ordered():
+            self._chk(lib.bt_get_finished(self.h, fl.data_ptr()))
         return fl
 
     def bt_force_last_ids(self, ids):
         assert ids.dtype == self.torch.int32 and ids.is_cuda
-        self._chk(lib.bt_force_last_ids(self.h, ids.data_ptr()))
+        with self._ordered():
+            self._chk(lib.bt_force_last_ids(self.h, ids.data_ptr()))
 
     def _ctx_dtype(self):
         if self.cfg.prefix_len == 0 or self.cfg.dtype != "bf16":
@@ -203,34 +245,40 @@ class Model:
 
     def bt_get_context(self):
         c = self.torch.empty(self.batch, self.cfg.d_model, dtype=self._ctx_dtype(), device=self.device)
-        self._chk(lib.bt_get_context(self.h, c.data_ptr()))
+        with self._ordered():
+            self._chk(lib.bt_get_context(self.h, c.data_ptr()))
         return c
 
     def bt_set_context(self, c):
         assert c.dtype == self._ctx_dtype() and c.is_cuda and c.is_contiguous()
-        self._chk(lib.bt_set_context(self.h, c.data_ptr()))
+        with self._ordered():
+            self._chk(lib.bt_set_context(self.h, c.data_ptr()))
 
     def bt_embed(self, tokens):
         """Embedder alone: int32 cuda [n_rows, L_B] -> float32 [n_rows, D]."""
         assert tokens.dtype == self.torch.int32 and tokens.is_cuda and tokens.is_contiguous()
         n = tokens.numel() // self.cfg.block_len
         out = self.torch.empty(n, self.cfg.d_model, dtype=self.torch.float32, device=self.device)
-        self._chk(lib.bt_embed(self.h, tokens.data_ptr(), n, out.data_ptr()))
+        with self._ordered():
+            self._chk(lib.bt_embed(self.h, tokens.data_ptr(), n, out.data_ptr()))
         return out
 
     def bt_set_profile(self, on):
         self._chk(lib.bt_set_profile(self.h, int(on)))
 
     def bt_reset_profile(self):
-        self._chk(lib.bt_reset_profile(self.h))
+        with self._ordered():
+            self._chk(lib.bt_reset_profile(self.h))
 
     def bt_get_stats(self) -> bt_stats:
         st = bt_stats()
-        self._chk(lib.bt_get_stats(self.h, C.byref(st)))
+        with self._ordered():
+            self._chk(lib.bt_get_stats(self.h, C.byref(st)))
         return st
 
     def close(self):
         if self.h:
+            self.stream.synchronize()       # the workspace goes back to torch's allocator after this
             lib.bt_destroy(self.h)
             self.h = _P()
 

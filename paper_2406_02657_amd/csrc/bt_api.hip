@@ -33,6 +33,7 @@ struct Layout {
 
 int check_config(const bt_config& c, std::string* why) {
   auto bad = [&](const char* s) { if (why) *why = s; return (int)BT_ERR_ARG; };
+  if (c.struct_size != (int32_t)sizeof(bt_config)) return bad("struct_size is not sizeof(bt_config) of this library");
   if (c.dtype != BT_F32 && c.dtype != BT_BF16) return bad("dtype must be BT_F32 or BT_BF16");
   if (c.vocab < 1 || c.block_len < 1 || c.d_model < 1 || c.n_heads < 1 || c.d_ff < 1) return bad("non-positive size");
   if (c.n_block_layers < 0 || c.n_token_layers < 0) return bad("negative layer count");
@@ -53,6 +54,9 @@ int check_config(const bt_config& c, std::string* why) {
   if (c.pad_id < 0 || c.pad_id >= c.vocab) return bad("pad_id outside the vocabulary");
   if (c.eos_id < -1 || c.eos_id >= c.vocab) return bad("eos_id must be -1 (none) or a vocabulary id");
   if (c.score_rows < 0) return bad("score_rows < 0");
+  if (c.keep_logits < 0 || c.keep_logits > 1) return bad("keep_logits must be 0 or 1");
+  if (c.token_mix != BT_MIX_PREFIX && c.token_mix != BT_MIX_SUM) return bad("token_mix must be BT_MIX_PREFIX or BT_MIX_SUM");
+  if (c.token_mix == BT_MIX_SUM && (c.prefix_len != 1 || c.score_rows != 0)) return bad("BT_MIX_SUM needs prefix_len == 1 and score_rows == 0");
   if (!(c.ln_eps >= 0.f)) return bad("ln_eps < 0");
   const int l_cap = (c.prefix_len > 0 ? c.prefix_len : 1) + c.block_len;
   if ((size_t)(2 * l_cap + 2) * dh * sizeof(float) > 60 * 1024) return bad("prefix_len + block_len too large for the local-attention kernel");
@@ -155,6 +159,8 @@ struct bt_model {
   struct StepGraph { hipGraphExec_t exec = nullptr; int seen = 0; };
   std::vector<StepGraph> graphs;   // one per step kind: r = 0..L_B-1 without, [L_B] with the block decoder
   bool graphs_ok;
+  int64_t graph_launches;
+  int graph_captures;
 
   template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
 };
@@ -487,6 +493,13 @@ int bt_create(const bt_config* cfg, const bt_weights* w, void* workspace_dev, si
   m->ev_used = 0;
   m->graphs.assign(cfg->block_len + 1, bt_model::StepGraph());
   m->graphs_ok = true;
+  m->graph_launches = 0;
+  m->graph_captures = 0;
+  if (cfg->use_graphs && !m->stream) {
+    m->graphs_ok = false;
+    m->err = "HIP graphs need a stream other than the default stream: decode steps are launched eagerly";
+  }
+  if (gemm_prepare_kernels() != hipSuccess) { (void)hipGetLastError(); delete m; return BT_ERR_HIP; }
 
   m->blk_frag.assign(cfg->n_block_layers, bt_model::FragLayer{nullptr, nullptr, nullptr, nullptr});
   m->tok_frag.assign(cfg->n_token_layers, bt_model::FragLayer{nullptr, nullptr, nullptr, nullptr});
@@ -639,7 +652,7 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
       BT_HIP(m, gemm_plan(c.dtype, &p, 1, &pl));
       BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));
     } else {
-      BT_HIP(m, hipMemcpyAsync(x, m->ws + L.ctx, (size_t)B * D * 4, hipMemcpyDeviceToDevice, s));
+      BT_HIP(m, launch_copy16(x, m->ws + L.ctx, (size_t)B * D * 4, s));
     }
     rows = L.n_pref;
     pos0 = 0;
@@ -662,7 +675,10 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
   // Greedy argmax: where the head's kernel can, it leaves per-tile (max, column) candidates per row
   // and a small kernel picks among them; otherwise one workgroup per row scans the logits.
   const int cand_tiles = gemm_row_max_tiles(p, pl);
-  if (cand_tiles > 0) p.row_max = m->at<float2>(L.cand);
+  if (cand_tiles > 0) {
+    p.row_max = m->at<float2>(L.cand);
+    if (!c.keep_logits) p.out = nullptr;      // the head's kernel leaves the candidates only
+  }
   BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));
   if (cand_tiles > 0)
     BT_HIP(m, launch_argmax_candidates(m->at<float2>(L.cand), cand_tiles, B, ids_out, cur, c.block_len, r, c.eos_id,
@@ -690,8 +706,15 @@ int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
   // eagerly, the second is captured into a graph, later ones replay it.
   const int kind = with_block ? c.block_len : r;
   bool done = false;
-  if (m->graphs_ok && c.use_graphs && !m->profile && c.prefix_len > 0) {
+  if (m->graphs_ok && c.use_graphs && !m->profile) {
     bt_model::StepGraph& g = m->graphs[kind];
+    // A failed capture or instantiation is not an error of the step (it then runs eagerly, now and
+    // from here on) but it is recorded: bt_stats.graph_fallback, and the reason in bt_last_error.
+    auto give_up = [&](const char* what, hipError_t e) {
+      m->graphs_ok = false;
+      m->err = std::string("HIP graph ") + what + " failed (" + hipGetErrorString(e) + "): decode steps are launched eagerly";
+      (void)hipGetLastError();
+    };
     if (g.exec) {
       BT_HIP(m, hipGraphLaunch(g.exec, s));
       done = true;
@@ -703,21 +726,24 @@ int bt_decode_step(bt_model* m, int32_t batch, int32_t* next_ids_dev) {
         e = hipStreamEndCapture(s, &graph);
         if (rc != BT_OK || e != hipSuccess || !graph) {
           if (graph) (void)hipGraphDestroy(graph);
-          (void)hipGetLastError();
-          m->graphs_ok = false;          // fall back to eager launches for good
+          give_up("capture", e != hipSuccess ? e : hipErrorUnknown);
         } else {
           e = hipGraphInstantiate(&g.exec, graph, nullptr, nullptr, 0);
           (void)hipGraphDestroy(graph);
-          if (e != hipSuccess) { g.exec = nullptr; m->graphs_ok = false; (void)hipGetLastError(); }
-          else { BT_HIP(m, hipGraphLaunch(g.exec, s)); done = true; }
+          if (e != hipSuccess) { g.exec = nullptr; give_up("instantiation", e); }
+          else {
+            m->graph_captures += 1;
+            BT_HIP(m, hipGraphLaunch(g.exec, s));
+            done = true;
+          }
         }
       } else {
-        (void)hipGetLastError();
-        m->graphs_ok = false;
+        give_up("capture", e);
       }
     }
     g.seen += 1;
   }
+  if (done) m->graph_launches += 1;
   if (done) {
     BT_HIP(m, launch_gather_ids(m->at<int32_t>(L.cur), next_ids_dev, batch, c.block_len, r, s));
   } else {
@@ -768,6 +794,7 @@ int bt_score(bt_model* m, const int32_t* tokens_dev, int32_t batch, int32_t len,
   hipStream_t s = m->stream;
   m->batch = 0;                                 // the block KV cache is overwritten: any generation state is gone
   m->have_context = false;
+  m->stepped = false;
   drop_graphs(m);
   BT_HIP(m, hipMemsetAsync(nll_dev, 0, (size_t)batch * len * sizeof(float), s));
   const bool lo_planes = c.dtype == BT_BF16 && c.act_split >= 1;
@@ -856,7 +883,8 @@ int bt_get_finished(bt_model* m, int32_t* flags_dev) {
 int bt_get_logits(bt_model* m, float* logits_dev) {
   if (!m) return BT_ERR_ARG;
   if (!logits_dev) return fail(m, BT_ERR_ARG, "logits_dev is null");
-  if (!m->stepped) return fail(m, BT_ERR_STATE, "no decode step yet");
+  if (!m->stepped || m->batch == 0) return fail(m, BT_ERR_STATE, "no decode step since the last prefill");
+  if (!m->cfg.keep_logits) return fail(m, BT_ERR_STATE, "the model was created with keep_logits == 0");
   BT_HIP(m, hipMemcpyAsync(logits_dev, m->ws + m->L.logits, (size_t)m->batch * m->cfg.vocab * 4,
                            hipMemcpyDeviceToDevice, m->stream));
   return BT_OK;
@@ -865,9 +893,10 @@ int bt_get_logits(bt_model* m, float* logits_dev) {
 int bt_force_last_ids(bt_model* m, const int32_t* ids_dev) {
   if (!m) return BT_ERR_ARG;
   if (!ids_dev) return fail(m, BT_ERR_ARG, "ids_dev is null");
-  if (!m->stepped) return fail(m, BT_ERR_STATE, "no decode step yet");
+  if (!m->stepped || m->batch == 0) return fail(m, BT_ERR_STATE, "no decode step since the last prefill");
   const int L_B = m->cfg.block_len;
-  BT_HIP(m, launch_scatter_ids(ids_dev, m->at<int32_t>(m->L.cur), m->batch, L_B, (m->r + L_B - 1) % L_B, m->stream));
+  BT_HIP(m, launch_scatter_ids(ids_dev, m->at<int32_t>(m->L.cur), m->batch, L_B, (m->r + L_B - 1) % L_B, m->cfg.eos_id,
+                               m->at<int32_t>(m->L.fin), m->stream));
   return BT_OK;
 }
 
@@ -932,6 +961,9 @@ int bt_get_stats(bt_model* m, bt_stats* out) {
   m->st.n_blocks = m->n_blocks;
   m->st.r = m->r;
   m->st.batch = m->batch;
+  m->st.graph_launches = m->graph_launches;
+  m->st.graph_captures = m->graph_captures;
+  m->st.graph_fallback = (m->cfg.use_graphs && !m->graphs_ok) ? 1 : 0;
   *out = m->st;
   return BT_OK;
 }

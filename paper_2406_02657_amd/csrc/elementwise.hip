@@ -407,13 +407,33 @@ hipError_t launch_argmax_candidates(const float2* cand, int n_tiles, int batch, 
 }
 
 __global__ void scatter_ids_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ cur, int batch,
-                                   int block_len, int r) {
+                                   int block_len, int r, int eos_id, int32_t* __restrict__ finished) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b < batch) cur[b * block_len + r] = ids[b];
+  if (b < batch) {
+    cur[b * block_len + r] = ids[b];
+    if (eos_id >= 0 && ids[b] == eos_id) finished[b] = 1;     // a forced end-of-sequence id ends the sequence too
+  }
 }
 
-hipError_t launch_scatter_ids(const int32_t* ids, int32_t* cur, int batch, int block_len, int r, hipStream_t s) {
-  scatter_ids_kernel<<<(batch + 255) / 256, 256, 0, s>>>(ids, cur, batch, block_len, r);
+hipError_t launch_scatter_ids(const int32_t* ids, int32_t* cur, int batch, int block_len, int r, int eos_id,
+                              int32_t* finished, hipStream_t s) {
+  if (batch <= 0) return hipErrorInvalidValue;
+  scatter_ids_kernel<<<(batch + 255) / 256, 256, 0, s>>>(ids, cur, batch, block_len, r, eos_id, finished);
+  return hipGetLastError();
+}
+
+// dst[i] = src[i] for n 16-byte chunks (a kernel rather than a copy node, so that the launch may sit
+// in a captured graph next to the others).
+__global__ void copy16_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
+hipError_t launch_copy16(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  if ((bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return hipErrorInvalidValue;
+  const size_t n = bytes / 16;
+  copy16_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(reinterpret_cast<uint4*>(dst), reinterpret_cast<const uint4*>(src), n);
   return hipGetLastError();
 }
 

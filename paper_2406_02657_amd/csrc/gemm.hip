@@ -197,11 +197,13 @@ __device__ __forceinline__ void epilogue_tiles(const EpiArgs& ea, int split, int
       for (int j = 0; j < TN; ++j)
         epilogue_store4<T, EPI_PARTIAL>(ea, split, row_base + i * 16 + row_l, col_base + j * 16 + col_l, acc[i][j]);
   } else if (ea.epi == EPI_F32) {
+    if (ea.out) {                    // null: the caller wants the argmax candidates only
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        epilogue_store4<T, EPI_F32>(ea, split, row_base + i * 16 + row_l, col_base + j * 16 + col_l, acc[i][j]);
+        for (int j = 0; j < TN; ++j)
+          epilogue_store4<T, EPI_F32>(ea, split, row_base + i * 16 + row_l, col_base + j * 16 + col_l, acc[i][j]);
+    }
     if (ea.row_max) {
       // argmax candidates: per row the largest value of this wave's 64 columns and its column, the
       // lowest on ties: own 16 values first (ascending columns), then the four lanes that share the row
@@ -729,8 +731,9 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(KsGroup g) {
       d.row_max[(size_t)row * d.tiles_n + tn] = make_float2(bv, __int_as_float(bi));
     }
   }
-  // EPI_F32 (the launcher admits nothing else here): out = acc + bias, float
-  {
+  // EPI_F32 (the launcher admits nothing else here): out = acc + bias, float; a null out means the
+  // caller wants the candidates only
+  if (d.out) {
     float* outp = reinterpret_cast<float*>(d.out);
 #pragma unroll
     for (int mc = 0; mc < MC; ++mc)
@@ -1084,15 +1087,16 @@ static int pack_kslice(const GemmGroup& g, int tile_cols, KsGroup& k) {
   return begin;
 }
 
+// Kernels that take more dynamic LDS than the default limit get the limit raised once per model
+// (gemm_prepare_kernels, called by bt_create with the model's device current): the attribute belongs
+// to the device's copy of the function, and the launchers keep no state of their own.
+static hipError_t raise_lds_limit(const void* fn) {
+  return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
 template <int KF, int NT, int MC, bool HL>
 static hipError_t launch_kslice(GemmGroup& g, size_t lds, hipStream_t s) {
-  static bool attr_set = false;
   auto kern = gemm_kslice_kernel<KF, NT, MC, HL>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
   KsGroup k;
   const int grid = pack_kslice(g, 64 * NT, k);
   kern<<<grid, 256, lds, s>>>(k);
@@ -1101,13 +1105,7 @@ static hipError_t launch_kslice(GemmGroup& g, size_t lds, hipStream_t s) {
 
 template <int KF, int NT, int MC>
 static hipError_t launch_kslice_pipe(GemmGroup& g, size_t lds, hipStream_t s) {
-  static bool attr_set = false;
   auto kern = gemm_kslice_pipe_kernel<KF, NT, MC>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
   KsGroup k;
   const int grid = pack_kslice(g, 64 * NT, k);
   kern<<<grid, 256, lds, s>>>(k);
@@ -1137,6 +1135,35 @@ static hipError_t launch_kslice_kf(GemmGroup& g, int nt, int mc, size_t lds, hip
     case 42: return launch_kslice<KF, 4, 2, HL>(g, lds, s);
     default: return hipErrorInvalidValue;
   }
+}
+
+template <int KF, bool HL>
+static hipError_t prepare_kslice_kf() {
+  hipError_t e = hipSuccess;
+  auto up = [&](const void* fn) { if (e == hipSuccess) e = raise_lds_limit(fn); };
+  up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 1, 1, HL>));
+  up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 1, 2, HL>));
+  up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 1, 4, HL>));
+  up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 2, 1, HL>));
+  up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 2, 2, HL>));
+  up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 2, 4, HL>));
+  up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 4, 1, HL>));
+  up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 4, 2, HL>));
+  return e;
+}
+
+hipError_t gemm_prepare_kernels() {
+  hipError_t e = hipSuccess;
+  auto step = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+  step(prepare_kslice_kf<2, false>()); step(prepare_kslice_kf<2, true>());
+  step(prepare_kslice_kf<4, false>()); step(prepare_kslice_kf<4, true>());
+  step(prepare_kslice_kf<6, false>()); step(prepare_kslice_kf<6, true>());
+  step(prepare_kslice_kf<8, false>()); step(prepare_kslice_kf<8, true>());
+  step(raise_lds_limit(reinterpret_cast<const void*>(gemm_kslice_pipe_kernel<2, 1, 4>)));
+  step(raise_lds_limit(reinterpret_cast<const void*>(gemm_kslice_pipe_kernel<2, 2, 4>)));
+  step(raise_lds_limit(reinterpret_cast<const void*>(gemm_bf16_big_kernel<true>)));
+  step(raise_lds_limit(reinterpret_cast<const void*>(gemm_bf16_big_kernel<false>)));
+  return e;
 }
 
 hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const GemmPlan& plan, hipStream_t s) {
@@ -1176,13 +1203,6 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
       break;
     case KIND_TILE256: {
       const size_t lds = (size_t)(512 + (hl ? 256 : 0)) * 72 * 2;
-      static bool attr_set[2] = {false, false};
-      const void* fn = hl ? reinterpret_cast<const void*>(gemm_bf16_big_kernel<true>) : reinterpret_cast<const void*>(gemm_bf16_big_kernel<false>);
-      if (!attr_set[hl]) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set[hl] = true;
-      }
       if (hl) gemm_bf16_big_kernel<true><<<fill_tiles<256, 256>(g), 512, lds, s>>>(g);
       else gemm_bf16_big_kernel<false><<<fill_tiles<256, 256>(g), 512, lds, s>>>(g);
       break;

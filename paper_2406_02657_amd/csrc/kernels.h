@@ -66,7 +66,11 @@ hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* nex
 hipError_t launch_argmax_candidates(const float2* cand, int n_tiles, int batch, int32_t* next_ids,
                                     int32_t* cur, int block_len, int r, int eos_id, int32_t* finished, hipStream_t s);
 
-hipError_t launch_scatter_ids(const int32_t* ids, int32_t* cur, int batch, int block_len, int r, hipStream_t s);
+// cur[b*L_B + r] = ids[b]; with eos_id >= 0 also finished[b] = 1 where ids[b] == eos_id
+hipError_t launch_scatter_ids(const int32_t* ids, int32_t* cur, int batch, int block_len, int r, int eos_id,
+                              int32_t* finished, hipStream_t s);
+// dst = src, `bytes` a multiple of 16, both 16-byte aligned
+hipError_t launch_copy16(void* dst, const void* src, size_t bytes, hipStream_t s);
 // out[b] = cur[b*L_B + r]
 hipError_t launch_gather_ids(const int32_t* cur, int32_t* out, int batch, int block_len, int r, hipStream_t s);
 // p[i] = value for i < n: the device-side counts of cached blocks, one per sequence
@@ -148,6 +152,9 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
 bool gemm_has_lse_epilogue(const GemmPlan& plan);
 // Number of candidate tiles the launch writes per row (0: this plan does not produce them).
 int gemm_row_max_tiles(const GemmProblem& p, const GemmPlan& plan);
+// Raises the dynamic-LDS limit of every GEMM kernel that needs it, for the current device.  Call once
+// per model before the first launch_gemm (and before any stream capture).
+hipError_t gemm_prepare_kernels();
 // Up to two independent problems in one launch.
 hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const GemmPlan& plan, hipStream_t s);
 

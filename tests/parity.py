@@ -13,17 +13,18 @@ import numpy as np
 def gpu_generate(model, prompts_np, n_new, want_logits=True):
     """Run prefill + n_new decode steps.  Returns (ids [B, n_new], logits [B, n_new, V] or None)."""
     import torch
-    toks = torch.from_numpy(np.ascontiguousarray(prompts_np, dtype=np.int32)).to(model.device)
-    model.bt_prefill(toks)
-    ids, lgs = [], []
-    for _ in range(n_new):
-        ids.append(model.bt_decode_step().clone())
-        if want_logits:
-            lgs.append(model.bt_get_logits())
+    with model.on_stream():          # the model's own stream is torch's current one: no waits between calls
+        toks = torch.from_numpy(np.ascontiguousarray(prompts_np, dtype=np.int32)).to(model.device)
+        model.bt_prefill(toks)
+        ids, lgs = [], []
+        for _ in range(n_new):
+            ids.append(model.bt_decode_step().clone())
+            if want_logits:
+                lgs.append(model.bt_get_logits())
+        ids = torch.stack(ids, 1)
+        lgs = torch.stack(lgs, 1) if want_logits else None
     torch.cuda.synchronize()
-    ids = torch.stack(ids, 1).cpu().numpy()
-    lgs = torch.stack(lgs, 1).cpu().numpy() if want_logits else None
-    return ids, lgs
+    return ids.cpu().numpy(), (lgs.cpu().numpy() if want_logits else None)
 
 
 def compare_with_oracle(cfg, weights, prompts_np, gpu_ids, gpu_logits, tol, margin=2e-2, seqs=None):
@@ -54,13 +55,15 @@ def gpu_generate_ragged(model, prompts, n_new):
     buf = np.full((len(prompts), max(lens)), 1, dtype=np.int32)      # the tail of a shorter row must not be read
     for b, p in enumerate(prompts):
         buf[b, :lens[b]] = p
-    model.bt_prefill_ragged(torch.from_numpy(buf).to(model.device), lens)
-    ids, lgs = [], []
-    for _ in range(n_new):
-        ids.append(model.bt_decode_step().clone())
-        lgs.append(model.bt_get_logits())
+    with model.on_stream():
+        model.bt_prefill_ragged(torch.from_numpy(buf).to(model.device), lens)
+        ids, lgs = [], []
+        for _ in range(n_new):
+            ids.append(model.bt_decode_step().clone())
+            lgs.append(model.bt_get_logits())
+        ids, lgs = torch.stack(ids, 1), torch.stack(lgs, 1)
     torch.cuda.synchronize()
-    return torch.stack(ids, 1).cpu().numpy(), torch.stack(lgs, 1).cpu().numpy()
+    return ids.cpu().numpy(), lgs.cpu().numpy()
 
 
 def compare_ragged_with_oracle(cfg, weights, prompts, gpu_ids, gpu_logits, tol, margin=2e-2):
@@ -94,16 +97,17 @@ def gpu_generate_sampled(model, prompts_np, n_new, seqs, steps):
     Returns (ids [B, n_new] int32, {step: float32 [len(seqs), V]}).
     """
     import torch
-    toks = torch.from_numpy(np.ascontiguousarray(prompts_np, dtype=np.int32)).to(model.device)
-    sel = torch.tensor(list(seqs), device=model.device, dtype=torch.long)
-    ids = torch.empty(n_new, prompts_np.shape[0], dtype=torch.int32, device=model.device)
     want = set(int(s) for s in steps)
     kept = {}
-    model.bt_prefill(toks)
-    for t in range(n_new):
-        model.bt_decode_step(ids[t])
-        if t in want:
-            kept[t] = model.bt_get_logits()[sel].clone()
+    with model.on_stream():
+        toks = torch.from_numpy(np.ascontiguousarray(prompts_np, dtype=np.int32)).to(model.device)
+        sel = torch.tensor(list(seqs), device=model.device, dtype=torch.long)
+        ids = torch.empty(n_new, prompts_np.shape[0], dtype=torch.int32, device=model.device)
+        model.bt_prefill(toks)
+        for t in range(n_new):
+            model.bt_decode_step(ids[t])
+            if t in want:
+                kept[t] = model.bt_get_logits()[sel].clone()
     torch.cuda.synchronize()
     return ids.t().contiguous().cpu().numpy(), {t: v.cpu().numpy() for t, v in kept.items()}
 

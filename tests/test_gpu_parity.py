@@ -233,7 +233,15 @@ def test_graph_replay_equals_eager(amd):
             ids, lgs = gpu_generate(m, prompts, 37)
             torch.cuda.synchronize()
             runs.append((ids, lgs))
+        st = m.bt_get_stats()
         m.close()
+        if mode:
+            # every step kind (r = 0..3 without, r = 0 with the block decoder) was captured at its second
+            # occurrence and replayed from then on: the comparison below is graph replay against eager
+            assert st.graph_fallback == 0 and st.graph_captures == cfg.block_len + 1, (st.graph_fallback, st.graph_captures)
+            assert st.graph_launches >= 2 * 37 - 2 * (cfg.block_len + 1), st.graph_launches
+        else:
+            assert st.graph_launches == 0 and st.graph_captures == 0 and st.graph_fallback == 0
         assert np.array_equal(runs[0][0], runs[1][0]) and np.array_equal(runs[0][1], runs[1][1])
         out[mode] = runs[0]
     assert np.array_equal(out[0][0], out[1][0])
@@ -502,3 +510,137 @@ def test_ragged_batch_with_eos(amd):
         else:
             assert np.array_equal(ids[b], free[b]) and flags[b] == 0
     assert flags[2] == 1
+
+
+def test_graph_replay_without_prefix(amd):
+    """L_B = 1 with no prefix (the context embedding is the token decoder's input row): the decode
+    steps are captured and replayed like any other, and equal the eager launches bit for bit."""
+    cfg = tiny_cfg(dtype="bf16", d_model=128, n_heads=2, d_ff=256, vocab=300, block_len=1, prefix_len=0, prompt_len=9)
+    W = make_weights(cfg)
+    prompts = make_prompts(cfg, batch=5)
+    out = {}
+    for mode in (0, 1):
+        m = amd.Model(cfg, W, max_batch=5, max_blocks=40, use_graphs=mode)
+        out[mode] = gpu_generate(m, prompts, 21)
+        st = m.bt_get_stats()
+        m.close()
+        if mode:
+            assert st.graph_fallback == 0 and st.graph_captures == 2 and st.graph_launches == 21 - 2, (
+                st.graph_fallback, st.graph_captures, st.graph_launches)
+    assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
+    rep = compare_with_oracle(cfg, W, prompts, out[1][0], out[1][1], TOL_BF16)
+    assert_parity(rep)
+
+
+def test_default_stream_falls_back_to_eager_and_says_so(amd):
+    """HIP cannot capture on the default stream: a model created on it runs eagerly and reports it."""
+    import ctypes as C
+    import torch
+    cfg = tiny_cfg(dtype="bf16", d_model=128, n_heads=2, d_ff=256, vocab=300, prompt_len=8)
+    W = make_weights(cfg)
+    prompts = make_prompts(cfg, batch=2)
+    ref = amd.Model(cfg, W, max_batch=2, max_blocks=16, use_graphs=0)
+    want = gpu_generate(ref, prompts, 13)
+    ref.close()
+    m = amd.Model(cfg, W, max_batch=2, max_blocks=16, use_graphs=1, stream=torch.cuda.default_stream())
+    got = gpu_generate(m, prompts, 13)
+    st = m.bt_get_stats()
+    msg = amd.lib.bt_last_error(m.h)
+    m.close()
+    assert st.graph_fallback == 1 and st.graph_launches == 0 and b"default stream" in msg
+    assert np.array_equal(want[0], got[0]) and np.array_equal(want[1], got[1])
+
+
+def test_state_after_scoring_and_forced_eos(amd):
+    """bt_score ends any generation in progress: the calls that need a decode step say so; a forced
+    end-of-sequence id marks its sequence finished like an emitted one."""
+    import torch
+    cfg = tiny_cfg(dtype="fp32", d_model=64, n_heads=2, d_ff=128, vocab=40, block_len=4, prefix_len=1, prompt_len=8,
+                   eos_id=7)
+    W = make_weights(cfg)
+    m = amd.Model(cfg, W, max_batch=3, max_blocks=8, score_rows=16)
+    toks = torch.from_numpy(make_prompts(cfg, batch=3)).to(m.device)
+    m.bt_prefill(toks)
+    ids = m.bt_decode_step().clone()
+    forced = ids.clone()
+    forced[1] = 7
+    forced[0] = 8 if int(ids[0]) != 7 else 7
+    m.bt_force_last_ids(forced)
+    fl = m.bt_get_finished().cpu().numpy()
+    assert fl[1] == 1 and fl[0] == (1 if int(ids[0]) == 7 else 0)
+    nxt = m.bt_decode_step().cpu().numpy()
+    assert nxt[1] == 7                                   # a finished sequence keeps emitting eos_id
+    m.bt_score(toks)
+    lg = torch.empty(3, cfg.vocab, device=m.device)
+    assert amd.lib.bt_get_logits(m.h, lg.data_ptr()) == amd.binding.BT_ERR_STATE
+    assert amd.lib.bt_force_last_ids(m.h, forced.data_ptr()) == amd.binding.BT_ERR_STATE
+    assert amd.lib.bt_decode_step(m.h, 3, forced.data_ptr()) == amd.binding.BT_ERR_STATE
+    torch.cuda.synchronize()
+    m.close()
+
+
+def test_keep_logits_off_same_ids(amd):
+    """keep_logits = 0 (what the benchmark times): the LM head leaves argmax candidates only; the ids
+    equal those of the run that also stores the logits, and bt_get_logits refuses."""
+    import torch
+    cfg = tiny_cfg(dtype="bf16", d_model=256, n_heads=4, d_ff=512, vocab=5000, block_len=4, prefix_len=1, prompt_len=16)
+    W = make_weights(cfg)
+    for B in (6, 200):                                   # K-slice head kernel; 256 x 256 tiled head kernel
+        prompts = make_prompts(cfg, batch=B)
+        ids = {}
+        for keep in (1, 0):
+            m = amd.Model(cfg, W, max_batch=B, max_blocks=16, keep_logits=keep)
+            ids[keep], _ = gpu_generate(m, prompts, 11, want_logits=False)
+            if not keep:
+                lg = torch.empty(B, cfg.vocab, device=m.device)
+                assert amd.lib.bt_get_logits(m.h, lg.data_ptr()) == amd.binding.BT_ERR_STATE
+            m.close()
+        assert np.array_equal(ids[0], ids[1])
+
+
+def _tie_weights(cfg, pair, zero_head=False):
+    """Weights whose final hidden state is the same known vector for every row (final LayerNorm with
+    gamma = 0, so its output is beta exactly), with two bit-identical LM-head rows that hold the
+    largest logit: an exact tie that greedy decoding must break towards the lower id."""
+    from synth import bf16_bits_to_f32, f32_to_bf16_bits
+    W = dict(make_weights(cfg))
+    W["tok_lnf_g"] = np.zeros_like(W["tok_lnf_g"])
+    beta = W["tok_lnf_b"].astype(np.float32)
+    head = W["W_head"]
+    if zero_head:
+        W["W_head"] = np.zeros_like(head)
+        return W
+    row = (beta / np.abs(beta).max() * 0.25).astype(np.float32)      # logit = 0.25 |beta|^2 / max|beta|, far above the rest
+    head = head.copy()
+    for v in pair:
+        head[v] = f32_to_bf16_bits(row) if head.dtype == np.uint16 else row
+    W["W_head"] = head
+    hf = bf16_bits_to_f32(head) if head.dtype == np.uint16 else head
+    lg = hf.astype(np.float64) @ beta.astype(np.float64)
+    top = np.sort(lg)[-3:]
+    assert top[-1] == top[-2] and top[-1] - top[-3] > 0.05 and set(np.argsort(lg)[-2:]) == set(pair)
+    return W
+
+
+@pytest.mark.parametrize("path,dtype,B,V", [("scan", "fp32", 3, 600), ("kslice", "bf16", 4, 4160), ("tiled", "bf16", 200, 4160)])
+def test_exact_logit_ties_pick_the_lowest_id(amd, path, dtype, B, V):
+    """Exact ties through each of the three argmax implementations (logit scan in fp32 mode; per-workgroup
+    candidates of the K-slice LM head; per-wave candidates of the tiled LM head): identical head rows
+    in the same 16-column group, in neighbouring 64-column groups and far apart, and an all-zero head."""
+    cfg = tiny_cfg(dtype=dtype, d_model=128, n_heads=2, d_ff=256, vocab=V, block_len=4, prefix_len=1, prompt_len=8)
+    prompts = make_prompts(cfg, batch=B)
+    pairs = [(33, 37), (40, 104), (100, V - 7), (V - 70, V - 1)]
+    for pair in pairs:
+        W = _tie_weights(cfg, pair)
+        m = amd.Model(cfg, W, max_batch=B, max_blocks=8)
+        ids, lgs = gpu_generate(m, prompts, 6)
+        m.close()
+        assert np.array_equal(lgs[..., pair[0]], lgs[..., pair[1]]), pair       # the tie is exact on the GPU
+        assert np.all(lgs.argmax(-1) == pair[0]) and np.all(ids == pair[0]), (path, pair, np.unique(ids))
+        rep = compare_with_oracle(cfg, W, prompts, ids, lgs, TOL_F32 if dtype == "fp32" else TOL_BF16)
+        assert rep["max_abs_logit_diff"] <= rep["tol"], rep
+    W = _tie_weights(cfg, None, zero_head=True)
+    m = amd.Model(cfg, W, max_batch=B, max_blocks=8)
+    ids, lgs = gpu_generate(m, prompts, 6)
+    m.close()
+    assert np.all(lgs == 0.0) and np.all(ids == 0)

@@ -626,3 +626,93 @@ def test_score_nll_of_a_length_that_is_not_whole_blocks():
     b = O.score_nll(P, cfg, by_hand)
     assert a.shape == (2, 10) and np.array_equal(a, b[:, 2:])
     assert np.all(a[:, :2] == 0.0) and np.all(a[:, 2:] > 0.0)      # first block = 2 pads + 2 tokens: those 2 are not scored
+
+
+# --------------------------------------------------------------------------
+# bf16 storage: the path by which bf16-mode weights reach the oracle's float64 arithmetic
+# (weights are drawn in float32, rounded to the nearest bf16 with ties to even, stored as
+# bit patterns, and widened exactly).  The format is fixed: 1 sign, 8 exponent, 7 mantissa bits,
+# the upper half of an IEEE float32.  Values below are worked out by hand from that definition.
+# --------------------------------------------------------------------------
+def test_bf16_bit_patterns_widen_to_hand_computed_values():
+    from synth import bf16_bits_to_f32
+    pats = np.array([0x3F80, 0xC000, 0x3DCD, 0x0001, 0x0000, 0x8000, 0x7F7F, 0x0080, 0x4049], dtype=np.uint16)
+    want = np.array([
+        1.0,                                   # exponent 127, mantissa 0
+        -2.0,                                  # sign, exponent 128
+        (1.0 + 77.0 / 128.0) * 2.0 ** -4,      # 0x3DCD: exponent 123, mantissa 0x4D = 77 -> 0.10009765625
+        2.0 ** -133,                           # smallest subnormal: 2^-126 * 1/128
+        0.0, -0.0,
+        (2.0 - 2.0 ** -7) * 2.0 ** 127,        # largest finite
+        2.0 ** -126,                           # smallest normal
+        (1.0 + 73.0 / 128.0) * 2.0,            # 0x4049 = 3.140625
+    ])
+    assert want[2] == 0.10009765625 and want[8] == 3.140625
+    got = bf16_bits_to_f32(pats)
+    assert got.dtype == np.float32 and np.array_equal(got.astype(np.float64), want)
+    assert np.signbit(got[5]) and not np.signbit(got[4])
+    # the oracle's own widening (Params) gives the same float64 values, for any array shape
+    P = O.Params({"w": pats.reshape(3, 3)})
+    w = P("w")
+    assert w.dtype == np.float64 and np.array_equal(w.ravel(), want) and np.signbit(w.ravel()[5])
+    # float32 arrays pass through Params unchanged in value
+    f = np.array([0.1, -3.5, 1e-30], dtype=np.float32)
+    assert np.array_equal(O.Params({"f": f})("f"), f.astype(np.float64))
+
+
+def test_f32_to_bf16_rounds_to_nearest_even():
+    from synth import bf16_bits_to_f32, f32_to_bf16_bits
+    def f32(bits):
+        return np.array([bits], dtype=np.uint32).view(np.float32)
+    cases = [
+        (f32(0x3F808000), 0x3F80),     # 1 + 2^-8: exactly between 0x3F80 and 0x3F81 -> the even one
+        (f32(0x3F818000), 0x3F82),     # 1 + 3*2^-8: between 0x3F81 and 0x3F82 -> even
+        (f32(0x3F808001), 0x3F81),     # just above the tie -> up
+        (f32(0x3F807FFF), 0x3F80),     # just below -> down
+        (f32(0x3FFFFFFF), 0x4000),     # just under 2: the carry runs into the exponent
+        (f32(0x7F7FFFFF), 0x7F80),     # largest float32 rounds to +inf, as IEEE rounding does
+        (f32(0xBF808000), 0xBF80),     # ties are symmetric in sign
+        (f32(0x00000000), 0x0000), (f32(0x80000000), 0x8000),
+        (np.array([0.1], dtype=np.float32), 0x3DCD),      # 0.1f = 0x3DCCCCCD -> 0x3DCD
+    ]
+    for x, want in cases:
+        assert int(f32_to_bf16_bits(x)[0]) == want, (hex(int(x.view(np.uint32)[0])), hex(want))
+    # every non-NaN bf16 value survives widening and rounding back unchanged (65 280 patterns)
+    allp = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    is_nan = ((allp & 0x7F80) == 0x7F80) & ((allp & 0x007F) != 0)
+    p = allp[~is_nan]
+    assert p.size == 65536 - 2 * 127
+    assert np.array_equal(f32_to_bf16_bits(bf16_bits_to_f32(p)), p)
+    # rounding error is at most half a unit in the last of 8 significant bits
+    rng = np.random.default_rng(3)
+    x = (rng.standard_normal(20000) * 0.02).astype(np.float32)
+    back = bf16_bits_to_f32(f32_to_bf16_bits(x)).astype(np.float64)
+    assert np.all(np.abs(back - x) <= np.abs(x.astype(np.float64)) * 2.0 ** -8)
+    # and it is the NEAREST bf16: neither neighbour is closer
+    bits = f32_to_bf16_bits(x).astype(np.int64)
+    for d in (-1, 1):
+        nb = bf16_bits_to_f32((bits + d).astype(np.uint16)).astype(np.float64)
+        assert np.all(np.abs(back - x) <= np.abs(nb - x))
+
+
+@pytest.mark.parametrize("lb,p", [(4, 2), (1, 0)])
+def test_cached_equals_full_with_bf16_weights(lb, p):
+    """The same T1 check through the bf16 storage path, and against float32 weights holding the
+    widened values: the oracle sees bf16-mode weights as exactly those numbers."""
+    from synth import bf16_bits_to_f32
+    cfg = tiny_cfg(dtype="bf16", block_len=lb, prefix_len=p, prompt_len=2 * lb, d_model=32, n_heads=2)
+    W = make_weights(cfg)
+    assert W["W_head"].dtype == np.uint16 and W["blk.0.W_qkv"].dtype == np.uint16 and W["blk.0.b_qkv"].dtype == np.float32
+    prompts = make_prompts(cfg, batch=3)
+    n_new = 2 * lb + 3
+    ids_f, lg_f = O.generate_full(O.Params(W), cfg, prompts, n_new)
+    ids_c, lg_c, _ = O.generate_cached(O.Params(W, keep=False), cfg, prompts, n_new)
+    assert np.array_equal(ids_f, ids_c) and np.max(np.abs(lg_f - lg_c)) < TOL
+    W32 = {k: (bf16_bits_to_f32(v) if v.dtype == np.uint16 else v) for k, v in W.items()}
+    ids_w, lg_w = O.generate_full(O.Params(W32), cfg.with_(dtype="fp32"), prompts, n_new)
+    assert np.array_equal(ids_f, ids_w) and np.array_equal(lg_f, lg_w)
+    # the rounding is really there: the float32 draw of the same seed gives other logits
+    Wf = make_weights(cfg.with_(dtype="fp32"))
+    assert np.array_equal(bf16_bits_to_f32(W["W_head"]), bf16_bits_to_f32(__import__("synth").f32_to_bf16_bits(Wf["W_head"])))
+    _, lg_u = O.generate_full(O.Params(Wf), cfg.with_(dtype="fp32"), prompts, 1)
+    assert np.max(np.abs(lg_u - lg_f[:, :1])) > 1e-6
