@@ -97,22 +97,23 @@ def score_bench(args, cfg, W):
     T = (cfg.prompt_len + cfg.gen_len) // cfg.block_len * cfg.block_len
     toks_np = make_prompts(cfg, prompt_len=T)
     model = amd.Model(cfg, W, max_blocks=T // cfg.block_len, score_rows=4096)
-    toks = torch.from_numpy(toks_np).cuda()
     log(f"scoring {cfg.batch} x {T} tokens; workspace {model.workspace_bytes / 2**30:.2f} GiB")
-    for _ in range(args.warmup):
-        model.bt_score(toks)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        model.bt_score(toks)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    model.bt_set_profile(True)
-    model.bt_reset_profile()
-    nll = model.bt_score(toks)
-    torch.cuda.synchronize()
-    st = model.bt_get_stats()
-    model.bt_set_profile(False)
+    with model.on_stream():
+        toks = torch.from_numpy(toks_np).cuda()
+        for _ in range(args.warmup):
+            model.bt_score(toks)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            model.bt_score(toks)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        model.bt_set_profile(True)
+        model.bt_reset_profile()
+        nll = model.bt_score(toks)
+        torch.cuda.synchronize()
+        st = model.bt_get_stats()
+        model.bt_set_profile(False)
     scored = cfg.batch * (T - cfg.block_len)
     ms = wall * 1e3 / args.steps
     planes = 2 if cfg.dtype == "bf16" else 1
@@ -180,6 +181,9 @@ def main():
                     help="time teacher-forced scoring (bt_score) of batch x (prompt + generated) tokens instead of "
                          "generation; a step is one scoring pass over the whole batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-workloads", action="store_true",
+                    help="the default run (workload cfg1, nothing overridden) also measures cfg2, cfg3 and cfg4 and reports "
+                         "them under \"workloads\"; this flag skips them")
     ap.add_argument("--no-attn-events", action="store_true", help="skip the profiled pass that brackets the "
                     "block-attention launches with HIP events (no roofline object)")
     ap.add_argument("--events-in-timed-region", action="store_true",
@@ -207,7 +211,7 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "copies": 4}))
         return
-    from synth import CONFIGS, make_prompts, make_weights
+    from synth import CONFIGS
     import paper_2406_02657_amd as amd
 
     cfg = CONFIGS[args.workload]
@@ -223,76 +227,130 @@ def main():
         cfg = cfg.with_(block_len=args.block_len)
     if args.max_batch:
         cfg = cfg.with_(batch=largest_batch(cfg, amd, torch))
+    if args.score:
+        from synth import make_weights
+        score_bench(args, cfg, make_weights(cfg))
+        return
+    overridden = bool(args.gen_len or args.batch or args.prompt_len or args.prefix_len >= 0 or args.block_len
+                      or args.max_batch)
+    res, W, prompts = run_generation(args, amd, torch, cfg, args.steps, args.warmup, overridden)
+    out = {
+        "metric": "output tokens/sec on 1 MI355X", "value": res.pop("tokens_per_s"), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": res.pop("ms_per_job"), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+    }
+    out.update(res)
+    # The metric names a decode-heavy and a prefill-heavy workload, and the 60 % target for the decode
+    # attention is a statement about the large configuration: the default run measures those as well,
+    # each with a short warm-up job, EXTRA_STEPS timed jobs and one profiled job.
+    if args.workload == "cfg1" and not overridden and not args.no_extra_workloads:
+        extra = {}
+        for name in ("cfg2", "cfg3", "cfg4"):
+            t0 = time.perf_counter()
+            r, _, _ = run_generation(args, amd, torch, CONFIGS[name], EXTRA_STEPS[name], 0, False, short_warmup=True,
+                                     keep_inputs=False)
+            r["steps"], r["warmup"] = EXTRA_STEPS[name], "one short job (prefill + 5 L_B decode steps)"
+            extra[name] = r
+            log(f"{name}: {r['tokens_per_s'] / 1e3:.1f} k tokens/s ({time.perf_counter() - t0:.0f} s with input generation)")
+        out["workloads"] = extra
+    if not args.no_cpu_baseline:
+        t0 = time.perf_counter()
+        out["cpu_baseline"] = cpu_baseline(cfg, W, prompts)
+        log(f"cpu baseline took {time.perf_counter() - t0:.1f} s")
+    print(json.dumps(out), flush=True)
+
+
+# timed whole jobs of the extra workloads of the default run (their own, small counts)
+EXTRA_STEPS = {"cfg2": 5, "cfg3": 2, "cfg4": 1}
+
+
+def read_profile_keys(fname, keys):
+    """key=value lines of a committed rocprofv3 summary under profiles/ (floats)."""
+    got = {}
+    try:
+        for line in open(os.path.join(ROOT, "profiles", fname)):
+            for key in keys:
+                if line.startswith(key + "="):
+                    got[key] = float(line.split("=")[1])
+    except OSError:
+        pass
+    return got
+
+
+def run_generation(args, amd, torch, cfg, steps, warmup, overridden, short_warmup=False, keep_inputs=True):
+    """Times `steps` whole jobs of the workload (after `warmup` whole jobs, or one short job) and runs one
+    more job with HIP events around the launches the roofline objects describe.  Returns (dict, W, prompts)."""
+    from synth import make_prompts, make_weights
     log(f"workload {cfg.name}: B={cfg.batch} prompt={cfg.prompt_len} gen={cfg.gen_len} L_B={cfg.block_len} "
         f"D={cfg.d_model} layers={cfg.n_block_layers}+{cfg.n_token_layers} P={cfg.prefix_len} dtype={cfg.dtype}")
     t0 = time.perf_counter()
     W = make_weights(cfg)
-    if args.score:
-        score_bench(args, cfg, W)
-        return
     prompts = make_prompts(cfg)
     log(f"inputs generated in {time.perf_counter() - t0:.1f} s")
-    model = amd.Model(cfg, W)
-    toks = torch.from_numpy(prompts).cuda()
-    out_ids = torch.empty(cfg.gen_len, cfg.batch, dtype=torch.int32, device="cuda")
-    log(f"workspace {model.workspace_bytes / 2**30:.2f} GiB")
+    # keep_logits = 0: greedy decoding needs the ids only; the LM head leaves the argmax candidates and does
+    # not write the float logits (tests check that the ids are those of the run that stores them)
+    model = amd.Model(cfg, W, keep_logits=0)
+    if not keep_inputs:
+        W = None
+    with model.on_stream():
+        toks = torch.from_numpy(prompts).cuda()
+        out_ids = torch.empty(cfg.gen_len, cfg.batch, dtype=torch.int32, device="cuda")
+        log(f"workspace {model.workspace_bytes / 2**30:.2f} GiB")
 
-    def job():
-        model.bt_prefill(toks)
-        for t in range(cfg.gen_len):
-            model.bt_decode_step(out_ids[t])
+        def job(n_steps=cfg.gen_len):
+            model.bt_prefill(toks)
+            for t in range(n_steps):
+                model.bt_decode_step(out_ids[t])
 
-    def timed_job():
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        ev[0].record()
-        model.bt_prefill(toks)
-        ev[1].record()
-        for t in range(cfg.gen_len):
-            model.bt_decode_step(out_ids[t])
-        ev[2].record()
-        return ev
+        def timed_job():
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            ev[0].record()
+            model.bt_prefill(toks)
+            ev[1].record()
+            for t in range(cfg.gen_len):
+                model.bt_decode_step(out_ids[t])
+            ev[2].record()
+            return ev
 
-    for _ in range(args.warmup):
-        job()
-    torch.cuda.synchronize()
-    in_region = args.events_in_timed_region and not args.no_attn_events
-    model.bt_set_profile(in_region)
-    model.bt_reset_profile()
-    evs = []
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        evs.append(timed_job())
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    if not in_region and not args.no_attn_events:
-        # One more job of the same workload, right after the timed steps, with HIP events around
-        # every block-attention launch (recorded by the library on the launch stream).  Events
-        # cannot sit inside a captured graph, so this pass issues its launches one by one; the
-        # kernel, its inputs and its launch shape are those of the timed steps.
-        model.bt_set_profile(True)
-        model.bt_reset_profile()
-        job()
+        if short_warmup:
+            job(min(cfg.gen_len, 5 * cfg.block_len))      # every step kind occurs three times: eager, captured, replayed
+        for _ in range(warmup):
+            job()
         torch.cuda.synchronize()
-    st = model.bt_get_stats()
-    model.bt_set_profile(False)
-    ms_per_step = wall * 1e3 / args.steps
-    prefill_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
-    decode_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
-    value = cfg.batch * cfg.gen_len / (ms_per_step / 1e3)
+        in_region = args.events_in_timed_region and not args.no_attn_events
+        model.bt_set_profile(in_region)
+        model.bt_reset_profile()
+        evs = []
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            evs.append(timed_job())
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        st_timed = model.bt_get_stats()
+        if not in_region and not args.no_attn_events:
+            # One more job of the same workload, right after the timed steps, with HIP events around
+            # every block-attention launch and every projection GEMM launch (recorded by the library on
+            # the launch stream).  Events cannot sit inside a captured graph, so this pass issues its
+            # launches one by one; kernels, inputs and launch shapes are those of the timed steps.
+            model.bt_set_profile(True)
+            model.bt_reset_profile()
+            job()
+            torch.cuda.synchronize()
+        st = model.bt_get_stats()
+        model.bt_set_profile(False)
+    ms_per_job = wall * 1e3 / steps
+    prefill_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / steps
+    decode_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / steps
+    value = cfg.batch * cfg.gen_len / (ms_per_job / 1e3)
 
     # HBM traffic of that kernel per launch, from the committed rocprofv3 --pmc summary (FETCH_SIZE and
     # WRITE_SIZE, each scaled by a plain copy of known size): K/V bytes are fetched `kv` times, and
     # the launch reads / writes a constant amount besides (q, k, v and MLP pieces in; GELU, output out)
-    pmc = {}
-    try:
-        for line in open(os.path.join(ROOT, "profiles", "cfg1_hbm_traffic_pmc.txt")):
-            for key in ("kv_read_over_algorithmic", "other_read_bytes", "write_bytes"):
-                if line.startswith(key + "="):
-                    pmc[key] = float(line.split("=")[1])
-    except OSError:
-        pass
-    pmc_ok = len(pmc) == 3 and cfg.name == "cfg1" and not args.batch
+    pmc = read_profile_keys("cfg1_hbm_traffic_pmc.txt", ("kv_read_over_algorithmic", "other_read_bytes", "write_bytes"))
+    pmc_ok = len(pmc) == 3 and cfg.name == "cfg1" and not overridden
+    trace = {} if overridden else read_profile_keys(f"{cfg.name}_generation_kernel_stats.txt",
+                                                    ("attn_block_decode_avg_us", "attn_block_decode_bytes_per_launch"))
     roofline = None
     if st.attn_block_launches > 0 and st.attn_block_ms > 0:
         ach = st.attn_block_bytes / (st.attn_block_ms * 1e-3) / 1e9
@@ -304,17 +362,25 @@ def main():
             "traffic": (pmc["kv_read_over_algorithmic"] * st.attn_block_bytes / st.attn_block_launches
                         + pmc["other_read_bytes"] + pmc["write_bytes"]) if pmc_ok else None,
             "traffic_note": "HBM bytes per launch from profiles/cfg1_hbm_traffic_pmc.txt (rocprofv3 --pmc FETCH_SIZE, "
-                            "WRITE_SIZE at two cache lengths): 1.015 x this run's K/V bytes per launch + 5.44 MB of other "
-                            "inputs (split-K pieces of q, k, v and of the MLP up-projection) + 1.18 MB written",
+                            "WRITE_SIZE at two cache lengths, scaled by a plain copy): K/V bytes x the measured factor + the "
+                            "launch's other inputs (split-K pieces of q, k, v and of the MLP up-projection) + what it writes"
+                            if pmc_ok else None,
             "launches": int(st.attn_block_launches),
             "avg_launch_us": st.attn_block_ms * 1e3 / st.attn_block_launches,
             "avg_bytes_per_launch": st.attn_block_bytes / st.attn_block_launches,
         }
+        if len(trace) == 2:
+            # the same kernel's average duration in the committed rocprofv3 kernel trace of this workload (an
+            # event pair also spans the dispatch of the launch, so the event figure is the lower one)
+            roofline["kernel_trace_avg_us"] = trace["attn_block_decode_avg_us"]
+            roofline["frac_kernel_trace"] = (trace["attn_block_decode_bytes_per_launch"]
+                                             / (trace["attn_block_decode_avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS)
+            roofline["kernel_trace_source"] = f"profiles/{cfg.name}_generation_kernel_stats.txt"
     roofline_gemm = None
+    planes = 2 if cfg.dtype == "bf16" else 1
     if st.gemm_decode_launches > 0 and st.gemm_decode_ms > 0:
         # Weight bytes are read once per launch; every weight meets batch rows x activation planes
         # (bf16 hi + remainder) in the matrix cores.  Which roof is nearer depends on the batch.
-        planes = 2 if cfg.dtype == "bf16" else 1
         secs = st.gemm_decode_ms * 1e-3
         gbs = st.gemm_decode_bytes / secs / 1e9
         esz_w = 2 if cfg.dtype == "bf16" else 4
@@ -322,7 +388,7 @@ def main():
         f_hbm, f_mfma = gbs / HBM_PEAK_GBS, tflops / MFMA_BF16_PEAK_TFLOPS
         by_mfma = cfg.dtype == "bf16" and f_mfma > f_hbm
         roofline_gemm = {
-            "kernel": "gemm_kslice_kernel (grouped projection GEMMs of the decode steps: QKV + MLP-up, O + MLP-down)",
+            "kernel": "grouped projection GEMMs of the decode steps (QKV + MLP-up, O + MLP-down)",
             "bound": "mfma" if by_mfma else "hbm",
             "achieved": tflops if by_mfma else gbs, "peak": MFMA_BF16_PEAK_TFLOPS if by_mfma else HBM_PEAK_GBS,
             "unit": "TFLOP/s" if by_mfma else "GB/s", "frac": f_mfma if by_mfma else f_hbm,
@@ -332,6 +398,22 @@ def main():
             "avg_bytes_per_launch": st.gemm_decode_bytes / st.gemm_decode_launches,
             "note": "bytes = weight bytes, each read once; flops = 2 x weights x batch rows x activation planes "
                     "(the multiplies the matrix cores execute); by time this is the largest kernel of the step",
+        }
+    roofline_prefill = None
+    if st.gemm_tiled_launches > 0 and st.gemm_tiled_ms > 0:
+        # the tiled MFMA launches of the profiled job: the prefill's grouped layer GEMMs (rows = batch x prompt blocks)
+        alg = float(st.gemm_tiled_flops) / (st.gemm_tiled_ms * 1e-3) / 1e12
+        split_prefill = planes if model.c.act_split == 2 else 1
+        roofline_prefill = {
+            "kernel": "tiled MFMA GEMM launches of the prefill (gemm_bf16_big_kernel 256 x 256 tiles / gemm_bf16_kernel<128,128>: "
+                      "QKV + MLP-up, O + MLP-down over batch x prompt-block rows)",
+            "bound": "mfma", "achieved": alg, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": alg / MFMA_BF16_PEAK_TFLOPS,
+            "executed_tflops": alg * split_prefill, "frac_executed": alg * split_prefill / MFMA_BF16_PEAK_TFLOPS,
+            "launches": int(st.gemm_tiled_launches), "avg_launch_us": st.gemm_tiled_ms * 1e3 / st.gemm_tiled_launches,
+            "algorithmic_flops": int(st.gemm_tiled_flops),
+            "note": "achieved = the method's own flops, 2 x rows x N x K, over summed HIP-event time; executed counts the "
+                    "bf16 hi + remainder activation planes the matrix cores multiply (act_split)",
         }
     # whole decode step against the HBM roofline: algorithmic bytes per step (weights + block KV)
     D, F, V, esz = cfg.d_model, cfg.d_ff, cfg.vocab, (2 if cfg.dtype == "bf16" else 4)
@@ -348,25 +430,25 @@ def main():
         "achieved_GBs": alg_bytes_decode / (decode_ms * 1e-3) / 1e9,
         "frac_of_hbm_peak": alg_bytes_decode / (decode_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
     }
+    kind = {"cfg1": "decode-heavy", "cfg3": "decode-heavy", "cfg2": "prefill-heavy", "cfg4": "long (2048 in / 2048 out)",
+            "cfg4v": "cfg4 with L_B = 1 and no prefix (vanilla-equivalent KV cache)"}.get(cfg.name)
     res = {
-        "metric": "output tokens/sec on 1 MI355X", "value": value, "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: decode-heavy" if cfg.name in ("cfg1", "cfg3") else cfg.name,
+        "tokens_per_s": value, "ms_per_job": ms_per_job,
+        "config": {"workload": f"{cfg.name}: {kind}" if kind else cfg.name,
                    "batch": cfg.batch, "prompt_len": cfg.prompt_len, "gen_len": cfg.gen_len,
                    "block_len": cfg.block_len, "d_model": cfg.d_model, "layers": [cfg.n_block_layers, cfg.n_token_layers],
                    "prefix_len": cfg.prefix_len, "vocab": cfg.vocab},
         "prefill_ms": prefill_ms, "decode_ms_per_token_step": decode_ms / cfg.gen_len,
-        "roofline": roofline, "roofline_gemm": roofline_gemm, "decode_step_roofline": step_roof,
+        "roofline": roofline, "roofline_gemm": roofline_gemm, "roofline_prefill_gemm": roofline_prefill,
+        "decode_step_roofline": step_roof,
+        "graphs": {"replayed_steps_in_timed_jobs": int(st_timed.graph_launches), "captures": int(st_timed.graph_captures),
+                   "fallback_to_eager": int(st_timed.graph_fallback),
+                   "decode_steps_in_timed_jobs": (steps + warmup) * cfg.gen_len + (min(cfg.gen_len, 5 * cfg.block_len) if short_warmup else 0)},
     }
     model.close()
     del model
     torch.cuda.empty_cache()
-    if not args.no_cpu_baseline:
-        t0 = time.perf_counter()
-        res["cpu_baseline"] = cpu_baseline(cfg, W, prompts)
-        log(f"cpu baseline took {time.perf_counter() - t0:.1f} s")
-    print(json.dumps(res), flush=True)
+    return res, W, prompts
 
 
 if __name__ == "__main__":

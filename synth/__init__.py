@@ -22,6 +22,9 @@ LayerNorm parameters stay fp32.
 """
 from __future__ import annotations
 
+import os
+import threading
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, replace
 from typing import Dict
 
@@ -172,21 +175,52 @@ def make_weights(cfg: BTConfig, std: float = 0.02) -> Dict[str, np.ndarray]:
     Matrices ~ N(0, std^2); biases and LN beta ~ N(0, std^2) so that every code
     path is exercised; LN gamma = 1 + N(0, std^2).  fp32 mode: float32 arrays.
     bf16 mode: matrices are uint16 bf16 bit patterns, vectors float32.
+
+    Large tensors are drawn piece by piece into one reused buffer (the generator's stream does not
+    depend on how a draw is cut up, so the values are those of a single draw): the billions of
+    weights of the large workloads would otherwise spend most of their time in page faults of
+    temporaries.
     """
     table = tensor_table(cfg)
     children = np.random.SeedSequence(cfg.weights_seed).spawn(len(table))
-    out: Dict[str, np.ndarray] = {}
-    for (name, shape, kind), ss in zip(table, children):
+    piece = 1 << 22
+    local = threading.local()
+
+    def one(item):
+        (name, shape, kind), ss = item
+        if not hasattr(local, "buf"):
+            local.buf = np.empty(piece, dtype=np.float32)
+            local.tmp = np.empty(piece, dtype=np.uint32)
         rng = np.random.Generator(np.random.PCG64(ss))
-        w = rng.standard_normal(shape, dtype=np.float32)
-        w *= np.float32(std)
-        if kind == "gamma":
-            w += np.float32(1.0)
-        if kind == "mat" and cfg.dtype == "bf16":
-            out[name] = f32_to_bf16_bits(w)
-        else:
-            out[name] = w
-    return out
+        n = int(np.prod(shape))
+        to_bf16 = kind == "mat" and cfg.dtype == "bf16"
+        res = np.empty(n, dtype=np.uint16 if to_bf16 else np.float32)
+        for i in range(0, n, piece):
+            m = min(piece, n - i)
+            w = local.buf[:m]
+            rng.standard_normal(m, dtype=np.float32, out=w)
+            w *= np.float32(std)
+            if kind == "gamma":
+                w += np.float32(1.0)
+            if to_bf16:
+                # round to nearest even, as f32_to_bf16_bits does, without temporaries
+                u = w.view(np.uint32)
+                t = local.tmp[:m]
+                np.right_shift(u, np.uint32(16), out=t)
+                t &= np.uint32(1)
+                t += np.uint32(0x7FFF)
+                t += u
+                t >>= np.uint32(16)
+                res[i:i + m] = t
+            else:
+                res[i:i + m] = w
+        return name, res.reshape(shape)
+
+    # every tensor has its own stream, so the tensors can be drawn side by side (numpy releases the
+    # interpreter lock inside the generator and the element-wise passes)
+    workers = max(1, min(8, os.cpu_count() or 1))
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        return dict(ex.map(one, zip(table, children)))
 
 
 # ----------------------------------------------------------------------------

@@ -525,7 +525,9 @@ def test_graph_replay_without_prefix(amd):
         st = m.bt_get_stats()
         m.close()
         if mode:
-            assert st.graph_fallback == 0 and st.graph_captures == 2 and st.graph_launches == 21 - 2, (
+            # step 0 uses the prefill's context (its kind occurs once: eager); the 20 steps that run the
+            # block decoder are one kind: first eager, then captured and replayed
+            assert st.graph_fallback == 0 and st.graph_captures == 1 and st.graph_launches == 21 - 2, (
                 st.graph_fallback, st.graph_captures, st.graph_launches)
     assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
     rep = compare_with_oracle(cfg, W, prompts, out[1][0], out[1][1], TOL_BF16)
