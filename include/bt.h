@@ -18,7 +18,9 @@
  *     asynchronous; outputs are valid once the caller synchronises that stream.
  *   - Every function returns BT_OK (0) or a negative bt_status.  Argument and
  *     state errors are detected on the host before anything is enqueued and
- *     leave the model unchanged.  No exceptions, no exit(), no global state.
+ *     leave the model unchanged.  No exceptions, no exit(); no state outside the
+ *     models except the static workspace of bt_create_static and the text of the
+ *     calling thread's last failed create call.
  *   - One model must not be used from two threads at once.
  *
  * Tensor layouts
@@ -179,12 +181,32 @@ int bt_workspace_bytes(const bt_config *cfg, size_t *bytes);
  * of at least bt_workspace_bytes, 256-byte aligned, owned by the caller.
  * hip_stream: a hipStream_t (NULL = the default stream).  *out receives the
  * handle.  In bf16 mode the call reads every GEMM weight matrix once (a small
- * kernel writes the re-ordered copy into the workspace) and synchronises the
- * stream; weights changed afterwards are not seen by the decode steps.
+ * kernel writes the re-ordered copy into the workspace), fills the rotary
+ * table and synchronises the stream; weights changed afterwards are not seen
+ * by the decode steps.
  * Errors: BT_ERR_ARG (bad config / null), BT_ERR_CAPACITY (workspace too
  * small), BT_ERR_HIP. */
 int bt_create(const bt_config *cfg, const bt_weights *w, void *workspace_dev,
               size_t workspace_bytes, void *hip_stream, bt_model **out);
+
+/* bt_create for callers that cannot allocate device memory (code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the workspace is a static device array inside the library,
+ * BT_STATIC_WORKSPACE_BYTES per GPU, held from library load to process end.
+ * The call allocates no device memory and calls no HIP allocation routine
+ * (the handle is a small host object); a model made by it never allocates
+ * later either: cfg.use_graphs is taken as 0 (graph instantiation allocates)
+ * and profiling events exist only after bt_set_profile(1).  The device is the
+ * one current at the call.  The array is shared by every call on that GPU and
+ * keeps the last model's contents; nothing in it is assumed to be zero (bt_create
+ * rewrites the tables, bt_prefill resets all sequence state).  Two live models
+ * on one GPU would race on it, so the call refuses while one exists:
+ * BT_ERR_STATE until bt_destroy of the earlier one (which waits for its
+ * stream).  Errors: BT_ERR_CAPACITY if bt_workspace_bytes(cfg) exceeds
+ * BT_STATIC_WORKSPACE_BYTES; otherwise as bt_create; text via
+ * bt_last_error(NULL). */
+#define BT_STATIC_WORKSPACE_BYTES (32u << 20)
+int bt_create_static(const bt_config *cfg, const bt_weights *w, void *hip_stream, bt_model **out);
 
 /* Prefill (Fig. 1; Sec. 2.4; App. C): run the embedder and the block decoder
  * over all prompt blocks, fill the block KV cache with ceil(prompt_len/L_B)
@@ -285,7 +307,8 @@ int bt_reset_profile(bt_model *m);
 
 int bt_get_stats(bt_model *m, bt_stats *out);
 
-/* Text of the last error on this model (host string owned by the model). */
+/* Text of the last error on this model (host string owned by the model).  With
+ * m == NULL: why the calling thread's last bt_create / bt_create_static failed. */
 const char *bt_last_error(const bt_model *m);
 
 void bt_destroy(bt_model *m);

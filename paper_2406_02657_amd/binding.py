@@ -60,6 +60,7 @@ class bt_stats(C.Structure):
 _P = C.c_void_p
 lib.bt_workspace_bytes.argtypes = [C.POINTER(bt_config), C.POINTER(C.c_size_t)]
 lib.bt_create.argtypes = [C.POINTER(bt_config), C.POINTER(bt_weights), _P, C.c_size_t, _P, C.POINTER(_P)]
+lib.bt_create_static.argtypes = [C.POINTER(bt_config), C.POINTER(bt_weights), _P, C.POINTER(_P)]
 lib.bt_prefill.argtypes = [_P, _P, C.c_int32, C.c_int32]
 lib.bt_prefill_ragged.argtypes = [_P, _P, C.POINTER(C.c_int32), C.c_int32, C.c_int32]
 lib.bt_decode_step.argtypes = [_P, C.c_int32, _P]
@@ -77,7 +78,7 @@ lib.bt_last_error.restype = C.c_char_p
 lib.bt_destroy.argtypes = [_P]
 lib.bt_destroy.restype = None
 lib.bt_embed.argtypes = [_P, _P, C.c_int32, _P]
-for _f in ("bt_workspace_bytes", "bt_create", "bt_prefill", "bt_prefill_ragged", "bt_decode_step", "bt_get_logits",
+for _f in ("bt_workspace_bytes", "bt_create", "bt_create_static", "bt_prefill", "bt_prefill_ragged", "bt_decode_step", "bt_get_logits",
            "bt_get_finished", "bt_score", "bt_force_last_ids",
            "bt_get_context", "bt_set_context", "bt_set_profile", "bt_reset_profile", "bt_get_stats", "bt_embed"):
     getattr(lib, _f).restype = C.c_int
@@ -130,7 +131,7 @@ class Model:
     """Owns the device copies of the weights and the workspace; forwards to the C ABI."""
 
     def __init__(self, cfg, weights, max_batch=None, max_blocks=None, prefill_rows=0, act_split=None,
-                 use_graphs=1, score_rows=0, keep_logits=1, device="cuda:0", stream=None):
+                 use_graphs=1, score_rows=0, keep_logits=1, device="cuda:0", stream=None, static_workspace=False):
         import torch
         self.torch = torch
         self.device = torch.device(device)
@@ -166,14 +167,20 @@ class Model:
         if rc:
             raise BTError(rc, "bt_workspace_bytes")
         self.workspace_bytes = nbytes.value
-        self.workspace = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=self.device)
-        base = (self.workspace.data_ptr() + 255) // 256 * 256
         self.h = _P()
-        with self._ordered():
-            rc = lib.bt_create(C.byref(self.c), C.byref(self.w), base, nbytes.value, self.stream.cuda_stream,
-                               C.byref(self.h))
+        if static_workspace:
+            # bt_create_static: the workspace is the library's static device array; nothing is allocated here
+            self.workspace = None
+            with self.torch.cuda.device(self.device), self._ordered():
+                rc = lib.bt_create_static(C.byref(self.c), C.byref(self.w), self.stream.cuda_stream, C.byref(self.h))
+        else:
+            self.workspace = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=self.device)
+            base = (self.workspace.data_ptr() + 255) // 256 * 256
+            with self._ordered():
+                rc = lib.bt_create(C.byref(self.c), C.byref(self.w), base, nbytes.value, self.stream.cuda_stream,
+                                   C.byref(self.h))
         if rc:
-            raise BTError(rc, "bt_create")
+            raise BTError(rc, (lib.bt_last_error(None) or b"").decode())
         self.batch = 0
 
     def on_stream(self):

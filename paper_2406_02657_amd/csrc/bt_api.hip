@@ -5,9 +5,9 @@
 #include "../../include/bt.h"
 #include "kernels.h"
 
-#include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -21,6 +21,19 @@ constexpr int kMaxSplits = 16;
 constexpr int kSkinnyRows = 256;     // GEMMs with at most this many rows may split K
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// Why the last bt_create / bt_create_static of this thread failed (bt_last_error(NULL)).
+thread_local std::string g_create_err;
+
+// Workspace of bt_create_static: one array per GPU, held until the process ends.  In host code the
+// array's name is only a stand-in for the symbol; the device address comes from
+// hipGetSymbolAddress, once per device (static_workspace), and that pointer is what the model and
+// every kernel use.
+static __device__ __align__(256) unsigned char scratch[BT_STATIC_WORKSPACE_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];            // device address of `scratch` on device i (null: not asked yet)
+const bt_model* g_scratch_owner[kMaxDevices];   // the live model that uses it, if any
 
 struct Layout {
   size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cand, cur, state, lens, fin, score_kv, score_logits, frag, total;
@@ -161,6 +174,7 @@ struct bt_model {
   bool graphs_ok;
   int64_t graph_launches;
   int graph_captures;
+  int static_dev = -1;             // >= 0: the workspace is the static array of this device (bt_create_static)
 
   template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
 };
@@ -453,30 +467,33 @@ int bt_workspace_bytes(const bt_config* cfg, size_t* bytes) {
   return BT_OK;
 }
 
-int bt_create(const bt_config* cfg, const bt_weights* w, void* workspace_dev, size_t workspace_bytes,
-              void* hip_stream, bt_model** out) {
-  if (!cfg || !w || !out) return BT_ERR_ARG;
+// Everything bt_create and bt_create_static share.  Calls no HIP allocation routine: the model
+// lives in host memory, all device memory is the caller's (or the static array).
+static int create_impl(const bt_config* cfg, const bt_weights* w, void* workspace_dev, size_t workspace_bytes,
+                       void* hip_stream, bt_model** out) {
+  auto bad = [](int code, const char* why) { g_create_err = why; return code; };
+  if (!cfg || !w || !out) return bad(BT_ERR_ARG, "null argument");
   *out = nullptr;
-  if (!workspace_dev || ((uintptr_t)workspace_dev & 255)) return BT_ERR_ARG;
-  int rc = check_config(*cfg, nullptr);
+  if (!workspace_dev || ((uintptr_t)workspace_dev & 255)) return bad(BT_ERR_ARG, "workspace is null or not 256-byte aligned");
+  int rc = check_config(*cfg, &g_create_err);
   if (rc) return rc;
   const bool need_tok_table = cfg->block_len > 1;
-  if (!w->E_emb || !w->W_head || !w->blk_lnf_g || !w->blk_lnf_b || !w->tok_lnf_g || !w->tok_lnf_b) return BT_ERR_ARG;
-  if (need_tok_table && !w->E_tok) return BT_ERR_ARG;
-  if (cfg->prefix_len > 0 && (!w->W_prefix || !w->b_prefix)) return BT_ERR_ARG;
-  if ((cfg->n_block_layers > 0 && !w->block_layers) || (cfg->n_token_layers > 0 && !w->token_layers)) return BT_ERR_ARG;
+  if (!w->E_emb || !w->W_head || !w->blk_lnf_g || !w->blk_lnf_b || !w->tok_lnf_g || !w->tok_lnf_b) return bad(BT_ERR_ARG, "a weight pointer is null");
+  if (need_tok_table && !w->E_tok) return bad(BT_ERR_ARG, "E_tok is null");
+  if (cfg->prefix_len > 0 && (!w->W_prefix || !w->b_prefix)) return bad(BT_ERR_ARG, "W_prefix or b_prefix is null");
+  if ((cfg->n_block_layers > 0 && !w->block_layers) || (cfg->n_token_layers > 0 && !w->token_layers)) return bad(BT_ERR_ARG, "layer array is null");
   auto layer_ok = [](const bt_layer_weights& l) {
     return l.ln1_g && l.ln1_b && l.W_qkv && l.b_qkv && l.W_o && l.b_o && l.ln2_g && l.ln2_b && l.W_up && l.b_up &&
            l.W_down && l.b_down;
   };
-  for (int i = 0; i < cfg->n_block_layers; ++i) if (!layer_ok(w->block_layers[i])) return BT_ERR_ARG;
-  for (int i = 0; i < cfg->n_token_layers; ++i) if (!layer_ok(w->token_layers[i])) return BT_ERR_ARG;
+  for (int i = 0; i < cfg->n_block_layers; ++i) if (!layer_ok(w->block_layers[i])) return bad(BT_ERR_ARG, "a block-decoder layer pointer is null");
+  for (int i = 0; i < cfg->n_token_layers; ++i) if (!layer_ok(w->token_layers[i])) return bad(BT_ERR_ARG, "a token-decoder layer pointer is null");
   Layout L;
   make_layout(*cfg, L);
-  if (workspace_bytes < L.total) return BT_ERR_CAPACITY;
+  if (workspace_bytes < L.total) return bad(BT_ERR_CAPACITY, "workspace smaller than bt_workspace_bytes");
 
   bt_model* m = new (std::nothrow) bt_model();
-  if (!m) return BT_ERR_ARG;
+  if (!m) return bad(BT_ERR_ARG, "out of host memory");
   m->cfg = *cfg;
   m->w = *w;
   m->blk.assign(w->block_layers, w->block_layers + cfg->n_block_layers);
@@ -499,7 +516,7 @@ int bt_create(const bt_config* cfg, const bt_weights* w, void* workspace_dev, si
     m->graphs_ok = false;
     m->err = "HIP graphs need a stream other than the default stream: decode steps are launched eagerly";
   }
-  if (gemm_prepare_kernels() != hipSuccess) { (void)hipGetLastError(); delete m; return BT_ERR_HIP; }
+  if (gemm_prepare_kernels() != hipSuccess) { (void)hipGetLastError(); delete m; return bad(BT_ERR_HIP, "hipFuncSetAttribute failed"); }
 
   m->blk_frag.assign(cfg->n_block_layers, bt_model::FragLayer{nullptr, nullptr, nullptr, nullptr});
   m->tok_frag.assign(cfg->n_token_layers, bt_model::FragLayer{nullptr, nullptr, nullptr, nullptr});
@@ -527,24 +544,53 @@ int bt_create(const bt_config* cfg, const bt_weights* w, void* workspace_dev, si
     m->head_frag = pack(w->W_head, cfg->vocab, D);
     if (cfg->prefix_len > 0) m->prefix_frag = pack(w->W_prefix, cfg->prefix_len * D, D);
     if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
-    if (e != hipSuccess || off > L.total) { delete m; return BT_ERR_HIP; }
+    if (e != hipSuccess || off > L.total) { delete m; return bad(BT_ERR_HIP, "re-ordering the weights failed"); }
   }
 
-  // rotary table: (cos, sin) of pos * 10000^(-2t/rot), computed in double on the host
-  const int half = cfg->rotary_dims / 2;
-  if (half > 0) {
-    std::vector<float2> tab((size_t)L.rope_len * half);
-    for (int pos = 0; pos < L.rope_len; ++pos)
-      for (int t = 0; t < half; ++t) {
-        const double ang = (double)pos * std::pow(10000.0, -2.0 * t / cfg->rotary_dims);
-        tab[(size_t)pos * half + t] = make_float2((float)std::cos(ang), (float)std::sin(ang));
-      }
-    hipError_t e = hipMemcpyAsync(m->ws + L.rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, m->stream);
+  // rotary table: (cos, sin) of pos * 10000^(-2t/rot), computed in double by a small kernel
+  if (cfg->rotary_dims > 0) {
+    hipError_t e = launch_rope_table(m->at<float2>(L.rope), L.rope_len, cfg->rotary_dims, m->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
-    if (e != hipSuccess) { delete m; return BT_ERR_HIP; }
+    if (e != hipSuccess) { delete m; return bad(BT_ERR_HIP, "filling the rotary table failed"); }
   }
   *out = m;
   return BT_OK;
+}
+
+int bt_create(const bt_config* cfg, const bt_weights* w, void* workspace_dev, size_t workspace_bytes,
+              void* hip_stream, bt_model** out) {
+  return create_impl(cfg, w, workspace_dev, workspace_bytes, hip_stream, out);
+}
+
+int bt_create_static(const bt_config* cfg, const bt_weights* w, void* hip_stream, bt_model** out) {
+  auto bad = [](int code, const char* why) { g_create_err = why; return code; };
+  if (!cfg || !w || !out) return bad(BT_ERR_ARG, "null argument");
+  *out = nullptr;
+  int rc = check_config(*cfg, &g_create_err);
+  if (rc) return rc;
+  Layout L;
+  make_layout(*cfg, L);
+  if (L.total > (size_t)BT_STATIC_WORKSPACE_BYTES)
+    return bad(BT_ERR_CAPACITY, "this config needs more workspace than BT_STATIC_WORKSPACE_BYTES: use bt_create with a workspace of bt_workspace_bytes");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return bad(BT_ERR_HIP, "hipGetDevice failed"); }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    // once per device, with that device current: each GPU holds its own copy of the array at its own address
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) { (void)hipGetLastError(); return bad(BT_ERR_HIP, "hipGetSymbolAddress(scratch) failed"); }
+    g_scratch_ptr[dev] = p;
+  }
+  if (g_scratch_owner[dev]) return bad(BT_ERR_STATE, "the static workspace of this GPU is in use by a live model: bt_destroy it first");
+  bt_config c = *cfg;
+  c.use_graphs = 0;                    // graph instantiation allocates; such a model never does
+  rc = create_impl(&c, w, g_scratch_ptr[dev], BT_STATIC_WORKSPACE_BYTES, hip_stream, out);
+  if (rc == BT_OK) {
+    (*out)->static_dev = dev;
+    g_scratch_owner[dev] = *out;
+  }
+  return rc;
 }
 
 // Prefill of `batch` prompts held in rows of `row_stride` ids.  lens_host null: every prompt has
@@ -968,10 +1014,16 @@ int bt_get_stats(bt_model* m, bt_stats* out) {
   return BT_OK;
 }
 
-const char* bt_last_error(const bt_model* m) { return m ? m->err.c_str() : "null model"; }
+const char* bt_last_error(const bt_model* m) { return m ? m->err.c_str() : g_create_err.c_str(); }
 
 void bt_destroy(bt_model* m) {
   if (!m) return;
+  if (m->static_dev >= 0) {
+    // the next model on the static workspace may overwrite it at once: let this one's work drain first
+    (void)hipStreamSynchronize(m->stream);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (g_scratch_owner[m->static_dev] == m) g_scratch_owner[m->static_dev] = nullptr;
+  }
   for (hipEvent_t e : m->ev) (void)hipEventDestroy(e);
   for (auto& g : m->graphs) if (g.exec) (void)hipGraphExecDestroy(g.exec);
   delete m;

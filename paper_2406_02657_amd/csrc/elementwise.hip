@@ -583,6 +583,23 @@ hipError_t launch_score_rows(const float* logits, int n_rows, int vocab, int row
   return hipGetLastError();
 }
 
+// Rotary table: tab[pos * (rot/2) + t] = (cos, sin) of pos * 10000^(-2t/rot), evaluated in double.
+__global__ void rope_table_kernel(float2* __restrict__ tab, int n_pos, int rot) {
+  const int half = rot / 2;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)n_pos * half) return;
+  const int pos = (int)(i / half), t = (int)(i - (size_t)pos * half);
+  const double ang = (double)pos * pow(10000.0, -2.0 * (double)t / (double)rot);
+  tab[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+hipError_t launch_rope_table(float2* tab, int n_pos, int rot, hipStream_t s) {
+  if (n_pos <= 0 || rot < 2 || (rot & 1)) return hipErrorInvalidValue;
+  const size_t n = (size_t)n_pos * (rot / 2);
+  rope_table_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(tab, n_pos, rot);
+  return hipGetLastError();
+}
+
 __global__ void state_set_kernel(int* p, int value, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = value;

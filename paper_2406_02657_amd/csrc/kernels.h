@@ -180,6 +180,7 @@ hipError_t launch_gelu_reduce(int dtype, const GeluJob& job, hipStream_t s);
 
 // ------------------------------------------------------------------ attention
 // Rotary tables: rope[pos * (rot/2) + t] = (cos, sin) of pos * 10000^(-2t/rot).
+hipError_t launch_rope_table(float2* tab, int n_pos, int rot, hipStream_t s);
 //
 // Block decoder prefill, after the QKV GEMM: rotate q in place (float, inside qkv),
 // rotate k, and store k, v into the block KV cache at position pos0 + m % n_new

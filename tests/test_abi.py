@@ -70,7 +70,14 @@ def test_create_rejects_null_and_small_workspace(B):
     # null model handles
     assert B.lib.bt_prefill(None, None, 1, 4) == B.BT_ERR_ARG
     assert B.lib.bt_decode_step(None, 1, None) == B.BT_ERR_ARG
-    assert B.lib.bt_last_error(None) == b"null model"
+    assert b"aligned" in B.lib.bt_last_error(None)          # the reason of this thread's last failed create
+    c.struct_size = 12
+    assert B.lib.bt_create(C.byref(c), C.byref(w), 4096, 1 << 30, None, C.byref(h)) == B.BT_ERR_ARG
+    assert b"struct_size" in B.lib.bt_last_error(None)
+    c = _cfg(B)
+    big = _cfg(B); big.max_batch = 4096; big.max_blocks = 4096
+    assert B.lib.bt_create_static(C.byref(big), C.byref(w), None, C.byref(h)) == B.BT_ERR_CAPACITY
+    assert b"BT_STATIC_WORKSPACE_BYTES" in B.lib.bt_last_error(None) and h.value is None
     B.lib.bt_destroy(None)
 
 
