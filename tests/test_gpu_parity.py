@@ -153,6 +153,16 @@ def test_bf16_streaming_gemm_shapes(amd, d, h, f, b, p, lb):
     run_case(amd, cfg, 2 * lb + 1, batch=b)
 
 
+@pytest.mark.parametrize("d,h,f,b,p", [(256, 4, 1024, 256, 1), (192, 3, 320, 200, 1), (256, 2, 512, 97, 2), (128, 2, 256, 193, 1)])
+def test_bf16_decode_gemm_193_to_256_rows(amd, d, h, f, b, p):
+    """Decode steps with 193 .. 256 rows (batch, or batch x prefix rows at the first step of a block): the
+    K-slice kernels with four 64-row chunks, full and ragged row tiles, column tiles that do not fill the
+    workgroup's columns (N = 576, 320), K of 2 .. 16 slices."""
+    cfg = tiny_cfg(dtype="bf16", block_len=4, prefix_len=p, d_model=d, n_heads=h, d_ff=f, vocab=1000,
+                   prompt_len=8, n_block_layers=2, n_token_layers=2)
+    run_case(amd, cfg, 9, batch=b, seqs=[0, 1, b // 2, b - 2, b - 1])
+
+
 @pytest.mark.parametrize("d,h,blocks", [(128, 4, 80), (256, 4, 145), (256, 2, 64), (128, 1, 97)])
 def test_bf16_prefill_attention_on_matrix_cores(amd, d, h, blocks):
     """Prompts of at least 64 blocks take the MFMA causal-attention kernel of the block decoder's
