@@ -10,6 +10,7 @@ import ctypes as C
 import os
 
 import numpy as np
+import torch  # noqa: F401  first: libbt.so must bind to the HIP runtime torch brings, not load a second copy
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 lib_path = os.path.join(HERE, "libbt.so")

@@ -516,7 +516,15 @@ static int create_impl(const bt_config* cfg, const bt_weights* w, void* workspac
     m->graphs_ok = false;
     m->err = "HIP graphs need a stream other than the default stream: decode steps are launched eagerly";
   }
-  if (gemm_prepare_kernels() != hipSuccess) { (void)hipGetLastError(); delete m; return bad(BT_ERR_HIP, "hipFuncSetAttribute failed"); }
+  {
+    const hipError_t pe = gemm_prepare_kernels();
+    if (pe != hipSuccess) {
+      (void)hipGetLastError();
+      delete m;
+      g_create_err = std::string("raising the LDS limit of the GEMM kernels failed: ") + hipGetErrorString(pe);
+      return BT_ERR_HIP;
+    }
+  }
 
   m->blk_frag.assign(cfg->n_block_layers, bt_model::FragLayer{nullptr, nullptr, nullptr, nullptr});
   m->tok_frag.assign(cfg->n_token_layers, bt_model::FragLayer{nullptr, nullptr, nullptr, nullptr});
