@@ -32,6 +32,13 @@ Readings taken where the paper is silent (each also listed in the design notes):
     (0 .. L_B-1 of cfg.pad_id) in FRONT of its first block; the pads are
     embedded like any token (App. "Random length padding", footnote of the
     zero-shot table in Sec. 3);
+  * the "Summation" token decoder of App. D.2 (cfg.token_mix == "sum"): the context embedding is
+    projected to L_B vectors of dimension D and vector k is added to the token decoder's input at
+    local position k.  The paper does not say what token embedding stands at position 0, the
+    position that predicts the block's first token (no token of the block is known yet, and the
+    token decoder sees nothing outside the block): here none does, input 0 is vector 0 alone, and
+    input k >= 1 is E_tok[token k-1 of the block] + vector k; the output at position k predicts
+    token k.  prefix_len must be 1 (position bookkeeping is that of one prefix row);
   * stopping is not part of the paper (it generates a fixed number of tokens):
     with cfg.eos_id >= 0 a sequence that has emitted eos_id emits eos_id at
     every later step; the batch stays static and the other sequences are
@@ -223,6 +230,34 @@ def prefix_tokens(P, cfg, c):
     return (c @ P("W_prefix").T + P("b_prefix")).reshape(B, cfg.prefix_len, D)
 
 
+def summands(P, cfg, c):
+    """Summation variant (App. D.2): context embeddings c [B, D] -> [B, L_B, D], one vector per
+    local position of the token decoder."""
+    B, D = c.shape
+    return (c @ P("W_prefix").T + P("b_prefix")).reshape(B, cfg.block_len, D)
+
+
+def local_inputs(P, cfg, c, block_tokens):
+    """Input rows of the token decoder for one block: context c [B, D] and the block's first r tokens
+    [B, r] -> [B, n_prefix_rows + r, D].
+
+    Prefix variant: the prefix rows, then E_tok of the tokens.  Summation variant: position 0 holds
+    summand 0 alone, position k >= 1 holds E_tok[token k-1] + summand k.
+    """
+    B, r = block_tokens.shape
+    if getattr(cfg, "token_mix", "prefix") == "sum":
+        assert cfg.prefix_len == 1
+        u = summands(P, cfg, c)
+        s = u[:, :r + 1].copy()
+        if r > 0:
+            s[:, 1:] += P("E_tok")[block_tokens]
+        return s
+    s = prefix_tokens(P, cfg, c)
+    if r > 0:
+        s = np.concatenate([s, P("E_tok")[block_tokens]], axis=1)
+    return s
+
+
 def token_decoder(P, cfg, s, pos0=0, caches=None):
     """Local sequence rows s [B, n, D] at local positions pos0.. -> hidden [B, n, D] after final LN."""
     g = s
@@ -272,9 +307,7 @@ def block_logits(P, cfg, c, block_tokens):
     """
     B, r = block_tokens.shape
     assert r <= max(cfg.block_len - 1, 0)
-    s = prefix_tokens(P, cfg, c)
-    if r > 0:
-        s = np.concatenate([s, P("E_tok")[block_tokens]], axis=1)
+    s = local_inputs(P, cfg, c, block_tokens)
     g = token_decoder(P, cfg, s)
     return lm_head(P, g[:, cfg.n_prefix_rows - 1:])
 
@@ -412,8 +445,10 @@ class CachedGenerator:
                 self.block_kv_rows_read += n_before + 1
             for c in self.loc:
                 c.clear()
-            s = prefix_tokens(P, cfg, self.c)
+            s = local_inputs(P, cfg, self.c, self.cur[:, :0])
             self.have_context = False
+        elif getattr(cfg, "token_mix", "prefix") == "sum":
+            s = (P("E_tok")[self.cur[:, self.r - 1]] + summands(P, cfg, self.c)[:, self.r])[:, None, :]
         else:
             s = P("E_tok")[self.cur[:, self.r - 1]][:, None, :]
         g = token_decoder(P, cfg, s, self.loc[0].n if self.loc else 0, self.loc)

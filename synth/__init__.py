@@ -59,6 +59,7 @@ class BTConfig:
     ln_eps: float = 1e-5
     pad_id: int = 0         # fills the first block of a prompt whose length is not a multiple of L_B
     eos_id: int = -1        # -1: none; else a sequence that emitted it keeps emitting it
+    token_mix: str = "prefix"   # how the context embedding enters the token decoder: "prefix" or "sum"
 
     @property
     def d_emb(self) -> int:
@@ -84,6 +85,12 @@ class BTConfig:
     def n_prefix_rows(self) -> int:
         """Rows the token decoder sees for the context embedding."""
         return max(self.prefix_len, 1)
+
+    @property
+    def n_proj(self) -> int:
+        """Vectors of dimension D the context embedding is projected to: prefix_len prefix tokens, or
+        block_len summands (token_mix == "sum"); W_prefix is [n_proj * D, D]."""
+        return self.block_len if self.token_mix == "sum" else self.prefix_len
 
     def with_(self, **kw) -> "BTConfig":
         return replace(self, **kw)
@@ -154,7 +161,7 @@ def _layer_shapes(cfg: BTConfig):
 
 def tensor_table(cfg: BTConfig):
     """Ordered list of (name, shape, kind) for every tensor of the model."""
-    D, V, P = cfg.d_model, cfg.vocab, cfg.prefix_len
+    D, V, P = cfg.d_model, cfg.vocab, cfg.n_proj
     out = [("E_emb", (V, cfg.d_emb), "mat"), ("E_tok", (V, D), "mat")]
     if P > 0:
         out += [("W_prefix", (P * D, D), "mat"), ("b_prefix", (P * D,), "vec")]

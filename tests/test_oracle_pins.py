@@ -716,3 +716,93 @@ def test_cached_equals_full_with_bf16_weights(lb, p):
     assert np.array_equal(bf16_bits_to_f32(W["W_head"]), bf16_bits_to_f32(__import__("synth").f32_to_bf16_bits(Wf["W_head"])))
     _, lg_u = O.generate_full(O.Params(Wf), cfg.with_(dtype="fp32"), prompts, 1)
     assert np.max(np.abs(lg_u - lg_f[:, :1])) > 1e-6
+
+
+# --------------------------------------------------------------------------
+# Summation token decoder (App. D.2 "Summation"): the context embedding, projected to L_B vectors,
+# is added to the token decoder's inputs position by position.
+# --------------------------------------------------------------------------
+def _sum_cfg(**kw):
+    base = dict(block_len=4, prefix_len=1, token_mix="sum", d_model=32, n_heads=2, prompt_len=8)
+    base.update(kw)
+    return tiny_cfg(**base)
+
+
+@pytest.mark.parametrize("lb", [1, 2, 4])
+@pytest.mark.parametrize("parallel", [1, 0])
+def test_summation_cached_equals_full(lb, parallel):
+    cfg = _sum_cfg(block_len=lb, prompt_len=2 * lb, parallel_residual=parallel)
+    W = make_weights(cfg)
+    assert W["W_prefix"].shape == (lb * cfg.d_model, cfg.d_model) and W["b_prefix"].shape == (lb * cfg.d_model,)
+    P = O.Params(W)
+    prompts = make_prompts(cfg, batch=3)
+    n_new = 2 * lb + 3
+    ids_f, lg_f = O.generate_full(P, cfg, prompts, n_new)
+    ids_c, lg_c, gen = O.generate_cached(P, cfg, prompts, n_new)
+    assert np.array_equal(ids_f, ids_c) and np.max(np.abs(lg_f - lg_c)) < TOL
+    assert gen.local_kv_high_water == lb                      # positions 0 .. L_B - 1: no prefix row besides position 0
+
+
+def test_summation_is_the_one_prefix_model_plus_added_vectors():
+    """With summands 1 .. L_B-1 zeroed the variant IS the prefix model with one prefix token whose
+    projection is summand 0; a non-zero summand k changes the logits of positions >= k only (the
+    token decoder is causal inside the block)."""
+    cfg = _sum_cfg()
+    D, L = cfg.d_model, cfg.block_len
+    W = make_weights(cfg)
+    rng = np.random.default_rng(4)
+    toks = rng.integers(0, cfg.vocab, size=(2, 12))
+    Wz = dict(W)
+    Wz["W_prefix"] = W["W_prefix"].copy(); Wz["b_prefix"] = W["b_prefix"].copy()
+    Wz["W_prefix"][D:] = 0; Wz["b_prefix"][D:] = 0
+    pcfg = cfg.with_(token_mix="prefix")
+    Wp = dict(W)
+    Wp["W_prefix"] = W["W_prefix"][:D].copy(); Wp["b_prefix"] = W["b_prefix"][:D].copy()
+    a = O.teacher_forced_logits(O.Params(Wz), cfg, toks, [1, 2])
+    b = O.teacher_forced_logits(O.Params(Wp), pcfg, toks, [1, 2])
+    for i in (1, 2):
+        assert np.max(np.abs(a[i] - b[i])) < TOL
+    # the full variant differs from it, and summand k alone moves positions >= k
+    full = O.teacher_forced_logits(O.Params(W), cfg, toks, [1, 2])
+    assert np.max(np.abs(full[1] - a[1])) > 1e-6
+    for k in range(1, L):
+        Wk = dict(Wz)
+        Wk["W_prefix"] = Wz["W_prefix"].copy(); Wk["b_prefix"] = Wz["b_prefix"].copy()
+        Wk["W_prefix"][k * D:(k + 1) * D] = W["W_prefix"][k * D:(k + 1) * D]
+        Wk["b_prefix"][k * D:(k + 1) * D] = W["b_prefix"][k * D:(k + 1) * D]
+        ck = O.teacher_forced_logits(O.Params(Wk), cfg, toks, [2])[2]
+        assert np.max(np.abs(ck[:, :k] - a[2][:, :k])) == 0.0
+        assert np.min(np.max(np.abs(ck[:, k:] - a[2][:, k:]), axis=-1)) > 1e-9
+
+
+def test_summation_inputs_written_out():
+    """The token decoder's input rows of one block, element by element."""
+    cfg = _sum_cfg()
+    D, L = cfg.d_model, cfg.block_len
+    W = make_weights(cfg)
+    P = O.Params(W)
+    rng = np.random.default_rng(5)
+    c = rng.standard_normal((2, D))
+    blk = rng.integers(0, cfg.vocab, size=(2, 3))
+    s = O.local_inputs(P, cfg, c, blk)
+    assert s.shape == (2, 4, D)
+    for b in range(2):
+        for k in range(4):
+            want = np.array([sum(W["W_prefix"][k * D + d, j].astype(np.float64) * c[b, j] for j in range(D)) + W["b_prefix"][k * D + d]
+                             for d in range(D)])
+            if k >= 1:
+                want = want + W["E_tok"][blk[b, k - 1]]
+            assert np.max(np.abs(s[b, k] - want)) < 1e-12
+    # locality: the logits of a block depend on earlier blocks only through the context embedding
+    lg1 = O.block_logits(P, cfg, c, blk)
+    lg2 = O.block_logits(P, cfg, c, blk.copy())
+    assert np.array_equal(lg1, lg2)
+
+
+def test_summation_at_block_length_one_is_the_one_prefix_model():
+    cfg = _sum_cfg(block_len=1, prompt_len=3)
+    W = make_weights(cfg)
+    prompts = make_prompts(cfg, batch=2)
+    _, a = O.generate_full(O.Params(W), cfg, prompts, 5)
+    _, b = O.generate_full(O.Params(W), cfg.with_(token_mix="prefix"), prompts, 5)
+    assert np.array_equal(a, b)
