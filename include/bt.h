@@ -124,8 +124,9 @@ typedef struct {
 typedef struct {
   const void *E_emb;             /* [V, D/L_B]  embedder table (Sec. 2.2) */
   const void *E_tok;             /* [V, D]      token decoder table (Sec. 2.4); unused when L_B == 1 */
-  const void *W_prefix;          /* [P*D, D]    context -> prefix tokens (App. D.2); NULL when P == 0 */
-  const void *b_prefix;          /* [P*D] float */
+  const void *W_prefix;          /* [P*D, D]    context -> prefix tokens (App. D.2); NULL when P == 0.
+                                    BT_MIX_SUM: [L_B*D, D], context -> the L_B summands */
+  const void *b_prefix;          /* [P*D] float (BT_MIX_SUM: [L_B*D]) */
   const void *W_head;            /* [V, D]      classifier, no bias */
   const void *blk_lnf_g, *blk_lnf_b;   /* final LayerNorm of the block decoder, [D] float */
   const void *tok_lnf_g, *tok_lnf_b;   /* final LayerNorm of the token decoder, [D] float */

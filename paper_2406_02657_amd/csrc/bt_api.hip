@@ -36,7 +36,7 @@ void* g_scratch_ptr[kMaxDevices];            // device address of `scratch` on d
 const bt_model* g_scratch_owner[kMaxDevices];   // the live model that uses it, if any
 
 struct Layout {
-  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cand, cur, state, lens, fin, score_kv, score_logits, frag, total;
+  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cand, cur, state, lens, fin, summands, score_kv, score_logits, frag, total;
   size_t blk_layer_stride, loc_layer_stride;   // bytes between layers (K then V inside)
   size_t part_elems;                           // floats in each of part_o, part_d
   size_t qkv_elems, part_u_elems;              // floats in qkv (may hold split-K pieces) and part_u
@@ -69,7 +69,8 @@ int check_config(const bt_config& c, std::string* why) {
   if (c.score_rows < 0) return bad("score_rows < 0");
   if (c.keep_logits < 0 || c.keep_logits > 1) return bad("keep_logits must be 0 or 1");
   if (c.token_mix != BT_MIX_PREFIX && c.token_mix != BT_MIX_SUM) return bad("token_mix must be BT_MIX_PREFIX or BT_MIX_SUM");
-  if (c.token_mix == BT_MIX_SUM && (c.prefix_len != 1 || c.score_rows != 0)) return bad("BT_MIX_SUM needs prefix_len == 1 and score_rows == 0");
+  if (c.token_mix == BT_MIX_SUM && (c.prefix_len != 1 || c.score_rows != 0 || c.n_token_layers < 1))
+    return bad("BT_MIX_SUM needs prefix_len == 1, score_rows == 0 and at least one token-decoder layer");
   if (!(c.ln_eps >= 0.f)) return bad("ln_eps < 0");
   const int l_cap = (c.prefix_len > 0 ? c.prefix_len : 1) + c.block_len;
   if ((size_t)(2 * l_cap + 2) * dh * sizeof(float) > 60 * 1024) return bad("prefix_len + block_len too large for the local-attention kernel");
@@ -124,6 +125,8 @@ void make_layout(const bt_config& c, Layout& L) {
   L.state = take(B * 4);       // cached blocks per sequence (device-side counters)
   L.lens = take(B * 4);        // prompt lengths of the last prefill
   L.fin = take(B * 4);         // per sequence: has emitted eos_id
+  // summation token decoder: the L_B vectors the context embedding was projected to, per sequence
+  L.summands = take(c.token_mix == BT_MIX_SUM ? B * c.block_len * D * 4 : 0);
   // teacher-forced scoring (score_rows > 0): the local KV of every block scored in one chunk (one
   // layer's worth, re-used by all layers) and the logits of score_rows rows at a time
   L.score_kv = L.score_logits = off;
@@ -142,7 +145,7 @@ void make_layout(const bt_config& c, Layout& L) {
                              align_up(gemm_packed_elems((int)F, (int)D) * 2) + align_up(gemm_packed_elems((int)D, (int)F) * 2);
     take(per_layer * (c.n_block_layers + c.n_token_layers));
     take(gemm_packed_elems(c.vocab, (int)D) * 2);
-    if (c.prefix_len > 0) take(gemm_packed_elems(c.prefix_len * (int)D, (int)D) * 2);
+    if (c.prefix_len > 0) take(gemm_packed_elems((c.token_mix == BT_MIX_SUM ? c.block_len : c.prefix_len) * (int)D, (int)D) * 2);
   }
   L.total = off;
 }
@@ -241,6 +244,10 @@ struct StackArgs {
   const int* fin_off_dev = nullptr;
   // Optional: where the final LayerNorm's remainder plane goes (elements after its output; 0: the default).
   size_t fin_lo_off = 0;
+  // Optional (summation token decoder): the stack's first LayerNorm launch adds add[i * add_stride ...] to
+  // row i (and, without emb_table, takes that vector as the row).
+  const float* add = nullptr;
+  int add_stride = 0;
   // Optional (MODE_TOKEN): local K (then V at +loc_half bytes) of `batch` sequences, shared by all layers.
   char* loc_base = nullptr;
   size_t loc_half = 0;
@@ -334,6 +341,10 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     r.lo_off = loD;
     if (!pO && !pD && a.emb_table) {        // first launch of the stack: rows come from the table
       r.emb_table = a.emb_table; r.emb_ids = a.emb_ids; r.emb_stride = a.emb_stride; r.emb_off = a.emb_off;
+      r.write_x = 1;
+    }
+    if (!pO && !pD && a.add) {              // ... plus (or only) the summand of this local position
+      r.add = a.add; r.add_stride = a.add_stride;
       r.write_x = 1;
     }
     BT_HIP(m, launch_resid_ln(dt, r, s));
@@ -550,7 +561,8 @@ static int create_impl(const bt_config* cfg, const bt_weights* w, void* workspac
     pack_layers(m->blk, m->blk_frag);
     pack_layers(m->tok, m->tok_frag);
     m->head_frag = pack(w->W_head, cfg->vocab, D);
-    if (cfg->prefix_len > 0) m->prefix_frag = pack(w->W_prefix, cfg->prefix_len * D, D);
+    if (cfg->prefix_len > 0)
+      m->prefix_frag = pack(w->W_prefix, (cfg->token_mix == BT_MIX_SUM ? cfg->block_len : cfg->prefix_len) * D, D);
     if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
     if (e != hipSuccess || off > L.total) { delete m; return bad(BT_ERR_HIP, "re-ordering the weights failed"); }
   }
@@ -700,8 +712,12 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
       if (rc) return rc;
     }
     if (c.prefix_len > 0) {
-      GemmProblem p{m->ws + L.ctx, m->w.W_prefix, (const float*)m->w.b_prefix, x, B, c.prefix_len * D, D, D,
-                    c.prefix_len * D, EPI_F32, fin_lo ? m->ws + L.ctx + fin_lo * 2 : nullptr, 0, m->prefix_frag};
+      // prefix tokens go straight into the residual stream; the summands of the summation variant wait in
+      // their own buffer and are added to the inputs position by position
+      const bool sum = c.token_mix == BT_MIX_SUM;
+      const int n_proj = sum ? c.block_len : c.prefix_len;
+      GemmProblem p{m->ws + L.ctx, m->w.W_prefix, (const float*)m->w.b_prefix, sum ? m->at<float>(L.summands) : x, B, n_proj * D, D, D,
+                    n_proj * D, EPI_F32, fin_lo ? m->ws + L.ctx + fin_lo * 2 : nullptr, 0, m->prefix_frag};
       GemmPlan pl{};
       BT_HIP(m, gemm_plan(c.dtype, &p, 1, &pl));
       BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));
@@ -719,6 +735,7 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
   }
   StackArgs a{MODE_TOKEN, B * rows, B, 0, rows, pos0};
   if (r != 0 && c.n_token_layers > 0) { a.emb_table = m->w.E_tok; a.emb_ids = cur; a.emb_stride = c.block_len; a.emb_off = r - 1; }
+  if (c.token_mix == BT_MIX_SUM) { a.add = m->at<float>(L.summands) + (size_t)r * D; a.add_stride = c.block_len * D; }
   int rc = run_stack(m, m->tok.data(), c.n_token_layers, a, m->w.tok_lnf_g, m->w.tok_lnf_b,
                      m->ws + L.hfin, 0, B, rows, rows - 1);
   if (rc) return rc;

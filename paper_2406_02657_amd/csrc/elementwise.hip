@@ -145,7 +145,8 @@ struct LnCold {
   const int32_t* emb_ids;
   int* counter_inc;
   const int* in_off_dev;
-  int emb_stride, emb_off;
+  const float* add;          // summation token decoder: row i also gets add[i * add_stride + col]
+  int emb_stride, emb_off, add_stride;
 };
 
 template <class T, int VPT, bool EXTRA, int BATCH = kLnBatch>
@@ -175,12 +176,16 @@ __device__ __forceinline__ void resid_ln_body(const LnHot& a, const LnCold& cold
       b2e = a.g2 ? *reinterpret_cast<const float4*>(a.b2 + 4 * g) : zero;
     }
     float4 acc;
+    const float* add = EXTRA ? cold.add : nullptr;
     if (emb_table) {
       const T* er = reinterpret_cast<const T*>(emb_table) + (size_t)cold.emb_ids[(size_t)i * cold.emb_stride + cold.emb_off] * D + 4 * g;
       acc = make_float4(to_float<T>(er[0]), to_float<T>(er[1]), to_float<T>(er[2]), to_float<T>(er[3]));
+    } else if (add) {
+      acc = zero;                                   // the row is the added vector alone
     } else {
       acc = *reinterpret_cast<const float4*>(xr + 4 * g);
     }
+    if (add) add4(acc, *reinterpret_cast<const float4*>(add + (size_t)i * cold.add_stride + 4 * g));
     if (nA && a.biasA) add4(acc, *reinterpret_cast<const float4*>(a.biasA + 4 * g));
     if (nB && a.biasB) add4(acc, *reinterpret_cast<const float4*>(a.biasB + 4 * g));
     if (nA + nB) add_partials<BATCH>(acc, a.partA, nA, a.partB, nB, a.part_stride, row * D + 4 * g);
@@ -264,8 +269,8 @@ static hipError_t launch_resid_ln_t(const ResidLnArgs& r, hipStream_t s, const i
   a.part_stride = r.part_stride; a.lo_off = (unsigned)r.lo_off; a.D = r.D; a.in_mul = r.in_mul; a.in_off = r.in_off;
   a.eps = r.eps;
   a.packed = (unsigned)r.splitsA | (unsigned)r.splitsB << 12 | (r.u1_f32 ? 1u << 24 : 0u) | (r.write_x ? 1u << 25 : 0u);
-  if (r.emb_table || r.counter_inc || in_off_dev) {
-    const LnCold c{r.emb_table, r.emb_ids, r.counter_inc, in_off_dev, r.emb_stride, r.emb_off};
+  if (r.emb_table || r.counter_inc || in_off_dev || r.add) {
+    const LnCold c{r.emb_table, r.emb_ids, r.counter_inc, in_off_dev, r.add, r.emb_stride, r.emb_off, r.add_stride};
     if (G <= kLnThreads) resid_ln_extra_kernel<T, 1><<<r.n_rows, kLnThreads, 0, s>>>(a, c);
     else if (G <= 2 * kLnThreads) resid_ln_extra_kernel<T, 2><<<r.n_rows, kLnThreads, 0, s>>>(a, c);
     else resid_ln_extra_kernel<T, 4><<<r.n_rows, kLnThreads, 0, s>>>(a, c);

@@ -51,6 +51,10 @@ struct ResidLnArgs {
   int emb_stride, emb_off;
   // Optional: row i adds 1 to counter_inc[i] (the device-side count of cached blocks of sequence i).
   int* counter_inc;
+  // Optional (summation token decoder, first launch of a stack): row i also gets the float vector
+  // add[i * add_stride ...]; without emb_table the row is that vector alone (x is not read).
+  const float* add;
+  int add_stride;
 };
 // in_off_dev (optional, device memory): row i takes in_off_dev[i] - 1 in place of a.in_off.  It is
 // a launch argument of its own, used by a separate instantiation: the size and field offsets of

@@ -656,3 +656,39 @@ def test_exact_logit_ties_pick_the_lowest_id(amd, path, dtype, B, V):
     ids, lgs = gpu_generate(m, prompts, 6)
     m.close()
     assert np.all(lgs == 0.0) and np.all(ids == 0)
+
+
+@pytest.mark.parametrize("dtype,lb,d,h,b", [("fp32", 4, 64, 2, 3), ("fp32", 2, 128, 4, 2), ("bf16", 4, 256, 4, 6), ("bf16", 8, 128, 2, 70),
+                                            ("bf16", 1, 128, 2, 5)])
+def test_summation_token_decoder(amd, dtype, lb, d, h, b):
+    """App. D.2 "Summation": the context embedding projected to L_B vectors, vector k added to the token
+    decoder's input at local position k (position 0 holds vector 0 alone); generation across several
+    blocks, graphs on, against the oracle."""
+    cfg = tiny_cfg(dtype=dtype, block_len=lb, prefix_len=1, token_mix="sum", d_model=d, n_heads=h, d_ff=2 * d, vocab=300,
+                   prompt_len=2 * lb, n_block_layers=2, n_token_layers=2)
+    rep, st, ids, _ = run_case(amd, cfg, 3 * lb + 2, batch=b)
+    assert st.local_kv_high_water == lb and st.token_rows == 3 * lb + 2
+    # and it is not the prefix model in disguise: the same weights read as one prefix token give other ids or logits
+    W = make_weights(cfg)
+    Wp = dict(W); Wp["W_prefix"] = W["W_prefix"][:d].copy(); Wp["b_prefix"] = W["b_prefix"][:d].copy()
+    if lb > 1:
+        m = amd.Model(cfg.with_(token_mix="prefix"), Wp, max_batch=b, max_blocks=8)
+        _, lg_p = gpu_generate(m, make_prompts(cfg, batch=b), 2)
+        m.close()
+        m = amd.Model(cfg, W, max_batch=b, max_blocks=8)
+        _, lg_s = gpu_generate(m, make_prompts(cfg, batch=b), 2)
+        m.close()
+        assert np.array_equal(lg_p[:, 0], lg_s[:, 0])          # position 0: summand 0 alone = the one prefix token
+        assert np.abs(lg_p[:, 1] - lg_s[:, 1]).max() > 1e-4    # position 1: the summand is there
+
+
+def test_summation_needs_its_configuration(amd):
+    import ctypes as C
+    cfg = tiny_cfg(dtype="fp32", block_len=4, prefix_len=2, token_mix="sum", d_model=64, n_heads=2, d_ff=128, vocab=50)
+    c = amd.binding.make_config(cfg, max_batch=2, max_blocks=8)
+    n = C.c_size_t(0)
+    assert amd.lib.bt_workspace_bytes(C.byref(c), C.byref(n)) == amd.binding.BT_ERR_ARG      # prefix_len must be 1
+    c.prefix_len = 1
+    assert amd.lib.bt_workspace_bytes(C.byref(c), C.byref(n)) == 0
+    c.score_rows = 8
+    assert amd.lib.bt_workspace_bytes(C.byref(c), C.byref(n)) == amd.binding.BT_ERR_ARG      # no scoring
