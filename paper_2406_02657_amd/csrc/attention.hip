@@ -158,18 +158,24 @@ __device__ __forceinline__ void wave_attend(const float* q, const T* __restrict_
 }
 
 // ---------------------------------------------------------------------------
-// Block decoder, decode step.  Grid: one workgroup per (b, h) (+ optional extra
+// Block decoder, decode step.  Grid: n_split workgroups per (b, h) (+ optional extra
 // workgroups that turn the MLP up-projection into its activation).  The
 // workgroup first finishes this head's q, k, v (split-K pieces + bias, rotary),
 // appends k, v to the cache at slot n_old, then its NW waves split the n_old
 // cached rows; partial (m, l, acc) meet in LDS, where the new row joins them.
+// With few (b, h) pairs (small batches) one workgroup per pair would leave most
+// CUs idle however long the cache is: the rows of a pair are then cut into
+// n_split contiguous ranges, one workgroup each; a workgroup leaves its
+// unnormalised (acc, m, l) in `split_out` and attn_split_combine_kernel merges
+// the ranges in a fixed order.  Range 0 appends the new row and counts it in.
 // ---------------------------------------------------------------------------
 template <class T, int DH, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(PartialSrc qkv, T* __restrict__ Kc, T* __restrict__ Vc,
                                                                     const float2* __restrict__ rope, int rot,
                                                                     T* __restrict__ out, size_t out_lo_off, int n_heads,
                                                                     int n_old_arg, const int* __restrict__ n_dev, int n_cap,
-                                                                    int n_attn_blocks, GeluJob gelu) {
+                                                                    int n_attn_blocks, GeluJob gelu, int n_split,
+                                                                    float* __restrict__ split_out) {
   using R = RowMap<T, DH>;
   constexpr int EPC = R::EPC, LPR = R::LPR;
   __shared__ float s_m[NW], s_l[NW];
@@ -182,7 +188,7 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(PartialSrc q
   }
   // the number of cached blocks may live in device memory, so that a captured graph of the
   // step stays valid while the cache grows
-  const int bh = blockIdx.x;
+  const int bh = blockIdx.x / n_split, sp = blockIdx.x - bh * n_split;
   const int b = bh / n_heads, h = bh - b * n_heads;
   const int n_old = n_dev ? min(n_dev[b], n_cap - 1) : n_old_arg;
   const int D = n_heads * DH, half = rot / 2;
@@ -190,9 +196,12 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(PartialSrc q
   const int sub = lane % LPR;
   T* K = Kc + (size_t)bh * n_cap * DH;
   T* V = Vc + (size_t)bh * n_cap * DH;
-  // the cached rows of this wave: their first batch of loads goes out before anything else
-  const int per = (n_old + NW - 1) / NW;
-  const int j0 = min(wave * per, n_old), j1 = min(j0 + per, n_old);
+  // the cached rows of this workgroup's range and, inside it, of this wave: their first batch of loads
+  // goes out before anything else
+  const int range = (n_old + n_split - 1) / n_split;
+  const int r0 = min(sp * range, n_old), r1 = min(r0 + range, n_old);
+  const int per = (r1 - r0 + NW - 1) / NW;
+  const int j0 = min(r0 + wave * per, r1), j1 = min(j0 + per, r1);
   uint4 kraw[kAttnU], vraw[kAttnU];
   if (j0 < j1) attend_issue<T, DH>(K, V, j0, j0, j1, kraw, vraw);
 
@@ -219,8 +228,10 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(PartialSrc q
   __syncthreads();
   if (d < DH) {
     const T kt = from_float<T>(kd), vt = from_float<T>(s_v[d]);
-    K[(size_t)n_old * DH + d] = kt;
-    V[(size_t)n_old * DH + d] = vt;
+    if (sp == 0) {
+      K[(size_t)n_old * DH + d] = kt;
+      V[(size_t)n_old * DH + d] = vt;
+    }
     s_q[d] = qd * rsqrtf((float)DH);
     s_k[d] = to_float<T>(kt);          // the new row takes part with its stored (rounded) values
     s_v[d] = to_float<T>(vt);
@@ -244,11 +255,12 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(PartialSrc q
     for (int e = 0; e < EPC; ++e) s_acc[wave][sub * EPC + e] = acc[e];
   }
   __syncthreads();
+  const float snew = sp == 0 ? s_new : kNegBig;          // the new row belongs to range 0
   for (int dd = threadIdx.x; dd < DH; dd += NW * 64) {
-    float M = s_new;
+    float M = snew;
 #pragma unroll
     for (int w = 0; w < NW; ++w) M = fmaxf(M, s_m[w]);
-    const float fn = __expf(s_new - M);
+    const float fn = sp == 0 ? __expf(snew - M) : 0.f;
     float L = fn, o = fn * s_v[dd];
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
@@ -256,7 +268,44 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(PartialSrc q
       L += s_l[w] * f;
       o += s_acc[w][dd] * f;
     }
-    store_act<T>(out, (size_t)b * D + h * DH + dd, out_lo_off, o / L);
+    if (n_split == 1) {
+      store_act<T>(out, (size_t)b * D + h * DH + dd, out_lo_off, o / L);
+    } else {
+      float* po = split_out + (size_t)blockIdx.x * (DH + 2);
+      po[dd] = o;
+      if (dd == 0) { po[DH] = M; po[DH + 1] = L; }
+    }
+  }
+}
+
+// Merge of the n_split ranges of every (b, h): one wave per pair, ranges in index order.
+template <class T, int DH>
+__global__ __launch_bounds__(256) void attn_split_combine_kernel(const float* __restrict__ split_out, int n_split, int n_pairs,
+                                                                 int n_heads, T* __restrict__ out, size_t out_lo_off) {
+  const int lane = threadIdx.x & 63;
+  const int bh = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (bh >= n_pairs) return;
+  const int b = bh / n_heads, h = bh - b * n_heads, D = n_heads * DH;
+  const float* p = split_out + (size_t)bh * n_split * (DH + 2);
+  float M = kNegBig;
+  for (int s = 0; s < n_split; ++s) M = fmaxf(M, p[(size_t)s * (DH + 2) + DH]);
+  float L = 0.f, o[(DH + 63) / 64];
+#pragma unroll
+  for (int c = 0; c < (DH + 63) / 64; ++c) o[c] = 0.f;
+  for (int s = 0; s < n_split; ++s) {
+    const float* ps = p + (size_t)s * (DH + 2);
+    const float f = __expf(ps[DH] - M);
+    L += ps[DH + 1] * f;
+#pragma unroll
+    for (int c = 0; c < (DH + 63) / 64; ++c) {
+      const int d = lane + 64 * c;
+      if (d < DH) o[c] += ps[d] * f;
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < (DH + 63) / 64; ++c) {
+    const int d = lane + 64 * c;
+    if (d < DH) store_act<T>(out, (size_t)b * D + h * DH + d, out_lo_off, o[c] / L);
   }
 }
 
@@ -777,20 +826,38 @@ hipError_t launch_gelu_reduce(int dtype, const GeluJob& job, hipStream_t s) {
 
 hipError_t launch_attn_block_decode(int dtype, const PartialSrc& qkv, void* Kc, void* Vc, const float2* rope, int rot,
                                     void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_old,
-                                    const int* n_dev, int n_cap, const GeluJob& gelu, hipStream_t s) {
+                                    const int* n_dev, int n_cap, const GeluJob& gelu, int n_split, float* split_buf,
+                                    hipStream_t s) {
   if (!n_dev && (n_old < 0 || n_old >= n_cap)) return hipErrorInvalidValue;
   if (gelu.rows > 0 && gelu.cols % 4) return hipErrorInvalidValue;
+  if (n_split < 1 || (n_split > 1 && !split_buf)) return hipErrorInvalidValue;
   constexpr int NW = 4;
-  const int n_attn = batch * n_heads;
+  const int n_pairs = batch * n_heads;
+  const int n_attn = n_pairs * n_split;
   const int grid = n_attn + gelu_blocks(gelu);
   if (dtype == BT_F32) {
     BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<float, DH, NW><<<grid, NW * 64, 0, s>>>(
-        qkv, (float*)Kc, (float*)Vc, rope, rot, (float*)out, 0, n_heads, n_old, n_dev, n_cap, n_attn, gelu)));
+        qkv, (float*)Kc, (float*)Vc, rope, rot, (float*)out, 0, n_heads, n_old, n_dev, n_cap, n_attn, gelu, n_split, split_buf)));
+    if (n_split > 1)
+      BT_DISPATCH_DH(d_head, (attn_split_combine_kernel<float, DH><<<(n_pairs + 3) / 4, 256, 0, s>>>(
+          split_buf, n_split, n_pairs, n_heads, (float*)out, 0)));
   } else {
     BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<bf16_t, DH, NW><<<grid, NW * 64, 0, s>>>(
-        qkv, (bf16_t*)Kc, (bf16_t*)Vc, rope, rot, (bf16_t*)out, out_lo_off, n_heads, n_old, n_dev, n_cap, n_attn, gelu)));
+        qkv, (bf16_t*)Kc, (bf16_t*)Vc, rope, rot, (bf16_t*)out, out_lo_off, n_heads, n_old, n_dev, n_cap, n_attn, gelu, n_split, split_buf)));
+    if (n_split > 1)
+      BT_DISPATCH_DH(d_head, (attn_split_combine_kernel<bf16_t, DH><<<(n_pairs + 3) / 4, 256, 0, s>>>(
+          split_buf, n_split, n_pairs, n_heads, (bf16_t*)out, out_lo_off)));
   }
   return hipGetLastError();
+}
+
+int attn_block_decode_splits(int batch, int n_heads, int n_cap) {
+  const int pairs = batch * n_heads;
+  if (pairs >= 256) return 1;                       // enough workgroups already
+  int s = 512 / pairs;                              // about two workgroups per CU
+  const int by_len = n_cap / 128 > 1 ? n_cap / 128 : 1;      // at least 128 cached rows per range at full cache
+  if (s > by_len) s = by_len;
+  return s > 16 ? 16 : (s < 1 ? 1 : s);
 }
 
 hipError_t launch_attn_block_prefill(int dtype, const float* qkv, const void* Kc, const void* Vc,

@@ -36,7 +36,7 @@ void* g_scratch_ptr[kMaxDevices];            // device address of `scratch` on d
 const bt_model* g_scratch_owner[kMaxDevices];   // the live model that uses it, if any
 
 struct Layout {
-  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cand, cur, state, lens, fin, summands, score_kv, score_logits, frag, total;
+  size_t blk_kv, loc_kv, rope, x, u1, u2, qkv, ao, hmid, part_o, part_d, part_u, ctx, hfin, logits, cand, cur, state, lens, fin, summands, attn_split, score_kv, score_logits, frag, total;
   size_t blk_layer_stride, loc_layer_stride;   // bytes between layers (K then V inside)
   size_t part_elems;                           // floats in each of part_o, part_d
   size_t qkv_elems, part_u_elems;              // floats in qkv (may hold split-K pieces) and part_u
@@ -125,6 +125,8 @@ void make_layout(const bt_config& c, Layout& L) {
   L.state = take(B * 4);       // cached blocks per sequence (device-side counters)
   L.lens = take(B * 4);        // prompt lengths of the last prefill
   L.fin = take(B * 4);         // per sequence: has emitted eos_id
+  // block-decoder decode attention at small batches: the ranges' partial results (at most 16 ranges of 255 pairs)
+  L.attn_split = take((size_t)16 * 256 * (dh + 2) * 4);
   // summation token decoder: the L_B vectors the context embedding was projected to, per sequence
   L.summands = take(c.token_mix == BT_MIX_SUM ? B * c.block_len * D * 4 : 0);
   // teacher-forced scoring (score_rows > 0): the local KV of every block scored in one chunk (one
@@ -375,7 +377,8 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
       int prc;
       if (m->profile && (prc = prof_begin(m, 0))) return prc;
       BT_HIP(m, launch_attn_block_decode(dt, qsrc, Kc, Vc, rope, c.rotary_dims, ao, loD, a.batch, H, dh, n_old,
-                                         m->at<int>(L.state), c.max_blocks, gelu, s));
+                                         m->at<int>(L.state), c.max_blocks, gelu,
+                                         attn_block_decode_splits(a.batch, H, c.max_blocks), m->at<float>(L.attn_split), s));
       if (m->profile) {
         if ((prc = prof_end(m))) return prc;
         m->st.attn_block_launches += 1;

@@ -201,10 +201,15 @@ hipError_t launch_rope_append(int dtype, const PartialSrc& src, void* Kc, void* 
 // also the bf16 remainder plane).  n_dev: when non-null, sequence b reads its own n_old from
 // device memory (n_dev[b]): a captured graph stays valid while the caches grow, and the
 // sequences of a batch may hold different numbers of blocks.  gelu: optional job
-// done by extra workgroups of the same launch.
+// done by extra workgroups of the same launch.  n_split > 1: the cached rows of every (b, h) are
+// cut into n_split ranges, one workgroup each, merged by a second small launch through split_buf
+// (float [batch * n_heads * n_split][d_head + 2]); attn_block_decode_splits() gives the count this
+// library uses for a batch, head count and cache capacity (1 when there are 256 pairs or more).
 hipError_t launch_attn_block_decode(int dtype, const PartialSrc& qkv, void* Kc, void* Vc, const float2* rope, int rot,
                                     void* out, size_t out_lo_off, int batch, int n_heads, int d_head, int n_old,
-                                    const int* n_dev, int n_cap, const GeluJob& gelu, hipStream_t s);
+                                    const int* n_dev, int n_cap, const GeluJob& gelu, int n_split, float* split_buf,
+                                    hipStream_t s);
+int attn_block_decode_splits(int batch, int n_heads, int n_cap);
 
 // Block decoder prefill: causal attention of n_q queries per (b, h); query i sees rows [0, i].
 hipError_t launch_attn_block_prefill(int dtype, const float* qkv, const void* Kc, const void* Vc,

@@ -692,3 +692,23 @@ def test_summation_needs_its_configuration(amd):
     assert amd.lib.bt_workspace_bytes(C.byref(c), C.byref(n)) == 0
     c.score_rows = 8
     assert amd.lib.bt_workspace_bytes(C.byref(c), C.byref(n)) == amd.binding.BT_ERR_ARG      # no scoring
+
+
+@pytest.mark.parametrize("dtype,b,h,d,prompt_len,max_blocks", [("bf16", 1, 2, 128, 2048, 1100), ("bf16", 3, 4, 128, 1400, 2100),
+                                                                ("fp32", 2, 2, 64, 700, 400), ("bf16", 2, 1, 128, 10, 2048)])
+def test_block_attention_split_over_workgroups(amd, dtype, b, h, d, prompt_len, max_blocks):
+    """Small batches: fewer than 256 (sequence, head) pairs, so the cached rows of a pair are cut into
+    ranges that run as workgroups of their own and are merged by a second launch (2 .. 16 ranges here;
+    the last case has more ranges than cached rows)."""
+    from parity import compare_sampled_with_oracle, gpu_generate_sampled
+    cfg = tiny_cfg(dtype=dtype, block_len=2, prefix_len=1, d_model=d, n_heads=h, d_ff=2 * d, vocab=200,
+                   prompt_len=prompt_len, n_block_layers=2, n_token_layers=1)
+    W = make_weights(cfg)
+    prompts = make_prompts(cfg, batch=b)
+    m = amd.Model(cfg, W, max_batch=b, max_blocks=max_blocks)
+    n_new = 9
+    ids, lgs = gpu_generate_sampled(m, prompts, n_new, list(range(b)), range(n_new))
+    m.close()
+    rep = compare_sampled_with_oracle(cfg, W, prompts, ids, lgs, list(range(b)), TOL_F32 if dtype == "fp32" else TOL_BF16)
+    print(rep)
+    assert_parity(rep)
