@@ -174,6 +174,8 @@ def main():
     ap.add_argument("--prefix-len", type=int, default=-1, help="override P, the prefix length of the token decoder "
                     "(0 only together with --block-len 1: the vanilla-equivalent run)")
     ap.add_argument("--block-len", type=int, default=0, help="override L_B (must divide the model width)")
+    ap.add_argument("--layers", default="", metavar="NB,NT", help="override the layer split: NB block-decoder and NT "
+                    "token-decoder layers (the paper's allocation-ratio sweep at a fixed total)")
     ap.add_argument("--max-batch", action="store_true",
                     help="use the largest batch (a multiple of 64) whose workspace plus weights fit the free device "
                          "memory, the paper's maximum-throughput setting; overrides --batch")
@@ -225,6 +227,9 @@ def main():
         cfg = cfg.with_(prefix_len=args.prefix_len)
     if args.block_len:
         cfg = cfg.with_(block_len=args.block_len)
+    if args.layers:
+        nb, nt = (int(v) for v in args.layers.split(","))
+        cfg = cfg.with_(n_block_layers=nb, n_token_layers=nt)
     if args.max_batch:
         cfg = cfg.with_(batch=largest_batch(cfg, amd, torch))
     if args.score:
@@ -232,7 +237,7 @@ def main():
         score_bench(args, cfg, make_weights(cfg))
         return
     overridden = bool(args.gen_len or args.batch or args.prompt_len or args.prefix_len >= 0 or args.block_len
-                      or args.max_batch)
+                      or args.max_batch or args.layers)
     res, W, prompts = run_generation(args, amd, torch, cfg, args.steps, args.warmup, overridden)
     out = {
         "metric": "output tokens/sec on 1 MI355X", "value": res.pop("tokens_per_s"), "unit": "tokens/s", "n_gpus": 1,

@@ -431,17 +431,47 @@ __global__ __launch_bounds__(256) void attn_block_prefill_mfma_kernel(const floa
 
   const int last_key_wg = min(q_wg + 63, n_q - 1);
   const int last_key_w = min(q_w + 15, n_q - 1);
-  for (int k0 = 0; k0 <= last_key_wg; k0 += KB) {
-    // V block -> LDS, transposed.  Thread t: key t / (DH/8), dims 8 (t % (DH/8)) .. + 8.
-    __syncthreads();                       // the previous block's fragments have been read
-    for (int c = tid; c < KB * (DH / 8); c += 256) {
-      const int key = c / (DH / 8), dc = c - key * (DH / 8);
-      uint4 v = *reinterpret_cast<const uint4*>(V + (size_t)min(k0 + key, n_cap - 1) * DH + dc * 8);
-      if (k0 + key >= n_q) v = make_uint4(0u, 0u, 0u, 0u);     // never-written rows may hold NaN patterns: 0 * NaN
-      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  // The V chunks and K fragments of a key block travel in registers while the block before it is
+  // worked on: thread t stages V of key c / (DH/8), dims 8 (c % (DH/8)) .. + 8 for its chunks c = t, t + 256;
+  // a lane's K fragments are rows k0 + 16 t + lr, dims 32 c + 8 lg .. + 8.
+  constexpr int VCH = (KB * (DH / 8) + 255) / 256;
+  uint4 vnext[VCH], knext[2][NC];
+  auto fetch = [&](int k0) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) sVt[(dc * 8 + e) * KP + key] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+    for (int u = 0; u < VCH; ++u) {
+      const int c = min(tid + u * 256, KB * (DH / 8) - 1);
+      const int key = c / (DH / 8), dc = c - key * (DH / 8);
+      vnext[u] = *reinterpret_cast<const uint4*>(V + (size_t)min(k0 + key, n_cap - 1) * DH + dc * 8);
     }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const bf16_t* kp = K + (size_t)min(k0 + t * 16 + lr, n_cap - 1) * DH + lg * 8;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) knext[t][c] = *reinterpret_cast<const uint4*>(kp + c * 32);
+    }
+  };
+  fetch(0);
+  for (int k0 = 0; k0 <= last_key_wg; k0 += KB) {
+    // V block -> LDS, transposed
+    __syncthreads();                       // the previous block's fragments have been read
+#pragma unroll
+    for (int u = 0; u < VCH; ++u) {
+      const int c = tid + u * 256;
+      if (c < KB * (DH / 8)) {
+        const int key = c / (DH / 8), dc = c - key * (DH / 8);
+        uint4 v = vnext[u];
+        if (k0 + key >= n_q) v = make_uint4(0u, 0u, 0u, 0u);     // never-written rows may hold NaN patterns: 0 * NaN
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sVt[(dc * 8 + e) * KP + key] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+      }
+    }
+    abf16x8_t kcur[2][NC];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int c = 0; c < NC; ++c) kcur[t][c] = __builtin_bit_cast(abf16x8_t, knext[t][c]);
+    if (k0 + KB <= last_key_wg) fetch(k0 + KB);          // uniform over the workgroup: the next block starts its trip
     __syncthreads();
     if (k0 <= last_key_w) {                // blocks entirely above this wave's diagonal contribute nothing
       // S = Q K^T for two 16-key tiles
@@ -449,10 +479,9 @@ __global__ __launch_bounds__(256) void attn_block_prefill_mfma_kernel(const floa
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         sacc[t] = af32x4_t{0.f, 0.f, 0.f, 0.f};
-        const bf16_t* kp = K + (size_t)min(k0 + t * 16 + lr, n_cap - 1) * DH + lg * 8;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-          const abf16x8_t kf = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(kp + c * 32));
+          const abf16x8_t kf = kcur[t][c];
           sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qh[c], kf, sacc[t], 0, 0, 0);
           sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ql[c], kf, sacc[t], 0, 0, 0);
         }
@@ -464,15 +493,11 @@ __global__ __launch_bounds__(256) void attn_block_prefill_mfma_kernel(const floa
         const int qi = q_w + 4 * lg + r;
         float s0 = (k0 + lr <= qi) ? sacc[0][r] : kNegBig;
         float s1 = (k0 + 16 + lr <= qi) ? sacc[1][r] : kNegBig;
-        float mx = fmaxf(s0, s1);
-#pragma unroll
-        for (int off = 8; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+        const float mx = row16_max(fmaxf(s0, s1));        // over the 16 lanes that hold this query's keys
         const float mn = fmaxf(m[r], mx);
         const float p0 = (k0 + lr <= qi) ? __expf(s0 - mn) : 0.f;
         const float p1 = (k0 + 16 + lr <= qi) ? __expf(s1 - mn) : 0.f;
-        float ps = p0 + p1;
-#pragma unroll
-        for (int off = 8; off > 0; off >>= 1) ps += __shfl_xor(ps, off, kWave);
+        const float ps = row16_sum(p0 + p1);
         alpha[r] = __expf(m[r] - mn);
         l[r] = l[r] * alpha[r] + ps;
         m[r] = mn;

@@ -329,6 +329,16 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
       (size_t)sQ * M * 3 * D > L.qkv_elems || (pieces && (size_t)sU * M * F > L.part_u_elems))
     return fail(m, BT_ERR_CAPACITY, "split-K partial buffer too small");
 
+  // Prefill with the tiled MFMA kernels: rotary and the KV append ride in the QKV GEMM's epilogue
+  const bool qkv_fused = a.mode == MODE_BLOCK_PREFILL && !pieces && dt == BT_BF16 && c.parallel_residual &&
+                         gemm_has_lse_epilogue(plan_in) && gemm_qkv_epilogue_ok(D, dh, c.rotary_dims);
+  auto qkv_epilogue = [&](int l, GemmProblem& p) {
+    char* base = m->ws + L.blk_kv + (size_t)l * L.blk_layer_stride;
+    const size_t half = (size_t)c.max_batch * H * c.max_blocks * dh * L.esz;
+    const size_t seq = (size_t)a.b0 * H * c.max_blocks * dh * L.esz;
+    p.epi = EPI_QKV;
+    p.qe = QkvEpilogue{rope, base + seq, base + half + seq, a.rows, a.pos0, H, dh, c.rotary_dims, c.max_blocks};
+  };
   auto ln = [&](const float* pO, const float* bO, int nO, const float* pD, const float* bD, int nD,
                 const void* g1, const void* b1, const void* g2, const void* b2) -> int {
     ResidLnArgs r{};
@@ -369,8 +379,9 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     char* Kc = base + seq;
     char* Vc = base + half + seq;
     if (a.mode == MODE_BLOCK_PREFILL) {
-      BT_HIP(m, launch_rope_append(dt, qsrc, Kc, Vc, rope, M, a.rows, a.pos0, H, dh, c.rotary_dims,
-                                   c.max_blocks, gelu, s));
+      if (!qkv_fused)        // else the QKV GEMM's epilogue has rotated q and k and filled the cache
+        BT_HIP(m, launch_rope_append(dt, qsrc, Kc, Vc, rope, M, a.rows, a.pos0, H, dh, c.rotary_dims,
+                                     c.max_blocks, gelu, s));
       BT_HIP(m, launch_attn_block_prefill(dt, qkv, Kc, Vc, ao, loD, a.batch, H, dh, a.rows, c.max_blocks, s));
     } else {
       const int n_old = a.pos0;
@@ -405,6 +416,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
       p[0].W = lw[l].W_qkv; p[1].W = lw[l].W_up;
       p[0].W_frag = fw[l].qkv; p[1].W_frag = fw[l].up;
       if (!pieces) { p[0].bias = (const float*)lw[l].b_qkv; p[1].bias = (const float*)lw[l].b_up; }
+      if (qkv_fused) qkv_epilogue(l, p[0]);
       const bool prof_gemm = m->profile && pieces, prof_tiled = m->profile && !pieces;
       if (m->profile && (rc = prof_begin(m, pieces ? 1 : 2))) return rc;
       BT_HIP(m, launch_gemm(dt, p, 2, plan_in, s));

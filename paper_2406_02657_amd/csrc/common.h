@@ -84,6 +84,24 @@ __device__ __forceinline__ void store_act4<bf16_t>(bf16_t* p, size_t i, size_t l
   }
 }
 
+// All-reduce over the 16 lanes of a DPP row (lanes 16 g .. 16 g + 15) by rotations inside the row
+// (control 0x120 + n = rotate right by n): register to register, where a shuffle goes through the
+// LDS crossbar.  After the four steps every lane of the row holds the result.
+template <int CTRL>
+__device__ __forceinline__ float dpp_row_ror(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_row_ror<0x128>(v)); v = fmaxf(v, dpp_row_ror<0x124>(v));
+  v = fmaxf(v, dpp_row_ror<0x122>(v)); v = fmaxf(v, dpp_row_ror<0x121>(v));
+  return v;
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_row_ror<0x128>(v); v += dpp_row_ror<0x124>(v);
+  v += dpp_row_ror<0x122>(v); v += dpp_row_ror<0x121>(v);
+  return v;
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

@@ -30,6 +30,7 @@ struct GemmDesc {
   float2* row_max;       // per (column tile, row) candidates for argmax, or null
   const int32_t* lse_targets;   // EPI_LSE: per row the column whose value goes to lse_target_out
   float* lse_target_out;
+  QkvEpilogue qe;               // EPI_QKV
   int tiles_m, tiles_n, tile_begin;   // tiles of this problem occupy blocks [tile_begin, tile_begin + tiles_m*tiles_n*splits)
 };
 struct GemmGroup {
@@ -98,9 +99,10 @@ struct EpiArgs {
   const int32_t* lse_targets;
   float* lse_target_out;
   float2* row_max;
+  QkvEpilogue qe;
 };
 __device__ __forceinline__ EpiArgs epi_args(const GemmDesc& d) {
-  return EpiArgs{d.out, d.bias, d.M, d.N, d.ldo, d.epi, d.out_lo_off, d.lse_targets, d.lse_target_out, d.row_max};
+  return EpiArgs{d.out, d.bias, d.M, d.N, d.ldo, d.epi, d.out_lo_off, d.lse_targets, d.lse_target_out, d.row_max, d.qe};
 }
 
 template <class T>
@@ -145,6 +147,58 @@ template <class T, int TM, int TN>
 __device__ __forceinline__ void epilogue_tiles(const EpiArgs& ea, int split, int row_base, int col_base, int lane,
                                                const f32x4_t (&acc)[TM][TN]) {
   const int row_l = lane & 15, col_l = (lane >> 4) * 4;
+  if (ea.epi == EPI_QKV) {
+    // Block-decoder prefill: q | k | v columns.  Rotary pairs column d with d + half inside a head's first
+    // `rot` dims: with half == 8 the partner is the same accumulator element of lane ^ 32, with half == 16
+    // the same lane's element of the neighbouring 16-column tile.  Every branch below depends on the tile
+    // only (wave-uniform), so the shuffles are executed by all lanes.
+    const QkvEpilogue& q = ea.qe;
+    const int D = ea.N / 3, DH = q.d_head, half = q.rot >> 1;
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int row = row_base + i * 16 + row_l;
+      const int rr = min(row, ea.M - 1);
+      const int b = rr / q.n_new, pos = q.pos0 + (rr - b * q.n_new);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col0 = col_base + j * 16;                  // first column of the tile (wave-uniform)
+        if (col0 >= ea.N) continue;
+        const int region = col0 / D, c0 = col0 - region * D;
+        const int h = c0 / DH, d0 = c0 - h * DH;             // the tile's 16 columns lie in one head (DH % 16 == 0)
+        const int col = col0 + col_l, d = d0 + col_l;
+        const float4 bia = ea.bias ? *reinterpret_cast<const float4*>(ea.bias + col) : zero4;
+        float v[4] = {acc[i][j][0] + bia.x, acc[i][j][1] + bia.y, acc[i][j][2] + bia.z, acc[i][j][3] + bia.w};
+        if (region < 2 && d0 < q.rot) {
+          float pv[4];
+          if (half == 8) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) pv[r] = __shfl_xor(v[r], 32, kWave);
+          } else {                                           // half == 16: tile j ^ 1 of this lane
+            const float4 pb = ea.bias ? *reinterpret_cast<const float4*>(ea.bias + (col ^ 16)) : zero4;
+            const f32x4_t pa = acc[i][j ^ 1];
+            pv[0] = pa[0] + pb.x; pv[1] = pa[1] + pb.y; pv[2] = pa[2] + pb.z; pv[3] = pa[3] + pb.w;
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int dd = d + r;
+            const bool lo = dd < half;
+            const float2 cs = q.rope[(size_t)pos * half + (lo ? dd : dd - half)];
+            v[r] = lo ? v[r] * cs.x - pv[r] * cs.y : v[r] * cs.x + pv[r] * cs.y;
+          }
+        }
+        if (row < ea.M) {
+          if (region == 0) {
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(ea.out) + (size_t)row * ea.ldo + col) = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
+            T* cache = reinterpret_cast<T*>(region == 1 ? q.Kc : q.Vc);
+            store_act4<T>(cache, ((size_t)(b * q.n_heads + h) * q.n_cap + pos) * DH + d, 0, v[0], v[1], v[2], v[3]);
+          }
+        }
+      }
+    }
+    return;
+  }
   if (ea.epi == EPI_LSE) {
     // Log-sum-exp pieces instead of the values: this wave holds, for each of its 16 * TM rows, 16 * TN
     // consecutive columns (one group when TN == 4); the four lanes that share a row combine by shuffles.
@@ -938,6 +992,11 @@ size_t kslice_lds_bytes(int M, int kf, bool hl) {
 }
 }  // namespace
 
+bool gemm_qkv_epilogue_ok(int d_model, int d_head, int rot) {
+  const int half = rot / 2;
+  return d_model % 64 == 0 && d_head % 16 == 0 && (rot == 0 || ((half == 8 || half == 16) && rot <= d_head));
+}
+
 bool gemm_has_lse_epilogue(const GemmPlan& plan) { return plan.kind == KIND_TILE256 || plan.kind == KIND_TILE128; }
 
 int gemm_row_max_tiles(const GemmProblem& p, const GemmPlan& plan) {
@@ -1179,6 +1238,10 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
     g.p[i].epi = p.epi; g.p[i].splits = sp;
     g.p[i].A_lo = p.A_lo; g.p[i].out_lo_off = p.out_lo_off; g.p[i].W_frag = p.W_frag; g.p[i].row_max = p.row_max;
     g.p[i].lse_targets = p.lse_targets; g.p[i].lse_target_out = p.lse_target_out;
+    g.p[i].qe = p.qe;
+    if (p.epi == EPI_QKV && ((plan.kind != KIND_TILE256 && plan.kind != KIND_TILE128) || sp != 1 || p.N % 3 ||
+                             !gemm_qkv_epilogue_ok(p.N / 3, p.qe.d_head, p.qe.rot) || !p.qe.Kc || !p.qe.Vc || p.qe.n_new < 1))
+      return hipErrorInvalidValue;
     if (p.epi == EPI_LSE && ((plan.kind != KIND_TILE256 && plan.kind != KIND_TILE128) || sp != 1 || !p.lse_target_out)) return hipErrorInvalidValue;
     if ((p.A_lo != nullptr) != (probs[0].A_lo != nullptr)) return hipErrorInvalidValue;
   }

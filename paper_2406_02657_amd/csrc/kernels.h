@@ -109,6 +109,10 @@ enum { EPI_F32 = 0,        // out float [M, ldo]: acc + bias
        EPI_GELU = 1,       // out storage dtype: gelu(acc + bias)
        EPI_PARTIAL = 2,    // out float [splits][M][N]: raw partial sums (no bias); the consumer
                            // sums the splits in order and applies bias / activation
+       EPI_QKV = 4,        // tiled bf16 kernels only, N = 3 D (q | k | v): the block decoder's prefill.  acc + bias,
+                           // then per column region: q rotated (rotary) and stored float into out [M, ldo];
+                           // k rotated, v as is, both stored in the storage dtype straight into the block KV
+                           // cache (see QkvEpilogue); the k and v columns of `out` are not written
        EPI_LSE = 3 };      // tiled bf16 kernels only: the values acc + bias are not stored; out is
                            // float2 [M][ceil(N/64)]: per row and group of 64 columns (max, sum of
                            // exp(value - max)), and the value at column lse_targets[row] goes to
@@ -120,6 +124,16 @@ enum { EPI_F32 = 0,        // out float [M, ldo]: acc + bias
 // out_lo_off (EPI_GELU, bf16 mode): != 0 stores the output as hi / remainder planes.
 // W_frag (bf16 mode, required when M <= 256): the same weights in MFMA fragment order
 // (see gemm_pack_weights); the decode kernel reads only this copy.
+// EPI_QKV: row m of the GEMM is block position pos0 + m % n_new of sequence m / n_new.  Cache layout per
+// layer: K [B][H][n_cap][d_head], V same; rope[pos * (rot/2) + t] = (cos, sin).  rot/2 must be 0, 8 or 16
+// (gemm_qkv_epilogue_ok): the rotation partner of a column then sits in the same wave's accumulators.
+struct QkvEpilogue {
+  const float2* rope;
+  void *Kc, *Vc;
+  int n_new, pos0, n_heads, d_head, rot, n_cap;
+};
+bool gemm_qkv_epilogue_ok(int d_model, int d_head, int rot);
+
 struct GemmProblem {
   const void* A;
   const void* W;
@@ -137,6 +151,8 @@ struct GemmProblem {
   // EPI_LSE only
   const int32_t* lse_targets;
   float* lse_target_out;
+  // EPI_QKV only
+  QkvEpilogue qe;
 };
 // bf16 weights W[N, K] (K % 32 == 0) re-ordered for the decode GEMM: tiles of 16 rows x 32 k,
 // tile (i, j) at element offset (i * K/32 + j) * 512; inside a tile lane l (0..63) owns the 8
@@ -152,7 +168,7 @@ struct GemmPlan {
   int splits[2];
 };
 hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan* plan);
-// Whether the kernel this plan selects implements EPI_LSE.
+// Whether the kernel this plan selects is one of the tiled MFMA kernels, which implement EPI_LSE and EPI_QKV.
 bool gemm_has_lse_epilogue(const GemmPlan& plan);
 // Number of candidate tiles the launch writes per row (0: this plan does not produce them).
 int gemm_row_max_tiles(const GemmProblem& p, const GemmPlan& plan);
