@@ -354,8 +354,8 @@ def run_generation(args, amd, torch, cfg, steps, warmup, overridden, short_warmu
     # the launch reads / writes a constant amount besides (q, k, v and MLP pieces in; GELU, output out)
     pmc = read_profile_keys("cfg1_hbm_traffic_pmc.txt", ("kv_read_over_algorithmic", "other_read_bytes", "write_bytes"))
     pmc_ok = len(pmc) == 3 and cfg.name == "cfg1" and not overridden
-    trace = {} if overridden else read_profile_keys(f"{cfg.name}_generation_kernel_stats.txt",
-                                                    ("attn_block_decode_avg_us", "attn_block_decode_bytes_per_launch"))
+    trace_file = "cfg2_prefill_heavy_kernel_stats.txt" if cfg.name == "cfg2" else f"{cfg.name}_generation_kernel_stats.txt"
+    trace = {} if overridden else read_profile_keys(trace_file, ("attn_block_decode_avg_us", "attn_block_decode_bytes_per_launch"))
     roofline = None
     if st.attn_block_launches > 0 and st.attn_block_ms > 0:
         ach = st.attn_block_bytes / (st.attn_block_ms * 1e-3) / 1e9
@@ -380,7 +380,7 @@ def run_generation(args, amd, torch, cfg, steps, warmup, overridden, short_warmu
             roofline["kernel_trace_avg_us"] = trace["attn_block_decode_avg_us"]
             roofline["frac_kernel_trace"] = (trace["attn_block_decode_bytes_per_launch"]
                                              / (trace["attn_block_decode_avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS)
-            roofline["kernel_trace_source"] = f"profiles/{cfg.name}_generation_kernel_stats.txt"
+            roofline["kernel_trace_source"] = f"profiles/{trace_file}"
     roofline_gemm = None
     planes = 2 if cfg.dtype == "bf16" else 1
     if st.gemm_decode_launches > 0 and st.gemm_decode_ms > 0:
