@@ -49,7 +49,11 @@ widened exactly); nothing else is rounded.
 Parity pins (tests/test_oracle_*.py): cached == full; locality and causality;
 reduction to an independently written vanilla transformer at L_B = 1;
 brute-force attention; closed forms (running mean, constant logits, one-hot
-head); rotary relative-position invariance; operation counts the paper states.
+head); rotary relative-position invariance; operation counts the paper states;
+the bf16 storage path (hand-computed values of bit patterns, round-to-nearest-
+even cases, cached == full on bf16 weights, bit-equal to float32 weights that
+hold the widened values); the summation variant (cached == full, reduction to
+the one-prefix model, causal effect of each summand, inputs written out).
 The numeric value of a logit is otherwise unpinned: the paper prints no worked
 example.
 """
