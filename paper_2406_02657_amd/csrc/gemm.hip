@@ -201,36 +201,40 @@ __device__ __forceinline__ void epilogue_tiles(const EpiArgs& ea, int split, int
   }
   if (ea.epi == EPI_LSE) {
     // Log-sum-exp pieces instead of the values: this wave holds, for each of its 16 * TM rows, 16 * TN
-    // consecutive columns (one group when TN == 4); the four lanes that share a row combine by shuffles.
-    static_assert(TN == 4, "a wave covers one 64-column group");
+    // consecutive columns (TN / 4 groups of 64); the four lanes that share a row combine by shuffles.
+    static_assert(TN % 4 == 0, "a wave covers whole 64-column groups");
     float2* stats = reinterpret_cast<float2*>(ea.out);
-    const int groups = (ea.N + 63) >> 6, group = col_base >> 6;
+    const int groups = (ea.N + 63) >> 6;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       const int row = row_base + i * 16 + row_l;
       const int tgt = (row < ea.M && ea.lse_targets) ? ea.lse_targets[row] : -1;
-      float v[TN][4];
-      float m = -INFINITY;
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int jg = 0; jg < TN / 4; ++jg) {
+        const int group = (col_base >> 6) + jg;
+        float v[4][4];
+        float m = -INFINITY;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int col = col_base + j * 16 + col_l + r;
-          const float x = acc[i][j][r] + ((ea.bias && col < ea.N) ? ea.bias[col] : 0.f);
-          v[j][r] = col < ea.N ? x : -INFINITY;
-          m = fmaxf(m, v[j][r]);
-          if (col == tgt) ea.lse_target_out[row] = x;
-        }
-      m = fmaxf(m, __shfl_xor(m, 16, kWave));
-      m = fmaxf(m, __shfl_xor(m, 32, kWave));
-      float ssum = 0.f;
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+          for (int r = 0; r < 4; ++r) {
+            const int col = col_base + (jg * 4 + j) * 16 + col_l + r;
+            const float x = acc[i][jg * 4 + j][r] + ((ea.bias && col < ea.N) ? ea.bias[col] : 0.f);
+            v[j][r] = col < ea.N ? x : -INFINITY;
+            m = fmaxf(m, v[j][r]);
+            if (col == tgt) ea.lse_target_out[row] = x;
+          }
+        m = fmaxf(m, __shfl_xor(m, 16, kWave));
+        m = fmaxf(m, __shfl_xor(m, 32, kWave));
+        float ssum = 0.f;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) ssum += v[j][r] > -INFINITY ? __expf(v[j][r] - m) : 0.f;
-      ssum += __shfl_xor(ssum, 16, kWave);
-      ssum += __shfl_xor(ssum, 32, kWave);
-      if (lane < 16 && row < ea.M && group < groups) stats[(size_t)row * groups + group] = make_float2(m, ssum);
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) ssum += v[j][r] > -INFINITY ? __expf(v[j][r] - m) : 0.f;
+        ssum += __shfl_xor(ssum, 16, kWave);
+        ssum += __shfl_xor(ssum, 32, kWave);
+        if (lane < 16 && row < ea.M && group < groups) stats[(size_t)row * groups + group] = make_float2(m, ssum);
+      }
     }
     return;
   }
@@ -261,32 +265,36 @@ __device__ __forceinline__ void epilogue_tiles(const EpiArgs& ea, int split, int
     if (ea.row_max) {
       // argmax candidates: per row the largest value of this wave's 64 columns and its column, the
       // lowest on ties: own 16 values first (ascending columns), then the four lanes that share the row
-      static_assert(TN == 4, "a wave covers one 64-column group");
-      const int groups = (ea.N + 63) >> 6, group = col_base >> 6;
+      static_assert(TN % 4 == 0, "a wave covers whole 64-column groups");
+      const int groups = (ea.N + 63) >> 6;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int row = row_base + i * 16 + row_l;
-        float bv = -INFINITY;
-        int bi = 0x7fffffff;
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int jg = 0; jg < TN / 4; ++jg) {
+          const int group = (col_base >> 6) + jg;
+          float bv = -INFINITY;
+          int bi = 0x7fffffff;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int col = col_base + j * 16 + col_l + r;
-            const float x = acc[i][j][r] + ((ea.bias && col < ea.N) ? ea.bias[col] : 0.f);
-            const bool take = (col < ea.N) & (x > bv);
-            bv = take ? x : bv;
-            bi = take ? col : bi;
+          for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int col = col_base + (jg * 4 + j) * 16 + col_l + r;
+              const float x = acc[i][jg * 4 + j][r] + ((ea.bias && col < ea.N) ? ea.bias[col] : 0.f);
+              const bool take = (col < ea.N) & (x > bv);
+              bv = take ? x : bv;
+              bi = take ? col : bi;
+            }
+#pragma unroll
+          for (int o = 16; o <= 32; o <<= 1) {
+            const float ov = __shfl_xor(bv, o, kWave);
+            const int oi = __shfl_xor(bi, o, kWave);
+            const bool take = (ov > bv) | ((ov == bv) & (oi < bi));
+            bv = take ? ov : bv;
+            bi = take ? oi : bi;
           }
-#pragma unroll
-        for (int o = 16; o <= 32; o <<= 1) {
-          const float ov = __shfl_xor(bv, o, kWave);
-          const int oi = __shfl_xor(bi, o, kWave);
-          const bool take = (ov > bv) | ((ov == bv) & (oi < bi));
-          bv = take ? ov : bv;
-          bi = take ? oi : bi;
+          if (lane < 16 && row < ea.M && group < groups) ea.row_max[(size_t)row * groups + group] = make_float2(bv, __int_as_float(bi));
         }
-        if (lane < 16 && row < ea.M && group < groups) ea.row_max[(size_t)row * groups + group] = make_float2(bv, __int_as_float(bi));
       }
     }
   } else {
@@ -296,6 +304,148 @@ __device__ __forceinline__ void epilogue_tiles(const EpiArgs& ea, int split, int
       for (int j = 0; j < TN; ++j)
         epilogue_store4<T, EPI_GELU>(ea, split, row_base + i * 16 + row_l, col_base + j * 16 + col_l, acc[i][j]);
   }
+}
+
+// ---------------------------------------------------------------------------
+// Epilogue of a wave that owns a 16 TM x 64 patch, with the stores turned through LDS.  In the MFMA result layout a store instruction covers 16 rows x 64 bytes
+// (fp32) or 16 rows x 32 bytes (a bf16 plane): a quarter or a half of a cache line per row, and the
+// output traffic of a tile with few k-steps then costs as much as its multiplies.  Here every row tile
+// (16 x 64 floats, finished: bias, GELU or rotary applied) goes to the wave's own LDS strip and comes
+// back with the lanes running along the rows, so that a store instruction writes whole rows of the
+// patch: 256 bytes (fp32) or 128 bytes (a bf16 plane, 16 bytes per lane) per row.  Only the wave
+// itself touches its strip and a wave's LDS operations complete in order, so no barrier is needed.
+// Preconditions (checked by epilogue_through_lds, else the register epilogue is used): col_base a
+// multiple of 64, N % 8 == 0, ldo % 8 == 0; EPI_QKV: D a multiple of 64.
+// ---------------------------------------------------------------------------
+constexpr int kEpiLd = 64 + 4;                  // floats per strip row: the pad keeps the 16-byte writes of 8 rows on distinct banks
+__device__ __forceinline__ bool epilogue_through_lds(const EpiArgs& ea) {
+  return ea.epi != EPI_LSE && (ea.N & 7) == 0 && (ea.ldo & 7) == 0 && (ea.out_lo_off & 7) == 0 &&
+         (ea.epi != EPI_QKV || (ea.N / 3) % 64 == 0);
+}
+template <int TM, int KIND>
+__device__ __forceinline__ void epilogue_patch_lds(const EpiArgs& ea, int split, int row_base, int col_base, int lane,
+                                                   const f32x4_t (&acc)[TM][4], float* ws) {
+  constexpr int LD = kEpiLd, NJ = 4;
+  const int row_l = lane & 15, col_l = (lane >> 4) * 4;
+  const QkvEpilogue& q = ea.qe;
+  const int D = ea.N / 3, DH = q.d_head, half = q.rot >> 1;
+  const int region = KIND == EPI_QKV ? col_base / D : 0;                 // q, k or v: the patch lies in one of them
+  const int c_reg = col_base - region * D;                               // column inside the region
+  float4 bias[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int col = col_base + j * 16 + col_l;
+    bias[j] = (KIND != EPI_PARTIAL && ea.bias && col < ea.N) ? *reinterpret_cast<const float4*>(ea.bias + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    // ---- finished values of row tile i into the strip, in the MFMA layout (row lane % 16, 4 columns per tile)
+    int pos = 0;
+    if constexpr (KIND == EPI_QKV) {
+      const int rr = min(row_base + i * 16 + row_l, ea.M - 1);
+      pos = q.pos0 + rr % q.n_new;
+    }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const f32x4_t a = acc[i][j];
+      float v[4] = {a[0] + bias[j].x, a[1] + bias[j].y, a[2] + bias[j].z, a[3] + bias[j].w};
+      if constexpr (KIND == EPI_GELU) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = gelu_erf_fast(v[r]);
+      }
+      if constexpr (KIND == EPI_QKV) {
+        const int d0 = (c_reg + j * 16) % DH;                            // first dim of the tile inside its head (wave-uniform)
+        if (region < 2 && d0 < q.rot) {
+          float pv[4];
+          if (half == 8) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) pv[r] = __shfl_xor(v[r], 32, kWave);
+          } else {                                                       // half == 16: tile j ^ 1 of this lane
+            const f32x4_t pa = acc[i][j ^ 1];
+            const float4 pb = bias[j ^ 1];
+            pv[0] = pa[0] + pb.x; pv[1] = pa[1] + pb.y; pv[2] = pa[2] + pb.z; pv[3] = pa[3] + pb.w;
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int dd = d0 + col_l + r;
+            const bool lo = dd < half;
+            const float2 cs = q.rope[(size_t)pos * half + (lo ? dd : dd - half)];
+            v[r] = lo ? v[r] * cs.x - pv[r] * cs.y : v[r] * cs.x + pv[r] * cs.y;
+          }
+        }
+      }
+      *reinterpret_cast<float4*>(ws + row_l * LD + j * 16 + col_l) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+    // ---- back out with the lanes along the rows
+    const bool as_f32 = KIND == EPI_F32 || KIND == EPI_PARTIAL || (KIND == EPI_QKV && region == 0);
+    if (as_f32) {
+      constexpr int LPR = 16, RPI = 64 / LPR;                            // lanes per row, rows per instruction
+      const int c = (lane % LPR) * 4, col = col_base + c;
+#pragma unroll
+      for (int p = 0; p < 16 / RPI; ++p) {
+        const int rr = RPI * p + lane / LPR, row = row_base + i * 16 + rr;
+        const float4 v = *reinterpret_cast<const float4*>(ws + rr * LD + c);
+        if (row < ea.M && col < ea.N) {
+          float* o = reinterpret_cast<float*>(ea.out) + (KIND == EPI_PARTIAL ? ((size_t)split * ea.M + row) * ea.N + col : (size_t)row * ea.ldo + col);
+          *reinterpret_cast<float4*>(o) = v;
+        }
+      }
+    } else {
+      constexpr int LPR = 8, RPI = 64 / LPR;
+      const int c = (lane % LPR) * 8, col = col_base + c;
+#pragma unroll
+      for (int p = 0; p < 16 / RPI; ++p) {
+        const int rr = RPI * p + lane / LPR, row = row_base + i * 16 + rr;
+        const float4 x = *reinterpret_cast<const float4*>(ws + rr * LD + c);
+        const float4 y = *reinterpret_cast<const float4*>(ws + rr * LD + c + 4);
+        const float f[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
+        uint32_t hb[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) hb[e] = float_to_bf16_bits(f[e]);
+        const uint4 hi = make_uint4(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16), hb[4] | (hb[5] << 16), hb[6] | (hb[7] << 16));
+        if (row < ea.M && col < ea.N) {
+          if constexpr (KIND == EPI_QKV) {                               // k or v: the block KV cache, [b][h][slot][DH]
+            const int b = row / q.n_new, slot = q.pos0 + (row - b * q.n_new);
+            const int h = (c_reg + c) / DH, dd = (c_reg + c) - h * DH;
+            uint16_t* cache = reinterpret_cast<uint16_t*>(region == 1 ? q.Kc : q.Vc);
+            *reinterpret_cast<uint4*>(cache + ((size_t)(b * q.n_heads + h) * q.n_cap + slot) * DH + dd) = hi;
+          } else {
+            uint16_t* o = reinterpret_cast<uint16_t*>(ea.out) + (size_t)row * ea.ldo + col;
+            *reinterpret_cast<uint4*>(o) = hi;
+            if (ea.out_lo_off) {
+              uint32_t lb[8];
+#pragma unroll
+              for (int e = 0; e < 8; ++e) lb[e] = float_to_bf16_bits(f[e] - bf16_bits_to_float(hb[e]));
+              *reinterpret_cast<uint4*>(o + ea.out_lo_off) =
+                  make_uint4(lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16), lb[4] | (lb[5] << 16), lb[6] | (lb[7] << 16));
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// All epilogue kinds of a patch: through LDS where the shapes allow, else from the registers.
+template <int TM>
+__device__ __forceinline__ void epilogue_patch(const EpiArgs& ea, int split, int row_base, int col_base, int lane,
+                                               const f32x4_t (&acc)[TM][4], float* ws) {
+  if (epilogue_through_lds(ea)) {
+    if (ea.epi == EPI_GELU) epilogue_patch_lds<TM, EPI_GELU>(ea, split, row_base, col_base, lane, acc, ws);
+    else if (ea.epi == EPI_PARTIAL) epilogue_patch_lds<TM, EPI_PARTIAL>(ea, split, row_base, col_base, lane, acc, ws);
+    else if (ea.epi == EPI_QKV) epilogue_patch_lds<TM, EPI_QKV>(ea, split, row_base, col_base, lane, acc, ws);
+    else {
+      if (ea.out)                      // null: the caller wants the argmax candidates only
+        epilogue_patch_lds<TM, EPI_F32>(ea, split, row_base, col_base, lane, acc, ws);
+      if (ea.row_max) {                // the argmax candidates come from the registers
+        EpiArgs ec = ea;
+        ec.out = nullptr;
+        epilogue_tiles<bf16_t, TM, 4>(ec, split, row_base, col_base, lane, acc);
+      }
+    }
+    return;
+  }
+  epilogue_tiles<bf16_t, TM, 4>(ea, split, row_base, col_base, lane, acc);
 }
 
 // ---------------------------------------------------------------------------
@@ -429,8 +579,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmGroup g) {
   }
 
   // The weight fragment is the MFMA's first operand: the 16 x 16 result is the tile transposed, and a
-  // lane holds output row lane%16, columns 4*(lane/16) + 0..3
-  epilogue_tiles<bf16_t, TM, TN>(ea, split, m0 + wm * (BM / WM), n0 + wn * (BN / WN), lane, acc);
+  // lane holds output row lane%16, columns 4*(lane/16) + 0..3.  The loop's closing barrier has passed:
+  // the four waves' strips (16 x 68 floats each) reuse the A tile.
+  static_assert(TN == 4 && 4 * 16 * kEpiLd * 4 <= BM * LDS * 2, "one 64-column patch per wave; strips fit into sA");
+  epilogue_patch<TM>(ea, split, m0 + wm * (BM / WM), n0 + wn * (BN / WN), lane, acc, reinterpret_cast<float*>(sA) + wave * (16 * kEpiLd));
 }
 
 // ---------------------------------------------------------------------------
@@ -539,8 +691,9 @@ __global__ __launch_bounds__(512) void gemm_bf16_big_kernel(GemmGroup g) {
     }
     __syncthreads();
   }
-  // weight fragment first: a lane holds output row lane%16, columns 4*(lane/16) + 0..3 of each MFMA tile
-  epilogue_tiles<bf16_t, 8, 4>(ea, split, m0 + wm * 128, n0 + wn * 64, lane, acc);
+  // weight fragment first: a lane holds output row lane%16, columns 4*(lane/16) + 0..3 of each MFMA tile.
+  // The loop's closing barrier has passed: the eight waves' strips (16 x 68 floats each) reuse the A tile.
+  epilogue_patch<8>(ea, split, m0 + wm * 128, n0 + wn * 64, lane, acc, reinterpret_cast<float*>(sbig) + wave * (16 * kEpiLd));
 }
 
 // ---------------------------------------------------------------------------
