@@ -194,6 +194,10 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="only run a few plain device copies of MIB MiB and exit: under rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE this gives the factor between the counters and real HBM bytes")
+    ap.add_argument("--peak-calibration", action="store_true",
+                    help="only measure what plain kernels reach on this GPU and exit: a streaming read of 4 GiB and a "
+                         "loop of nothing but bf16 MFMAs, on constant and on pseudo-random operands "
+                         "(profiles/mi355x_measured_peaks.txt holds the figures the roofline objects quote)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (the path would shard by batch, with no exchange "
@@ -215,6 +219,9 @@ def main():
         return
     from synth import CONFIGS
     import paper_2406_02657_amd as amd
+    if args.peak_calibration:
+        print(json.dumps(peak_calibration(amd, torch)))
+        return
 
     cfg = CONFIGS[args.workload]
     if args.gen_len:
@@ -267,6 +274,37 @@ def main():
 
 # timed whole jobs of the extra workloads of the default run (their own, small counts)
 EXTRA_STEPS = {"cfg2": 5, "cfg3": 2, "cfg4": 1}
+
+
+def peak_calibration(amd, torch):
+    """Achievable rates of plain kernels (the library's probes), timed with HIP events on their stream."""
+    from paper_2406_02657_amd import binding as B
+    st = torch.cuda.Stream()
+    out = torch.empty(B.PROBE_WORKGROUPS * 256, dtype=torch.float32, device="cuda")
+    res = {}
+    with torch.cuda.stream(st):
+        n = (4 << 30) // B.PROBE_READ_GRAIN * B.PROBE_READ_GRAIN          # 4 GiB: sixteen times the 256 MB cache
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
+        best = 0.0
+        for rep in range(6):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st); B.probe_read(src, st, out); e1.record(st); e1.synchronize()
+            if rep:
+                best = max(best, n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        res["hbm_read_gbs"] = best
+        del src
+        iters = 20000
+        flops = B.PROBE_WORKGROUPS * 4 * iters * 64 * 16384.0
+        for name, rnd in (("mfma_bf16_tflops_constant", 0), ("mfma_bf16_tflops_random", 1)):
+            best = 0.0
+            for rep in range(4):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(st); B.probe_mfma(iters, rnd, st, out); e1.record(st); e1.synchronize()
+                if rep:
+                    best = max(best, flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+            res[name] = best
+    res["note"] = "best of the repeats after one warm-up launch; published peaks: 8000 GB/s, 2500 TFLOP/s"
+    return res
 
 
 def read_profile_keys(fname, keys):

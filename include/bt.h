@@ -306,6 +306,23 @@ int bt_set_context(bt_model *m, const void *ctx_dev);
 int bt_set_profile(bt_model *m, int32_t on);
 int bt_reset_profile(bt_model *m);
 
+/* Calibration probes for the benchmark's "measured achievable" peaks (no model
+ * needed; the caller times the launch with HIP events on hip_stream):
+ *   bt_probe_read streams `bytes` bytes at src_dev (device; a multiple of
+ *     BT_PROBE_READ_GRAIN) through BT_PROBE_WORKGROUPS workgroups with 16-byte
+ *     loads and leaves one word per workgroup in out_dev: a plain read of HBM.
+ *   bt_probe_mfma makes every wave of BT_PROBE_WORKGROUPS workgroups x 4 waves
+ *     issue iters x 64 bf16 MFMAs (16 x 16 x 32) on 16 independent accumulators
+ *     and nothing else: BT_PROBE_WORKGROUPS * 4 * iters * 64 * 16384 flops.
+ *     random_operands != 0 gives every lane pseudo-random operand values (the
+ *     clock the chip holds depends on the data); 0 gives constants.
+ * out_dev: device, at least BT_PROBE_WORKGROUPS * 256 floats, overwritten.
+ * Errors: BT_ERR_ARG, BT_ERR_HIP. */
+#define BT_PROBE_WORKGROUPS 2048
+#define BT_PROBE_READ_GRAIN ((size_t)BT_PROBE_WORKGROUPS * 256 * 16)
+int bt_probe_read(const void *src_dev, size_t bytes, void *hip_stream, float *out_dev);
+int bt_probe_mfma(int32_t iters, int32_t random_operands, void *hip_stream, float *out_dev);
+
 int bt_get_stats(bt_model *m, bt_stats *out);
 
 /* Text of the last error on this model (host string owned by the model).  With

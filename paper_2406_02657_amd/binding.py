@@ -79,9 +79,14 @@ lib.bt_last_error.restype = C.c_char_p
 lib.bt_destroy.argtypes = [_P]
 lib.bt_destroy.restype = None
 lib.bt_embed.argtypes = [_P, _P, C.c_int32, _P]
+lib.bt_probe_read.argtypes = [_P, C.c_size_t, _P, _P]
+lib.bt_probe_mfma.argtypes = [C.c_int32, C.c_int32, _P, _P]
+PROBE_WORKGROUPS = 2048
+PROBE_READ_GRAIN = PROBE_WORKGROUPS * 256 * 16
 for _f in ("bt_workspace_bytes", "bt_create", "bt_create_static", "bt_prefill", "bt_prefill_ragged", "bt_decode_step", "bt_get_logits",
            "bt_get_finished", "bt_score", "bt_force_last_ids",
-           "bt_get_context", "bt_set_context", "bt_set_profile", "bt_reset_profile", "bt_get_stats", "bt_embed"):
+           "bt_get_context", "bt_set_context", "bt_set_profile", "bt_reset_profile", "bt_get_stats", "bt_embed",
+           "bt_probe_read", "bt_probe_mfma"):
     getattr(lib, _f).restype = C.c_int
 
 
@@ -295,3 +300,17 @@ class Model:
             self.close()
         except Exception:
             pass
+
+
+def probe_read(src, stream, out):
+    """bt_probe_read on torch tensors: src uint8 (numel a multiple of PROBE_READ_GRAIN), out float32 scratch."""
+    rc = lib.bt_probe_read(src.data_ptr(), src.numel(), stream.cuda_stream, out.data_ptr())
+    if rc:
+        raise BTError(rc, "bt_probe_read")
+
+
+def probe_mfma(iters, random_operands, stream, out):
+    rc = lib.bt_probe_mfma(int(iters), int(random_operands), stream.cuda_stream, out.data_ptr())
+    if rc:
+        raise BTError(rc, "bt_probe_mfma")
+

@@ -72,7 +72,16 @@ struct RowMap {
 // the query is known (its loads do not depend on it).
 constexpr int kAttnU = 4;
 
-template <class T, int DH>
+// 16 bytes with the streaming hint: the line is not kept in L2 after it has been delivered.
+__device__ __forceinline__ uint4 load16_stream(const void* p) {
+  typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
+  const v4u_t v = __builtin_nontemporal_load(reinterpret_cast<const v4u_t*>(p));
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// STREAM: the rows are read once per launch (decode steps: every (b, h) has its own rows); without it they
+// are read again by other queries of the launch (prefill) and should stay in L2.
+template <class T, int DH, bool STREAM = false>
 __device__ __forceinline__ void attend_issue(const T* __restrict__ K, const T* __restrict__ V, int base, int j0, int j1,
                                              uint4* kraw, uint4* vraw) {
   using R = RowMap<T, DH>;
@@ -83,13 +92,18 @@ __device__ __forceinline__ void attend_issue(const T* __restrict__ K, const T* _
   for (int u = 0; u < kAttnU; ++u) {
     const int j = base + u * RPL + rr;
     const size_t off = (size_t)(j < j1 ? j : j0) * DH + sub * EPC;      // clamped: no branch around the loads
-    kraw[u] = *reinterpret_cast<const uint4*>(K + off);
-    vraw[u] = *reinterpret_cast<const uint4*>(V + off);
+    if constexpr (STREAM) {
+      kraw[u] = load16_stream(K + off);
+      vraw[u] = load16_stream(V + off);
+    } else {
+      kraw[u] = *reinterpret_cast<const uint4*>(K + off);
+      vraw[u] = *reinterpret_cast<const uint4*>(V + off);
+    }
   }
 }
 
 // kraw / vraw: the batch at base = j0, already issued by attend_issue (only if j0 < j1).
-template <class T, int DH>
+template <class T, int DH, bool STREAM = false>
 __device__ __forceinline__ void wave_attend(const float* q, const T* __restrict__ K, const T* __restrict__ V,
                                             int j0, int j1, uint4* kraw, uint4* vraw,
                                             float& m_out, float& l_out, float* acc) {
@@ -104,7 +118,7 @@ __device__ __forceinline__ void wave_attend(const float* q, const T* __restrict_
   for (int base = j0; base < j1; base += RPL * U) {
     uint4 knext[U], vnext[U];
     const int nb = base + RPL * U;
-    if (nb < j1) attend_issue<T, DH>(K, V, nb, j0, j1, knext, vnext);
+    if (nb < j1) attend_issue<T, DH, STREAM>(K, V, nb, j0, j1, knext, vnext);
     float s[U];
     float mx = m;
 #pragma unroll
@@ -203,7 +217,7 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(PartialSrc q
   const int per = (r1 - r0 + NW - 1) / NW;
   const int j0 = min(r0 + wave * per, r1), j1 = min(j0 + per, r1);
   uint4 kraw[kAttnU], vraw[kAttnU];
-  if (j0 < j1) attend_issue<T, DH>(K, V, j0, j0, j1, kraw, vraw);
+  if (j0 < j1) attend_issue<T, DH, true>(K, V, j0, j0, j1, kraw, vraw);
 
   // q, k, v of this head: sum the pieces, rotate q and k at position n_old, append k and v
   const int d = threadIdx.x;
@@ -248,7 +262,7 @@ __global__ __launch_bounds__(NW * 64) void attn_block_decode_kernel(PartialSrc q
   for (int e = 0; e < EPC; ++e) q[e] = s_q[sub * EPC + e];
 
   float m, l, acc[EPC];
-  wave_attend<T, DH>(q, K, V, j0, j1, kraw, vraw, m, l, acc);
+  wave_attend<T, DH, true>(q, K, V, j0, j1, kraw, vraw, m, l, acc);
   if (lane < LPR) {
     if (lane == 0) { s_m[wave] = m; s_l[wave] = l; }
 #pragma unroll

@@ -1013,6 +1013,16 @@ int bt_set_profile(bt_model* m, int32_t on) {
   return BT_OK;
 }
 
+int bt_probe_read(const void* src_dev, size_t bytes, void* hip_stream, float* out_dev) {
+  if (!src_dev || !out_dev || bytes == 0 || bytes % BT_PROBE_READ_GRAIN) return BT_ERR_ARG;
+  return launch_probe_read(src_dev, bytes, BT_PROBE_WORKGROUPS, out_dev, (hipStream_t)hip_stream) == hipSuccess ? BT_OK : BT_ERR_HIP;
+}
+
+int bt_probe_mfma(int32_t iters, int32_t random_operands, void* hip_stream, float* out_dev) {
+  if (!out_dev || iters <= 0) return BT_ERR_ARG;
+  return launch_probe_mfma(iters, random_operands, BT_PROBE_WORKGROUPS, out_dev, (hipStream_t)hip_stream) == hipSuccess ? BT_OK : BT_ERR_HIP;
+}
+
 int bt_reset_profile(bt_model* m) {
   if (!m) return BT_ERR_ARG;
   BT_HIP(m, hipStreamSynchronize(m->stream));

@@ -625,4 +625,65 @@ hipError_t launch_seq_blocks(const int* lens, int* n_blocks, int block_len, int 
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Calibration probes: what a plain kernel reaches on this chip, to set beside the published peaks.
+// ---------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(4))) unsigned probe_u32x4_t;
+__global__ __launch_bounds__(256) void probe_read_kernel(const probe_u32x4_t* __restrict__ src, size_t chunks_per_wg, float* __restrict__ out) {
+  const probe_u32x4_t* p = src + (size_t)blockIdx.x * chunks_per_wg + threadIdx.x;
+  probe_u32x4_t acc = {0u, 0u, 0u, 0u};
+  // a workgroup walks its own contiguous range, 4 KB per step, eight independent loads in flight per thread
+  size_t c = 0;
+  for (; c + 8 * 256 <= chunks_per_wg; c += 8 * 256) {
+    probe_u32x4_t v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + c + u * 256);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  for (; c < chunks_per_wg; c += 256) acc ^= __builtin_nontemporal_load(p + c);
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = __uint_as_float((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) & 0x3fffffffu);
+}
+
+hipError_t launch_probe_read(const void* src, size_t bytes, int workgroups, float* out, hipStream_t s) {
+  if (!src || !out || workgroups <= 0 || bytes == 0 || bytes % ((size_t)workgroups * 256 * 16)) return hipErrorInvalidValue;
+  probe_read_kernel<<<workgroups, 256, 0, s>>>(reinterpret_cast<const probe_u32x4_t*>(src), bytes / 16 / workgroups, out);
+  return hipGetLastError();
+}
+
+typedef __attribute__((ext_vector_type(4))) float probe_f32x4_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8_t;
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int random_operands, float* __restrict__ out) {
+  probe_f32x4_t acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = probe_f32x4_t{0.f, 0.f, 0.f, 0.f};
+  probe_bf16x8_t a, b;
+  unsigned x = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    x = x * 1664525u + 1013904223u;
+    const float ra = ((int)((x >> 8) % 2001u) - 1000) * 1e-3f;
+    x = x * 1664525u + 1013904223u;
+    const float rb = ((int)((x >> 8) % 2001u) - 1000) * 1e-3f;
+    a[i] = (__bf16)(random_operands ? ra : (float)(threadIdx.x & 3));
+    b[i] = (__bf16)(random_operands ? rb : 1.0f);
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sum += (acc[i][0] + acc[i][1]) + (acc[i][2] + acc[i][3]);
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
+hipError_t launch_probe_mfma(int iters, int random_operands, int workgroups, float* out, hipStream_t s) {
+  if (!out || iters <= 0 || workgroups <= 0) return hipErrorInvalidValue;
+  probe_mfma_kernel<<<workgroups, 256, 0, s>>>(iters, random_operands, out);
+  return hipGetLastError();
+}
+
 }  // namespace bt

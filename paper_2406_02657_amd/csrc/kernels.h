@@ -104,6 +104,12 @@ hipError_t launch_score_targets(const int32_t* tokens, int32_t* targets, int n_r
 hipError_t launch_score_combine(const float2* stats, int groups, const float* target_logit, int n_rows, int row0,
                                 float* nll, int P, int block_len, int n_blocks, int seq_len, hipStream_t s);
 
+// --------------------------------------------------------------- calibration probes
+// A plain streaming read of `bytes` (a multiple of grid * 256 * 16) and a loop of nothing but MFMAs; one
+// float per thread / workgroup lands in out so that nothing is optimised away.
+hipError_t launch_probe_read(const void* src, size_t bytes, int workgroups, float* out, hipStream_t s);
+hipError_t launch_probe_mfma(int iters, int random_operands, int workgroups, float* out, hipStream_t s);
+
 // ----------------------------------------------------------------------- GEMM
 enum { EPI_F32 = 0,        // out float [M, ldo]: acc + bias
        EPI_GELU = 1,       // out storage dtype: gelu(acc + bias)
