@@ -394,6 +394,8 @@ def run_generation(args, amd, torch, cfg, steps, warmup, overridden, short_warmu
     pmc_ok = len(pmc) == 3 and cfg.name == "cfg1" and not overridden
     trace_file = "cfg2_prefill_heavy_kernel_stats.txt" if cfg.name == "cfg2" else f"{cfg.name}_generation_kernel_stats.txt"
     trace = {} if overridden else read_profile_keys(trace_file, ("attn_block_decode_avg_us", "attn_block_decode_bytes_per_launch"))
+    # what plain kernels reach on this GPU (python bench.py --peak-calibration, committed under profiles/)
+    measured = read_profile_keys("mi355x_measured_peaks.txt", ("hbm_read_gbs", "mfma_bf16_tflops_random"))
     roofline = None
     if st.attn_block_launches > 0 and st.attn_block_ms > 0:
         ach = st.attn_block_bytes / (st.attn_block_ms * 1e-3) / 1e9
@@ -419,6 +421,10 @@ def run_generation(args, amd, torch, cfg, steps, warmup, overridden, short_warmu
             roofline["frac_kernel_trace"] = (trace["attn_block_decode_bytes_per_launch"]
                                              / (trace["attn_block_decode_avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS)
             roofline["kernel_trace_source"] = f"profiles/{trace_file}"
+        if "hbm_read_gbs" in measured:
+            roofline["peak_measured"] = measured["hbm_read_gbs"]
+            roofline["frac_of_measured"] = ach / measured["hbm_read_gbs"]
+            roofline["peak_measured_source"] = "profiles/mi355x_measured_peaks.txt (a plain streaming read with non-temporal loads)"
     roofline_gemm = None
     planes = 2 if cfg.dtype == "bf16" else 1
     if st.gemm_decode_launches > 0 and st.gemm_decode_ms > 0:
@@ -455,6 +461,9 @@ def run_generation(args, amd, torch, cfg, steps, warmup, overridden, short_warmu
             "executed_tflops": alg * split_prefill, "frac_executed": alg * split_prefill / MFMA_BF16_PEAK_TFLOPS,
             "launches": int(st.gemm_tiled_launches), "avg_launch_us": st.gemm_tiled_ms * 1e3 / st.gemm_tiled_launches,
             "algorithmic_flops": int(st.gemm_tiled_flops),
+            "peak_measured": measured.get("mfma_bf16_tflops_random"),
+            "frac_executed_of_measured": (alg * split_prefill / measured["mfma_bf16_tflops_random"]
+                                          if "mfma_bf16_tflops_random" in measured else None),
             "note": "achieved = the method's own flops, 2 x rows x N x K, over summed HIP-event time; executed counts the "
                     "bf16 hi + remainder activation planes the matrix cores multiply (act_split)",
         }
