@@ -317,6 +317,11 @@ __device__ __forceinline__ void epilogue_tiles(const EpiArgs& ea, int split, int
 // Preconditions (checked by epilogue_through_lds, else the register epilogue is used): col_base a
 // multiple of 64, N % 8 == 0, ldo % 8 == 0; EPI_QKV: D a multiple of 64.
 // ---------------------------------------------------------------------------
+// 16-byte store with the streaming hint: an output row is written once and read by a later launch, so it
+// should not displace the operand tiles the other workgroups of the XCD are still reading from L2.
+__device__ __forceinline__ void store16_stream(void* p, uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  __builtin_nontemporal_store(u32x4_t{a, b, c, d}, reinterpret_cast<u32x4_t*>(p));
+}
 constexpr int kEpiLd = 64 + 4;                  // floats per strip row: the pad keeps the 16-byte writes of 8 rows on distinct banks
 __device__ __forceinline__ bool epilogue_through_lds(const EpiArgs& ea) {
   return ea.epi != EPI_LSE && (ea.N & 7) == 0 && (ea.ldo & 7) == 0 && (ea.out_lo_off & 7) == 0 &&
@@ -387,7 +392,7 @@ __device__ __forceinline__ void epilogue_patch_lds(const EpiArgs& ea, int split,
         const float4 v = *reinterpret_cast<const float4*>(ws + rr * LD + c);
         if (row < ea.M && col < ea.N) {
           float* o = reinterpret_cast<float*>(ea.out) + (KIND == EPI_PARTIAL ? ((size_t)split * ea.M + row) * ea.N + col : (size_t)row * ea.ldo + col);
-          *reinterpret_cast<float4*>(o) = v;
+          store16_stream(o, __float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w));
         }
       }
     } else {
@@ -408,16 +413,15 @@ __device__ __forceinline__ void epilogue_patch_lds(const EpiArgs& ea, int split,
             const int b = row / q.n_new, slot = q.pos0 + (row - b * q.n_new);
             const int h = (c_reg + c) / DH, dd = (c_reg + c) - h * DH;
             uint16_t* cache = reinterpret_cast<uint16_t*>(region == 1 ? q.Kc : q.Vc);
-            *reinterpret_cast<uint4*>(cache + ((size_t)(b * q.n_heads + h) * q.n_cap + slot) * DH + dd) = hi;
+            store16_stream(cache + ((size_t)(b * q.n_heads + h) * q.n_cap + slot) * DH + dd, hi.x, hi.y, hi.z, hi.w);
           } else {
             uint16_t* o = reinterpret_cast<uint16_t*>(ea.out) + (size_t)row * ea.ldo + col;
-            *reinterpret_cast<uint4*>(o) = hi;
+            store16_stream(o, hi.x, hi.y, hi.z, hi.w);
             if (ea.out_lo_off) {
               uint32_t lb[8];
 #pragma unroll
               for (int e = 0; e < 8; ++e) lb[e] = float_to_bf16_bits(f[e] - bf16_bits_to_float(hb[e]));
-              *reinterpret_cast<uint4*>(o + ea.out_lo_off) =
-                  make_uint4(lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16), lb[4] | (lb[5] << 16), lb[6] | (lb[7] << 16));
+              store16_stream(o + ea.out_lo_off, lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16), lb[4] | (lb[5] << 16), lb[6] | (lb[7] << 16));
             }
           }
         }
