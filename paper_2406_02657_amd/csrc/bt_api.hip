@@ -180,6 +180,13 @@ struct bt_model {
   int64_t graph_launches;
   int graph_captures;
   int static_dev = -1;             // >= 0: the workspace is the static array of this device (bt_create_static)
+  // Decode GEMMs read a stack's weights with non-temporal loads when those weights will not be read again
+  // before the caches have turned over: the block decoder's when it runs once per L_B > 1 steps, and
+  // whatever is read at every step (token decoder, LM head, the block decoder at L_B = 1) when that
+  // exceeds the 256 MB cache.  Measured (us per step, weights
+  // of neither / block stack / token stack and head / both streamed): cfg1 444.6 / 443.5 / 451.0 / 456.8,
+  // cfg2 401.1 / 394.0 / 393.1 / 394.5, cfg3 (token stack 506 MB) 883.0 / 883.6 / 874.0 / 872.4.
+  int stream_token_w = 0, stream_block_w = 1;
 
   template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
 };
@@ -310,6 +317,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
                  lo(a_up, loD), loF};
   GemmProblem po{ao, nullptr, nullptr, part_o, M, D, D, D, D, EPI_PARTIAL, lo(ao, loD), 0};
   GemmProblem pd{hmid, nullptr, nullptr, part_d, M, D, F, F, D, EPI_PARTIAL, lo(hmid, loF), 0};
+  pq.stream_w = pu.stream_w = po.stream_w = pd.stream_w = (a.mode == MODE_TOKEN) ? m->stream_token_w : m->stream_block_w;
   GemmPlan plan_in{}, plan_out{}, plan_q{}, plan_u{}, plan_o{}, plan_d{};
   int sQ, sU, sO, sD;
   if (c.parallel_residual) {
@@ -521,6 +529,14 @@ static int create_impl(const bt_config* cfg, const bt_weights* w, void* workspac
   bt_model* m = new (std::nothrow) bt_model();
   if (!m) return bad(BT_ERR_ARG, "out of host memory");
   m->cfg = *cfg;
+  {
+    const size_t esz = cfg->dtype == BT_BF16 ? 2 : 4, D = (size_t)cfg->d_model;
+    const size_t layer = 4 * D * D + 2 * D * (size_t)cfg->d_ff;
+    const size_t every_step = ((size_t)(cfg->n_token_layers + (cfg->block_len == 1 ? cfg->n_block_layers : 0)) * layer +
+                               (size_t)cfg->vocab * D) * esz;
+    m->stream_token_w = every_step > ((size_t)256 << 20);
+    m->stream_block_w = cfg->block_len > 1 || m->stream_token_w;
+  }
   m->w = *w;
   m->blk.assign(w->block_layers, w->block_layers + cfg->n_block_layers);
   m->tok.assign(w->token_layers, w->token_layers + cfg->n_token_layers);
@@ -733,6 +749,7 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
       const int n_proj = sum ? c.block_len : c.prefix_len;
       GemmProblem p{m->ws + L.ctx, m->w.W_prefix, (const float*)m->w.b_prefix, sum ? m->at<float>(L.summands) : x, B, n_proj * D, D, D,
                     n_proj * D, EPI_F32, fin_lo ? m->ws + L.ctx + fin_lo * 2 : nullptr, 0, m->prefix_frag};
+      p.stream_w = 1;                    // used once per block
       GemmPlan pl{};
       BT_HIP(m, gemm_plan(c.dtype, &p, 1, &pl));
       BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));
@@ -756,6 +773,7 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
   if (rc) return rc;
   GemmProblem p{m->ws + L.hfin, m->w.W_head, nullptr, m->ws + L.logits, B, c.vocab, D, D, c.vocab, EPI_F32,
                 fin_lo ? m->ws + L.hfin + fin_lo * 2 : nullptr, 0, m->head_frag};
+  p.stream_w = m->stream_token_w;
   GemmPlan pl{};
   BT_HIP(m, gemm_plan(c.dtype, &p, 1, &pl));
   // Greedy argmax: where the head's kernel can, it leaves per-tile (max, column) candidates per row

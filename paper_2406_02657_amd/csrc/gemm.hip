@@ -36,6 +36,7 @@ struct GemmDesc {
 struct GemmGroup {
   GemmDesc p[2];
   int n;
+  bool stream_w;         // host side only: selects the kernel variant that streams the weights
 };
 
 // The decode (K-slice) kernels take a compact form of the same description: one 64-byte cache line
@@ -773,7 +774,14 @@ __device__ __forceinline__ int row_min_step(int v) {
   return min(v, __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false));
 }
 
-template <int KF, int NT, int MC, bool HL>
+// One weight fragment (16 bytes per lane); STREAM: with the non-temporal hint (GemmProblem::stream_w).
+template <bool STREAM>
+__device__ __forceinline__ u32x4_t load_w_fragment(const uint16_t* p) {
+  if constexpr (STREAM) return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  else return *reinterpret_cast<const u32x4_t*>(p);
+}
+
+template <int KF, int NT, int MC, bool HL, bool SW = false>
 __global__ __launch_bounds__(256) void gemm_kslice_kernel(KsGroup g) {
   constexpr int KS = 32 * KF, LDK = KS + 8, CPR = KS / 8, PL = HL ? 2 : 1;
   extern __shared__ __attribute__((aligned(16))) uint16_t sA[];
@@ -814,7 +822,7 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(KsGroup g) {
       const int tile = min((n0 >> 4) + nt, last_tile);
       const uint16_t* wp = Wf + ((size_t)tile * kblocks + (kbase >> 5)) * 512 + lane * 8;
 #pragma unroll
-      for (int kf = 0; kf < KF; ++kf) wf[nt][kf] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wp + kf * 512));
+      for (int kf = 0; kf < KF; ++kf) wf[nt][kf] = __builtin_bit_cast(bf16x8_t, load_w_fragment<SW>(wp + kf * 512));
     }
     // activation slice -> LDS.  No branches here: chunk indices past the end are clamped to the
     // last chunk (which is then loaded and stored more than once, with the same bytes), so the
@@ -968,7 +976,7 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(KsGroup g) {
 // LDS, so they travel while slice it is multiplied.  hi + remainder planes only;
 // MC * KF <= 8 (registers: the whole next slice is held by the 256 threads).
 // ---------------------------------------------------------------------------
-template <int KF, int NT, int MC>
+template <int KF, int NT, int MC, bool SW = false>
 __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(KsGroup g) {
   constexpr int KS = 32 * KF, LDK = KS + 8, CPR = KS / 8, NCH = MC * KF;
   extern __shared__ __attribute__((aligned(16))) uint16_t sA[];
@@ -1016,7 +1024,7 @@ __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(KsGroup g) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-      for (int kf = 0; kf < KF; ++kf) wn[nt][kf] = *reinterpret_cast<const u32x4_t*>(w_base[nt] + (size_t)((kbase >> 5) + kf) * 512);
+      for (int kf = 0; kf < KF; ++kf) wn[nt][kf] = load_w_fragment<SW>(w_base[nt] + (size_t)((kbase >> 5) + kf) * 512);
 #pragma unroll
     for (int u = 0; u < NCH; ++u) {
       ah[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kbase);
@@ -1040,7 +1048,7 @@ __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(KsGroup g) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-        for (int kf = 0; kf < KF; ++kf) wn[nt][kf] = *reinterpret_cast<const u32x4_t*>(w_base[nt] + (size_t)((kbase >> 5) + kf) * 512);
+        for (int kf = 0; kf < KF; ++kf) wn[nt][kf] = load_w_fragment<SW>(w_base[nt] + (size_t)((kbase >> 5) + kf) * 512);
 #pragma unroll
       for (int u = 0; u < NCH; ++u) {
         ah[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kbase);
@@ -1312,19 +1320,24 @@ static hipError_t raise_lds_limit(const void* fn) {
 
 template <int KF, int NT, int MC, bool HL>
 static hipError_t launch_kslice(GemmGroup& g, size_t lds, hipStream_t s) {
-  auto kern = gemm_kslice_kernel<KF, NT, MC, HL>;
   KsGroup k;
   const int grid = pack_kslice(g, 64 * NT, k);
-  kern<<<grid, 256, lds, s>>>(k);
+  if constexpr (HL) {                     // the streaming variants exist for the two-plane kernels only
+    if (g.stream_w) {
+      gemm_kslice_kernel<KF, NT, MC, HL, true><<<grid, 256, lds, s>>>(k);
+      return hipSuccess;
+    }
+  }
+  gemm_kslice_kernel<KF, NT, MC, HL><<<grid, 256, lds, s>>>(k);
   return hipSuccess;
 }
 
 template <int KF, int NT, int MC>
 static hipError_t launch_kslice_pipe(GemmGroup& g, size_t lds, hipStream_t s) {
-  auto kern = gemm_kslice_pipe_kernel<KF, NT, MC>;
   KsGroup k;
   const int grid = pack_kslice(g, 64 * NT, k);
-  kern<<<grid, 256, lds, s>>>(k);
+  if (g.stream_w) gemm_kslice_pipe_kernel<KF, NT, MC, true><<<grid, 256, lds, s>>>(k);
+  else gemm_kslice_pipe_kernel<KF, NT, MC><<<grid, 256, lds, s>>>(k);
   return hipSuccess;
 }
 
@@ -1365,6 +1378,16 @@ static hipError_t prepare_kslice_kf() {
   up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 2, 4, HL>));
   up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 4, 1, HL>));
   up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 4, 2, HL>));
+  if constexpr (HL) {
+    up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 1, 1, HL, true>));
+    up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 1, 2, HL, true>));
+    up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 1, 4, HL, true>));
+    up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 2, 1, HL, true>));
+    up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 2, 2, HL, true>));
+    up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 2, 4, HL, true>));
+    up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 4, 1, HL, true>));
+    up(reinterpret_cast<const void*>(gemm_kslice_kernel<KF, 4, 2, HL, true>));
+  }
   return e;
 }
 
@@ -1377,6 +1400,8 @@ hipError_t gemm_prepare_kernels() {
   step(prepare_kslice_kf<8, false>()); step(prepare_kslice_kf<8, true>());
   step(raise_lds_limit(reinterpret_cast<const void*>(gemm_kslice_pipe_kernel<2, 1, 4>)));
   step(raise_lds_limit(reinterpret_cast<const void*>(gemm_kslice_pipe_kernel<2, 2, 4>)));
+  step(raise_lds_limit(reinterpret_cast<const void*>(gemm_kslice_pipe_kernel<2, 1, 4, true>)));
+  step(raise_lds_limit(reinterpret_cast<const void*>(gemm_kslice_pipe_kernel<2, 2, 4, true>)));
   step(raise_lds_limit(reinterpret_cast<const void*>(gemm_bf16_big_kernel<true>)));
   step(raise_lds_limit(reinterpret_cast<const void*>(gemm_bf16_big_kernel<false>)));
   return e;
@@ -1386,6 +1411,7 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
   if (n_probs < 1 || n_probs > 2) return hipErrorInvalidValue;
   GemmGroup g;
   g.n = n_probs;
+  g.stream_w = probs[0].stream_w != 0;
   for (int i = 0; i < n_probs; ++i) {
     const GemmProblem& p = probs[i];
     const int sp = plan.splits[i];
@@ -1401,6 +1427,7 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
       return hipErrorInvalidValue;
     if (p.epi == EPI_LSE && ((plan.kind != KIND_TILE256 && plan.kind != KIND_TILE128) || sp != 1 || !p.lse_target_out)) return hipErrorInvalidValue;
     if ((p.A_lo != nullptr) != (probs[0].A_lo != nullptr)) return hipErrorInvalidValue;
+    if ((p.stream_w != 0) != (probs[0].stream_w != 0)) return hipErrorInvalidValue;
   }
   const bool hl = probs[0].A_lo != nullptr;
   if (hl && dtype != BT_BF16) return hipErrorInvalidValue;

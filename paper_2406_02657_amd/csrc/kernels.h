@@ -159,6 +159,11 @@ struct GemmProblem {
   float* lse_target_out;
   // EPI_QKV only
   QkvEpilogue qe;
+  // Decode (K-slice) kernels with both activation planes: read W_frag with non-temporal loads.  For weights
+  // that will not be read again before the caches have turned over (a block decoder's, used once per L_B
+  // steps; any stack too large for the 256 MB cache) this keeps them from displacing what is re-read.
+  // All problems of a launch share the setting.
+  int stream_w = 0;
 };
 // bf16 weights W[N, K] (K % 32 == 0) re-ordered for the decode GEMM: tiles of 16 rows x 32 k,
 // tile (i, j) at element offset (i * K/32 + j) * 512; inside a tile lane l (0..63) owns the 8
