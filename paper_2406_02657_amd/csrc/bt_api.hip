@@ -18,6 +18,10 @@ namespace {
 
 constexpr int kDefaultPrefillRows = 16384;
 constexpr int kMaxSplits = 16;
+// Weight bytes the decode steps try to keep in the 256 MB cache from one step to the next; the rest of the
+// cache is left to activations and partial sums.  cfg1: 170 MB of token-decoder layers stay, the 77 MB head
+// is streamed (443.1 -> 430.9 us per step against keeping both).
+constexpr size_t kResidentBytes = (size_t)200 << 20;
 constexpr int kSkinnyRows = 256;     // GEMMs with at most this many rows may split K
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
@@ -180,13 +184,11 @@ struct bt_model {
   int64_t graph_launches;
   int graph_captures;
   int static_dev = -1;             // >= 0: the workspace is the static array of this device (bt_create_static)
-  // Decode GEMMs read a stack's weights with non-temporal loads when those weights will not be read again
-  // before the caches have turned over: the block decoder's when it runs once per L_B > 1 steps, and
-  // whatever is read at every step (token decoder, LM head, the block decoder at L_B = 1) when that
-  // exceeds the 256 MB cache.  Measured (us per step, weights
-  // of neither / block stack / token stack and head / both streamed): cfg1 444.6 / 443.5 / 451.0 / 456.8,
-  // cfg2 401.1 / 394.0 / 393.1 / 394.5, cfg3 (token stack 506 MB) 883.0 / 883.6 / 874.0 / 872.4.
-  int stream_token_w = 0, stream_block_w = 1;
+  // Decode GEMMs read weights with non-temporal loads unless they are to stay in the 256 MB cache until the
+  // next step reads them again.  What a step re-reads (the token decoder, the LM head, and the block decoder
+  // when L_B = 1) is kept, in execution order and a whole stack at a time, while it fits kResidentBytes; the
+  // rest, and a block decoder that runs once per L_B > 1 steps, is streamed past the cache.
+  int resident_block_layers = 0, resident_token_layers = 0, resident_head = 0;
 
   template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
 };
@@ -317,7 +319,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
                  lo(a_up, loD), loF};
   GemmProblem po{ao, nullptr, nullptr, part_o, M, D, D, D, D, EPI_PARTIAL, lo(ao, loD), 0};
   GemmProblem pd{hmid, nullptr, nullptr, part_d, M, D, F, F, D, EPI_PARTIAL, lo(hmid, loF), 0};
-  pq.stream_w = pu.stream_w = po.stream_w = pd.stream_w = (a.mode == MODE_TOKEN) ? m->stream_token_w : m->stream_block_w;
+  const int n_resident = (a.mode == MODE_TOKEN) ? m->resident_token_layers : m->resident_block_layers;
   GemmPlan plan_in{}, plan_out{}, plan_q{}, plan_u{}, plan_o{}, plan_d{};
   int sQ, sU, sO, sD;
   if (c.parallel_residual) {
@@ -422,6 +424,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
     for (int l = 0; l < n_layers; ++l) {
       GemmProblem p[2] = {pq, pu};
       p[0].W = lw[l].W_qkv; p[1].W = lw[l].W_up;
+      p[0].stream_w = p[1].stream_w = l >= n_resident;
       p[0].W_frag = fw[l].qkv; p[1].W_frag = fw[l].up;
       if (!pieces) { p[0].bias = (const float*)lw[l].b_qkv; p[1].bias = (const float*)lw[l].b_up; }
       if (qkv_fused) qkv_epilogue(l, p[0]);
@@ -439,7 +442,9 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
       }
       if ((rc = attention(l, gelu_job(l)))) return rc;
       p[0] = po; p[0].W = lw[l].W_o; p[0].W_frag = fw[l].o;
+      p[0].stream_w = l >= n_resident;
       p[1] = pd; p[1].W = lw[l].W_down; p[1].W_frag = fw[l].down;
+      p[1].stream_w = l >= n_resident;
       if (m->profile && (rc = prof_begin(m, pieces ? 1 : 2))) return rc;
       BT_HIP(m, launch_gemm(dt, p, 2, plan_out, s));
       if (m->profile && (rc = prof_end(m))) return rc;
@@ -462,6 +467,7 @@ int run_stack(bt_model* m, const bt_layer_weights* lw, int n_layers, const Stack
   } else {
     if ((rc = ln(nullptr, nullptr, 0, nullptr, nullptr, 0, lw[0].ln1_g, lw[0].ln1_b, nullptr, nullptr))) return rc;
     for (int l = 0; l < n_layers; ++l) {
+      pq.stream_w = po.stream_w = pu.stream_w = pd.stream_w = l >= n_resident;
       GemmProblem p = pq;
       p.W = lw[l].W_qkv; p.W_frag = fw[l].qkv;
       if (!pieces) p.bias = (const float*)lw[l].b_qkv;
@@ -531,11 +537,14 @@ static int create_impl(const bt_config* cfg, const bt_weights* w, void* workspac
   m->cfg = *cfg;
   {
     const size_t esz = cfg->dtype == BT_BF16 ? 2 : 4, D = (size_t)cfg->d_model;
-    const size_t layer = 4 * D * D + 2 * D * (size_t)cfg->d_ff;
-    const size_t every_step = ((size_t)(cfg->n_token_layers + (cfg->block_len == 1 ? cfg->n_block_layers : 0)) * layer +
-                               (size_t)cfg->vocab * D) * esz;
-    m->stream_token_w = every_step > ((size_t)256 << 20);
-    m->stream_block_w = cfg->block_len > 1 || m->stream_token_w;
+    const size_t layer = (4 * D * D + 2 * D * (size_t)cfg->d_ff) * esz, head = (size_t)cfg->vocab * D * esz;
+    size_t room = kResidentBytes;
+    // a stack is kept whole or not at all: with half of cfg3's token decoder kept (8 of 16 layers, 201 MB) a step took
+    // 886.7 us against 870.5 us with all of it streamed
+    auto keep = [&](int n_layers) { const int k = (size_t)n_layers * layer <= room ? n_layers : 0; room -= (size_t)k * layer; return k; };
+    if (cfg->block_len == 1) m->resident_block_layers = keep(cfg->n_block_layers);
+    m->resident_token_layers = (cfg->block_len > 1 || m->resident_block_layers == cfg->n_block_layers) ? keep(cfg->n_token_layers) : 0;
+    m->resident_head = m->resident_token_layers == cfg->n_token_layers && head <= room;
   }
   m->w = *w;
   m->blk.assign(w->block_layers, w->block_layers + cfg->n_block_layers);
@@ -773,7 +782,7 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
   if (rc) return rc;
   GemmProblem p{m->ws + L.hfin, m->w.W_head, nullptr, m->ws + L.logits, B, c.vocab, D, D, c.vocab, EPI_F32,
                 fin_lo ? m->ws + L.hfin + fin_lo * 2 : nullptr, 0, m->head_frag};
-  p.stream_w = m->stream_token_w;
+  p.stream_w = !m->resident_head;
   GemmPlan pl{};
   BT_HIP(m, gemm_plan(c.dtype, &p, 1, &pl));
   // Greedy argmax: where the head's kernel can, it leaves per-tile (max, column) candidates per row
