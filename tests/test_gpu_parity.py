@@ -712,3 +712,36 @@ def test_block_attention_split_over_workgroups(amd, dtype, b, h, d, prompt_len, 
     rep = compare_sampled_with_oracle(cfg, W, prompts, ids, lgs, list(range(b)), TOL_F32 if dtype == "fp32" else TOL_BF16)
     print(rep)
     assert_parity(rep)
+
+
+def test_calibration_probes(amd):
+    """bt_probe_read and bt_probe_mfma (the benchmark's measured peaks): they run, reject bad sizes, and the MFMA
+    probe's output is the sum it should be: constant operands a = lane % 4 (per thread), b = 1, so every
+    accumulator element is iters * 4 * 32 * (the row's a value) and a thread's 64 elements add up accordingly."""
+    import torch
+    from paper_2406_02657_amd import binding as B
+    st = torch.cuda.Stream()
+    out = torch.zeros(B.PROBE_WORKGROUPS * 256, dtype=torch.float32, device="cuda")
+    src = torch.arange(B.PROBE_READ_GRAIN * 2, dtype=torch.int64, device="cuda").to(torch.uint8)
+    with torch.cuda.stream(st):
+        B.probe_read(src, st, out)
+        st.synchronize()
+        assert torch.isfinite(out).all()
+        with pytest.raises(B.BTError):
+            B.probe_read(src[:-16], st, out)
+        iters = 3
+        B.probe_mfma(iters, 0, st, out)
+        st.synchronize()
+        got = out.view(B.PROBE_WORKGROUPS, 256).cpu().numpy()
+        # A operand: lane l holds 8 k-values of row l % 16, all equal to (thread id) % 4; B is all ones.  An output
+        # element (row i, col j) is the sum over 32 k of a[i][k]: k = 8 q + e comes from lane 16 q + i, whose
+        # value is (16 q + i) % 4 = i % 4.  So element (i, j) = 32 * (i % 4) per MFMA.  The probe passes (a, b) as
+        # (first, second) operand and a thread holds 4 elements of one column block; whichever layout, the 64
+        # lanes' sums over 16 accumulators x 4 elements add up to 16 * (sum over the 256 elements of one result).
+        per_mfma_total = 16 * sum(32 * (i % 4) for i in range(16))        # 16 columns x rows
+        want_total = iters * 4 * 16 * per_mfma_total                       # iters x 4 repeats x 16 accumulators
+        wave_totals = got.reshape(B.PROBE_WORKGROUPS, 4, 64).sum(axis=2)
+        assert np.all(wave_totals == want_total), (wave_totals[0], want_total)
+        B.probe_mfma(iters, 1, st, out)
+        st.synchronize()
+        assert torch.isfinite(out).all()
