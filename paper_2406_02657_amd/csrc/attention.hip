@@ -870,23 +870,33 @@ hipError_t launch_attn_block_decode(int dtype, const PartialSrc& qkv, void* Kc, 
   if (!n_dev && (n_old < 0 || n_old >= n_cap)) return hipErrorInvalidValue;
   if (gelu.rows > 0 && gelu.cols % 4) return hipErrorInvalidValue;
   if (n_split < 1 || (n_split > 1 && !split_buf)) return hipErrorInvalidValue;
-  constexpr int NW = 4;
   const int n_pairs = batch * n_heads;
   const int n_attn = n_pairs * n_split;
   const int grid = n_attn + gelu_blocks(gelu);
+  // Waves per workgroup.  Four waves share the rows of a (b, h) when there are few pairs (the chip wants some
+  // thousand waves with loads in flight) or when a pair's rows are many bytes; with many pairs of short caches
+  // two waves do better (fewer partial results to merge, longer streams per wave).  Per launch at NW = 4 -> 2:
+  // cfg3 (2048 pairs, up to 272 rows) 26.7 -> 23.4 us, cfg1's model at batch 256 34.0 -> 28.3, cfg1 17.5 -> 17.3;
+  // but cfg2 (384 pairs) 17.2 -> 17.8 and cfg4 (4096 pairs, 1024 rows of 256 bytes) 193.6 -> 200.1.
+  const size_t pair_bytes = (size_t)n_cap * d_head * (dtype == BT_F32 ? 4 : 2) * 2;
+  const bool two_waves = n_attn >= 768 && pair_bytes <= (192u << 10);
+#define BT_LAUNCH_ATTN_BLOCK_DECODE(T, NWV)                                                                          \
+  BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<T, DH, NWV><<<grid, NWV * 64, 0, s>>>(                             \
+      qkv, (T*)Kc, (T*)Vc, rope, rot, (T*)out, lo_off, n_heads, n_old, n_dev, n_cap, n_attn, gelu, n_split, split_buf)))
   if (dtype == BT_F32) {
-    BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<float, DH, NW><<<grid, NW * 64, 0, s>>>(
-        qkv, (float*)Kc, (float*)Vc, rope, rot, (float*)out, 0, n_heads, n_old, n_dev, n_cap, n_attn, gelu, n_split, split_buf)));
+    const size_t lo_off = 0;
+    if (two_waves) { BT_LAUNCH_ATTN_BLOCK_DECODE(float, 2); } else { BT_LAUNCH_ATTN_BLOCK_DECODE(float, 4); }
     if (n_split > 1)
       BT_DISPATCH_DH(d_head, (attn_split_combine_kernel<float, DH><<<(n_pairs + 3) / 4, 256, 0, s>>>(
           split_buf, n_split, n_pairs, n_heads, (float*)out, 0)));
   } else {
-    BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<bf16_t, DH, NW><<<grid, NW * 64, 0, s>>>(
-        qkv, (bf16_t*)Kc, (bf16_t*)Vc, rope, rot, (bf16_t*)out, out_lo_off, n_heads, n_old, n_dev, n_cap, n_attn, gelu, n_split, split_buf)));
+    const size_t lo_off = out_lo_off;
+    if (two_waves) { BT_LAUNCH_ATTN_BLOCK_DECODE(bf16_t, 2); } else { BT_LAUNCH_ATTN_BLOCK_DECODE(bf16_t, 4); }
     if (n_split > 1)
       BT_DISPATCH_DH(d_head, (attn_split_combine_kernel<bf16_t, DH><<<(n_pairs + 3) / 4, 256, 0, s>>>(
           split_buf, n_split, n_pairs, n_heads, (bf16_t*)out, out_lo_off)));
   }
+#undef BT_LAUNCH_ATTN_BLOCK_DECODE
   return hipGetLastError();
 }
 
