@@ -872,7 +872,6 @@ hipError_t launch_attn_block_decode(int dtype, const PartialSrc& qkv, void* Kc, 
   if (n_split < 1 || (n_split > 1 && !split_buf)) return hipErrorInvalidValue;
   const int n_pairs = batch * n_heads;
   const int n_attn = n_pairs * n_split;
-  const int grid = n_attn + gelu_blocks(gelu);
   // Waves per workgroup.  Four waves share the rows of a (b, h) when there are few pairs (the chip wants some
   // thousand waves with loads in flight) or when a pair's rows are many bytes; with many pairs of short caches
   // two waves do better (fewer partial results to merge, longer streams per wave).  Per launch at NW = 4 -> 2:
@@ -880,6 +879,7 @@ hipError_t launch_attn_block_decode(int dtype, const PartialSrc& qkv, void* Kc, 
   // but cfg2 (384 pairs) 17.2 -> 17.8 and cfg4 (4096 pairs, 1024 rows of 256 bytes) 193.6 -> 200.1.
   const size_t pair_bytes = (size_t)n_cap * d_head * (dtype == BT_F32 ? 4 : 2) * 2;
   const bool two_waves = n_attn >= 768 && pair_bytes <= (192u << 10);
+  const int grid = n_attn + gelu_blocks(gelu) * (two_waves ? 2 : 1);      // the GELU workgroups are sized for 256 threads
 #define BT_LAUNCH_ATTN_BLOCK_DECODE(T, NWV)                                                                          \
   BT_DISPATCH_DH(d_head, (attn_block_decode_kernel<T, DH, NWV><<<grid, NWV * 64, 0, s>>>(                             \
       qkv, (T*)Kc, (T*)Vc, rope, rot, (T*)out, lo_off, n_heads, n_old, n_dev, n_cap, n_attn, gelu, n_split, split_buf)))
