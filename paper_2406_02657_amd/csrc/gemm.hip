@@ -970,15 +970,22 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(KsGroup g) {
   }
 }
 
-// The same kernel for workgroups that walk several K-slices (k_iters >= 2): the
-// loads of slice it + 1 (weight fragments and the thread's share of the activation
-// slice, all into registers) are issued right after slice it has been handed to
-// LDS, so they travel while slice it is multiplied.  hi + remainder planes only;
-// MC * KF <= 8 (registers: the whole next slice is held by the 256 threads).
+// The same kernel for workgroups that walk several K-slices (k_iters >= 2), as a
+// software pipeline over two LDS buffers: while slice it is multiplied out of one
+// buffer, the registers holding slice it + 1 are written to the other and refilled
+// with slice it + 2 from global memory, one 256-thread chunk per multiply step, so
+// the loads, the LDS stores and the matrix instructions of a wave interleave
+// instead of taking turns (one workgroup per CU: nobody else would fill the gaps).
+// One barrier per slice.  hi + remainder planes only; MC * KF <= 8 (registers: a
+// whole slice is held by the 256 threads); LDS: twice the slice.
 // ---------------------------------------------------------------------------
-template <int KF, int NT, int MC, bool SW = false>
+template <int KF, int NT, int MC, bool SW = false, int WM = 1>
 __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(KsGroup g) {
   constexpr int KS = 32 * KF, LDK = KS + 8, CPR = KS / 8, NCH = MC * KF;
+  // the four waves as WM x (4 / WM) over the workgroup's rows and columns: a wave multiplies
+  // MCW 64-row chunks by NTW 16-column tiles
+  constexpr int MCW = MC / WM, NTW = NT * WM;
+  static_assert(MC % WM == 0 && (WM == 1 || WM == 2), "wave grid");
   extern __shared__ __attribute__((aligned(16))) uint16_t sA[];
   const int bid = blockIdx.x;
   KsDesc c = g.p[0];
@@ -987,7 +994,9 @@ __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(KsGroup g) {
   const int t = bid - d.tile_begin;
   const int split = t / d.tiles_n, tn = t - split * d.tiles_n;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n0 = tn * 64 * NT + wave * 16 * NT;
+  const int wave_m = wave % WM, wave_n = wave / WM;
+  const int n0 = tn * 64 * NT + wave_n * 16 * NTW;
+  const int m0 = wave_m * 64 * MCW;
   const int Mpad = (d.M + 15) & ~15;
   const int k_iters = d.K / KS / d.splits;
   const int kblocks = d.K >> 5, last_tile = ((d.N + 15) >> 4) - 1;
@@ -995,11 +1004,11 @@ __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(KsGroup g) {
   const uint16_t* Wf = reinterpret_cast<const uint16_t*>(d.W_frag);
   const ptrdiff_t lo_delta = reinterpret_cast<const uint16_t*>(d.A_lo) - A;
 
-  f32x4_t acc[MC][NT][4];
+  f32x4_t acc[MCW][NTW][4];
 #pragma unroll
-  for (int mc = 0; mc < MC; ++mc)
+  for (int mc = 0; mc < MCW; ++mc)
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+    for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
       for (int mt = 0; mt < 4; ++mt) acc[mc][nt][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
@@ -1013,84 +1022,124 @@ __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(KsGroup g) {
     a_off[u] = min(row, d.M - 1) * d.lda + kc * 8;
     lds_off[u] = row * LDK + kc * 8;
   }
-  const uint16_t* w_base[NT];
+  const uint16_t* w_base[NTW];
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt)
+  for (int nt = 0; nt < NTW; ++nt)
     w_base[nt] = Wf + (size_t)min((n0 >> 4) + nt, last_tile) * kblocks * 512 + lane * 8;
 
-  u32x4_t wn[NT][KF], ah[NCH], al[NCH];
+  // Order within a slice: MC * KF multiply steps; step s reads the fragments of step s + 1,
+  // hands chunk s of slice it + 1 to LDS and reloads its registers with chunk s of slice
+  // it + 2 (the last slice again once there is no further one: same bytes, harmless).
+  constexpr int STEPS = MCW * KF, CPS = NCH / STEPS;      // CPS staged chunks per multiply step
+  const int plane = Mpad * LDK;                    // elements of one plane; a buffer holds two
+  const int slice0 = split * k_iters;
+  u32x4_t wn[NTW][KF], ah[NCH], al[NCH];
+  bf16x8_t wf[NTW][KF];
   {
-    const int kbase = split * k_iters * KS;
+    const int kbase = slice0 * KS;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+    for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
-      for (int kf = 0; kf < KF; ++kf) wn[nt][kf] = load_w_fragment<SW>(w_base[nt] + (size_t)((kbase >> 5) + kf) * 512);
+      for (int kf = 0; kf < KF; ++kf)
+        wf[nt][kf] = __builtin_bit_cast(bf16x8_t, load_w_fragment<SW>(w_base[nt] + (size_t)((kbase >> 5) + kf) * 512));
 #pragma unroll
     for (int u = 0; u < NCH; ++u) {
       ah[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kbase);
       al[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kbase + lo_delta);
     }
-  }
-  for (int it = 0; it < k_iters; ++it) {
-    bf16x8_t wf[NT][KF];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-      for (int kf = 0; kf < KF; ++kf) wf[nt][kf] = __builtin_bit_cast(bf16x8_t, wn[nt][kf]);
 #pragma unroll
     for (int u = 0; u < NCH; ++u) {
       *reinterpret_cast<u32x4_t*>(&sA[lds_off[u]]) = ah[u];
-      *reinterpret_cast<u32x4_t*>(&sA[Mpad * LDK + lds_off[u]]) = al[u];
+      *reinterpret_cast<u32x4_t*>(&sA[plane + lds_off[u]]) = al[u];
     }
-    __syncthreads();
-    if (it + 1 < k_iters) {                       // uniform: the next slice starts its trip now
-      const int kbase = (split * k_iters + it + 1) * KS;
+    const int kbase1 = (slice0 + min(1, k_iters - 1)) * KS;
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
+    for (int u = 0; u < NCH; ++u) {
+      ah[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kbase1);
+      al[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kbase1 + lo_delta);
+    }
+  }
+  __syncthreads();
+  auto lds_frags = [&](const uint16_t* buf, int step, bf16x8_t (&f)[8]) {
+    const int mc = step / KF, kf = step - mc * KF;
 #pragma unroll
-        for (int kf = 0; kf < KF; ++kf) wn[nt][kf] = load_w_fragment<SW>(w_base[nt] + (size_t)((kbase >> 5) + kf) * 512);
+    for (int mt = 0; mt < 4; ++mt) {
+      const int row = min(m0 + mc * 64 + mt * 16 + (lane & 15), Mpad - 1);
+      const uint16_t* sp = buf + row * LDK + (lane >> 4) * 8 + kf * 32;
+      f[mt] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(sp));
+      f[4 + mt] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(sp + plane));
+    }
+  };
+  for (int it = 0; it < k_iters; ++it) {
+    const uint16_t* cur = sA + (it & 1) * 2 * plane;
+    uint16_t* nxt = sA + ((it + 1) & 1) * 2 * plane;
+    const int kb1 = (slice0 + min(it + 1, k_iters - 1)) * KS;
+    const int kb2 = (slice0 + min(it + 2, k_iters - 1)) * KS;
+    bf16x8_t fr[2][8];
+    lds_frags(cur, 0, fr[0]);
 #pragma unroll
-      for (int u = 0; u < NCH; ++u) {
-        ah[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kbase);
-        al[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kbase + lo_delta);
+    for (int nt = 0; nt < NTW; ++nt)
+#pragma unroll
+      for (int kf = 0; kf < KF; ++kf) wn[nt][kf] = load_w_fragment<SW>(w_base[nt] + (size_t)((kb1 >> 5) + kf) * 512);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int step = 0; step < STEPS; ++step) {
+      const int mc = step / KF, kf = step - mc * KF;
+      if (step + 1 < STEPS) lds_frags(cur, step + 1, fr[(step + 1) & 1]);
+#pragma unroll
+      for (int u = step * CPS; u < (step + 1) * CPS; ++u) {
+        *reinterpret_cast<u32x4_t*>(&nxt[lds_off[u]]) = ah[u];
+        *reinterpret_cast<u32x4_t*>(&nxt[plane + lds_off[u]]) = al[u];
+        ah[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kb2);
+        al[u] = *reinterpret_cast<const u32x4_t*>(A + a_off[u] + kb2 + lo_delta);
       }
-    }
 #pragma unroll
-    for (int mc = 0; mc < MC; ++mc) {
+      for (int pl = 0; pl < 2; ++pl)
 #pragma unroll
-      for (int kf = 0; kf < KF; ++kf) {
-        bf16x8_t af[4], afl[4];
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-          const int row = min(mc * 64 + mt * 16 + (lane & 15), Mpad - 1);
-          const uint16_t* sp = &sA[row * LDK + (lane >> 4) * 8 + kf * 32];
-          af[mt] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(sp));
-          afl[mt] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(sp + Mpad * LDK));
-        }
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
+        for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
           for (int mt = 0; mt < 4; ++mt)
-            acc[mc][nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[mt], wf[nt][kf], acc[mc][nt][mt], 0, 0, 0);
+            acc[mc][nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr[step & 1][pl * 4 + mt], wf[nt][kf], acc[mc][nt][mt], 0, 0, 0);
+      // issue order of the step: one memory instruction in the shadow of each matrix instruction
+      // (a wave issues in order; a block of loads ahead of the multiplies would leave the matrix
+      // unit idle while they queue)
+      constexpr int MF = 8 * NTW;                  // matrix instructions of the step
+      constexpr int MEM = 8 + 4 * CPS;             // fragment reads, LDS stores and global loads
+      constexpr int PER = MF / MEM > 0 ? MF / MEM : 1;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-          for (int mt = 0; mt < 4; ++mt)
-            acc[mc][nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afl[mt], wf[nt][kf], acc[mc][nt][mt], 0, 0, 0);
+      for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
+#pragma unroll
+      for (int i = 0; i < 2 * CPS; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
+        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < 2 * CPS; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, MF - PER * MEM, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
+#pragma unroll
+    for (int nt = 0; nt < NTW; ++nt)
+#pragma unroll
+      for (int kf = 0; kf < KF; ++kf) wf[nt][kf] = __builtin_bit_cast(bf16x8_t, wn[nt][kf]);
     __syncthreads();
   }
   if (d.epi == EPI_PARTIAL) {
     float* outp = reinterpret_cast<float*>(d.out) + (size_t)split * d.M * d.N;
 #pragma unroll
-    for (int mc = 0; mc < MC; ++mc)
+    for (int mc = 0; mc < MCW; ++mc)
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
+      for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) {
           const int col = n0 + nt * 16 + (lane & 15);
-          const int row0 = mc * 64 + mt * 16 + (lane >> 4) * 4;
+          const int row0 = m0 + mc * 64 + mt * 16 + (lane >> 4) * 4;
 #pragma unroll
           for (int r = 0; r < 4; ++r)
             if (row0 + r < d.M && col < d.N) outp[(size_t)(row0 + r) * d.N + col] = acc[mc][nt][mt][r];
@@ -1101,13 +1150,13 @@ __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(KsGroup g) {
   {
     float* outp = reinterpret_cast<float*>(d.out);
 #pragma unroll
-    for (int mc = 0; mc < MC; ++mc)
+    for (int mc = 0; mc < MCW; ++mc)
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
+      for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) {
           const int col = n0 + nt * 16 + (lane & 15);
-          const int row0 = mc * 64 + mt * 16 + (lane >> 4) * 4;
+          const int row0 = m0 + mc * 64 + mt * 16 + (lane >> 4) * 4;
           const float bcol = (d.bias && col < d.N) ? d.bias[col] : 0.f;
 #pragma unroll
           for (int r = 0; r < 4; ++r)
@@ -1336,8 +1385,9 @@ template <int KF, int NT, int MC>
 static hipError_t launch_kslice_pipe(GemmGroup& g, size_t lds, hipStream_t s) {
   KsGroup k;
   const int grid = pack_kslice(g, 64 * NT, k);
-  if (g.stream_w) gemm_kslice_pipe_kernel<KF, NT, MC, true><<<grid, 256, lds, s>>>(k);
-  else gemm_kslice_pipe_kernel<KF, NT, MC><<<grid, 256, lds, s>>>(k);
+  // two LDS buffers (at 256 rows and 64-element slices: 2 x 72 KB of the CU's 160 KB)
+  if (g.stream_w) gemm_kslice_pipe_kernel<KF, NT, MC, true><<<grid, 256, 2 * lds, s>>>(k);
+  else gemm_kslice_pipe_kernel<KF, NT, MC><<<grid, 256, 2 * lds, s>>>(k);
   return hipSuccess;
 }
 
