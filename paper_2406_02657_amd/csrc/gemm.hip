@@ -979,7 +979,9 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(KsGroup g) {
 // One barrier per slice.  hi + remainder planes only; MC * KF <= 8 (registers: a
 // whole slice is held by the 256 threads); LDS: twice the slice.
 // ---------------------------------------------------------------------------
-template <int KF, int NT, int MC, bool SW = false, int WM = 1>
+constexpr int kPipeWaveRows = 1;               // waves along the rows of the workgroup's tile: 1 or 2 (measured equal)
+
+template <int KF, int NT, int MC, bool SW = false, int WM = kPipeWaveRows>
 __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(KsGroup g) {
   constexpr int KS = 32 * KF, LDK = KS + 8, CPR = KS / 8, NCH = MC * KF;
   // the four waves as WM x (4 / WM) over the workgroup's rows and columns: a wave multiplies
@@ -1132,6 +1134,32 @@ __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(KsGroup g) {
   }
   if (d.epi == EPI_PARTIAL) {
     float* outp = reinterpret_cast<float*>(d.out) + (size_t)split * d.M * d.N;
+    if ((d.N & 3) == 0 && (reinterpret_cast<uintptr_t>(outp) & 15) == 0) {
+      // whole rows: each 16-row piece of the wave's tile goes through a strip of LDS of the wave's
+      // own (behind the two slice buffers), so that a store instruction writes 16 bytes per lane
+      // and whole 64-byte (NTW = 1: the tile is 16 columns wide) or 128-byte row segments
+      constexpr int LDP = 16 * NTW + 4;            // floats per strip row
+      constexpr int LPR = 4 * NTW;                 // lanes per row (16 bytes each)
+      constexpr int RPI = 64 / LPR;                // rows per store instruction
+      float* strip = reinterpret_cast<float*>(sA + 4 * plane) + wave * (16 * LDP);
+      const int srow = lane / LPR, scol = (lane % LPR) * 4;
+#pragma unroll
+      for (int mc = 0; mc < MCW; ++mc)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+          for (int nt = 0; nt < NTW; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) strip[((lane >> 4) * 4 + r) * LDP + nt * 16 + (lane & 15)] = acc[mc][nt][mt][r];
+#pragma unroll
+          for (int h = 0; h < 16 / RPI; ++h) {
+            const int row = m0 + mc * 64 + mt * 16 + h * RPI + srow;
+            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(&strip[(h * RPI + srow) * LDP + scol]);
+            if (row < d.M && n0 + scol < d.N) *reinterpret_cast<f32x4_t*>(&outp[(size_t)row * d.N + n0 + scol]) = v;
+          }
+        }
+      return;
+    }
 #pragma unroll
     for (int mc = 0; mc < MCW; ++mc)
 #pragma unroll
@@ -1386,8 +1414,11 @@ static hipError_t launch_kslice_pipe(GemmGroup& g, size_t lds, hipStream_t s) {
   KsGroup k;
   const int grid = pack_kslice(g, 64 * NT, k);
   // two LDS buffers (at 256 rows and 64-element slices: 2 x 72 KB of the CU's 160 KB)
-  if (g.stream_w) gemm_kslice_pipe_kernel<KF, NT, MC, true><<<grid, 256, 2 * lds, s>>>(k);
-  else gemm_kslice_pipe_kernel<KF, NT, MC><<<grid, 256, 2 * lds, s>>>(k);
+  // ... and a strip of 16 rows per wave for the epilogue's whole-row stores
+  const size_t bytes = 2 * lds + 4 * 16 * (16 * NT * kPipeWaveRows + 4) * sizeof(float);
+  if (bytes > 160 * 1024) return hipErrorInvalidValue;
+  if (g.stream_w) gemm_kslice_pipe_kernel<KF, NT, MC, true><<<grid, 256, bytes, s>>>(k);
+  else gemm_kslice_pipe_kernel<KF, NT, MC><<<grid, 256, bytes, s>>>(k);
   return hipSuccess;
 }
 
