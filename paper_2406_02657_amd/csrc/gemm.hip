@@ -6,6 +6,8 @@
 // fp32 mode: an LDS-tiled VALU kernel (small models only).
 // Both operands are K-contiguous, so a lane's MFMA fragment (8 consecutive k of
 // one row) is one 16-byte load.  Up to two independent problems share a launch.
+#include <algorithm>
+
 #include "common.h"
 #include "kernels.h"
 #include "../../include/bt.h"
@@ -1000,7 +1002,10 @@ __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(KsGroup g) {
   const int n0 = tn * 64 * NT + wave_n * 16 * NTW;
   const int m0 = wave_m * 64 * MCW;
   const int Mpad = (d.M + 15) & ~15;
-  const int k_iters = d.K / KS / d.splits;
+  // the K-slices of a problem are dealt to its splits as evenly as they go: the first
+  // (slices % splits) splits walk one slice more
+  const int slices = d.K / KS, q = slices / d.splits, rem = slices - q * d.splits;
+  const int k_iters = q + (split < rem ? 1 : 0);
   const int kblocks = d.K >> 5, last_tile = ((d.N + 15) >> 4) - 1;
   const uint16_t* A = reinterpret_cast<const uint16_t*>(d.A);
   const uint16_t* Wf = reinterpret_cast<const uint16_t*>(d.W_frag);
@@ -1034,7 +1039,7 @@ __global__ __launch_bounds__(256) void gemm_kslice_pipe_kernel(KsGroup g) {
   // it + 2 (the last slice again once there is no further one: same bytes, harmless).
   constexpr int STEPS = MCW * KF, CPS = NCH / STEPS;      // CPS staged chunks per multiply step
   const int plane = Mpad * LDK;                    // elements of one plane; a buffer holds two
-  const int slice0 = split * k_iters;
+  const int slice0 = split * q + min(split, rem);
   u32x4_t wn[NTW][KF], ah[NCH], al[NCH];
   bf16x8_t wf[NTW][KF];
   {
@@ -1275,6 +1280,7 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
   plan->kf = 0;
   plan->nt = 1;
   plan->mc = 1;
+  plan->uneven = 0;
   const bool hl = probs[0].A_lo != nullptr;
   if (dtype == BT_F32) {
     plan->kind = KIND_F32;
@@ -1353,6 +1359,45 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
         plan->nt = nt;
         plan->splits[0] = spl[0];
         plan->splits[1] = spl[1];
+      }
+    }
+  }
+  // The pipelined kernel (two planes, 129-256 rows, 64-element slices) runs one workgroup per CU
+  // and deals K-slices to splits unevenly, so the slices per workgroup need not divide the slice
+  // counts: take the q (longest walk) that minimises  q * (time of a slice) + partial sums out and
+  // back,  with all workgroups in one round.  Measured on 256 x 2048 x {2048, 8192} in one launch:
+  // 16 slices per workgroup on 160 CUs against 11 on 240.
+  if (hl && plan->mc == 4 && kf == 2 && plan->nt <= 2) {
+    constexpr double kSliceUs[3] = {0, 1.3, 1.9};          // per 64-element slice at nt = 1, 2
+    constexpr double kPartialBytesPerUs = 5e6;
+    auto model = [&](const int* spl) {
+      int q_max = 0;
+      double bytes = 0;
+      for (int i = 0; i < n_probs; ++i) {
+        const int slices = probs[i].K / 64;
+        q_max = std::max(q_max, (slices + spl[i] - 1) / spl[i]);
+        if (probs[i].epi == EPI_PARTIAL) bytes += (double)spl[i] * probs[i].M * probs[i].N * 8;
+      }
+      return q_max * kSliceUs[plan->nt] + bytes / kPartialBytesPerUs;
+    };
+    double best = model(plan->splits);
+    int max_slices = 0;
+    for (int i = 0; i < n_probs; ++i) max_slices = std::max(max_slices, probs[i].K / 64);
+    for (int q = 1; q <= max_slices; ++q) {
+      int spl[2] = {1, 1};
+      int wgs = 0;
+      for (int i = 0; i < n_probs; ++i) {
+        const int slices = probs[i].K / 64, tiles = (probs[i].N + 64 * plan->nt - 1) / (64 * plan->nt);
+        if (probs[i].epi == EPI_PARTIAL) spl[i] = (slices + q - 1) / q;
+        wgs += tiles * spl[i];
+      }
+      if (wgs > kNumCU) continue;
+      const double t = model(spl);
+      if (t < best * 0.97) {                               // keep the dividing plan unless this one is clearly shorter
+        best = t;
+        plan->splits[0] = spl[0];
+        plan->splits[1] = spl[1];
+        plan->uneven = 1;
       }
     }
   }
@@ -1496,7 +1541,7 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
   for (int i = 0; i < n_probs; ++i) {
     const GemmProblem& p = probs[i];
     const int sp = plan.splits[i];
-    if (sp < 1 || p.K % sp || (sp > 1 && p.epi != EPI_PARTIAL)) return hipErrorInvalidValue;
+    if (sp < 1 || (!plan.uneven && p.K % sp) || (sp > 1 && p.epi != EPI_PARTIAL)) return hipErrorInvalidValue;
     g.p[i].A = p.A; g.p[i].W = p.W; g.p[i].bias = p.bias; g.p[i].out = p.out;
     g.p[i].M = p.M; g.p[i].N = p.N; g.p[i].K = p.K; g.p[i].lda = p.lda; g.p[i].ldo = p.ldo;
     g.p[i].epi = p.epi; g.p[i].splits = sp;
@@ -1538,7 +1583,9 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
     case KIND_KSLICE: {
       for (int i = 0; i < n_probs; ++i) {
         const GemmProblem& p = probs[i];
-        if (p.K % (32 * plan.kf * plan.splits[i]) || !p.W_frag || p.epi == EPI_GELU) return hipErrorInvalidValue;
+        if (plan.uneven ? (p.K % (32 * plan.kf) || plan.splits[i] > p.K / (32 * plan.kf)) : p.K % (32 * plan.kf * plan.splits[i]))
+          return hipErrorInvalidValue;
+        if (!p.W_frag || p.epi == EPI_GELU) return hipErrorInvalidValue;
         // the compact argument form implies dense rows and a remainder plane within 2^31 elements
         if (p.lda != p.K || (p.epi == EPI_F32 && p.ldo != p.N) || plan.splits[i] > 0xffff) return hipErrorInvalidValue;
         if (p.A_lo) {
@@ -1554,10 +1601,11 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
       // With few rows several workgroups share a CU and overlap each other's phases better than one
       // pipelined workgroup does (LM head at 64 rows: 24 us against 27 us), so the pipelined
       // variant serves the shapes that leave room for one workgroup per CU only.
-      if (hl && several_slices && plan.mc >= 4 && launch_kslice_pipe_any(g, plan.kf, plan.nt, plan.mc, lds, s, &e)) {
+      if (hl && (several_slices || plan.uneven) && plan.mc >= 4 && launch_kslice_pipe_any(g, plan.kf, plan.nt, plan.mc, lds, s, &e)) {
         if (e != hipSuccess) return e;
         break;
       }
+      if (plan.uneven) return hipErrorInvalidValue;   // only the pipelined kernel deals slices unevenly
       switch (plan.kf * 2 + (hl ? 1 : 0)) {
         case 4:  e = launch_kslice_kf<2, false>(g, plan.nt, plan.mc, lds, s); break;
         case 5:  e = launch_kslice_kf<2, true>(g, plan.nt, plan.mc, lds, s); break;

@@ -177,6 +177,7 @@ hipError_t gemm_pack_weights(const void* W, void* W_frag, int N, int K, hipStrea
 struct GemmPlan {
   int kind, kf, nt, mc;
   int splits[2];
+  int uneven;    // 1: splits need not divide the K-slice count (the first slices % splits walk one slice more)
 };
 hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan* plan);
 // Whether the kernel this plan selects is one of the tiled MFMA kernels, which implement EPI_LSE and EPI_QKV.

@@ -121,7 +121,8 @@ int main() {
     bt_destroy(nullptr);
   }
 
-  // the GEMM planner over many shapes: whatever it answers, the splits divide K into whole slices
+  // the GEMM planner over many shapes: whatever it answers, the splits divide K into whole slices, or (uneven
+  // plans: two planes, 129-256 rows, 64-element slices) there are at most as many splits as slices
   {
     using namespace bt;
     const int Ms[] = {1, 5, 16, 63, 64, 65, 128, 129, 192, 193, 255, 256, 257, 1000, 16384};
@@ -147,9 +148,15 @@ int main() {
                   std::memset(&plan, 0, sizeof(plan));
                   EXPECT(gemm_plan(dtype, p, 1 + two, &plan) == hipSuccess);
                   for (int i = 0; i <= two; ++i) {
-                    EXPECT(plan.splits[i] >= 1 && p[i].K % plan.splits[i] == 0);
+                    EXPECT(plan.uneven == 0 || plan.uneven == 1);
+                    if (plan.uneven) {
+                      EXPECT(hl && M > 128 && M <= 256 && plan.kind == 2 && plan.kf == 2 && plan.mc == 4 && plan.nt <= 2);
+                      EXPECT(plan.splits[i] >= 1 && p[i].K % 64 == 0 && plan.splits[i] <= p[i].K / 64);
+                    } else {
+                      EXPECT(plan.splits[i] >= 1 && p[i].K % plan.splits[i] == 0);
+                      if (plan.kf > 0 && dtype == BT_BF16 && M <= 256) EXPECT(p[i].K % (32 * plan.kf * plan.splits[i]) == 0 || plan.kind != 2);
+                    }
                     if (epi != EPI_PARTIAL) EXPECT(plan.splits[i] == 1);
-                    if (plan.kf > 0 && dtype == BT_BF16 && M <= 256) EXPECT(p[i].K % (32 * plan.kf * plan.splits[i]) == 0 || plan.kind != 2);
                   }
                   const int tiles = gemm_row_max_tiles(p[0], plan);
                   EXPECT(tiles >= 0 && tiles <= (N + 63) / 64);
