@@ -794,7 +794,7 @@ static int enqueue_step(bt_model* m, int r, bool with_block, int32_t* ids_out) {
   }
   BT_HIP(m, launch_gemm(c.dtype, &p, 1, pl, s));
   if (cand_tiles > 0)
-    BT_HIP(m, launch_argmax_candidates(m->at<float2>(L.cand), cand_tiles, B, ids_out, cur, c.block_len, r, c.eos_id,
+    BT_HIP(m, launch_argmax_candidates(m->at<float2>(L.cand), cand_tiles, B, c.vocab, ids_out, cur, c.block_len, r, c.eos_id,
                                        m->at<int32_t>(L.fin), s));
   else
     BT_HIP(m, launch_argmax(m->at<float>(L.logits), B, c.vocab, ids_out, cur, c.block_len, r, c.eos_id,

@@ -367,7 +367,7 @@ hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* nex
 }
 
 // Greedy argmax from per-tile candidates: one wave per sequence scans cand[b * n_tiles + tile].
-__device__ __forceinline__ void argmax_candidates_body(const float2* __restrict__ cand, int n_tiles,
+__device__ __forceinline__ void argmax_candidates_body(const float2* __restrict__ cand, int n_tiles, int vocab,
                                                        int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
                                                        int block_len, int r, int eos_id, int32_t* __restrict__ finished) {
   const int b = blockIdx.x;
@@ -384,30 +384,32 @@ __device__ __forceinline__ void argmax_candidates_body(const float2* __restrict_
     argmax_take(ov, oi, best, bi);
   }
   if (threadIdx.x == 0) {
-    if (bi == 0x7fffffff) bi = 0;           // every logit was NaN or -inf
+    // every logit was NaN or -inf; or the column is not one: the id indexes the embedding table in the
+    // next step, so a candidate buffer its producer did not fill must not turn into a wild row
+    if ((unsigned)bi >= (unsigned)vocab) bi = 0;
     bi = apply_eos(bi, eos_id, finished, b);
     if (next_ids) next_ids[b] = bi;
     cur[b * block_len + r] = bi;
   }
 }
 
-__global__ __launch_bounds__(64) void argmax_candidates_kernel(const float2* __restrict__ cand, int n_tiles, int batch,
+__global__ __launch_bounds__(64) void argmax_candidates_kernel(const float2* __restrict__ cand, int n_tiles, int vocab,
                                                                int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
                                                                int block_len, int r) {
-  argmax_candidates_body(cand, n_tiles, next_ids, cur, block_len, r, -1, nullptr);
+  argmax_candidates_body(cand, n_tiles, vocab, next_ids, cur, block_len, r, -1, nullptr);
 }
-__global__ __launch_bounds__(64) void argmax_candidates_eos_kernel(const float2* __restrict__ cand, int n_tiles,
+__global__ __launch_bounds__(64) void argmax_candidates_eos_kernel(const float2* __restrict__ cand, int n_tiles, int vocab,
                                                                    int32_t* __restrict__ next_ids, int32_t* __restrict__ cur,
                                                                    int block_len, int r, int eos_id,
                                                                    int32_t* __restrict__ finished) {
-  argmax_candidates_body(cand, n_tiles, next_ids, cur, block_len, r, eos_id, finished);
+  argmax_candidates_body(cand, n_tiles, vocab, next_ids, cur, block_len, r, eos_id, finished);
 }
 
-hipError_t launch_argmax_candidates(const float2* cand, int n_tiles, int batch, int32_t* next_ids,
+hipError_t launch_argmax_candidates(const float2* cand, int n_tiles, int batch, int vocab, int32_t* next_ids,
                                     int32_t* cur, int block_len, int r, int eos_id, int32_t* finished, hipStream_t s) {
-  if (n_tiles < 1) return hipErrorInvalidValue;
-  if (eos_id >= 0) argmax_candidates_eos_kernel<<<batch, 64, 0, s>>>(cand, n_tiles, next_ids, cur, block_len, r, eos_id, finished);
-  else argmax_candidates_kernel<<<batch, 64, 0, s>>>(cand, n_tiles, batch, next_ids, cur, block_len, r);
+  if (n_tiles < 1 || vocab < 1) return hipErrorInvalidValue;
+  if (eos_id >= 0) argmax_candidates_eos_kernel<<<batch, 64, 0, s>>>(cand, n_tiles, vocab, next_ids, cur, block_len, r, eos_id, finished);
+  else argmax_candidates_kernel<<<batch, 64, 0, s>>>(cand, n_tiles, vocab, next_ids, cur, block_len, r);
   return hipGetLastError();
 }
 

@@ -66,8 +66,9 @@ hipError_t launch_resid_ln(int dtype, const ResidLnArgs& a, hipStream_t s, const
 // (finished[b] is then set, device memory), every later id of b is eos_id.
 hipError_t launch_argmax(const float* logits, int batch, int vocab, int32_t* next_ids,
                          int32_t* cur, int block_len, int r, int eos_id, int32_t* finished, hipStream_t s);
-// The same from per-tile candidates cand[b * n_tiles + tile] = (value, column as int bits).
-hipError_t launch_argmax_candidates(const float2* cand, int n_tiles, int batch, int32_t* next_ids,
+// The same from per-tile candidates cand[b * n_tiles + tile] = (value, column as int bits); a column outside
+// [0, vocab) counts as "no candidate" (id 0).
+hipError_t launch_argmax_candidates(const float2* cand, int n_tiles, int batch, int vocab, int32_t* next_ids,
                                     int32_t* cur, int block_len, int r, int eos_id, int32_t* finished, hipStream_t s);
 
 // cur[b*L_B + r] = ids[b]; with eos_id >= 0 also finished[b] = 1 where ids[b] == eos_id
