@@ -1362,15 +1362,21 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
       }
     }
   }
-  // The pipelined kernel (two planes, 129-256 rows, 64-element slices) runs one workgroup per CU
-  // and deals K-slices to splits unevenly, so the slices per workgroup need not divide the slice
-  // counts: take the q (longest walk) that minimises  q * (time of a slice) + partial sums out and
-  // back,  with all workgroups in one round.  Measured on 256 x 2048 x {2048, 8192} in one launch:
-  // 16 slices per workgroup on 160 CUs against 11 on 240.
-  if (hl && plan->mc == 4 && kf == 2 && plan->nt <= 2) {
-    constexpr double kSliceUs[3] = {0, 1.3, 1.9};          // per 64-element slice at nt = 1, 2
+  // The pipelined kernel (two planes, 64-element slices) runs one workgroup per CU and deals
+  // K-slices to splits unevenly, so the slices per workgroup need not divide the slice counts:
+  // take the q (longest walk) that minimises  q * (time of a slice) + partial sums out and back,
+  // with all workgroups in one round.  Measured on 256 x 2048 x {2048, 8192} in one launch:
+  // 16 slices per workgroup on 160 CUs against 11 on 240.  At 129-256 rows it serves every launch
+  // (the plan above stands unless a q is clearly shorter); at 65-128 rows only launches made of
+  // partial-sum problems (the others leave argmax candidates, which the plain kernel writes).
+  bool all_partial = true;
+  for (int i = 0; i < n_probs; ++i) all_partial &= probs[i].epi == EPI_PARTIAL;
+  const bool rows256 = hl && plan->mc == 4 && kf == 2 && plan->nt <= 2;
+  const bool rows128 = hl && plan->mc == 2 && kf == 2 && all_partial;
+  if (rows256 || rows128) {
+    const double slice_us[3] = {0, rows256 ? 1.3 : 0.7, rows256 ? 1.9 : 1.0};   // per 64-element slice at nt = 1, 2
     constexpr double kPartialBytesPerUs = 5e6;
-    auto model = [&](const int* spl) {
+    auto model = [&](int nt, const int* spl) {
       int q_max = 0;
       double bytes = 0;
       for (int i = 0; i < n_probs; ++i) {
@@ -1378,28 +1384,31 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
         q_max = std::max(q_max, (slices + spl[i] - 1) / spl[i]);
         if (probs[i].epi == EPI_PARTIAL) bytes += (double)spl[i] * probs[i].M * probs[i].N * 8;
       }
-      return q_max * kSliceUs[plan->nt] + bytes / kPartialBytesPerUs;
+      return q_max * slice_us[nt] + bytes / kPartialBytesPerUs;
     };
-    double best = model(plan->splits);
+    double best = rows256 ? model(plan->nt, plan->splits) : 1e300;
     int max_slices = 0;
     for (int i = 0; i < n_probs; ++i) max_slices = std::max(max_slices, probs[i].K / 64);
-    for (int q = 1; q <= max_slices; ++q) {
-      int spl[2] = {1, 1};
-      int wgs = 0;
-      for (int i = 0; i < n_probs; ++i) {
-        const int slices = probs[i].K / 64, tiles = (probs[i].N + 64 * plan->nt - 1) / (64 * plan->nt);
-        if (probs[i].epi == EPI_PARTIAL) spl[i] = (slices + q - 1) / q;
-        wgs += tiles * spl[i];
+    const int nt_first = rows256 ? plan->nt : 2, nt_last = rows256 ? plan->nt : 1;
+    for (int nt = nt_first; nt >= nt_last; --nt)
+      for (int q = 1; q <= max_slices; ++q) {
+        int spl[2] = {1, 1};
+        int wgs = 0;
+        for (int i = 0; i < n_probs; ++i) {
+          const int slices = probs[i].K / 64, tiles = (probs[i].N + 64 * nt - 1) / (64 * nt);
+          if (probs[i].epi == EPI_PARTIAL) spl[i] = (slices + q - 1) / q;
+          wgs += tiles * spl[i];
+        }
+        if (wgs > kNumCU) continue;
+        const double t = model(nt, spl);
+        if (t < best * 0.97) {                             // keep the plan in hand unless this one is clearly shorter
+          best = t;
+          plan->nt = nt;
+          plan->splits[0] = spl[0];
+          plan->splits[1] = spl[1];
+          plan->uneven = 1;
+        }
       }
-      if (wgs > kNumCU) continue;
-      const double t = model(spl);
-      if (t < best * 0.97) {                               // keep the dividing plan unless this one is clearly shorter
-        best = t;
-        plan->splits[0] = spl[0];
-        plan->splits[1] = spl[1];
-        plan->uneven = 1;
-      }
-    }
   }
   return hipSuccess;
 }
@@ -1470,6 +1479,8 @@ static hipError_t launch_kslice_pipe(GemmGroup& g, size_t lds, hipStream_t s) {
 // The pipelined variant exists for these (kf, nt, mc); returns false when there is none.
 static bool launch_kslice_pipe_any(GemmGroup& g, int kf, int nt, int mc, size_t lds, hipStream_t s, hipError_t* e) {
   switch (kf * 100 + nt * 10 + mc) {
+    case 212: *e = launch_kslice_pipe<2, 1, 2>(g, lds, s); return true;
+    case 222: *e = launch_kslice_pipe<2, 2, 2>(g, lds, s); return true;
     case 214: *e = launch_kslice_pipe<2, 1, 4>(g, lds, s); return true;
     case 224: *e = launch_kslice_pipe<2, 2, 4>(g, lds, s); return true;
     default: return false;
@@ -1524,6 +1535,10 @@ hipError_t gemm_prepare_kernels() {
   step(prepare_kslice_kf<4, false>()); step(prepare_kslice_kf<4, true>());
   step(prepare_kslice_kf<6, false>()); step(prepare_kslice_kf<6, true>());
   step(prepare_kslice_kf<8, false>()); step(prepare_kslice_kf<8, true>());
+  step(raise_lds_limit(reinterpret_cast<const void*>(gemm_kslice_pipe_kernel<2, 1, 2>)));
+  step(raise_lds_limit(reinterpret_cast<const void*>(gemm_kslice_pipe_kernel<2, 2, 2>)));
+  step(raise_lds_limit(reinterpret_cast<const void*>(gemm_kslice_pipe_kernel<2, 1, 2, true>)));
+  step(raise_lds_limit(reinterpret_cast<const void*>(gemm_kslice_pipe_kernel<2, 2, 2, true>)));
   step(raise_lds_limit(reinterpret_cast<const void*>(gemm_kslice_pipe_kernel<2, 1, 4>)));
   step(raise_lds_limit(reinterpret_cast<const void*>(gemm_kslice_pipe_kernel<2, 2, 4>)));
   step(raise_lds_limit(reinterpret_cast<const void*>(gemm_kslice_pipe_kernel<2, 1, 4, true>)));
@@ -1601,7 +1616,12 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
       // With few rows several workgroups share a CU and overlap each other's phases better than one
       // pipelined workgroup does (LM head at 64 rows: 24 us against 27 us), so the pipelined
       // variant serves the shapes that leave room for one workgroup per CU only.
-      if (hl && (several_slices || plan.uneven) && plan.mc >= 4 && launch_kslice_pipe_any(g, plan.kf, plan.nt, plan.mc, lds, s, &e)) {
+      // ... and, at 65-128 rows, launches the planner marked for it (partial-sum problems only: the
+      // pipelined kernel leaves no argmax candidates)
+      bool all_partial = true;
+      for (int i = 0; i < n_probs; ++i) all_partial &= probs[i].epi == EPI_PARTIAL;
+      if (plan.mc == 2 && plan.uneven && !all_partial) return hipErrorInvalidValue;
+      if (hl && (several_slices || plan.uneven) && (plan.mc >= 4 || (plan.mc == 2 && plan.uneven)) && launch_kslice_pipe_any(g, plan.kf, plan.nt, plan.mc, lds, s, &e)) {
         if (e != hipSuccess) return e;
         break;
       }

@@ -163,6 +163,16 @@ def test_bf16_decode_gemm_193_to_256_rows(amd, d, h, f, b, p):
     run_case(amd, cfg, 9, batch=b, seqs=[0, 1, b // 2, b - 2, b - 1])
 
 
+@pytest.mark.parametrize("d,h,f,b,p", [(256, 4, 1024, 128, 1), (192, 3, 320, 120, 1), (256, 2, 512, 57, 2), (128, 2, 256, 113, 1)])
+def test_bf16_decode_gemm_113_to_128_rows(amd, d, h, f, b, p):
+    """Decode steps with 113 .. 128 rows (64-element K-slices of two 64-row chunks): the layer GEMMs take the
+    pipelined K-slice kernel (partial sums, one slice or several per workgroup), the LM head the plain one
+    (argmax candidates); full and ragged row tiles, K of 2 .. 16 slices."""
+    cfg = tiny_cfg(dtype="bf16", block_len=4, prefix_len=p, d_model=d, n_heads=h, d_ff=f, vocab=1000,
+                   prompt_len=8, n_block_layers=2, n_token_layers=2)
+    run_case(amd, cfg, 9, batch=b, seqs=[0, 1, b // 2, b - 2, b - 1])
+
+
 @pytest.mark.parametrize("d,h,blocks", [(128, 4, 80), (256, 4, 145), (256, 2, 64), (128, 1, 97)])
 def test_bf16_prefill_attention_on_matrix_cores(amd, d, h, blocks):
     """Prompts of at least 64 blocks take the MFMA causal-attention kernel of the block decoder's
