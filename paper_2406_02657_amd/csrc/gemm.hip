@@ -1367,14 +1367,19 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
   // take the q (longest walk) that minimises  q * (time of a slice) + partial sums out and back,
   // with all workgroups in one round.  Measured on 256 x 2048 x {2048, 8192} in one launch:
   // 16 slices per workgroup on 160 CUs against 11 on 240.  At 129-256 rows it serves every launch
-  // (the plan above stands unless a q is clearly shorter); at 65-128 rows only launches made of
-  // partial-sum problems (the others leave argmax candidates, which the plain kernel writes).
+  // (the plan above stands unless a q is clearly shorter); with fewer rows only launches made of
+  // partial-sum problems (the others leave argmax candidates, which the plain kernel writes): at
+  // 65-128 rows where the slice length above is 64 already, up to 64 rows always, with the slice
+  // length set to 64 here (cfg1, 64 rows: 430 -> 409 us per decode step against the plain kernel's
+  // one-shot 192-element slices; longer walks with fewer partial planes 418).
   bool all_partial = true;
   for (int i = 0; i < n_probs; ++i) all_partial &= probs[i].epi == EPI_PARTIAL;
   const bool rows256 = hl && plan->mc == 4 && kf == 2 && plan->nt <= 2;
   const bool rows128 = hl && plan->mc == 2 && kf == 2 && all_partial;
-  if (rows256 || rows128) {
-    const double slice_us[3] = {0, rows256 ? 1.3 : 0.7, rows256 ? 1.9 : 1.0};   // per 64-element slice at nt = 1, 2
+  bool rows64 = hl && plan->mc == 1 && all_partial;
+  for (int i = 0; i < n_probs; ++i) rows64 &= probs[i].K % 64 == 0;
+  if (rows256 || rows128 || rows64) {
+    const double slice_us[3] = {0, rows256 ? 1.3 : rows128 ? 0.7 : 0.35, rows256 ? 1.9 : rows128 ? 1.0 : 0.5};   // per 64-element slice at nt = 1, 2
     constexpr double kPartialBytesPerUs = 5e6;
     auto model = [&](int nt, const int* spl) {
       int q_max = 0;
@@ -1407,6 +1412,7 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
           plan->splits[0] = spl[0];
           plan->splits[1] = spl[1];
           plan->uneven = 1;
+          if (rows64) plan->kf = 2;
         }
       }
   }
@@ -1479,6 +1485,8 @@ static hipError_t launch_kslice_pipe(GemmGroup& g, size_t lds, hipStream_t s) {
 // The pipelined variant exists for these (kf, nt, mc); returns false when there is none.
 static bool launch_kslice_pipe_any(GemmGroup& g, int kf, int nt, int mc, size_t lds, hipStream_t s, hipError_t* e) {
   switch (kf * 100 + nt * 10 + mc) {
+    case 211: *e = launch_kslice_pipe<2, 1, 1>(g, lds, s); return true;
+    case 221: *e = launch_kslice_pipe<2, 2, 1>(g, lds, s); return true;
     case 212: *e = launch_kslice_pipe<2, 1, 2>(g, lds, s); return true;
     case 222: *e = launch_kslice_pipe<2, 2, 2>(g, lds, s); return true;
     case 214: *e = launch_kslice_pipe<2, 1, 4>(g, lds, s); return true;
@@ -1620,8 +1628,8 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
       // pipelined kernel leaves no argmax candidates)
       bool all_partial = true;
       for (int i = 0; i < n_probs; ++i) all_partial &= probs[i].epi == EPI_PARTIAL;
-      if (plan.mc == 2 && plan.uneven && !all_partial) return hipErrorInvalidValue;
-      if (hl && (several_slices || plan.uneven) && (plan.mc >= 4 || (plan.mc == 2 && plan.uneven)) && launch_kslice_pipe_any(g, plan.kf, plan.nt, plan.mc, lds, s, &e)) {
+      if (plan.mc <= 2 && plan.uneven && !all_partial) return hipErrorInvalidValue;
+      if (hl && (several_slices || plan.uneven) && (plan.mc >= 4 || (plan.mc <= 2 && plan.uneven)) && launch_kslice_pipe_any(g, plan.kf, plan.nt, plan.mc, lds, s, &e)) {
         if (e != hipSuccess) return e;
         break;
       }

@@ -122,7 +122,7 @@ int main() {
   }
 
   // the GEMM planner over many shapes: whatever it answers, the splits divide K into whole slices, or (uneven
-  // plans: two planes, 64-element slices, 129-256 rows or partial sums at 65-128 rows) there are at most as many splits as slices
+  // plans: two planes, 64-element slices, 129-256 rows or partial sums with fewer rows) there are at most as many splits as slices
   {
     using namespace bt;
     const int Ms[] = {1, 5, 16, 63, 64, 65, 128, 129, 192, 193, 255, 256, 257, 1000, 16384};
@@ -151,7 +151,8 @@ int main() {
                     EXPECT(plan.uneven == 0 || plan.uneven == 1);
                     if (plan.uneven) {
                       EXPECT(hl && plan.kind == 2 && plan.kf == 2 && plan.nt <= 2);
-                      EXPECT((plan.mc == 4 && M > 128 && M <= 256) || (plan.mc == 2 && M > 64 && M <= 128 && epi == EPI_PARTIAL));
+                      EXPECT((plan.mc == 4 && M > 128 && M <= 256) || (plan.mc == 2 && M > 64 && M <= 128 && epi == EPI_PARTIAL) ||
+                             (plan.mc == 1 && M <= 64 && epi == EPI_PARTIAL));
                       EXPECT(plan.splits[i] >= 1 && p[i].K % 64 == 0 && plan.splits[i] <= p[i].K / 64);
                     } else {
                       EXPECT(plan.splits[i] >= 1 && p[i].K % plan.splits[i] == 0);
