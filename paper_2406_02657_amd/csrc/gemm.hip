@@ -972,14 +972,16 @@ __global__ __launch_bounds__(256) void gemm_kslice_kernel(KsGroup g) {
   }
 }
 
-// The same kernel for workgroups that walk several K-slices (k_iters >= 2), as a
-// software pipeline over two LDS buffers: while slice it is multiplied out of one
-// buffer, the registers holding slice it + 1 are written to the other and refilled
-// with slice it + 2 from global memory, one 256-thread chunk per multiply step, so
-// the loads, the LDS stores and the matrix instructions of a wave interleave
-// instead of taking turns (one workgroup per CU: nobody else would fill the gaps).
-// One barrier per slice.  hi + remainder planes only; MC * KF <= 8 (registers: a
-// whole slice is held by the 256 threads); LDS: twice the slice.
+// The K-slice kernel as a software pipeline over two LDS buffers, for launches whose
+// workgroups walk several 64-element K-slices (a single slice works too): while slice it
+// is multiplied out of one buffer, the registers holding slice it + 1 are written to the
+// other and refilled with slice it + 2 from global memory, one 256-thread chunk per
+// multiply step, so the loads, the LDS stores and the matrix instructions of a wave
+// interleave instead of taking turns (one workgroup per CU at 129-256 rows: nobody else
+// would fill the gaps).  One barrier per slice.  The K-slices of a problem are dealt to
+// its splits as evenly as they go.  hi + remainder planes only; EPI_PARTIAL or EPI_F32
+// without argmax candidates; MC * KF <= 8 (registers: a whole slice is held by the 256
+// threads); LDS: twice the slice, and a 16-row strip per wave for the epilogue.
 // ---------------------------------------------------------------------------
 constexpr int kPipeWaveRows = 1;               // waves along the rows of the workgroup's tile: 1 or 2 (measured equal)
 
