@@ -1370,16 +1370,18 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
   // with all workgroups in one round.  Measured on 256 x 2048 x {2048, 8192} in one launch:
   // 16 slices per workgroup on 160 CUs against 11 on 240.  At 129-256 rows it serves every launch
   // (the plan above stands unless a q is clearly shorter); with fewer rows only launches made of
-  // partial-sum problems (the others leave argmax candidates, which the plain kernel writes): at
-  // 65-128 rows where the slice length above is 64 already, up to 64 rows always, with the slice
-  // length set to 64 here (cfg1, 64 rows: 430 -> 409 us per decode step against the plain kernel's
-  // one-shot 192-element slices; longer walks with fewer partial planes 418).
+  // partial-sum problems (the others leave argmax candidates, which the plain kernel writes), with
+  // the slice length set to 64 here (cfg1, 64 rows: 430 -> 409 us per decode step against the plain
+  // kernel's one-shot 192-element slices; longer walks with fewer partial planes 418).
   bool all_partial = true;
   for (int i = 0; i < n_probs; ++i) all_partial &= probs[i].epi == EPI_PARTIAL;
   const bool rows256 = hl && plan->mc == 4 && kf == 2 && plan->nt <= 2;
-  const bool rows128 = hl && plan->mc == 2 && kf == 2 && all_partial;
+  bool rows128 = hl && plan->mc == 2 && all_partial;
   bool rows64 = hl && plan->mc == 1 && all_partial;
-  for (int i = 0; i < n_probs; ++i) rows64 &= probs[i].K % 64 == 0;
+  for (int i = 0; i < n_probs; ++i) {
+    rows128 &= probs[i].K % 64 == 0;
+    rows64 &= probs[i].K % 64 == 0;
+  }
   if (rows256 || rows128 || rows64) {
     const double slice_us[3] = {0, rows256 ? 1.3 : rows128 ? 0.7 : 0.35, rows256 ? 1.9 : rows128 ? 1.0 : 0.5};   // per 64-element slice at nt = 1, 2
     constexpr double kPartialBytesPerUs = 5e6;
@@ -1414,7 +1416,7 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
           plan->splits[0] = spl[0];
           plan->splits[1] = spl[1];
           plan->uneven = 1;
-          if (rows64) plan->kf = 2;
+          plan->kf = 2;
         }
       }
   }
