@@ -1311,9 +1311,10 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
   plan->kind = KIND_KSLICE;
   plan->mc = (max_m + 63) / 64;
   if (plan->mc == 3) plan->mc = 4;
-  // Up to 128 rows the slice stays within 64 KB (two workgroups per CU overlap their phases).
-  // With more rows the multiply dominates and one workgroup per CU walks many slices; it then
-  // overlaps load and multiply itself (pipelined kernel), which needs mc * kf <= 8.
+  // Plain kernel: up to 128 rows the slice stays within 64 KB (two workgroups per CU overlap their
+  // phases).  With more rows one workgroup per CU walks many slices and overlaps load and multiply
+  // itself (pipelined kernel), which needs mc * kf <= 8; the two-plane partial-sum launches with
+  // fewer rows are moved to that kernel, with 64-element slices, further down.
   const size_t lds_cap = max_m <= 128 ? 64 * 1024 : 144 * 1024;
   int kf = 2;
   for (int c : {8, 6, 4, 2}) {
@@ -1625,11 +1626,10 @@ hipError_t launch_gemm(int dtype, const GemmProblem* probs, int n_probs, const G
       hipError_t e;
       bool several_slices = false;
       for (int i = 0; i < n_probs; ++i) several_slices |= probs[i].K / (32 * plan.kf * plan.splits[i]) >= 2;
-      // With few rows several workgroups share a CU and overlap each other's phases better than one
-      // pipelined workgroup does (LM head at 64 rows: 24 us against 27 us), so the pipelined
-      // variant serves the shapes that leave room for one workgroup per CU only.
-      // ... and, at 65-128 rows, launches the planner marked for it (partial-sum problems only: the
-      // pipelined kernel leaves no argmax candidates)
+      // The pipelined kernel serves every two-plane launch at 129-256 rows and, with fewer rows, the
+      // launches the planner marked for it (partial-sum problems only: it leaves no argmax
+      // candidates; the LM head at 64 rows was no faster on it than on the plain kernel, where
+      // several workgroups per CU overlap each other's phases).
       bool all_partial = true;
       for (int i = 0; i < n_probs; ++i) all_partial &= probs[i].epi == EPI_PARTIAL;
       if (plan.mc <= 2 && plan.uneven && !all_partial) return hipErrorInvalidValue;
