@@ -1373,12 +1373,13 @@ hipError_t gemm_plan(int dtype, const GemmProblem* probs, int n_probs, GemmPlan*
   // (the plan above stands unless a q is clearly shorter); with fewer rows only launches made of
   // partial-sum problems (the others leave argmax candidates, which the plain kernel writes), with
   // the slice length set to 64 here (cfg1, 64 rows: 430 -> 409 us per decode step against the plain
-  // kernel's one-shot 192-element slices; longer walks with fewer partial planes 418).
+  // kernel's one-shot 192-element slices; longer walks with fewer partial planes 418; batch 1 and 4
+  // on the same model: 341 -> 350 and 345 -> 358 us, hence not below 8 rows).
   bool all_partial = true;
   for (int i = 0; i < n_probs; ++i) all_partial &= probs[i].epi == EPI_PARTIAL;
   const bool rows256 = hl && plan->mc == 4 && kf == 2 && plan->nt <= 2;
   bool rows128 = hl && plan->mc == 2 && all_partial;
-  bool rows64 = hl && plan->mc == 1 && all_partial;
+  bool rows64 = hl && plan->mc == 1 && max_m >= 8 && all_partial;     // below 8 rows the plain kernel's one slice per workgroup is faster
   for (int i = 0; i < n_probs; ++i) {
     rows128 &= probs[i].K % 64 == 0;
     rows64 &= probs[i].K % 64 == 0;
